@@ -1,0 +1,276 @@
+"""ctypes front end of the plain f64 CPU oracle (``scd_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY: imported by the tests, by the smoke check and by the benchmark's
+CPU-baseline leg.  The GPU package never imports this module.
+
+Every function takes and returns numpy arrays; sign vectors are ``uint64`` bitsets in which a
+1 bit stands for -1 (Section 3.1 of the paper), element ``64p+q`` in bit ``q`` of word ``p``.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from pathlib import Path
+
+import numpy as np
+
+_HERE = Path(__file__).resolve().parent
+_SRC = _HERE / "scd_oracle.c"
+_LIB = _HERE / "libscd_oracle.so"
+_lib = None
+
+_f64p = np.ctypeslib.ndpointer(dtype=np.float64, flags="C_CONTIGUOUS")
+_u64p = np.ctypeslib.ndpointer(dtype=np.uint64, flags="C_CONTIGUOUS")
+_i32p = np.ctypeslib.ndpointer(dtype=np.int32, flags="C_CONTIGUOUS")
+_i64p = np.ctypeslib.ndpointer(dtype=np.int64, flags="C_CONTIGUOUS")
+
+
+def build(force: bool = False) -> Path:
+    """Compile the oracle with gcc (-O2, OpenMP).  Rebuilds when the source is newer."""
+    if force or not _LIB.exists() or _LIB.stat().st_mtime < _SRC.stat().st_mtime:
+        cmd = ["gcc", "-O2", "-fopenmp", "-fno-fast-math", "-ffp-contract=off", "-std=c11", "-shared",
+               "-fPIC", "-o", str(_LIB), str(_SRC), "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    build()
+    L = C.CDLL(str(_LIB))
+    vp = C.c_void_p
+    L.scdo_set_threads.argtypes = [C.c_int]
+    L.scdo_get_threads.restype = C.c_int
+    L.scdo_rng_word.argtypes = [C.c_uint64, C.c_uint64, C.c_uint32, C.c_uint64]
+    L.scdo_rng_word.restype = C.c_uint64
+    L.scdo_rng_signs.argtypes = [C.c_uint64, C.c_uint64, C.c_uint32, C.c_int64, _u64p]
+    L.scdo_pack.argtypes = [_f64p, C.c_int64, _u64p]
+    L.scdo_unpack.argtypes = [_u64p, C.c_int64, _f64p]
+    L.scdo_row_signed_sum.argtypes = [_f64p, C.c_int64, C.c_int64, _u64p, _f64p]
+    L.scdo_col_signed_sum.argtypes = [_f64p, C.c_int64, C.c_int64, _u64p, _f64p]
+    L.scdo_fro2.argtypes = [_f64p, C.c_int64, C.c_int64]
+    L.scdo_fro2.restype = C.c_double
+    L.scdo_rank1_update.argtypes = [_f64p, C.c_int64, C.c_int64, C.c_double, _u64p, _u64p]
+    L.scdo_greedy_signed_cut.argtypes = [_f64p, C.c_int64, C.c_int64, _u64p, _u64p,
+                                         C.POINTER(C.c_double), C.c_int32, C.POINTER(C.c_int32), vp, vp]
+    L.scdo_greedy_signed_cut.restype = C.c_int
+    L.scdo_decompose.argtypes = [_f64p, C.c_int64, C.c_int64, C.c_int64, C.c_uint64, C.c_int32,
+                                 _u64p, _u64p, _f64p, _f64p, vp, vp, vp]
+    L.scdo_decompose.restype = C.c_int
+    L.scdo_mode_signed_sum.argtypes = [_f64p, C.c_int, _i64p, C.POINTER(vp), C.c_int, _f64p]
+    L.scdo_tensor_inner.argtypes = [_f64p, C.c_int, _i64p, C.POINTER(vp)]
+    L.scdo_tensor_inner.restype = C.c_double
+    L.scdo_tensor_update.argtypes = [_f64p, C.c_int, _i64p, C.c_double, C.POINTER(vp)]
+    L.scdo_axial_greedy_cut.argtypes = [_f64p, C.c_int, _i64p, C.POINTER(vp), C.POINTER(C.c_double),
+                                        C.c_int32, C.POINTER(C.c_int32), vp, vp]
+    L.scdo_axial_greedy_cut.restype = C.c_int
+    L.scdo_tensor_decompose.argtypes = [_f64p, C.c_int, _i64p, C.c_int64, C.c_uint64, C.c_int32,
+                                        C.POINTER(vp), _f64p, _f64p, vp, vp, vp]
+    L.scdo_tensor_decompose.restype = C.c_int
+    L.scdo_expand.argtypes = [C.c_int, _i64p, C.c_int64, C.POINTER(vp), _f64p, _f64p]
+    L.scdo_bruteforce_signed_cut_norm.argtypes = [_f64p, C.c_int64, C.c_int64, C.POINTER(C.c_uint64)]
+    L.scdo_bruteforce_signed_cut_norm.restype = C.c_double
+    _lib = L
+    return L
+
+
+DEFAULT_MAX_ITERS = 4096
+
+
+def words(n: int) -> int:
+    return (int(n) + 63) // 64
+
+
+def set_threads(n: int) -> None:
+    _load().scdo_set_threads(int(n))
+
+
+def get_threads() -> int:
+    return int(_load().scdo_get_threads())
+
+
+def _f64(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def _u64(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.uint64)
+
+
+def _ptrs(arrs):
+    arr = (C.c_void_p * len(arrs))()
+    for i, a in enumerate(arrs):
+        arr[i] = a.ctypes.data
+    return arr
+
+
+def _opt(a):
+    return None if a is None else a.ctypes.data
+
+
+def rng_word(seed: int, term: int, mode: int, word: int) -> int:
+    return int(_load().scdo_rng_word(seed, term, mode, word))
+
+
+def rng_signs(seed: int, term: int, mode: int, n: int) -> np.ndarray:
+    """Uniform random sign bitset of length n for (seed, term, mode); padding bits are 0."""
+    out = np.zeros(words(n), dtype=np.uint64)
+    _load().scdo_rng_signs(seed, term, mode, n, out)
+    return out
+
+
+def pack(x) -> np.ndarray:
+    x = _f64(x).ravel()
+    out = np.zeros(words(x.size), dtype=np.uint64)
+    _load().scdo_pack(x, x.size, out)
+    return out
+
+
+def unpack(bits, n: int) -> np.ndarray:
+    out = np.empty(int(n), dtype=np.float64)
+    _load().scdo_unpack(_u64(bits), int(n), out)
+    return out
+
+
+def row_signed_sum(R, tbits) -> np.ndarray:
+    """u = R t."""
+    R = _f64(R)
+    m, n = R.shape
+    u = np.empty(m, dtype=np.float64)
+    _load().scdo_row_signed_sum(R, m, n, _u64(tbits), u)
+    return u
+
+
+def col_signed_sum(R, sbits) -> np.ndarray:
+    """v = R^T s."""
+    R = _f64(R)
+    m, n = R.shape
+    v = np.empty(n, dtype=np.float64)
+    _load().scdo_col_signed_sum(R, m, n, _u64(sbits), v)
+    return v
+
+
+def fro2(R) -> float:
+    R = _f64(R)
+    R2 = R.reshape(R.shape[0], -1) if R.ndim > 1 else R.reshape(1, -1)
+    return float(_load().scdo_fro2(R2, R2.shape[0], R2.shape[1]))
+
+
+def rank1_update(R, ck: float, sbits, tbits) -> None:
+    """In place R <- R - ck s t^T; R must be a C-contiguous float64 array."""
+    assert R.dtype == np.float64 and R.flags.c_contiguous
+    m, n = R.shape
+    _load().scdo_rank1_update(R, m, n, float(ck), _u64(sbits), _u64(tbits))
+
+
+def greedy_signed_cut(R, t0bits, max_iters: int = DEFAULT_MAX_ITERS):
+    """Algorithm 4.  Returns dict(c=<s,Rt> unnormalised, s, t, iters, c_hist, margin, capped)."""
+    R = _f64(R)
+    m, n = R.shape
+    t = _u64(t0bits).copy()
+    s = np.zeros(words(m), dtype=np.uint64)
+    c = C.c_double()
+    it = C.c_int32()
+    hist = np.zeros(max_iters, dtype=np.float64)
+    margin = np.zeros(2, dtype=np.float64)
+    capped = _load().scdo_greedy_signed_cut(R, m, n, t, s, C.byref(c), max_iters, C.byref(it),
+                                            hist.ctypes.data, margin.ctypes.data)
+    return dict(c=c.value, s=s, t=t, iters=it.value, c_hist=hist[: it.value].copy(), margin=margin,
+                capped=bool(capped))
+
+
+def decompose(A, w: int, seed: int, max_iters: int = DEFAULT_MAX_ITERS, want_remainder: bool = False):
+    """Algorithm 5.  Returns dict(S, T, c, trace, iters, margins, capped[, R])."""
+    A = _f64(A)
+    m, n = A.shape
+    S = np.zeros((w, words(m)), dtype=np.uint64)
+    T = np.zeros((w, words(n)), dtype=np.uint64)
+    c = np.zeros(w, dtype=np.float64)
+    trace = np.zeros(w + 1, dtype=np.float64)
+    iters = np.zeros(w, dtype=np.int32)
+    margins = np.zeros((w, 2), dtype=np.float64)
+    R = np.empty_like(A) if want_remainder else None
+    capped = _load().scdo_decompose(A, m, n, w, seed, max_iters, S, T, c, trace, iters.ctypes.data,
+                                    margins.ctypes.data, _opt(R))
+    out = dict(S=S, T=T, c=c, trace=trace, iters=iters, margins=margins, capped=int(capped))
+    if want_remainder:
+        out["R"] = R
+    return out
+
+
+def mode_signed_sum(a, signs, mode: int) -> np.ndarray:
+    a = _f64(a)
+    dims = np.asarray(a.shape, dtype=np.int64)
+    sg = [_u64(s) for s in signs]
+    u = np.empty(a.shape[mode], dtype=np.float64)
+    _load().scdo_mode_signed_sum(a.reshape(-1), a.ndim, dims, _ptrs(sg), mode, u)
+    return u
+
+
+def tensor_inner(a, signs) -> float:
+    a = _f64(a)
+    dims = np.asarray(a.shape, dtype=np.int64)
+    sg = [_u64(s) for s in signs]
+    return float(_load().scdo_tensor_inner(a.reshape(-1), a.ndim, dims, _ptrs(sg)))
+
+
+def tensor_update(r, ck: float, signs) -> None:
+    assert r.dtype == np.float64 and r.flags.c_contiguous
+    dims = np.asarray(r.shape, dtype=np.int64)
+    sg = [_u64(s) for s in signs]
+    _load().scdo_tensor_update(r.reshape(-1), r.ndim, dims, float(ck), _ptrs(sg))
+
+
+def axial_greedy_cut(a, signs0, max_iters: int = DEFAULT_MAX_ITERS):
+    """Algorithm 12.  signs0: one bitset per mode (mode 0's is never read)."""
+    a = _f64(a)
+    dims = np.asarray(a.shape, dtype=np.int64)
+    sg = [_u64(s).copy() for s in signs0]
+    c = C.c_double()
+    it = C.c_int32()
+    hist = np.zeros(max_iters, dtype=np.float64)
+    margin = np.zeros(a.ndim, dtype=np.float64)
+    capped = _load().scdo_axial_greedy_cut(a.reshape(-1), a.ndim, dims, _ptrs(sg), C.byref(c), max_iters,
+                                           C.byref(it), hist.ctypes.data, margin.ctypes.data)
+    return dict(c=c.value, signs=sg, iters=it.value, c_hist=hist[: it.value].copy(), margin=margin,
+                capped=bool(capped))
+
+
+def tensor_decompose(a, w: int, seed: int, max_iters: int = DEFAULT_MAX_ITERS, want_remainder: bool = False):
+    """Algorithm 13.  Returns dict(signs=[per-mode (w, words) arrays], c, trace, iters, margins[, r])."""
+    a = _f64(a)
+    dims = np.asarray(a.shape, dtype=np.int64)
+    sg = [np.zeros((w, words(d)), dtype=np.uint64) for d in a.shape]
+    c = np.zeros(w, dtype=np.float64)
+    trace = np.zeros(w + 1, dtype=np.float64)
+    iters = np.zeros(w, dtype=np.int32)
+    margins = np.zeros((w, a.ndim), dtype=np.float64)
+    r = np.empty_like(a) if want_remainder else None
+    capped = _load().scdo_tensor_decompose(a.reshape(-1), a.ndim, dims, w, seed, max_iters, _ptrs(sg), c,
+                                           trace, iters.ctypes.data, margins.ctypes.data, _opt(r))
+    out = dict(signs=sg, c=c, trace=trace, iters=iters, margins=margins, capped=int(capped))
+    if want_remainder:
+        out["r"] = r
+    return out
+
+
+def expand(signs, c, dims) -> np.ndarray:
+    """sum_j c[j] * (tensor product of term j's sign vectors), f64, terms added in order."""
+    dims = np.asarray(dims, dtype=np.int64)
+    sg = [_u64(s) for s in signs]
+    c = _f64(c).ravel()
+    out = np.empty(int(np.prod(dims)), dtype=np.float64)
+    _load().scdo_expand(len(dims), dims, c.size, _ptrs(sg), c, out)
+    return out.reshape(tuple(int(d) for d in dims))
+
+
+def bruteforce_signed_cut_norm(A):
+    """max_s ||A^T s||_1 by enumeration (m <= 24).  Returns (norm, s bitmask as int)."""
+    A = _f64(A)
+    m, n = A.shape
+    arg = C.c_uint64()
+    val = _load().scdo_bruteforce_signed_cut_norm(A, m, n, C.byref(arg))
+    return float(val), int(arg.value)

@@ -1,0 +1,354 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix (no GPU needed).
+
+Each test names the passage of arXiv 2410.01799 it rests on.  The checks are written with plain
+numpy on dense +-1 vectors, independently of the oracle's bitset code, so that a dropped term, a
+wrong sign, a wrong index or a transposed operand in the oracle fails at least one of them.
+"""
+import itertools
+import math
+from pathlib import Path
+
+import numpy as np
+import pytest
+
+GOLD = Path(__file__).parent / "golden"
+
+
+def dense(bits, n):
+    """Independent unpack: +-1 float64 vector from a uint64 bitset (1 bit = -1, LSB first)."""
+    b = np.asarray(bits, dtype=np.uint64)
+    idx = np.arange(n)
+    return 1.0 - 2.0 * ((b[idx // 64] >> (idx % 64).astype(np.uint64)) & np.uint64(1)).astype(np.float64)
+
+
+def bits_of(vec):
+    """Independent pack of a +-1 vector."""
+    vec = np.asarray(vec)
+    out = np.zeros((vec.size + 63) // 64, dtype=np.uint64)
+    for i, x in enumerate(vec):
+        if x < 0:
+            out[i // 64] |= np.uint64(1) << np.uint64(i % 64)
+    return out
+
+
+def rng_matrix(m, n, seed):
+    return np.random.default_rng(seed).standard_normal((m, n))
+
+
+# ------------------------------------------------------------------ bitsets and the random stream
+
+
+def test_pack_unpack_convention(oracle):
+    # Section 3.1: a 1 bit stands for -1.  Reading fixed here: sgn(+-0) = +1.
+    x = np.array([1.5, -2.0, 0.0, -0.0, -1e-300, 3.0] + [(-1.0) ** k for k in range(70)])
+    bits = oracle.pack(x)
+    assert bits.dtype == np.uint64 and bits.size == 2
+    expect = np.where(x < 0, -1.0, 1.0)
+    assert np.array_equal(dense(bits, x.size), expect)
+    assert np.array_equal(oracle.unpack(bits, x.size), expect)
+    assert int(bits[0]) & 0b111111 == 0b010010          # elements 1 and 4 are negative
+    assert int(bits[1]) >> (x.size - 64) == 0            # padding bits stay clear
+
+
+def test_rng_stream_is_uniform_and_keyed(oracle):
+    n = 64 * 300 + 17
+    a = oracle.rng_signs(7, 0, 1, n)
+    assert a.size == 301 and int(a[-1]) >> 17 == 0
+    frac = (dense(a, n) < 0).mean()
+    assert abs(frac - 0.5) < 4 * 0.5 / math.sqrt(n)
+    # every key component changes the stream; the stream is a pure function of its key
+    assert np.array_equal(a, oracle.rng_signs(7, 0, 1, n))
+    for other in (oracle.rng_signs(8, 0, 1, n), oracle.rng_signs(7, 1, 1, n), oracle.rng_signs(7, 0, 2, n)):
+        agree = (dense(other, n) == dense(a, n)).mean()
+        assert abs(agree - 0.5) < 5 * 0.5 / math.sqrt(n)
+    # words are independent of the length asked for (counter based)
+    assert np.array_equal(oracle.rng_signs(7, 0, 1, 640)[:5], a[:5])
+    assert oracle.rng_word(7, 0, 1, 3) == int(a[3])
+
+
+# ------------------------------------------------------------------ the two products
+
+
+@pytest.mark.parametrize("m,n", [(5, 9), (70, 33), (64, 128), (1, 7), (130, 1)])
+def test_signed_sums_match_dense_products(oracle, m, n):
+    R = rng_matrix(m, n, 10 * m + n)
+    t = np.sign(np.random.default_rng(1).standard_normal(n))
+    s = np.sign(np.random.default_rng(2).standard_normal(m))
+    u = oracle.row_signed_sum(R, bits_of(t))
+    v = oracle.col_signed_sum(R, bits_of(s))
+    assert u.shape == (m,) and v.shape == (n,)
+    np.testing.assert_allclose(u, R @ t, rtol=0, atol=1e-12 * n)
+    np.testing.assert_allclose(v, R.T @ s, rtol=0, atol=1e-12 * m)
+
+
+def test_thread_count_does_not_change_results(oracle):
+    R = rng_matrix(96, 200, 3)
+    old = oracle.get_threads()
+    try:
+        oracle.set_threads(1)
+        d1 = oracle.decompose(R, 6, 11)
+        oracle.set_threads(4)
+        d4 = oracle.decompose(R, 6, 11)
+    finally:
+        oracle.set_threads(old)
+    for k in ("S", "T", "c", "trace", "iters"):
+        assert np.array_equal(d1[k], d4[k])
+
+
+# ------------------------------------------------------------------ Algorithm 4
+
+
+@pytest.mark.parametrize("m,n,seed", [(8, 8, 0), (40, 70, 1), (129, 65, 2), (256, 256, 3)])
+def test_greedy_cut_is_monotone_and_a_fixed_point(oracle, m, n, seed):
+    # Algorithm 4 keeps going only while c_j > c_{j-1}; Section 3.1 (Left/RightSgnCut) shows
+    # c_j = ||R^T s_j||_1 >= <s_j, R t_{j-1}> = ||R t_{j-1}||_1 >= c_{j-1}.
+    R = rng_matrix(m, n, seed)
+    t0 = oracle.rng_signs(seed, 0, 1, n)
+    g = oracle.greedy_signed_cut(R, t0)
+    assert not g["capped"] and g["iters"] >= 2
+    h = g["c_hist"]
+    assert np.all(np.diff(h[:-1]) > 0)
+    assert h[-1] <= h[-2] and h[-1] >= h[-2] * (1 - 1e-12)
+    s, t = dense(g["s"], m), dense(g["t"], n)
+    # the returned triple: c = <s, R t> = ||R^T s||_1 = ||R t||_1 at the fixed point
+    assert g["c"] == pytest.approx(s @ R @ t, rel=1e-12)
+    assert g["c"] == pytest.approx(np.abs(R.T @ s).sum(), rel=1e-12)
+    assert g["c"] == pytest.approx(np.abs(R @ t).sum(), rel=1e-12)
+    assert np.array_equal(np.where(R @ t < 0, -1.0, 1.0), s)
+    assert np.array_equal(np.where(R.T @ s < 0, -1.0, 1.0), t)
+    # first alternation replayed by hand from t_0
+    t0d = dense(t0, n)
+    s1 = np.where(R @ t0d < 0, -1.0, 1.0)
+    t1 = np.where(R.T @ s1 < 0, -1.0, 1.0)
+    assert h[0] == pytest.approx(s1 @ R @ t1, rel=1e-12)
+    # margins are the smallest relative |entry| seen at any sign decision
+    assert 0 <= g["margin"][0] <= 1 and 0 <= g["margin"][1] <= 1
+
+
+def test_greedy_cut_against_brute_force(oracle):
+    # Section 2.2: ||A|| = max_{s,t} <s, A t>.  Greedy never exceeds it, ends 1-flip optimal,
+    # and the best start among all 2^n reaches it.
+    for seed, (m, n) in enumerate([(3, 4), (6, 5), (8, 8), (7, 3)]):
+        A = rng_matrix(m, n, 100 + seed)
+        best = -np.inf
+        for sv in itertools.product((-1.0, 1.0), repeat=m):
+            best = max(best, np.abs(A.T @ np.array(sv)).sum())
+        bf, arg = oracle.bruteforce_signed_cut_norm(A)
+        assert bf == pytest.approx(best, rel=1e-13)
+        sbest = np.array([-1.0 if (arg >> i) & 1 else 1.0 for i in range(m)])
+        assert np.abs(A.T @ sbest).sum() == pytest.approx(best, rel=1e-13)
+        reached = -np.inf
+        for tv in itertools.product((-1.0, 1.0), repeat=n):
+            g = oracle.greedy_signed_cut(A, bits_of(tv))
+            assert g["c"] <= best * (1 + 1e-12)
+            s, t = dense(g["s"], m), dense(g["t"], n)
+            base = s @ A @ t
+            for i in range(m):            # flipping one s_i changes <s,At> by -2 s_i (At)_i <= 0
+                s2 = s.copy(); s2[i] = -s2[i]
+                assert s2 @ A @ t <= base + 1e-12
+            for l in range(n):
+                t2 = t.copy(); t2[l] = -t2[l]
+                assert s @ A @ t2 <= base + 1e-12
+            reached = max(reached, g["c"])
+        assert reached == pytest.approx(best, rel=1e-12)
+
+
+def test_one_term_recovery(oracle):
+    # A = c s t^T is recovered exactly in one term (odd n so that <t, t_0> != 0).
+    m, n, c = 37, 51, 0.625
+    rs = np.random.default_rng(5)
+    s = np.sign(rs.standard_normal(m)); t = np.sign(rs.standard_normal(n))
+    for coef in (c, -c):
+        A = coef * np.outer(s, t)
+        d = oracle.decompose(A, 2, 9, want_remainder=True)
+        assert d["c"][0] == pytest.approx(abs(coef), rel=1e-14)
+        got = d["c"][0] * np.outer(dense(d["S"][0], m), dense(d["T"][0], n))
+        np.testing.assert_allclose(got, A, rtol=0, atol=1e-15)
+        assert d["trace"][1] <= 1e-14 * d["trace"][0]
+        assert d["iters"][0] == 2
+
+
+# ------------------------------------------------------------------ Algorithm 5
+
+
+@pytest.mark.parametrize("m,n,w,seed", [(64, 64, 20, 1), (33, 100, 25, 2), (200, 47, 25, 3)])
+def test_decomposition_invariants(oracle, m, n, w, seed):
+    A = rng_matrix(m, n, 40 + seed)
+    d = oracle.decompose(A, w, seed, want_remainder=True)
+    F = d["trace"] ** 2
+    c = d["c"]
+    assert d["capped"] == 0
+    # Section 3.2 identity, with the normalised coefficient: ||R_{k+1}||^2 = ||R_k||^2 - m n c^2
+    np.testing.assert_allclose(F[1:], F[:-1] - m * n * c ** 2, rtol=1e-12)
+    assert F[0] == pytest.approx((A ** 2).sum(), rel=1e-13)
+    assert np.all(c > 0) and np.all(np.diff(d["trace"]) < 0)
+    # definition (abstract, Section 2.2): A - R_w = sum_j c_j s_j t_j^T, rebuilt densely here
+    R = A.copy()
+    for k in range(w):
+        s, t = dense(d["S"][k], m), dense(d["T"][k], n)
+        # coefficient of term k is <s, R_k t> / (mn) on the remainder it was found on
+        assert c[k] == pytest.approx(s @ R @ t / (m * n), rel=1e-10)
+        # and it starts from the keyed random t_0: first s is sgn(R t_0)
+        R -= c[k] * np.outer(s, t)
+        # Algorithm 5 caption: the new remainder is orthogonal to s t^T
+        assert abs(s @ R @ t) <= 1e-10 * np.abs(R).sum()
+        assert np.linalg.norm(R) == pytest.approx(d["trace"][k + 1], rel=1e-11)
+    np.testing.assert_allclose(d["R"], R, rtol=0, atol=1e-12)
+    # the independent expansion agrees with the definition
+    E = oracle.expand([d["S"], d["T"]], c, (m, n))
+    np.testing.assert_allclose(A - E, R, rtol=0, atol=1e-12)
+
+
+def test_decompose_is_algorithm4_repeated(oracle):
+    # Term k of Algorithm 5 is Algorithm 4 on R_k started from the keyed t_0 of term k.
+    m, n, w, seed = 48, 80, 5, 21
+    A = rng_matrix(m, n, 77)
+    d = oracle.decompose(A, w, seed)
+    R = A.copy()
+    for k in range(w):
+        g = oracle.greedy_signed_cut(R, oracle.rng_signs(seed, k, 1, n))
+        assert np.array_equal(g["s"], d["S"][k]) and np.array_equal(g["t"], d["T"][k])
+        assert g["iters"] == d["iters"][k]
+        assert g["c"] / (m * n) == d["c"][k]
+        oracle.rank1_update(R, d["c"][k], g["s"], g["t"])
+        assert math.sqrt(oracle.fro2(R)) == d["trace"][k + 1]
+
+
+def test_expand_order_and_rounding(oracle):
+    # Per entry the terms are added in the order j = 0..w-1 into one f64 accumulator.
+    rs = np.random.default_rng(8)
+    m, n, w = 9, 70, 40
+    S = np.array([bits_of(np.sign(rs.standard_normal(m))) for _ in range(w)])
+    T = np.array([bits_of(np.sign(rs.standard_normal(n))) for _ in range(w)])
+    c = rs.standard_normal(w) * 10.0 ** rs.uniform(-8, 8, w)
+    E = oracle.expand([S, T], c, (m, n))
+    ref = np.zeros((m, n))
+    for j in range(w):
+        ref = ref + c[j] * np.outer(dense(S[j], m), dense(T[j], n))
+    assert np.array_equal(E, ref)
+
+
+# ------------------------------------------------------------------ printed values
+
+
+def read_scalars():
+    out = {}
+    for line in (GOLD / "printed_values.txt").read_text().splitlines():
+        line = line.split("#")[0].split()
+        if len(line) == 2:
+            out[line[0]] = float(line[1])
+    return out
+
+
+def test_fig7_cast_errors():
+    # Figure 7: bf16 and f16 down-cast errors of an N(0,1) matrix -- pins the error metric r_k.
+    from paper_2410_01799_amd import workloads as W
+
+    g = read_scalars()
+    A = W.gaussian_matrix(1024, 1024, 2, np.float64)
+    bf = W.round_to_bf16(A.astype(np.float32)).astype(np.float64)
+    assert W.relative_error(bf, A) == pytest.approx(g["bf16_cast_rel_error"], rel=0.02)
+    assert W.relative_error(A.astype(np.float16), A) == pytest.approx(g["f16_cast_rel_error"], rel=0.02)
+
+
+def test_fig7_decay_slope(oracle):
+    # Figure 7: the break-even rates 0.2064 (bf16, error 0.00166) and 0.2734 (f16, 0.000208) at
+    # 64+m+n bits per term on 4096^2 fix the per-term decay of ln r_k.  Both points give the same
+    # slope; the oracle must reproduce it on a 4096^2 N(0,1) matrix (prefix of the run).
+    g = read_scalars()
+    bits = 64 * 4096 * 4096 / (64 + 8192)
+    k_bf, k_f = g["breakeven_rate_bf16"] * bits, g["breakeven_rate_f16"] * bits
+    slope_bf = math.log(g["bf16_cast_rel_error"]) / k_bf
+    slope_f = math.log(g["f16_cast_rel_error"]) / k_f
+    assert slope_bf == pytest.approx(slope_f, rel=5e-3)
+    from paper_2410_01799_amd import workloads as W
+
+    A = W.gaussian_matrix(4096, 4096, 2, np.float64)
+    w = 10
+    d = oracle.decompose(A, w, 2)
+    slope = math.log(d["trace"][w] / d["trace"][0]) / w
+    assert slope == pytest.approx(slope_bf, rel=0.04)
+
+
+# ------------------------------------------------------------------ tensors (Section 5)
+
+
+def kron_sign(vecs):
+    out = np.array([1.0])
+    for v in vecs:
+        out = np.multiply.outer(out, v)
+    return out.reshape([len(v) for v in vecs])
+
+
+def test_mode_sums_match_einsum(oracle):
+    rs = np.random.default_rng(12)
+    a = rs.standard_normal((5, 7, 3))
+    sv = [np.sign(rs.standard_normal(d)) for d in a.shape]
+    sb = [bits_of(v) for v in sv]
+    np.testing.assert_allclose(oracle.mode_signed_sum(a, sb, 0), np.einsum("ijk,j,k->i", a, sv[1], sv[2]), atol=1e-12)
+    np.testing.assert_allclose(oracle.mode_signed_sum(a, sb, 1), np.einsum("ijk,i,k->j", a, sv[0], sv[2]), atol=1e-12)
+    np.testing.assert_allclose(oracle.mode_signed_sum(a, sb, 2), np.einsum("ijk,i,j->k", a, sv[0], sv[1]), atol=1e-12)
+    assert oracle.tensor_inner(a, sb) == pytest.approx((a * kron_sign(sv)).sum(), rel=1e-12)
+
+
+def test_axial_cut_sweeps_in_order_and_is_monotone(oracle):
+    # Algorithm 12: mode i uses the new signs of modes < i and the old signs of modes > i.
+    rs = np.random.default_rng(13)
+    a = rs.standard_normal((6, 5, 4))
+    s0 = [oracle.rng_signs(3, 0, i, d) for i, d in enumerate(a.shape)]
+    g = oracle.axial_greedy_cut(a, s0)
+    h = g["c_hist"]
+    assert np.all(np.diff(h[:-1]) > 0) and h[-1] <= h[-2]
+    cur = [dense(b, d) for b, d in zip(s0, a.shape)]
+    cur[0] = np.where(np.einsum("ijk,j,k->i", a, cur[1], cur[2]) < 0, -1.0, 1.0)
+    cur[1] = np.where(np.einsum("ijk,i,k->j", a, cur[0], cur[2]) < 0, -1.0, 1.0)
+    cur[2] = np.where(np.einsum("ijk,i,j->k", a, cur[0], cur[1]) < 0, -1.0, 1.0)
+    assert h[0] == pytest.approx((a * kron_sign(cur)).sum(), rel=1e-12)
+    fin = [dense(b, d) for b, d in zip(g["signs"], a.shape)]
+    assert g["c"] == pytest.approx((a * kron_sign(fin)).sum(), rel=1e-12)
+    # brute force over all sign tensors of this tiny shape bounds the greedy value
+    best = -np.inf
+    for s1 in itertools.product((-1.0, 1.0), repeat=6):
+        for s2 in itertools.product((-1.0, 1.0), repeat=5):
+            w = np.einsum("ijk,i,j->k", a, np.array(s1), np.array(s2))
+            best = max(best, np.abs(w).sum())
+    assert g["c"] <= best * (1 + 1e-12)
+
+
+@pytest.mark.parametrize("shape,w,seed", [((6, 5, 4), 12, 1), ((3, 4, 2, 5), 10, 2), ((70, 9, 3), 8, 3)])
+def test_tensor_decomposition_invariants(oracle, shape, w, seed):
+    a = np.random.default_rng(50 + seed).standard_normal(shape)
+    N = a.size
+    d = oracle.tensor_decompose(a, w, seed, want_remainder=True)
+    F = d["trace"] ** 2
+    # Algorithm 13 line 8 with the normalised coefficient: ||r_{k+1}||^2 = ||r_k||^2 - N c^2
+    np.testing.assert_allclose(F[1:], F[:-1] - N * d["c"] ** 2, rtol=1e-12)
+    r = a.copy()
+    for k in range(w):
+        sg = kron_sign([dense(d["signs"][i][k], n) for i, n in enumerate(shape)])
+        assert d["c"][k] == pytest.approx((r * sg).sum() / N, rel=1e-10)
+        r -= d["c"][k] * sg
+    np.testing.assert_allclose(d["r"], r, atol=1e-12)
+    E = oracle.expand(d["signs"], d["c"], shape)
+    np.testing.assert_allclose(a - E, r, atol=1e-12)
+
+
+def test_order2_tensor_path_is_the_matrix_path(oracle):
+    # Section 5.1: Algorithm 12 extends Algorithm 4; with two modes they coincide.
+    A = rng_matrix(40, 56, 31)
+    dm = oracle.decompose(A, 8, 5)
+    dt = oracle.tensor_decompose(A, 8, 5)
+    assert np.array_equal(dm["S"], dt["signs"][0]) and np.array_equal(dm["T"], dt["signs"][1])
+    assert np.array_equal(dm["iters"], dt["iters"])
+    np.testing.assert_allclose(dm["c"], dt["c"], rtol=1e-12)
+    np.testing.assert_allclose(dm["trace"], dt["trace"], rtol=1e-12)
+
+
+def test_rank_one_tensor_recovery(oracle):
+    rs = np.random.default_rng(4)
+    shape = (7, 5, 3)
+    sv = [np.sign(rs.standard_normal(d)) for d in shape]
+    a = -1.75 * kron_sign(sv)
+    d = oracle.tensor_decompose(a, 1, 6, want_remainder=True)
+    assert d["c"][0] == pytest.approx(1.75, rel=1e-14)
+    assert np.abs(d["r"]).max() <= 1e-15
