@@ -1,0 +1,135 @@
+/*
+ * scd.h -- C ABI of the MI355X signed cut decomposition library (libscd.so).
+ *
+ * Method: "Efficient 1-bit tensor approximations", arXiv 2410.01799.
+ * A width-w signed cut decomposition of a matrix A (m x n) is
+ *        A - R_w = sum_{j<w} c_j * s_j t_j^T ,   s_j in {-1,1}^m, t_j in {-1,1}^n      (abstract, Section 2.2)
+ * and of an order-k tensor a (n_1 x ... x n_k)
+ *        a - r_w = sum_{j<w} c_j * s_j^(1) (x) ... (x) s_j^(k)                          (Section 5.2).
+ * The library builds it with the greedy width loop: Algorithm 4 (Algorithm 12 for tensors)
+ * finds one term by alternating s = sgn(R t), t = sgn(R^T s) until <s, R t> stops increasing,
+ * Algorithm 5 (Algorithm 13) subtracts it from the remainder and repeats.
+ *
+ * Conventions shared by every entry point
+ *  - Every data pointer is a DEVICE pointer (HIP global memory on the current device) unless the
+ *    argument is documented "host".  The caller owns every buffer it passes; the library neither
+ *    frees nor keeps them after the call returns.  The library owns only scd_ctx internals.
+ *  - Arrays are dense row-major, last mode fastest.  A matrix is order 2, dims = {m, n}.
+ *  - dtype: SCD_F32 (float) or SCD_F64 (double) for the input, the remainder and the coefficients.
+ *  - Sign vectors are bitsets of uint64 words (Section 3.1: a 1 bit stands for -1).  Element
+ *    64p+q is bit q (least significant first) of word p; a vector of length n takes
+ *    ceil(n/64) words; padding bits are 0.  Sign matrices are term-major: term j of mode i
+ *    starts at word j*ceil(dims[i]/64).
+ *  - sgn(x) = -1 iff x < 0 (both zeros give +1).
+ *  - Coefficients are normalised, c_j = <s_j, R_{j-1} t_j> / (product of dims), which is what the
+ *    definition above needs; Algorithm 5 line 10 divides by mn at the update, the same sequence.
+ *  - The random start t_0 of Algorithm 4 line 2 (Algorithm 12 line 1) for (seed, term, mode) is
+ *    word p = mix(mix(mix(seed ^ G*(term+1)) + H*(mode+1)) + K*(p+1)) with mix the SplitMix64
+ *    finaliser and G,H,K = 0x9E3779B97F4A7C15, 0xD1B54A32D192ED03, 0x8CB92BA72F3D8DD7; modes are
+ *    0-based, the matrix t_0 is mode 1; padding bits cleared.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls are
+ *    synchronous: results are complete in the caller's buffers when the call returns.
+ *  - Return value: SCD_OK (0) or a negative scd_status; SCD_WMAXITER (positive) is a warning:
+ *    results are valid but some term ended on the iteration cap instead of on the test of
+ *    Algorithm 4 line 8.  No call aborts or throws.  Calls on one context must not overlap.
+ */
+#ifndef SCD_H
+#define SCD_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { SCD_F32 = 0, SCD_F64 = 1 } scd_dtype;
+
+typedef enum {
+    SCD_OK = 0,
+    SCD_WMAXITER = 1,    /* warning: a term stopped on the iteration cap */
+    SCD_EINVAL = -1,     /* null pointer, order < 2 or > SCD_MAX_ORDER, dim < 1, w < 0, bad dtype */
+    SCD_ENOMEM = -2,     /* device or host allocation failed */
+    SCD_EHIP = -3,       /* a HIP call failed; scd_last_hip_error() gives its code */
+    SCD_EFULL = -4,      /* the context already holds w_capacity terms */
+    SCD_ENONFINITE = -5, /* the input (or a remainder given to the context) holds NaN or Inf */
+    SCD_ENODEVICE = -6   /* no usable HIP device */
+} scd_status;
+
+#define SCD_MAX_ORDER 8
+#define SCD_DEFAULT_MAX_ITERS 4096
+
+typedef struct scd_ctx scd_ctx; /* opaque: remainder, scratch, outputs so far, position in the random stream */
+
+/* ---- one-shot decomposition (Algorithm 5 / Algorithm 13) --------------------------------------
+ * A        in : order-`order` array of `dt`, dims[order] (host array); not modified.
+ * w        in : number of terms (>= 0).          seed: key of the random starts.
+ * signs    in : host array of `order` device pointers; signs[i] receives w*ceil(dims[i]/64) words
+ *               (matrix: signs[0] = S_w, signs[1] = T_w).
+ * c        out: w coefficients of `dt`.
+ * fro_trace out: w+1 doubles, ||R_0||_F .. ||R_w||_F, each computed from the remainder itself.
+ * iters    out: optional (NULL ok), w int32: alternations (sweeps) each term took. */
+int scd_decompose(const void* A, scd_dtype dt, int order, const int64_t* dims, int64_t w, uint64_t seed,
+                  void* stream, uint64_t* const* signs, void* c, double* fro_trace, int32_t* iters);
+
+/* ---- stateful form ---------------------------------------------------------------------------
+ * scd_create copies A into an internal remainder R_0, computes ||R_0||_F and is ready for term 0.
+ * w_capacity bounds the number of terms the context can hold. */
+int scd_create(scd_ctx** out, const void* A, scd_dtype dt, int order, const int64_t* dims,
+               int64_t w_capacity, uint64_t seed, void* stream);
+void scd_destroy(scd_ctx* ctx);
+
+/* Iteration cap of Algorithm 4's loop (the paper's loop is unbounded); default SCD_DEFAULT_MAX_ITERS. */
+int scd_set_max_iters(scd_ctx* ctx, int32_t max_iters);
+
+/* Advance exactly one term (Algorithm 5 lines 6-10): greedy cut from the keyed random start of the
+ * current term, append (s, t, c), update the remainder, record ||R||_F. */
+int scd_step(scd_ctx* ctx);
+/* Advance n terms (n >= 0) without returning to the host in between. */
+int scd_run(scd_ctx* ctx, int64_t n);
+/* Test hook: one term whose start is given by the caller instead of the random stream.
+ * init_signs: host array of `order` device pointers to bitsets; entry 0 is ignored (Algorithm 4
+ * overwrites s_0 before reading it) and may be NULL. */
+int scd_step_from(scd_ctx* ctx, const uint64_t* const* init_signs);
+
+int scd_width(const scd_ctx* ctx, int64_t* k /* host */);
+/* Copy out the first k = scd_width() terms; layouts as in scd_decompose (fro_trace gets k+1 values).
+ * Any of signs / c / fro_trace / iters may be NULL to skip it. */
+int scd_results(const scd_ctx* ctx, uint64_t* const* signs, void* c, double* fro_trace, int32_t* iters);
+/* Copy the current remainder R_k out (same dtype and shape as A), or replace it.  Replacing keeps
+ * k and the results so far, recomputes ||R_k||_F and restarts the current term. */
+int scd_remainder(const scd_ctx* ctx, void* R_out);
+int scd_set_remainder(scd_ctx* ctx, const void* R_in);
+
+/* ---- half steps of Algorithm 4 on caller data (lines 5 and 6-7) --------------------------------
+ * Row signed sum: u = R t (m doubles, optional) and s = sgn(u) packed (ceil(m/64) words, optional).
+ * Column signed sum: v = R^T s (n doubles, optional), t = sgn(v) packed (optional) and
+ * c = sum_l |v_l| = <s, R t> (one double, optional; not normalised).  R is m x n of `dt`. */
+int scd_row_signed_sum(const void* R, scd_dtype dt, int64_t m, int64_t n, const uint64_t* tbits,
+                       void* stream, double* u, uint64_t* sbits);
+int scd_col_signed_sum(const void* R, scd_dtype dt, int64_t m, int64_t n, const uint64_t* sbits,
+                       void* stream, double* v, uint64_t* tbits, double* c);
+
+/* ---- expansion (the definition, Section 2.2 / 5.2) ---------------------------------------------
+ * out (dtype dt, dims) = sum_{j<w} c_j * tensor product of term j's sign vectors.  Per entry the
+ * terms are added in the order j = 0..w-1 into one f64 accumulator, rounded once to dt, so the
+ * result is reproducible bit for bit.  signs: host array of `order` device pointers. */
+int scd_expand(const uint64_t* const* signs, const void* c, scd_dtype dt, int order, const int64_t* dims,
+               int64_t w, void* stream, void* out);
+
+/* ---- bitsets (Section 3.1) -------------------------------------------------------------------- */
+int scd_pack(const void* values, scd_dtype dt, int64_t n, void* stream, uint64_t* bits);   /* x < 0 -> 1 */
+int scd_unpack(const uint64_t* bits, int64_t n, scd_dtype dt, void* stream, void* values); /* 1 -> -1.0 */
+/* The keyed random start of Algorithm 4 line 2 for (seed, term, mode), n signs, padding cleared. */
+int scd_rng_signs(uint64_t seed, uint64_t term, uint32_t mode, int64_t n, void* stream, uint64_t* bits);
+
+/* ---- diagnostics ------------------------------------------------------------------------------ */
+const char* scd_strerror(int code);
+int scd_last_hip_error(void);        /* hipError_t of the most recent SCD_EHIP on this thread */
+/* Algorithmic bytes the row-pass kernels of this context have read+written so far and the number
+ * of passes (launches) they took: the counters behind the bandwidth figures.  host pointers. */
+int scd_traffic(const scd_ctx* ctx, double* bytes, int64_t* passes, int64_t* sweeps);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SCD_H */

@@ -1,0 +1,667 @@
+// Host driver and C ABI of libscd (see include/scd.h for the contract of every entry point).
+//
+// The greedy loop runs as a stream of kernel launches that the host enqueues blindly: which pass a
+// launch performs (a further alternation, or the update that ends a term and starts the next) is
+// decided on the device from device-resident state, so tens of thousands of dependent steps never
+// wait for the host.  The host only reads the state back once per batch of sweeps to see whether
+// the requested number of terms is reached.
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "scd_device.h"
+
+using namespace scd;
+
+namespace {
+
+thread_local int g_last_hip = 0;
+
+#define HIP_TRY(expr)                    \
+    do {                                 \
+        hipError_t _e = (expr);          \
+        if (_e != hipSuccess) {          \
+            g_last_hip = (int)_e;        \
+            (void)hipGetLastError();     \
+            return SCD_EHIP;             \
+        }                                \
+    } while (0)
+
+int64_t words_for(int64_t n) { return (n + 63) / 64; }
+
+int env_int(const char* name, int dflt)
+{
+    const char* v = getenv(name);
+    if (!v || !*v) return dflt;
+    return atoi(v);
+}
+
+struct Level {
+    int64_t rows = 0, cols = 0;
+    void* X = nullptr;          // level 0: the remainder; else the previous level's W
+    void* partials = nullptr;   // [grid][cols]
+    int grid = 0, rows_per_wg = 0;
+    double* W = nullptr;        // [cols]
+    double* u = nullptr;        // [rows]
+    uint64_t* kron_cur = nullptr;
+    uint64_t* kron_rng = nullptr;
+    RowPassArgs pass;
+    ReduceArgs red;
+};
+
+}  // namespace
+
+struct scd_ctx {
+    scd_dtype dt = SCD_F32;
+    int order = 0;
+    int nlevels = 0;
+    int64_t dims[SCD_MAX_ORDER] = {0};
+    int64_t total = 0;
+    int64_t w_capacity = 0;
+    uint64_t seed = 0;
+    size_t esize = 4;
+    hipStream_t stream = nullptr;
+    void* R = nullptr;
+    Level lv[SCD_MAX_ORDER];
+    uint64_t* s_bits[SCD_MAX_ORDER] = {nullptr};
+    uint64_t* rng_last = nullptr;
+    double* cparts = nullptr;
+    int ncparts = 0;
+    double* fparts = nullptr;
+    State* cur = nullptr;
+    State* next = nullptr;
+    State* pinned = nullptr;   // host-pinned landing zone for state read-backs
+    State hs;                  // host mirror of `cur` as of the last synchronisation
+    uint64_t* out_signs[SCD_MAX_ORDER] = {nullptr};
+    void* c_out = nullptr;
+    double* trace = nullptr;
+    int32_t* iters = nullptr;
+    KronArgs kron;
+    int variant = 1;
+    int batch = 64;
+    std::vector<void*> allocs;
+};
+
+namespace {
+
+int dev_alloc(scd_ctx* c, void** p, size_t bytes)
+{
+    if (bytes == 0) bytes = 8;
+    hipError_t e = hipMalloc(p, bytes);
+    if (e != hipSuccess) {
+        g_last_hip = (int)e;
+        (void)hipGetLastError();
+        return SCD_ENOMEM;
+    }
+    c->allocs.push_back(*p);
+    return SCD_OK;
+}
+
+#define SCD_TRY(expr)              \
+    do {                           \
+        int _s = (expr);           \
+        if (_s < 0) return _s;     \
+    } while (0)
+
+int write_state(scd_ctx* c)
+{
+    // through the pinned buffer, and complete on return: the host copy may change right after
+    *c->pinned = c->hs;
+    HIP_TRY(hipMemcpyAsync(c->cur, c->pinned, sizeof(State), hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(hipMemcpyAsync(c->next, c->pinned, sizeof(State), hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(hipStreamSynchronize(c->stream));
+    return SCD_OK;
+}
+
+int read_state(scd_ctx* c)
+{
+    HIP_TRY(hipMemcpyAsync(c->pinned, c->cur, sizeof(State), hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(hipStreamSynchronize(c->stream));
+    c->hs = *c->pinned;
+    return SCD_OK;
+}
+
+int launch_sweep(scd_ctx* c)
+{
+    for (int l = 0; l < c->nlevels; ++l) {
+        Level& L = c->lv[l];
+        HIP_TRY(launch_rowpass(L.pass, c->dt, L.grid, c->variant, c->stream));
+        const bool f32p = (l == 0 && c->dt == SCD_F32);
+        HIP_TRY(launch_reduce(L.red, f32p, c->stream));
+    }
+    if (c->order >= 3) HIP_TRY(launch_kron(c->kron, c->stream));
+    return SCD_OK;
+}
+
+// (Re)draw the random start of the current term into the device buffers.
+int seed_current_term(scd_ctx* c, int term_offset, bool with_last)
+{
+    KronArgs k = c->kron;
+    k.force = 1;
+    k.term_offset = term_offset;
+    k.with_last = with_last ? 1 : 0;
+    HIP_TRY(launch_kron(k, c->stream));
+    return SCD_OK;
+}
+
+// Enqueue sweeps until the device reports that w_target terms are complete.
+int run_until_done(scd_ctx* c, int batch)
+{
+    const int64_t terms = c->hs.w_target - c->hs.k;
+    // every term takes at most max_iters alternations plus its update pass
+    const double bound = ((double)(terms > 0 ? terms : 0) + 2.0) * ((double)c->hs.max_iters + 2.0) + 4.0;
+    double launched = 0;
+    if (batch < 1) batch = 1;
+    for (;;) {
+        for (int b = 0; b < batch; ++b) SCD_TRY(launch_sweep(c));
+        launched += batch;
+        SCD_TRY(read_state(c));
+        if (c->hs.done) return SCD_OK;
+        if (launched > bound + batch) return SCD_EINVAL;  // cannot happen: the device loop is bounded
+    }
+}
+
+void setup_levels(scd_ctx* c)
+{
+    const int order = c->order;
+    for (int l = 0; l < c->nlevels; ++l) {
+        Level& L = c->lv[l];
+        RowPassArgs& p = L.pass;
+        memset(&p, 0, sizeof(p));
+        p.X = L.X;
+        p.rows = L.rows;
+        p.cols = L.cols;
+        p.level = l;
+        p.rows_per_wg = L.rows_per_wg;
+        p.sign_cur = L.kron_cur;
+        p.sign_rng = L.kron_rng;
+        p.row_bits = c->s_bits[l];
+        p.partials = L.partials;
+        p.u = L.u;
+        p.fparts = c->fparts;
+        p.cparts = c->cparts;
+        p.ncparts = c->ncparts;
+        p.order = order;
+        p.cur = c->cur;
+        p.next = c->next;
+        p.c_out = c->c_out;
+        p.iters_out = c->iters;
+        p.total = (double)c->total;
+        for (int i = 0; i < order; ++i) {
+            p.out_signs[i] = c->out_signs[i];
+            p.cur_signs[i] = c->s_bits[i];
+            p.words[i] = (int32_t)words_for(c->dims[i]);
+        }
+        ReduceArgs& r = L.red;
+        memset(&r, 0, sizeof(r));
+        r.partials = L.partials;
+        r.nparts = L.grid;
+        r.level = l;
+        r.cols = L.cols;
+        r.rows = L.rows;
+        r.W = L.W;
+        r.u = L.u;
+        r.row_bits = c->s_bits[l];
+        r.final = (l == c->nlevels - 1) ? 1 : 0;
+        r.last_bits = c->s_bits[order - 1];
+        r.cparts = c->cparts;
+        r.rng_last = c->rng_last;
+        r.fparts = c->fparts;
+        r.nfparts = c->lv[0].grid;
+        r.last_mode = order - 1;
+        r.trace = c->trace;
+        r.seed = c->seed;
+        r.cur = c->cur;
+        r.next = c->next;
+    }
+    KronArgs& k = c->kron;
+    memset(&k, 0, sizeof(k));
+    k.order = order;
+    k.term_offset = 1;
+    for (int i = 0; i < order; ++i) {
+        k.dims[i] = c->dims[i];
+        k.cur_signs[i] = c->s_bits[i];
+    }
+    for (int l = 0; l + 2 < order; ++l) {
+        k.kron_cur[l] = c->lv[l].kron_cur;
+        k.kron_rng[l] = c->lv[l].kron_rng;
+        k.cols[l] = c->lv[l].cols;
+    }
+    k.rng_last = c->rng_last;
+    k.seed = c->seed;
+    k.cur = c->cur;
+    k.next = c->next;
+}
+
+int check_dims(int order, const int64_t* dims, int64_t* total)
+{
+    if (!dims || order < 2 || order > SCD_MAX_ORDER) return SCD_EINVAL;
+    double t = 1.0;
+    int64_t n = 1;
+    for (int i = 0; i < order; ++i) {
+        if (dims[i] < 1) return SCD_EINVAL;
+        t *= (double)dims[i];
+        n *= dims[i];
+    }
+    if (t > 4.0e12) return SCD_EINVAL;
+    *total = n;
+    return SCD_OK;
+}
+
+bool dtype_ok(int dt) { return dt == SCD_F32 || dt == SCD_F64; }
+
+}  // namespace
+
+extern "C" {
+
+int scd_create(scd_ctx** out, const void* A, scd_dtype dt, int order, const int64_t* dims, int64_t w_capacity,
+               uint64_t seed, void* stream)
+{
+    if (!out) return SCD_EINVAL;
+    *out = nullptr;
+    int64_t total = 0;
+    if (!A || !dtype_ok(dt) || w_capacity < 0) return SCD_EINVAL;
+    SCD_TRY(check_dims(order, dims, &total));
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1) {
+        (void)hipGetLastError();
+        return SCD_ENODEVICE;
+    }
+    scd_ctx* c = new (std::nothrow) scd_ctx();
+    if (!c) return SCD_ENOMEM;
+    c->dt = dt;
+    c->order = order;
+    c->nlevels = order - 1;
+    c->total = total;
+    c->w_capacity = w_capacity;
+    c->seed = seed;
+    c->esize = dt == SCD_F32 ? 4 : 8;
+    c->stream = (hipStream_t)stream;
+    c->variant = env_int("SCD_ROWPASS_VARIANT", 1);
+    c->batch = env_int("SCD_SWEEP_BATCH", 64);
+    for (int i = 0; i < order; ++i) c->dims[i] = dims[i];
+    const int wg_target = env_int("SCD_WORKGROUPS", 512);
+
+    int st = SCD_OK;
+    auto fail = [&](int code) {
+        scd_destroy(c);
+        return code;
+    };
+#define CTRY(expr)                     \
+    do {                               \
+        st = (expr);                   \
+        if (st < 0) return fail(st);   \
+    } while (0)
+#define CHIP(expr)                         \
+    do {                                   \
+        hipError_t _e = (expr);            \
+        if (_e != hipSuccess) {            \
+            g_last_hip = (int)_e;          \
+            (void)hipGetLastError();       \
+            return fail(SCD_EHIP);         \
+        }                                  \
+    } while (0)
+
+    CTRY(dev_alloc(c, &c->R, (size_t)total * c->esize));
+    for (int i = 0; i < order; ++i) {
+        CTRY(dev_alloc(c, (void**)&c->s_bits[i], (size_t)words_for(dims[i]) * 8));
+        CHIP(hipMemsetAsync(c->s_bits[i], 0, (size_t)words_for(dims[i]) * 8, c->stream));
+        CTRY(dev_alloc(c, (void**)&c->out_signs[i], (size_t)w_capacity * words_for(dims[i]) * 8));
+    }
+    CTRY(dev_alloc(c, (void**)&c->rng_last, (size_t)words_for(dims[order - 1]) * 8));
+    CTRY(dev_alloc(c, &c->c_out, (size_t)w_capacity * c->esize));
+    CTRY(dev_alloc(c, (void**)&c->trace, (size_t)(w_capacity + 1) * 8));
+    CTRY(dev_alloc(c, (void**)&c->iters, (size_t)w_capacity * 4));
+    CTRY(dev_alloc(c, (void**)&c->cur, sizeof(State)));
+    CTRY(dev_alloc(c, (void**)&c->next, sizeof(State)));
+    CHIP(hipHostMalloc((void**)&c->pinned, sizeof(State), hipHostMallocDefault));
+
+    int64_t cols = total;
+    for (int l = 0; l < c->nlevels; ++l) {
+        Level& L = c->lv[l];
+        L.rows = dims[l];
+        cols /= dims[l];
+        L.cols = cols;
+        int64_t rpw = (L.rows + wg_target - 1) / wg_target;
+        if (rpw < 1) rpw = 1;
+        if (rpw > kMaxRowsPerWg) rpw = kMaxRowsPerWg;
+        L.rows_per_wg = (int)rpw;
+        L.grid = (int)((L.rows + rpw - 1) / rpw);
+        const size_t es = (l == 0) ? c->esize : 8;
+        CTRY(dev_alloc(c, &L.partials, (size_t)L.grid * (size_t)L.cols * es));
+        CTRY(dev_alloc(c, (void**)&L.W, (size_t)L.cols * 8));
+        CTRY(dev_alloc(c, (void**)&L.u, (size_t)L.rows * 8));
+        L.X = (l == 0) ? c->R : (void*)c->lv[l - 1].W;
+        if (l == c->nlevels - 1) {
+            L.kron_cur = c->s_bits[order - 1];
+            L.kron_rng = c->rng_last;
+        } else {
+            CTRY(dev_alloc(c, (void**)&L.kron_cur, (size_t)words_for(L.cols) * 8));
+            CTRY(dev_alloc(c, (void**)&L.kron_rng, (size_t)words_for(L.cols) * 8));
+        }
+    }
+    c->ncparts = (int)words_for(dims[order - 1]);
+    CTRY(dev_alloc(c, (void**)&c->cparts, (size_t)c->ncparts * 8));
+    CHIP(hipMemsetAsync(c->cparts, 0, (size_t)c->ncparts * 8, c->stream));
+    CTRY(dev_alloc(c, (void**)&c->fparts, (size_t)c->lv[0].grid * 8));
+    setup_levels(c);
+
+    CHIP(hipMemcpyAsync(c->R, A, (size_t)total * c->esize, hipMemcpyDeviceToDevice, c->stream));
+    memset(&c->hs, 0, sizeof(State));
+    c->hs.c_prev = -INFINITY;
+    c->hs.max_iters = SCD_DEFAULT_MAX_ITERS;
+    CTRY(write_state(c));
+    CTRY(seed_current_term(c, 0, true));
+    // first pass of term 0; it also yields ||R_0||_F.  w_target = 0 stops the device right after.
+    CTRY(launch_sweep(c));
+    CTRY(read_state(c));
+    double f0 = 0.0;
+    CHIP(hipMemcpy(&f0, c->trace, sizeof(double), hipMemcpyDeviceToHost));
+    if (!isfinite(f0)) return fail(SCD_ENONFINITE);
+    *out = c;
+    return SCD_OK;
+#undef CTRY
+#undef CHIP
+}
+
+void scd_destroy(scd_ctx* c)
+{
+    if (!c) return;
+    (void)hipStreamSynchronize(c->stream);
+    for (void* p : c->allocs) (void)hipFree(p);
+    if (c->pinned) (void)hipHostFree(c->pinned);
+    (void)hipGetLastError();
+    delete c;
+}
+
+int scd_set_max_iters(scd_ctx* c, int32_t max_iters)
+{
+    if (!c || max_iters < 1) return SCD_EINVAL;
+    c->hs.max_iters = max_iters;
+    return write_state(c);
+}
+
+int scd_run(scd_ctx* c, int64_t n)
+{
+    if (!c || n < 0) return SCD_EINVAL;
+    if (n == 0) return c->hs.warn ? SCD_WMAXITER : SCD_OK;
+    if (c->hs.k + n > c->w_capacity) return SCD_EFULL;
+    c->hs.w_target = c->hs.k + n;
+    c->hs.done = 0;
+    SCD_TRY(write_state(c));
+    int batch = c->batch;
+    if (n == 1 && batch > 16) batch = 16;
+    SCD_TRY(run_until_done(c, batch));
+    return c->hs.warn ? SCD_WMAXITER : SCD_OK;
+}
+
+int scd_step(scd_ctx* c) { return scd_run(c, 1); }
+
+int scd_step_from(scd_ctx* c, const uint64_t* const* init_signs)
+{
+    if (!c || !init_signs) return SCD_EINVAL;
+    for (int i = 1; i < c->order; ++i)
+        if (!init_signs[i]) return SCD_EINVAL;
+    if (c->hs.k + 1 > c->w_capacity) return SCD_EFULL;
+    for (int i = 1; i < c->order; ++i)
+        HIP_TRY(hipMemcpyAsync(c->s_bits[i], init_signs[i], (size_t)words_for(c->dims[i]) * 8, hipMemcpyDeviceToDevice,
+                               c->stream));
+    c->hs.w_target = c->hs.k + 1;
+    c->hs.done = 0;
+    c->hs.j = 0;
+    c->hs.t0_given = 1;
+    c->hs.c_prev = -INFINITY;
+    SCD_TRY(write_state(c));
+    if (c->order >= 3) SCD_TRY(seed_current_term(c, 1, false));
+    SCD_TRY(run_until_done(c, c->batch > 16 ? 16 : c->batch));
+    return c->hs.warn ? SCD_WMAXITER : SCD_OK;
+}
+
+int scd_width(const scd_ctx* c, int64_t* k)
+{
+    if (!c || !k) return SCD_EINVAL;
+    *k = c->hs.k;
+    return SCD_OK;
+}
+
+int scd_results(const scd_ctx* c, uint64_t* const* signs, void* cvec, double* fro_trace, int32_t* iters)
+{
+    if (!c) return SCD_EINVAL;
+    const int64_t k = c->hs.k;
+    if (signs && k > 0) {
+        for (int i = 0; i < c->order; ++i) {
+            if (!signs[i]) return SCD_EINVAL;
+            HIP_TRY(hipMemcpyAsync(signs[i], c->out_signs[i], (size_t)k * words_for(c->dims[i]) * 8,
+                                   hipMemcpyDeviceToDevice, c->stream));
+        }
+    }
+    if (cvec && k > 0) HIP_TRY(hipMemcpyAsync(cvec, c->c_out, (size_t)k * c->esize, hipMemcpyDeviceToDevice, c->stream));
+    if (fro_trace)
+        HIP_TRY(hipMemcpyAsync(fro_trace, c->trace, (size_t)(k + 1) * 8, hipMemcpyDeviceToDevice, c->stream));
+    if (iters && k > 0) HIP_TRY(hipMemcpyAsync(iters, c->iters, (size_t)k * 4, hipMemcpyDeviceToDevice, c->stream));
+    HIP_TRY(hipStreamSynchronize(c->stream));
+    return SCD_OK;
+}
+
+int scd_remainder(const scd_ctx* c, void* R_out)
+{
+    if (!c || !R_out) return SCD_EINVAL;
+    HIP_TRY(hipMemcpyAsync(R_out, c->R, (size_t)c->total * c->esize, hipMemcpyDeviceToDevice, c->stream));
+    HIP_TRY(hipStreamSynchronize(c->stream));
+    return SCD_OK;
+}
+
+int scd_set_remainder(scd_ctx* c, const void* R_in)
+{
+    if (!c || !R_in) return SCD_EINVAL;
+    HIP_TRY(hipMemcpyAsync(c->R, R_in, (size_t)c->total * c->esize, hipMemcpyDeviceToDevice, c->stream));
+    c->hs.w_target = c->hs.k;
+    c->hs.done = 0;
+    c->hs.j = 0;
+    c->hs.t0_given = 0;
+    c->hs.c_prev = -INFINITY;
+    SCD_TRY(write_state(c));
+    SCD_TRY(seed_current_term(c, 0, true));
+    SCD_TRY(launch_sweep(c));
+    SCD_TRY(read_state(c));
+    double f = 0.0;
+    HIP_TRY(hipMemcpy(&f, c->trace + c->hs.k, sizeof(double), hipMemcpyDeviceToHost));
+    if (!isfinite(f)) return SCD_ENONFINITE;
+    return SCD_OK;
+}
+
+int scd_traffic(const scd_ctx* c, double* bytes, int64_t* passes, int64_t* sweeps)
+{
+    if (!c) return SCD_EINVAL;
+    const double pass_bytes = (double)c->total * (double)c->esize;
+    if (bytes) *bytes = pass_bytes * ((double)c->hs.passes + (double)c->hs.updates);
+    if (passes) *passes = c->hs.passes;
+    if (sweeps) *sweeps = c->hs.passes;
+    return SCD_OK;
+}
+
+int scd_decompose(const void* A, scd_dtype dt, int order, const int64_t* dims, int64_t w, uint64_t seed, void* stream,
+                  uint64_t* const* signs, void* cvec, double* fro_trace, int32_t* iters)
+{
+    if (!A || !fro_trace || w < 0 || (w > 0 && (!signs || !cvec))) return SCD_EINVAL;
+    scd_ctx* c = nullptr;
+    int st = scd_create(&c, A, dt, order, dims, w, seed, stream);
+    if (st < 0) return st;
+    int run = scd_run(c, w);
+    if (run < 0) {
+        scd_destroy(c);
+        return run;
+    }
+    st = scd_results(c, signs, cvec, fro_trace, iters);
+    scd_destroy(c);
+    return st < 0 ? st : run;
+}
+
+// ---------------------------------------------------------------------------------------------- half steps
+
+static int halfstep_geometry(int64_t m, int* rows_per_wg, int* grid)
+{
+    int64_t rpw = (m + 1023) / 1024;
+    if (rpw < 1) rpw = 1;
+    if (rpw > kMaxRowsPerWg) rpw = kMaxRowsPerWg;
+    *rows_per_wg = (int)rpw;
+    *grid = (int)((m + rpw - 1) / rpw);
+    return SCD_OK;
+}
+
+int scd_row_signed_sum(const void* R, scd_dtype dt, int64_t m, int64_t n, const uint64_t* tbits, void* stream, double* u,
+                       uint64_t* sbits)
+{
+    if (!R || !tbits || !dtype_ok(dt) || m < 1 || n < 1) return SCD_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    double* utmp = nullptr;
+    if (!u) {
+        hipError_t e = hipMalloc((void**)&utmp, (size_t)m * 8);
+        if (e != hipSuccess) {
+            g_last_hip = (int)e;
+            (void)hipGetLastError();
+            return SCD_ENOMEM;
+        }
+        u = utmp;
+    }
+    int rpw, grid;
+    halfstep_geometry(m, &rpw, &grid);
+    int rc = SCD_OK;
+    hipError_t e = launch_halfstep(R, dt, m, n, rpw, grid, 1, tbits, nullptr, nullptr, u, st);
+    if (e == hipSuccess && sbits) e = launch_pack(u, SCD_F64, m, sbits, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (e != hipSuccess) {
+        g_last_hip = (int)e;
+        (void)hipGetLastError();
+        rc = SCD_EHIP;
+    }
+    if (utmp) (void)hipFree(utmp);
+    return rc;
+}
+
+int scd_col_signed_sum(const void* R, scd_dtype dt, int64_t m, int64_t n, const uint64_t* sbits, void* stream, double* v,
+                       uint64_t* tbits, double* cout)
+{
+    if (!R || !sbits || !dtype_ok(dt) || m < 1 || n < 1) return SCD_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    int rpw, grid;
+    halfstep_geometry(m, &rpw, &grid);
+    const size_t es = dt == SCD_F32 ? 4 : 8;
+    const int ncp = (int)words_for(n);
+    void* partials = nullptr;
+    double* cparts = nullptr;
+    double* ctmp = nullptr;
+    int rc = SCD_OK;
+    hipError_t e = hipMalloc(&partials, (size_t)grid * (size_t)n * es);
+    if (e == hipSuccess) e = hipMalloc((void**)&cparts, (size_t)ncp * 8);
+    if (e == hipSuccess && !cout) e = hipMalloc((void**)&ctmp, 8);
+    if (e != hipSuccess) {
+        g_last_hip = (int)e;
+        (void)hipGetLastError();
+        rc = SCD_ENOMEM;
+    } else {
+        e = launch_halfstep(R, dt, m, n, rpw, grid, 0, nullptr, sbits, partials, nullptr, st);
+        if (e == hipSuccess) e = launch_reduce_plain(partials, dt, grid, n, v, tbits, cparts, st);
+        if (e == hipSuccess) e = launch_sum_parts(cparts, ncp, cout ? cout : ctmp, st);
+        if (e == hipSuccess) e = hipStreamSynchronize(st);
+        if (e != hipSuccess) {
+            g_last_hip = (int)e;
+            (void)hipGetLastError();
+            rc = SCD_EHIP;
+        }
+    }
+    if (partials) (void)hipFree(partials);
+    if (cparts) (void)hipFree(cparts);
+    if (ctmp) (void)hipFree(ctmp);
+    return rc;
+}
+
+// ---------------------------------------------------------------------------------------------- expand, bitsets
+
+int scd_expand(const uint64_t* const* signs, const void* cvec, scd_dtype dt, int order, const int64_t* dims, int64_t w,
+               void* stream, void* out)
+{
+    int64_t total = 0;
+    if (!signs || !out || !dtype_ok(dt) || w < 0 || (w > 0 && !cvec)) return SCD_EINVAL;
+    SCD_TRY(check_dims(order, dims, &total));
+    for (int i = 0; i < order; ++i)
+        if (w > 0 && !signs[i]) return SCD_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    const int64_t m = dims[0], cols = total / dims[0];
+    uint64_t* kr = nullptr;
+    const uint64_t* T = signs[1];
+    if (order >= 3 && w > 0) {
+        hipError_t e = hipMalloc((void**)&kr, (size_t)w * (size_t)words_for(cols) * 8);
+        if (e != hipSuccess) {
+            g_last_hip = (int)e;
+            (void)hipGetLastError();
+            return SCD_ENOMEM;
+        }
+        e = launch_kron_terms(order, dims, signs, w, kr, cols, st);
+        if (e != hipSuccess) {
+            g_last_hip = (int)e;
+            (void)hipGetLastError();
+            (void)hipFree(kr);
+            return SCD_EHIP;
+        }
+        T = kr;
+    }
+    hipError_t e = launch_expand(signs[0], T, cvec, dt, m, cols, w, out, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    if (kr) (void)hipFree(kr);
+    if (e != hipSuccess) {
+        g_last_hip = (int)e;
+        (void)hipGetLastError();
+        return SCD_EHIP;
+    }
+    return SCD_OK;
+}
+
+int scd_pack(const void* values, scd_dtype dt, int64_t n, void* stream, uint64_t* bits)
+{
+    if (!values || !bits || !dtype_ok(dt) || n < 0) return SCD_EINVAL;
+    if (n == 0) return SCD_OK;
+    HIP_TRY(launch_pack(values, dt, n, bits, (hipStream_t)stream));
+    HIP_TRY(hipStreamSynchronize((hipStream_t)stream));
+    return SCD_OK;
+}
+
+int scd_unpack(const uint64_t* bits, int64_t n, scd_dtype dt, void* stream, void* values)
+{
+    if (!values || !bits || !dtype_ok(dt) || n < 0) return SCD_EINVAL;
+    if (n == 0) return SCD_OK;
+    HIP_TRY(launch_unpack(bits, n, dt, values, (hipStream_t)stream));
+    HIP_TRY(hipStreamSynchronize((hipStream_t)stream));
+    return SCD_OK;
+}
+
+int scd_rng_signs(uint64_t seed, uint64_t term, uint32_t mode, int64_t n, void* stream, uint64_t* bits)
+{
+    if (!bits || n < 0) return SCD_EINVAL;
+    if (n == 0) return SCD_OK;
+    HIP_TRY(launch_rng(seed, term, mode, n, bits, (hipStream_t)stream));
+    HIP_TRY(hipStreamSynchronize((hipStream_t)stream));
+    return SCD_OK;
+}
+
+const char* scd_strerror(int code)
+{
+    switch (code) {
+        case SCD_OK: return "ok";
+        case SCD_WMAXITER: return "warning: a term stopped on the iteration cap";
+        case SCD_EINVAL: return "invalid argument";
+        case SCD_ENOMEM: return "out of memory";
+        case SCD_EHIP: return "HIP runtime error";
+        case SCD_EFULL: return "context is at its width capacity";
+        case SCD_ENONFINITE: return "input holds NaN or Inf";
+        case SCD_ENODEVICE: return "no HIP device";
+        default: return "unknown status";
+    }
+}
+
+int scd_last_hip_error(void) { return g_last_hip; }
+
+}  // extern "C"

@@ -1,0 +1,122 @@
+// Internal declarations shared by the kernels and the host driver of libscd (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "scd.h"
+
+namespace scd {
+
+constexpr int kWave = 64;        // gfx950 wavefront
+constexpr int kBlock = 256;      // threads per workgroup of the row-pass and reduce kernels
+constexpr int kWavesPerBlock = kBlock / kWave;
+constexpr int kMaxRowsPerWg = 2048;
+
+// What the next row pass over the remainder has to do; decided on the device by every workgroup
+// from the same data, so that no launch depends on the host.
+enum PassMode : int32_t {
+    PASS_START = 0,  // first alternation of a term on an unchanged remainder (also computes ||R||^2)
+    PASS_CONT = 1,   // a further alternation (Algorithm 4 lines 5-7)
+    PASS_UPDATE = 2  // the term converged: subtract it (Algorithm 5 line 10), then act as PASS_START
+};
+
+// Device-resident position of the greedy loop.  `cur` is read by the level-0 row pass, which
+// writes `next`; every later kernel of the sweep reads `next`; the last reduce copies next->cur.
+struct State {
+    int64_t k;         // terms completed
+    int64_t w_target;  // stop once k == w_target
+    int64_t passes;    // level-0 row passes executed
+    int64_t updates;   // rank-1 updates executed
+    double c_prev;     // c of the previous alternation of the current term (-inf before the first)
+    double c_last;     // most recent c
+    int32_t j;         // alternations completed for the current term (0: none yet)
+    int32_t done;      // k == w_target and the remainder is up to date
+    int32_t t0_given;  // the start of the current term is in the sign buffers, not the random stream
+    int32_t warn;      // some term ended on max_iters
+    int32_t norm_pending;  // the pass of this sweep summed squares: the last reduce records ||R_k||_F
+    int32_t sweep_rng;     // levels >= 1 of this sweep read the random Kronecker signs
+    int32_t active;        // written by the level-0 pass only: 0 = this sweep is skipped
+    int32_t max_iters;
+};
+
+struct RowPassArgs {
+    void* X;               // rows x cols, row-major.  level 0: the remainder (dtype), else f64 partial contraction
+    int64_t rows, cols;
+    int32_t level;
+    int32_t rows_per_wg;
+    const uint64_t* sign_cur;  // cols bits: Kronecker product of the current signs of the later modes
+    const uint64_t* sign_rng;  // cols bits: the same for the random start of the next term
+    const uint64_t* row_bits;  // rows bits: current signs of this level's mode
+    void* partials;            // [grid][cols], element type of X
+    double* u;                 // [rows]
+    double* fparts;            // [grid] partial sums of squares (level 0)
+    const double* cparts;      // partial sums of |v| written by the last reduce of the previous sweep
+    int32_t ncparts;
+    int32_t order;
+    State* cur;
+    State* next;
+    void* c_out;               // [w] dtype
+    int32_t* iters_out;        // [w]
+    double total;              // prod dims (the mn of Algorithm 5 line 10)
+    uint64_t* out_signs[SCD_MAX_ORDER];        // term-major outputs
+    const uint64_t* cur_signs[SCD_MAX_ORDER];  // current sign bitsets per mode
+    int32_t words[SCD_MAX_ORDER];
+};
+
+struct ReduceArgs {
+    const void* partials;  // [nparts][cols]
+    int32_t nparts;
+    int32_t level;
+    int64_t cols;
+    int64_t rows;          // rows of this level (length of u)
+    double* W;             // [cols] f64 sums
+    const double* u;       // [rows]
+    uint64_t* row_bits;    // rows bits <- sgn(u)
+    int32_t final;         // last level: W is R^T s (the last mode's vector)
+    uint64_t* last_bits;   // cols bits <- sgn(W)            (final)
+    double* cparts;        // [ceil(cols/64)] sums of |W|    (final)
+    uint64_t* rng_last;    // cols bits: random start of term k+1, last mode (final)
+    const double* fparts;  // level-0 partial sums of squares
+    int32_t nfparts;
+    int32_t last_mode;
+    double* trace;         // [w+1]
+    uint64_t seed;
+    State* cur;
+    State* next;
+};
+
+struct KronArgs {
+    int32_t order;
+    int32_t term_offset;   // random signs are drawn for term cur->k + term_offset
+    int32_t force;         // run even when the sweep is inactive (host-driven set-up)
+    int32_t with_last;     // also write the last mode's random bitset
+    int64_t dims[SCD_MAX_ORDER];
+    const uint64_t* cur_signs[SCD_MAX_ORDER];
+    uint64_t* kron_cur[SCD_MAX_ORDER];  // levels 0..order-3
+    uint64_t* kron_rng[SCD_MAX_ORDER];  // levels 0..order-3
+    uint64_t* rng_last;
+    int64_t cols[SCD_MAX_ORDER];        // cols of level l = prod dims[l+1..]
+    uint64_t seed;
+    const State* cur;
+    const State* next;
+};
+
+// ---- launchers implemented in scd_kernels.hip ----------------------------------------------------
+hipError_t launch_rowpass(const RowPassArgs& a, scd_dtype dt, int grid, int variant, hipStream_t st);
+hipError_t launch_reduce(const ReduceArgs& a, bool f32_partials, hipStream_t st);
+hipError_t launch_kron(const KronArgs& a, hipStream_t st);
+hipError_t launch_pack(const void* values, scd_dtype dt, int64_t n, uint64_t* bits, hipStream_t st);
+hipError_t launch_unpack(const uint64_t* bits, int64_t n, scd_dtype dt, void* values, hipStream_t st);
+hipError_t launch_rng(uint64_t seed, uint64_t term, uint32_t mode, int64_t n, uint64_t* bits, hipStream_t st);
+hipError_t launch_kron_terms(int order, const int64_t* dims, const uint64_t* const* signs, int64_t w,
+                             uint64_t* out, int64_t cols, hipStream_t st);
+hipError_t launch_expand(const uint64_t* S, const uint64_t* T, const void* c, scd_dtype dt, int64_t m,
+                         int64_t n, int64_t w, void* out, hipStream_t st);
+hipError_t launch_halfstep(const void* R, scd_dtype dt, int64_t m, int64_t n, int rows_per_wg, int grid, int do_rows,
+                           const uint64_t* sumbits, const uint64_t* rowbits, void* partials, double* u, hipStream_t st);
+hipError_t launch_reduce_plain(const void* partials, scd_dtype dt, int nparts, int64_t cols, double* W, uint64_t* bits,
+                               double* cparts, hipStream_t st);
+hipError_t launch_sum_parts(const double* parts, int n, double* out, hipStream_t st);
+bool fast_rowpass_supported(scd_dtype dt, int64_t cols, int level);
+
+}  // namespace scd

@@ -1,0 +1,367 @@
+"""GPU parity tests: the HIP path (through the C ABI) against the f64 CPU oracle, element by element,
+on the same seeded inputs.  Sizes span several tiles and ragged tails; both row-pass kernels
+(the generic one and the register-tiled one) are exercised.
+
+Tolerances (north-star): bit-exact for bitsets, random streams and expansion; signs identical except
+where the reference value is within 1e-6 of a tie; c within 1e-5; Frobenius identity within 1e-6;
+error curve within 1e-3.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from helpers import (C_RTOL, CURVE_RTOL, ID_RTOL, TIE_TOL, assert_signs_match, dense, sign_mismatch, to_dev_bits,
+                     to_np_bits)
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def scd():
+    from paper_2410_01799_amd import scd as mod
+
+    mod.lib()
+    assert torch.cuda.is_available()
+    return mod
+
+
+@pytest.fixture(params=[1, 0], ids=["tiled", "generic"])
+def variant(request):
+    old = os.environ.get("SCD_ROWPASS_VARIANT")
+    os.environ["SCD_ROWPASS_VARIANT"] = str(request.param)
+    yield request.param
+    if old is None:
+        os.environ.pop("SCD_ROWPASS_VARIANT", None)
+    else:
+        os.environ["SCD_ROWPASS_VARIANT"] = old
+
+
+def gauss(shape, seed, dtype=np.float32):
+    return np.random.Generator(np.random.PCG64(seed)).standard_normal(shape).astype(dtype)
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+# ------------------------------------------------------------------ bit-exact pieces
+
+
+@pytest.mark.parametrize("n", [1, 63, 64, 65, 1000, 4096, 14336 + 17])
+def test_rng_stream_bit_exact(scd, oracle, n):
+    for seed, term, mode in [(0, 0, 1), (2, 8191, 1), (2 ** 63 + 5, 3, 0), (77, 12345678, 2)]:
+        got = to_np_bits(scd.scd_rng_signs(seed, term, mode, n))
+        assert np.array_equal(got, oracle.rng_signs(seed, term, mode, n)), (seed, term, mode, n)
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("n", [1, 64, 100, 8191, 100003])
+def test_pack_unpack_bit_exact(scd, oracle, dtype, n):
+    x = gauss(n, n, dtype)
+    x[::7] = 0.0
+    x[3::11] = -0.0
+    bits = scd.scd_pack(dev(x))
+    ref = oracle.pack(x.astype(np.float64))
+    assert np.array_equal(to_np_bits(bits), ref)
+    back = scd.scd_unpack(bits, n, torch.float32 if dtype == np.float32 else torch.float64).cpu().numpy()
+    assert np.array_equal(back.astype(np.float64), oracle.unpack(ref, n))
+
+
+@pytest.mark.parametrize("shape,w,dtype", [((70, 130), 33, np.float32), ((64, 64), 1, np.float64),
+                                           ((257, 100), 200, np.float64), ((5, 3), 7, np.float32),
+                                           ((33, 10, 3), 40, np.float32), ((6, 5, 4, 3), 25, np.float64)])
+def test_expand_bit_exact(scd, oracle, shape, w, dtype):
+    rs = np.random.Generator(np.random.PCG64(w))
+    signs = [np.stack([oracle.pack(rs.standard_normal(d)) for _ in range(w)]) for d in shape]
+    c = (rs.standard_normal(w) * 10.0 ** rs.uniform(-6, 6, w)).astype(dtype)
+    got = scd.scd_expand([to_dev_bits(s) for s in signs], dev(c), shape).cpu().numpy()
+    ref = oracle.expand(signs, c.astype(np.float64), shape).astype(dtype)
+    assert got.dtype == dtype and np.array_equal(got, ref)
+
+
+def test_expand_zero_terms(scd):
+    out = scd.scd_expand([torch.zeros((0, 1), dtype=torch.int64, device="cuda")] * 2,
+                         torch.zeros(0, dtype=torch.float32, device="cuda"), (40, 50))
+    assert float(out.abs().max()) == 0.0
+
+
+# ------------------------------------------------------------------ half steps (Algorithm 4 lines 5, 6-7)
+
+
+HALF_SHAPES = [(256, 256), (100, 77), (1024, 4096), (130, 8200), (3, 5), (2049, 64), (520, 14336)]
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("m,n", HALF_SHAPES)
+def test_half_steps(scd, oracle, m, n, dtype):
+    R = gauss((m, n), 1000 * m + n, dtype)
+    R64 = R.astype(np.float64)
+    t = oracle.rng_signs(5, 0, 1, n)
+    s = oracle.rng_signs(6, 0, 0, m)
+    u_ref = oracle.row_signed_sum(R64, t)
+    v_ref = oracle.col_signed_sum(R64, s)
+    Rd = dev(R)
+    u, sb = scd.scd_row_signed_sum(Rd, to_dev_bits(t))
+    v, tb, c = scd.scd_col_signed_sum(Rd, to_dev_bits(s))
+    tol = 2e-6 if dtype == np.float32 else 1e-13
+    np.testing.assert_allclose(u.cpu().numpy(), u_ref, rtol=0, atol=tol * np.abs(u_ref).max())
+    np.testing.assert_allclose(v.cpu().numpy(), v_ref, rtol=0, atol=tol * np.abs(v_ref).max())
+    assert_signs_match(to_np_bits(sb), oracle.pack(u_ref), u_ref, m, "s = sgn(R t)")
+    assert_signs_match(to_np_bits(tb), oracle.pack(v_ref), v_ref, n, "t = sgn(R^T s)")
+    assert float(c) == pytest.approx(np.abs(v_ref).sum(), rel=C_RTOL)
+
+
+# ------------------------------------------------------------------ one term from the same remainder and start
+
+
+def check_term(scd, oracle, A, seed, variant_name):
+    """scd_step_from vs Algorithm 4 + update of the oracle, same R and t_0."""
+    m, n = A.shape
+    A64 = A.astype(np.float64)
+    t0 = oracle.rng_signs(seed, 0, 1, n)
+    g = oracle.greedy_signed_cut(A64, t0)
+    with scd.ScdContext(dev(A), 4, seed) as ctx:
+        ctx.step_from([None, to_dev_bits(t0)])
+        assert ctx.width == 1
+        res = ctx.results()
+        Rg = ctx.remainder().cpu().numpy().astype(np.float64)
+    s_g, t_g = to_np_bits(res["signs"][0])[0], to_np_bits(res["signs"][1])[0]
+    c_g = float(res["c"][0])
+    trace = res["trace"].cpu().numpy()
+    sd, td = dense(s_g, m), dense(t_g, n)
+    c_from_signs = sd @ A64 @ td / (m * n)
+    assert c_g == pytest.approx(c_from_signs, rel=C_RTOL)
+    # identity of Section 3.2 on the GPU's own numbers
+    assert trace[1] ** 2 == pytest.approx(trace[0] ** 2 - m * n * c_g ** 2, rel=ID_RTOL)
+    assert trace[0] == pytest.approx(np.linalg.norm(A64), rel=ID_RTOL)
+    # the stored remainder is R - c s t^T
+    np.testing.assert_allclose(Rg, A64 - c_g * np.outer(sd, td), rtol=0,
+                               atol=(1e-6 if A.dtype == np.float32 else 1e-14) * np.abs(A64).max())
+    tie_free = g["margin"].min() >= TIE_TOL
+    if tie_free or A.dtype == np.float64:
+        assert np.array_equal(s_g, g["s"]) and np.array_equal(t_g, g["t"]), variant_name
+        assert int(res["iters"][0]) == g["iters"]
+        assert c_g == pytest.approx(g["c"] / (m * n), rel=C_RTOL)
+    else:
+        # tie-sensitive start: the result must still be a fixed point of its own alternation
+        assert_signs_match(s_g, oracle.pack(A64 @ td), A64 @ td, m, "fixed point s")
+        assert_signs_match(t_g, oracle.pack(A64.T @ sd), A64.T @ sd, n, "fixed point t")
+    return tie_free
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("m,n", [(256, 256), (100, 77), (64, 1024), (1000, 4096), (130, 8200), (7, 5)])
+def test_term_parity(scd, oracle, variant, m, n, dtype):
+    A = gauss((m, n), 31 * m + n, dtype)
+    check_term(scd, oracle, A, seed=m + n, variant_name=variant)
+
+
+# ------------------------------------------------------------------ whole decompositions
+
+
+def lockstep_check(oracle, A64, seed, S, T, c, trace, iters, f32):
+    """The oracle follows the GPU: term k is recomputed by Algorithm 4 on the oracle's own f64
+    remainder from the keyed start; where its signs differ from the GPU's the term must have been
+    tie-sensitive, and the oracle then adopts the GPU's signs.  Returns the oracle's curve."""
+    m, n = A64.shape
+    R = A64.copy()
+    curve = [np.linalg.norm(R)]
+    adopted = 0
+    for k in range(len(c)):
+        g = oracle.greedy_signed_cut(R, oracle.rng_signs(seed, k, 1, n))
+        same = np.array_equal(g["s"], S[k]) and np.array_equal(g["t"], T[k])
+        if same:
+            assert iters[k] == g["iters"], f"term {k}: iteration count"
+            assert c[k] == pytest.approx(g["c"] / (m * n), rel=C_RTOL), f"term {k}"
+        else:
+            assert f32 and g["margin"].min() < 10 * TIE_TOL, \
+                f"term {k}: signs differ although the oracle's margin is {g['margin'].min():.2e}"
+            adopted += 1
+        sd, td = dense(S[k], m), dense(T[k], n)
+        ck = sd @ R @ td / (m * n)
+        assert c[k] == pytest.approx(ck, rel=C_RTOL), f"term {k}: c does not match <s,Rt>/(mn)"
+        oracle.rank1_update(R, ck, S[k], T[k])
+        curve.append(math.sqrt(oracle.fro2(R)))
+    return np.array(curve), adopted
+
+
+@pytest.mark.parametrize("m,n,w,dtype", [(256, 256, 64, np.float32), (256, 256, 64, np.float64),
+                                         (200, 333, 40, np.float32), (77, 1024, 30, np.float32),
+                                         (1030, 520, 24, np.float32)])
+def test_decompose_lockstep_and_free_run(scd, oracle, variant, m, n, w, dtype):
+    seed = 1
+    A = gauss((m, n), 1 if (m, n) == (256, 256) else m * n, dtype)
+    A64 = A.astype(np.float64)
+    res = scd.scd_decompose(dev(A), w, seed)
+    assert res["status"] == 0
+    S, T = to_np_bits(res["signs"][0]), to_np_bits(res["signs"][1])
+    c = res["c"].cpu().numpy().astype(np.float64)
+    trace = res["trace"].cpu().numpy()
+    iters = res["iters"].cpu().numpy()
+    # Frobenius identity on the GPU's own outputs, every term
+    np.testing.assert_allclose(trace[1:] ** 2, trace[:-1] ** 2 - m * n * c ** 2, rtol=ID_RTOL)
+    curve, adopted = lockstep_check(oracle, A64, seed, S, T, c, trace, iters, dtype == np.float32)
+    np.testing.assert_allclose(trace / trace[0], curve / curve[0], rtol=CURVE_RTOL)
+    np.testing.assert_allclose(trace, curve, rtol=2e-5 if dtype == np.float32 else 1e-11)
+    # free run of the oracle on the same input and seed
+    free = oracle.decompose(A64, w, seed)
+    np.testing.assert_allclose(trace / trace[0], free["trace"] / free["trace"][0], rtol=CURVE_RTOL)
+    if adopted == 0:
+        assert np.array_equal(S, free["S"]) and np.array_equal(T, free["T"])
+    # definition: A - expand(S,T,c) has the norm the trace reports
+    E = scd.scd_expand(res["signs"], res["c"], (m, n)).cpu().numpy().astype(np.float64)
+    assert np.linalg.norm(A64 - E) == pytest.approx(trace[-1], rel=1e-4 if dtype == np.float32 else 1e-10)
+
+
+def test_step_run_results_agree_with_one_shot(scd, variant):
+    A = dev(gauss((300, 260), 9))
+    one = scd.scd_decompose(A, 12, 4)
+    with scd.ScdContext(A, 12, 4) as ctx:
+        ctx.step()
+        ctx.run(5)
+        assert ctx.width == 6
+        for _ in range(6):
+            ctx.step()
+        with pytest.raises(scd.ScdError) as e:
+            ctx.step()
+        assert e.value.code == scd.EFULL
+        res = ctx.results()
+        R = ctx.remainder()
+    for a, b in zip(one["signs"], res["signs"]):
+        assert torch.equal(a, b)
+    assert torch.equal(one["c"], res["c"]) and torch.equal(one["trace"], res["trace"])
+    assert torch.equal(one["iters"], res["iters"])
+    E = scd.scd_expand(res["signs"], res["c"], (300, 260))
+    assert float((A - E - R).abs().max()) <= 2e-6 * float(A.abs().max())
+
+
+def test_two_runs_are_bit_identical(scd):
+    A = dev(gauss((512, 768), 10))
+    a = scd.scd_decompose(A, 20, 7)
+    b = scd.scd_decompose(A, 20, 7)
+    for x, y in zip(a["signs"] + [a["c"], a["trace"], a["iters"]], b["signs"] + [b["c"], b["trace"], b["iters"]]):
+        assert torch.equal(x, y)
+
+
+def test_tiled_and_generic_kernels_agree(scd):
+    A = dev(gauss((384, 1024), 12))
+    out = []
+    for v in ("1", "0"):
+        os.environ["SCD_ROWPASS_VARIANT"] = v
+        out.append(scd.scd_decompose(A, 10, 3))
+    os.environ.pop("SCD_ROWPASS_VARIANT")
+    np.testing.assert_allclose(out[0]["trace"].cpu().numpy(), out[1]["trace"].cpu().numpy(), rtol=1e-5)
+
+
+def test_set_remainder_resumes_exactly(scd, variant):
+    A = dev(gauss((256, 512), 13))
+    full = scd.scd_decompose(A, 8, 21)
+    with scd.ScdContext(A, 8, 21) as ctx:
+        ctx.run(5)
+        R5 = ctx.remainder()
+        ctx.set_remainder(R5)          # same remainder: the rest of the run must not change
+        ctx.run(3)
+        res = ctx.results()
+    assert torch.equal(full["signs"][0], res["signs"][0]) and torch.equal(full["signs"][1], res["signs"][1])
+    assert torch.equal(full["c"], res["c"])
+    # trace[5] was recomputed by a pass of another kind (different rounding of the f32 partial sums)
+    np.testing.assert_allclose(full["trace"].cpu().numpy(), res["trace"].cpu().numpy(), rtol=1e-8)
+
+
+def test_one_term_recovery_and_iteration_cap(scd, oracle):
+    rs = np.random.Generator(np.random.PCG64(3))
+    m, n = 130, 257
+    s, t = np.sign(rs.standard_normal(m)), np.sign(rs.standard_normal(n))
+    A = (0.375 * np.outer(s, t)).astype(np.float32)
+    res = scd.scd_decompose(dev(A), 1, 5)
+    assert float(res["c"][0]) == pytest.approx(0.375, rel=1e-6)
+    assert float(res["trace"][1]) <= 1e-6 * float(res["trace"][0])
+    sg, tg = dense(to_np_bits(res["signs"][0])[0], m), dense(to_np_bits(res["signs"][1])[0], n)
+    assert np.array_equal(np.outer(sg, tg), np.outer(s, t))
+    # the cap is reported as a warning and the result is still a valid term
+    B = dev(gauss((200, 200), 4))
+    with scd.ScdContext(B, 2, 1) as ctx:
+        ctx.set_max_iters(1)
+        assert ctx.step() == scd.WMAXITER
+        r = ctx.results()
+        assert int(r["iters"][0]) == 1
+        tr = r["trace"].cpu().numpy()
+        assert tr[1] ** 2 == pytest.approx(tr[0] ** 2 - 200 * 200 * float(r["c"][0]) ** 2, rel=ID_RTOL)
+
+
+def test_error_paths(scd):
+    A = dev(gauss((64, 64), 1))
+    bad = A.clone()
+    bad[3, 5] = float("nan")
+    with pytest.raises(scd.ScdError) as e:
+        scd.ScdContext(bad, 2, 0)
+    assert e.value.code == scd.ENONFINITE
+    with scd.ScdContext(A, 2, 0) as ctx:
+        inf = A.clone()
+        inf[0, 0] = float("inf")
+        with pytest.raises(scd.ScdError) as e:
+            ctx.set_remainder(inf)
+        assert e.value.code == scd.ENONFINITE
+    res = scd.scd_decompose(A, 0, 0)
+    assert res["trace"].numel() == 1 and float(res["trace"][0]) == pytest.approx(float(A.double().norm()), rel=1e-6)
+
+
+# ------------------------------------------------------------------ tensors (Algorithms 12 and 13)
+
+
+def kron_dense(sign_rows, shape):
+    out = np.array([1.0])
+    for b, d in zip(sign_rows, shape):
+        out = np.multiply.outer(out, dense(b, d))
+    return out.reshape(shape)
+
+
+@pytest.mark.parametrize("shape,w,dtype", [((40, 30, 3), 16, np.float32), ((40, 30, 3), 16, np.float64),
+                                           ((130, 64, 4), 12, np.float32), ((9, 8, 7, 6), 10, np.float32),
+                                           ((300, 200, 3), 8, np.float32)])
+def test_tensor_decompose(scd, oracle, variant, shape, w, dtype):
+    seed = 4
+    a = gauss(shape, int(np.prod(shape)), dtype)
+    a64 = a.astype(np.float64)
+    N = a.size
+    res = scd.scd_decompose(dev(a), w, seed)
+    signs = [to_np_bits(s) for s in res["signs"]]
+    c = res["c"].cpu().numpy().astype(np.float64)
+    trace = res["trace"].cpu().numpy()
+    iters = res["iters"].cpu().numpy()
+    np.testing.assert_allclose(trace[1:] ** 2, trace[:-1] ** 2 - N * c ** 2, rtol=ID_RTOL)
+    # lockstep against Algorithm 12 on the oracle's own remainder
+    r = a64.copy()
+    for k in range(w):
+        s0 = [oracle.rng_signs(seed, k, i, d) for i, d in enumerate(shape)]
+        g = oracle.axial_greedy_cut(r, s0)
+        mine = [sg[k] for sg in signs]
+        same = all(np.array_equal(x, y) for x, y in zip(g["signs"], mine))
+        if same:
+            assert iters[k] == g["iters"]
+            assert c[k] == pytest.approx(g["c"] / N, rel=C_RTOL)
+        else:
+            assert dtype == np.float32 and g["margin"].min() < 10 * TIE_TOL, f"term {k} differs, margin {g['margin']}"
+        ck = (r * kron_dense(mine, shape)).sum() / N
+        assert c[k] == pytest.approx(ck, rel=C_RTOL)
+        oracle.tensor_update(r, ck, mine)
+        assert trace[k + 1] == pytest.approx(np.linalg.norm(r), rel=2e-5 if dtype == np.float32 else 1e-11)
+    E = scd.scd_expand(res["signs"], res["c"], shape).cpu().numpy().astype(np.float64)
+    assert np.linalg.norm(a64 - E) == pytest.approx(trace[-1], rel=1e-4 if dtype == np.float32 else 1e-10)
+
+
+def test_tensor_step_from(scd, oracle):
+    shape = (50, 40, 3)
+    a = gauss(shape, 99)
+    s0 = [oracle.rng_signs(8, 0, i, d) for i, d in enumerate(shape)]
+    g = oracle.axial_greedy_cut(a.astype(np.float64), s0)
+    with scd.ScdContext(dev(a), 2, 123) as ctx:
+        ctx.step_from([None] + [to_dev_bits(b) for b in s0[1:]])
+        res = ctx.results()
+    if g["margin"].min() >= TIE_TOL:
+        for i in range(3):
+            assert np.array_equal(to_np_bits(res["signs"][i])[0], g["signs"][i])
+        assert float(res["c"][0]) == pytest.approx(g["c"] / a.size, rel=C_RTOL)
