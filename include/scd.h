@@ -129,6 +129,20 @@ int scd_last_hip_error(void);        /* hipError_t of the most recent SCD_EHIP o
  * of passes (launches) they took: the counters behind the bandwidth figures.  host pointers. */
 int scd_traffic(const scd_ctx* ctx, double* bytes, int64_t* passes, int64_t* sweeps);
 
+/* Measurement: run n (<= 4096) further sweeps of the greedy loop with a HIP event before and after
+ * each kernel of the pass over the remainder; returns the average duration of the row-pass launch
+ * and of the reduce launch that follows it (host pointers, seconds).  The terms found meanwhile are
+ * ordinary terms of the decomposition; SCD_EFULL if the context is at capacity. */
+int scd_profile_sweeps(scd_ctx* ctx, int n, double* rowpass_seconds, double* reduce_seconds);
+
+/* Plain streaming kernels, for measurement only.  dst == NULL: read `bytes` (a multiple of 16) from
+ * src and discard them; else copy src to dst.  `grid` workgroups of 256 threads, one untimed launch
+ * and then `reps` timed ones; *seconds (host) = average time of one launch by HIP events on `stream`.
+ * The read rate of a buffer that is re-read gives the ceiling of the cache-resident row pass; the
+ * copy of known size calibrates the memory counters of the profiler. */
+int scd_probe_stream(const void* src, void* dst, int64_t bytes, int grid, int reps, void* stream,
+                     double* seconds);
+
 #ifdef __cplusplus
 }
 #endif

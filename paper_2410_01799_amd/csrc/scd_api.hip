@@ -283,7 +283,17 @@ int scd_create(scd_ctx** out, const void* A, scd_dtype dt, int order, const int6
     c->variant = env_int("SCD_ROWPASS_VARIANT", 1);
     c->batch = env_int("SCD_SWEEP_BATCH", 64);
     for (int i = 0; i < order; ++i) c->dims[i] = dims[i];
-    const int wg_target = env_int("SCD_WORKGROUPS", 512);
+    // one workgroup per compute unit: every partial row costs a write and a read per alternation
+    int cus = 256;
+    {
+        int devid = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&devid) == hipSuccess && hipGetDeviceProperties(&prop, devid) == hipSuccess &&
+            prop.multiProcessorCount > 0)
+            cus = prop.multiProcessorCount;
+        (void)hipGetLastError();
+    }
+    const int wg_target = env_int("SCD_WORKGROUPS", cus);
 
     int st = SCD_OK;
     auto fail = [&](int code) {
@@ -483,6 +493,54 @@ int scd_traffic(const scd_ctx* c, double* bytes, int64_t* passes, int64_t* sweep
     return SCD_OK;
 }
 
+int scd_profile_sweeps(scd_ctx* c, int n, double* rowpass_seconds, double* reduce_seconds)
+{
+    if (!c || n < 1 || n > 4096 || !rowpass_seconds || !reduce_seconds) return SCD_EINVAL;
+    if (c->hs.k >= c->w_capacity) return SCD_EFULL;
+    // keep the device loop running for the whole sample: aim at the capacity, restore nothing (the
+    // terms found while sampling are ordinary terms)
+    c->hs.w_target = c->w_capacity;
+    c->hs.done = 0;
+    SCD_TRY(write_state(c));
+    std::vector<hipEvent_t> ev((size_t)3 * n, nullptr);
+    int rc = SCD_OK;
+    hipError_t e = hipSuccess;
+    for (size_t i = 0; i < ev.size() && e == hipSuccess; ++i) e = hipEventCreate(&ev[i]);
+    Level& L = c->lv[0];
+    for (int i = 0; i < n && e == hipSuccess; ++i) {
+        e = hipEventRecord(ev[3 * i], c->stream);
+        if (e == hipSuccess) e = launch_rowpass(L.pass, c->dt, L.grid, c->variant, c->stream);
+        if (e == hipSuccess) e = hipEventRecord(ev[3 * i + 1], c->stream);
+        if (e == hipSuccess) e = launch_reduce(L.red, c->dt == SCD_F32, c->stream);
+        if (e == hipSuccess) e = hipEventRecord(ev[3 * i + 2], c->stream);
+        for (int l = 1; l < c->nlevels && e == hipSuccess; ++l) {
+            e = launch_rowpass(c->lv[l].pass, c->dt, c->lv[l].grid, c->variant, c->stream);
+            if (e == hipSuccess) e = launch_reduce(c->lv[l].red, false, c->stream);
+        }
+        if (e == hipSuccess && c->order >= 3) e = launch_kron(c->kron, c->stream);
+    }
+    if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+    double tp = 0.0, tr = 0.0;
+    for (int i = 0; i < n && e == hipSuccess; ++i) {
+        float a = 0.f, b = 0.f;
+        e = hipEventElapsedTime(&a, ev[3 * i], ev[3 * i + 1]);
+        if (e == hipSuccess) e = hipEventElapsedTime(&b, ev[3 * i + 1], ev[3 * i + 2]);
+        tp += a;
+        tr += b;
+    }
+    for (hipEvent_t x : ev)
+        if (x) (void)hipEventDestroy(x);
+    if (e != hipSuccess) {
+        g_last_hip = (int)e;
+        (void)hipGetLastError();
+        return SCD_EHIP;
+    }
+    *rowpass_seconds = tp * 1e-3 / n;
+    *reduce_seconds = tr * 1e-3 / n;
+    rc = read_state(c);
+    return rc;
+}
+
 int scd_decompose(const void* A, scd_dtype dt, int order, const int64_t* dims, int64_t w, uint64_t seed, void* stream,
                   uint64_t* const* signs, void* cvec, double* fro_trace, int32_t* iters)
 {
@@ -645,6 +703,41 @@ int scd_rng_signs(uint64_t seed, uint64_t term, uint32_t mode, int64_t n, void* 
     HIP_TRY(launch_rng(seed, term, mode, n, bits, (hipStream_t)stream));
     HIP_TRY(hipStreamSynchronize((hipStream_t)stream));
     return SCD_OK;
+}
+
+// ---------------------------------------------------------------------------------------------- probes
+
+int scd_probe_stream(const void* src, void* dst, int64_t bytes, int grid, int reps, void* stream, double* seconds)
+{
+    if (!src || bytes < 16 || (bytes % 16) || grid < 1 || reps < 1 || !seconds) return SCD_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    float* sink = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    int rc = SCD_OK;
+    hipError_t e = hipMalloc((void**)&sink, 4);
+    if (e == hipSuccess) e = hipEventCreate(&e0);
+    if (e == hipSuccess) e = hipEventCreate(&e1);
+    // one untimed launch, then `reps` timed ones
+    for (int r = -1; r < reps && e == hipSuccess; ++r) {
+        if (r == 0) e = hipEventRecord(e0, st);
+        if (e != hipSuccess) break;
+        e = dst ? launch_stream_copy(src, dst, bytes, grid, st) : launch_stream_read(src, bytes, grid, sink, st);
+    }
+    if (e == hipSuccess) e = hipEventRecord(e1, st);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    float ms = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    if (e != hipSuccess) {
+        g_last_hip = (int)e;
+        (void)hipGetLastError();
+        rc = SCD_EHIP;
+    } else {
+        *seconds = (double)ms * 1e-3 / reps;
+    }
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    if (sink) (void)hipFree(sink);
+    return rc;
 }
 
 const char* scd_strerror(int code)

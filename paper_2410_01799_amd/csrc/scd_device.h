@@ -117,6 +117,8 @@ hipError_t launch_halfstep(const void* R, scd_dtype dt, int64_t m, int64_t n, in
 hipError_t launch_reduce_plain(const void* partials, scd_dtype dt, int nparts, int64_t cols, double* W, uint64_t* bits,
                                double* cparts, hipStream_t st);
 hipError_t launch_sum_parts(const double* parts, int n, double* out, hipStream_t st);
+hipError_t launch_stream_read(const void* x, int64_t bytes, int grid, float* sink, hipStream_t st);
+hipError_t launch_stream_copy(const void* x, void* y, int64_t bytes, int grid, hipStream_t st);
 bool fast_rowpass_supported(scd_dtype dt, int64_t cols, int level);
 
 }  // namespace scd

@@ -10,6 +10,8 @@
 //             via Section 3.1: <s, R t> = ||R^T s||_1), packs s from u with 64-lane ballots.
 //  kron     : Kronecker products of sign bitsets for the tensor sweep (Algorithm 12 lines 5-7).
 //  expand   : the definition sum_j c_j s_j t_j^T with one f64 accumulator per entry.
+#include <stddef.h>
+
 #include "scd_device.h"
 
 namespace scd {
@@ -57,6 +59,13 @@ __device__ __forceinline__ float flip(float x, uint32_t neg)
 __device__ __forceinline__ double flip(double x, uint32_t neg)
 {
     return __longlong_as_double(__double_as_longlong(x) ^ ((long long)neg << 63));
+}
+
+// Workgroup barrier for LDS exchange only.  __syncthreads() would also wait for every outstanding
+// global load, i.e. for the rows being prefetched for the next batch; this waits for LDS alone.
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
 // Sum over the 64 lanes by an xor butterfly.  a+b and b+a round alike, so every lane ends with
@@ -145,6 +154,28 @@ __device__ void rowpass_generic_body(TE* __restrict__ X, int64_t rows, int64_t c
     }
 }
 
+// The fields of the device state a row pass needs, read one by one: a whole-struct copy would be
+// placed in LDS or scratch by the compiler and serialise the loads behind it.
+struct StateView {
+    int64_t k;
+    double c_prev;
+    int32_t j, done, t0_given, max_iters, active, sweep_rng;
+};
+
+__device__ __forceinline__ StateView view_state(const State* s)
+{
+    StateView v;
+    v.k = s->k;
+    v.c_prev = s->c_prev;
+    v.j = s->j;
+    v.done = s->done;
+    v.t0_given = s->t0_given;
+    v.max_iters = s->max_iters;
+    v.active = s->active;
+    v.sweep_rng = s->sweep_rng;
+    return v;
+}
+
 // What the level-0 pass of this sweep has to do, decided alike by every workgroup (Algorithm 4
 // line 8: stop when c_j <= c_{j-1}).  Returns false when the sweep is to be skipped.
 struct Decision {
@@ -153,26 +184,25 @@ struct Decision {
     double ck;
 };
 
-__device__ __forceinline__ bool decide_level0(const RowPassArgs& a, const State& st, Decision& d)
+__device__ __forceinline__ bool decide_level0(const RowPassArgs& a, const StateView& st, double c, Decision& d)
 {
     d.c = 0.0;
     d.ck = 0.0;
+    d.mode = PASS_START;
     if (st.done) return false;
-    if (st.j == 0) {
-        d.mode = PASS_START;
-        return true;
-    }
-    d.c = sum_fixed(a.cparts, a.ncparts);
+    if (st.j == 0) return true;
+    d.c = c;  // sum of the partial sums of |R^T s|, the same bits in every workgroup
     bool conv = (d.c <= st.c_prev) || (st.j >= st.max_iters);
     d.mode = conv ? PASS_UPDATE : PASS_CONT;
     d.ck = d.c / a.total;
     return true;
 }
 
-// Bookkeeping of the level-0 pass: append the finished term and write the state the rest of the
-// sweep reads.  Called by every thread of every workgroup; only the sign copy is spread out.
+// Bookkeeping of the level-0 pass, done after the pass itself: append the finished term and write
+// the state the rest of the sweep reads.  Called by every thread of every workgroup; the sign copy
+// is spread over all of them, the state is written by one thread, field by field.
 template <typename TE>
-__device__ __forceinline__ void level0_bookkeeping(const RowPassArgs& a, const State& st, const Decision& d)
+__device__ __forceinline__ void level0_bookkeeping(const RowPassArgs& a, const StateView& st, const Decision& d)
 {
     if (d.mode == PASS_UPDATE) {
         // S_{k+1} = [S_k s], T_{k+1} = [T_k t]  (Algorithm 5 lines 8-9): every workgroup copies a slice
@@ -183,33 +213,42 @@ __device__ __forceinline__ void level0_bookkeeping(const RowPassArgs& a, const S
         }
     }
     if (blockIdx.x == 0 && threadIdx.x == 0) {
-        State nx = st;
-        nx.active = 1;
-        nx.passes = st.passes + 1;
-        nx.c_last = d.c;
+        const State* cu = a.cur;
+        State* nx = a.next;
+        nx->w_target = cu->w_target;
+        nx->max_iters = st.max_iters;
+        nx->done = 0;
+        nx->active = 1;
+        nx->passes = cu->passes + 1;
+        nx->c_last = d.c;
+        nx->t0_given = 0;
         if (d.mode == PASS_START) {
-            nx.j = 1;
-            nx.c_prev = -INFINITY;
-            nx.norm_pending = 1;
-            nx.sweep_rng = st.t0_given ? 0 : 1;
-            nx.t0_given = 0;
+            nx->k = st.k;
+            nx->updates = cu->updates;
+            nx->warn = cu->warn;
+            nx->j = 1;
+            nx->c_prev = -INFINITY;
+            nx->norm_pending = 1;
+            nx->sweep_rng = st.t0_given ? 0 : 1;
         } else if (d.mode == PASS_CONT) {
-            nx.j = st.j + 1;
-            nx.c_prev = d.c;
-            nx.norm_pending = 0;
-            nx.sweep_rng = 0;
+            nx->k = st.k;
+            nx->updates = cu->updates;
+            nx->warn = cu->warn;
+            nx->j = st.j + 1;
+            nx->c_prev = d.c;
+            nx->norm_pending = 0;
+            nx->sweep_rng = 0;
         } else {
             ((TE*)a.c_out)[st.k] = (TE)d.ck;  // c_{k+1} (Algorithm 5 line 7), normalised
             a.iters_out[st.k] = st.j;
-            if (!(d.c <= st.c_prev)) nx.warn = 1;
-            nx.k = st.k + 1;
-            nx.updates = st.updates + 1;
-            nx.j = 1;
-            nx.c_prev = -INFINITY;
-            nx.norm_pending = 1;
-            nx.sweep_rng = 1;
+            nx->warn = (d.c <= st.c_prev) ? cu->warn : 1;
+            nx->k = st.k + 1;
+            nx->updates = cu->updates + 1;
+            nx->j = 1;
+            nx->c_prev = -INFINITY;
+            nx->norm_pending = 1;
+            nx->sweep_rng = 1;
         }
-        *a.next = nx;
     }
 }
 
@@ -219,20 +258,20 @@ __global__ void __launch_bounds__(kBlock) rowpass_generic_kernel(RowPassArgs a)
     __shared__ uint8_t sh_s[kMaxRowsPerWg];
     __shared__ double sh_red[kWavesPerBlock];
     if (a.level == 0) {
-        const State st = *a.cur;
+        const StateView st = view_state(a.cur);
         Decision d;
-        if (!decide_level0(a, st, d)) {
+        if (!decide_level0(a, st, sum_fixed(a.cparts, a.ncparts), d)) {
             if (blockIdx.x == 0 && threadIdx.x == 0) a.next->active = 0;
             return;
         }
-        level0_bookkeeping<TE>(a, st, d);
         const bool upd = d.mode == PASS_UPDATE;
         const bool start = d.mode == PASS_START;
         const uint64_t* sumbits = (upd || (start && !st.t0_given)) ? a.sign_rng : a.sign_cur;
         rowpass_generic_body<TE>((TE*)a.X, a.rows, a.cols, a.rows_per_wg, upd, upd || start, true, true, sumbits,
                                  a.sign_cur, a.row_bits, (TE)d.ck, (TE*)a.partials, a.u, a.fparts, sh_s, sh_red);
+        level0_bookkeeping<TE>(a, st, d);
     } else {
-        const State st = *a.next;
+        const StateView st = view_state(a.next);
         if (!st.active) return;
         const uint64_t* sumbits = st.sweep_rng ? a.sign_rng : a.sign_cur;
         rowpass_generic_body<TE>((TE*)a.X, a.rows, a.cols, a.rows_per_wg, false, false, true, true, sumbits,
@@ -260,6 +299,10 @@ __global__ void __launch_bounds__(kBlock)
 // time and the next RB rows are already being loaded while these are reduced.  Because a thread
 // keeps its own columns for every row, the column partial sums never leave its registers until
 // the workgroup is done: the matrix is read exactly once per alternation.
+//
+// Loads are never predicated: a row or chunk index past the end is clamped to the last valid one
+// (the address stays in bounds) and the value is zeroed afterwards, only in the code path that
+// handles a ragged batch.  Full batches run without any select.
 
 template <typename TE>
 struct Vec16;
@@ -278,28 +321,43 @@ template <typename TE, int CPT, int RB>
 struct Tile {
     static constexpr int VE = Vec16<TE>::N;
     TE x[RB][CPT * VE];
+    uint32_t rowsign;  // bit r: current sign of row rb+r (read by the update)
 };
 
 template <typename TE, int CPT, int RB>
 __device__ __forceinline__ void tile_load(Tile<TE, CPT, RB>& t, const TE* __restrict__ X, int64_t cols, int64_t rb,
-                                          int64_t r1, int64_t nch)
+                                          int64_t r1, int64_t nch, const uint64_t* __restrict__ rowbits, int64_t rows,
+                                          bool valid)
 {
+    // Never predicated and never behind a branch: a conditional prefetch would make the compiler
+    // wait for it at the next join.  A batch that does not exist (`valid` false) is loaded from one
+    // 16-byte location instead, a broadcast that costs next to nothing and is never used.
     constexpr int VE = Vec16<TE>::N;
     typedef typename Vec16<TE>::type V;
+    {
+        const int64_t wlast = (rows - 1) >> 6;
+        int64_t w0i = rb >> 6;
+        w0i = w0i < wlast ? w0i : wlast;
+        const int64_t w1i = w0i < wlast ? w0i + 1 : wlast;
+        const uint64_t w0 = rowbits[w0i], w1 = rowbits[w1i];
+        const int sh = (int)(rb & 63);
+        t.rowsign = (uint32_t)((w0 >> sh) | (sh ? (w1 << (64 - sh)) : 0ull));
+    }
+    int64_t chs[CPT];
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) {
+        const int64_t ch = threadIdx.x + c * kBlock;
+        const int64_t chc = ch < nch ? ch : nch - 1;
+        chs[c] = valid ? chc : 0;
+    }
 #pragma unroll
     for (int r = 0; r < RB; ++r) {
-        const bool rok = rb + r < r1;
-        const V* rowp = (const V*)(X + (rb + r) * cols);
+        int64_t row = rb + r;
+        row = row < r1 ? row : r1 - 1;
+        const V* rowp = (const V*)(X + row * cols);
 #pragma unroll
         for (int c = 0; c < CPT; ++c) {
-            const int64_t ch = threadIdx.x + c * kBlock;
-            V v;
-            if (rok && ch < nch) {
-                v = rowp[ch];
-            } else {
-                if constexpr (VE == 4) v = V{0, 0, 0, 0};
-                else v = V{0, 0};
-            }
+            const V v = rowp[chs[c]];
             if constexpr (VE == 4) {
                 t.x[r][c * 4 + 0] = v.x;
                 t.x[r][c * 4 + 1] = v.y;
@@ -313,7 +371,7 @@ __device__ __forceinline__ void tile_load(Tile<TE, CPT, RB>& t, const TE* __rest
     }
 }
 
-// Sign bits of this thread's columns, element e of chunk c in bit c*VE+e.
+// Sign bits of this thread's columns, element e of chunk c in bit c*VE+e (0 past the end).
 template <typename TE, int CPT>
 __device__ __forceinline__ uint64_t gather_bits(const uint64_t* __restrict__ bits, int64_t nch)
 {
@@ -322,20 +380,21 @@ __device__ __forceinline__ uint64_t gather_bits(const uint64_t* __restrict__ bit
 #pragma unroll
     for (int c = 0; c < CPT; ++c) {
         const int64_t ch = threadIdx.x + c * kBlock;
-        if (ch < nch) {
-            const int64_t col = ch * VE;  // VE divides 64: a chunk never straddles a word
-            const uint64_t w = bits[col >> 6];
-            out |= ((w >> (col & 63)) & ((1ull << VE) - 1)) << (c * VE);
-        }
+        const int64_t chc = ch < nch ? ch : nch - 1;
+        const int64_t col = chc * VE;  // VE divides 64: a chunk never straddles a word
+        const uint64_t w = bits[col >> 6];
+        const uint64_t b = (w >> (col & 63)) & ((1ull << VE) - 1);
+        out |= (ch < nch ? b : 0ull) << (c * VE);
     }
     return out;
 }
 
-template <typename TE, int CPT, int RB, bool UPD, bool NORM>
+// One batch of RB rows.  FULL: every row of the batch and every chunk of this thread exists.
+template <typename TE, int CPT, int RB, bool UPD, bool FULL>
 __device__ __forceinline__ void tile_process(Tile<TE, CPT, RB>& t, TE* __restrict__ X, int64_t cols, int64_t rb,
-                                             int64_t r1, int64_t nch, uint64_t sumb, uint64_t updb,
-                                             const uint64_t* __restrict__ rowbits, TE ck, TE* acc, double& fsq,
-                                             double* __restrict__ u, double (*sh_u)[kWavesPerBlock][RB], int parity)
+                                             int64_t r1, int64_t nch, uint64_t sumb, uint64_t updb, TE ck, TE* acc,
+                                             double& fsq, double* __restrict__ u,
+                                             double (*sh_u)[kWavesPerBlock][RB], int parity)
 {
     constexpr int VE = Vec16<TE>::N;
     constexpr int NE = CPT * VE;
@@ -343,38 +402,48 @@ __device__ __forceinline__ void tile_process(Tile<TE, CPT, RB>& t, TE* __restric
     const int lane = threadIdx.x & (kWave - 1);
     const int wv = threadIdx.x / kWave;
     double ps[RB];
+    if constexpr (!FULL) {
+#pragma unroll
+        for (int r = 0; r < RB; ++r) {
+            const bool rok = rb + r < r1;
+#pragma unroll
+            for (int c = 0; c < CPT; ++c) {
+                const bool ok = rok && (threadIdx.x + c * kBlock < nch);
+#pragma unroll
+                for (int e = 0; e < VE; ++e) t.x[r][c * VE + e] = ok ? t.x[r][c * VE + e] : (TE)0;
+            }
+        }
+    }
 #pragma unroll
     for (int r = 0; r < RB; ++r) {
         if constexpr (UPD) {
-            const bool rok = rb + r < r1;
-            const uint32_t sold = rok ? bit_at(rowbits, rb + r) : 0u;
+            // R <- R - ck s t^T (Algorithm 5 line 10), and the squares of the new remainder
+            const bool rok = FULL || (rb + r < r1);
+            const int64_t rowc = rok ? rb + r : r1 - 1;
+            const uint32_t sold = (t.rowsign >> r) & 1u;
+            TE f = 0;
 #pragma unroll
             for (int e = 0; e < NE; ++e) {
                 const uint32_t neg = sold ^ (uint32_t)((updb >> e) & 1ull);
                 t.x[r][e] = t.x[r][e] - flip(ck, neg);
             }
-            if (rok) {
-                V* rowp = (V*)(X + (rb + r) * cols);
+            V* rowp = (V*)(X + rowc * cols);
 #pragma unroll
-                for (int c = 0; c < CPT; ++c) {
-                    const int64_t ch = threadIdx.x + c * kBlock;
-                    if (ch < nch) {
-                        V v;
-                        if constexpr (VE == 4) v = V{t.x[r][c * 4], t.x[r][c * 4 + 1], t.x[r][c * 4 + 2], t.x[r][c * 4 + 3]};
-                        else v = V{t.x[r][c * 2], t.x[r][c * 2 + 1]};
-                        rowp[ch] = v;
-                    } else {
+            for (int c = 0; c < CPT; ++c) {
+                V v;
+                if constexpr (VE == 4) v = V{t.x[r][c * 4], t.x[r][c * 4 + 1], t.x[r][c * 4 + 2], t.x[r][c * 4 + 3]};
+                else v = V{t.x[r][c * 2], t.x[r][c * 2 + 1]};
+                if constexpr (FULL) {
+                    rowp[threadIdx.x + c * kBlock] = v;
+                } else {
+                    const bool ok = rok && (threadIdx.x + c * kBlock < nch);
+                    if (ok) rowp[threadIdx.x + c * kBlock] = v;
+                    else {
 #pragma unroll
-                        for (int e = 0; e < VE; ++e) t.x[r][c * VE + e] = 0;  // keep the padding at zero
+                        for (int e = 0; e < VE; ++e) t.x[r][c * VE + e] = 0;  // padding stays zero
                     }
                 }
-            } else {
-#pragma unroll
-                for (int e = 0; e < NE; ++e) t.x[r][e] = 0;
             }
-        }
-        if constexpr (NORM) {
-            TE f = 0;
 #pragma unroll
             for (int e = 0; e < NE; ++e) f += t.x[r][e] * t.x[r][e];
             fsq += (double)f;
@@ -390,23 +459,35 @@ __device__ __forceinline__ void tile_process(Tile<TE, CPT, RB>& t, TE* __restric
 #pragma unroll
         for (int r = 0; r < RB; ++r) sh_u[parity][wv][r] = ps[r];
     }
-    __syncthreads();
+    lds_barrier();
 #pragma unroll
     for (int r = 0; r < RB; ++r) {
         double ur = 0.0;
 #pragma unroll
         for (int q = 0; q < kWavesPerBlock; ++q) ur += sh_u[parity][q][r];
-        if (threadIdx.x == r && rb + r < r1) u[rb + r] = ur;
+        if (threadIdx.x == r && (FULL || rb + r < r1)) u[rb + r] = ur;
         const uint32_t neg = ur < 0.0 ? 1u : 0u;
 #pragma unroll
         for (int e = 0; e < NE; ++e) acc[e] += flip(t.x[r][e], neg);
     }
 }
 
-template <typename TE, int CPT, int RB, bool UPD, bool NORM>
-__device__ __forceinline__ void rowpass_tiled_body(TE* __restrict__ X, int64_t rows, int64_t cols, int rows_per_wg,
-                                                   const uint64_t* __restrict__ sumbits,
-                                                   const uint64_t* __restrict__ updbits,
+template <typename TE, int CPT, int RB, bool UPD>
+__device__ __forceinline__ void tile_step(Tile<TE, CPT, RB>& t, TE* __restrict__ X, int64_t cols, int64_t rb,
+                                          int64_t r1, int64_t nch, bool full_cols, uint64_t sumb, uint64_t updb, TE ck,
+                                          TE* acc, double& fsq, double* __restrict__ u,
+                                          double (*sh_u)[kWavesPerBlock][RB], int parity)
+{
+    if (full_cols && rb + RB <= r1)
+        tile_process<TE, CPT, RB, UPD, true>(t, X, cols, rb, r1, nch, sumb, updb, ck, acc, fsq, u, sh_u, parity);
+    else
+        tile_process<TE, CPT, RB, UPD, false>(t, X, cols, rb, r1, nch, sumb, updb, ck, acc, fsq, u, sh_u, parity);
+}
+
+// `ta` already holds the first batch (its loads were issued before the pass was decided).
+template <typename TE, int CPT, int RB, bool UPD>
+__device__ __forceinline__ void rowpass_tiled_body(Tile<TE, CPT, RB>& ta, TE* __restrict__ X, int64_t rows,
+                                                   int64_t cols, int64_t r0, int64_t r1, uint64_t sumb, uint64_t updb,
                                                    const uint64_t* __restrict__ rowbits, TE ck,
                                                    TE* __restrict__ partials, double* __restrict__ u,
                                                    double* __restrict__ fparts)
@@ -417,26 +498,26 @@ __device__ __forceinline__ void rowpass_tiled_body(TE* __restrict__ X, int64_t r
     __shared__ double sh_u[2][kWavesPerBlock][RB];
     __shared__ double sh_f[kWavesPerBlock];
     const int64_t nch = cols / VE;
-    const int64_t r0 = (int64_t)blockIdx.x * rows_per_wg;
-    const int64_t r1 = (r0 + rows_per_wg < rows) ? r0 + rows_per_wg : rows;
-    const uint64_t sumb = gather_bits<TE, CPT>(sumbits, nch);
-    const uint64_t updb = UPD ? gather_bits<TE, CPT>(updbits, nch) : 0ull;
+    const bool full_cols = nch == (int64_t)CPT * kBlock;
     TE acc[NE];
 #pragma unroll
     for (int e = 0; e < NE; ++e) acc[e] = 0;
     double fsq = 0.0;
 
-    Tile<TE, CPT, RB> ta, tb;
-    tile_load<TE, CPT, RB>(ta, X, cols, r0, r1, nch);
-    for (int64_t rb = r0; rb < r1; rb += 2 * RB) {
-        if (rb + RB < r1) tile_load<TE, CPT, RB>(tb, X, cols, rb + RB, r1, nch);
-        tile_process<TE, CPT, RB, UPD, NORM>(ta, X, cols, rb, r1, nch, sumb, updb, rowbits, ck, acc, fsq, u, sh_u, 0);
-        if (rb + RB < r1) {
-            if (rb + 2 * RB < r1) tile_load<TE, CPT, RB>(ta, X, cols, rb + 2 * RB, r1, nch);
-            tile_process<TE, CPT, RB, UPD, NORM>(tb, X, cols, rb + RB, r1, nch, sumb, updb, rowbits, ck, acc, fsq, u,
-                                                 sh_u, 1);
-        }
+    // Two register tiles alternate: while one batch is reduced, the loads of the next one are in
+    // flight.  Inside the loop every load is unconditional (see tile_load).
+    Tile<TE, CPT, RB> tb;
+    const int64_t nb = (r1 - r0 + RB - 1) / RB;
+    int64_t b = 0;
+    for (; b + 1 < nb; b += 2) {
+        const int64_t rb = r0 + b * RB;
+        tile_load<TE, CPT, RB>(tb, X, cols, rb + RB, r1, nch, rowbits, rows, true);
+        tile_step<TE, CPT, RB, UPD>(ta, X, cols, rb, r1, nch, full_cols, sumb, updb, ck, acc, fsq, u, sh_u, 0);
+        tile_load<TE, CPT, RB>(ta, X, cols, rb + 2 * RB, r1, nch, rowbits, rows, b + 2 < nb);
+        tile_step<TE, CPT, RB, UPD>(tb, X, cols, rb + RB, r1, nch, full_cols, sumb, updb, ck, acc, fsq, u, sh_u, 1);
     }
+    if (b < nb)
+        tile_step<TE, CPT, RB, UPD>(ta, X, cols, r0 + b * RB, r1, nch, full_cols, sumb, updb, ck, acc, fsq, u, sh_u, 0);
     V* pp = (V*)(partials + (int64_t)blockIdx.x * cols);
 #pragma unroll
     for (int c = 0; c < CPT; ++c) {
@@ -448,7 +529,7 @@ __device__ __forceinline__ void rowpass_tiled_body(TE* __restrict__ X, int64_t r
             pp[ch] = v;
         }
     }
-    if constexpr (NORM) {
+    if constexpr (UPD) {
         fsq = wave_sum(fsq);
         if ((threadIdx.x & (kWave - 1)) == 0) sh_f[threadIdx.x / kWave] = fsq;
         __syncthreads();
@@ -463,59 +544,104 @@ __device__ __forceinline__ void rowpass_tiled_body(TE* __restrict__ X, int64_t r
 template <typename TE, int CPT, int RB>
 __global__ void __launch_bounds__(kBlock) rowpass_tiled_kernel(RowPassArgs a)
 {
+    constexpr int VE = Vec16<TE>::N;
+    const int64_t r0 = (int64_t)blockIdx.x * a.rows_per_wg;
+    const int64_t r1 = (r0 + a.rows_per_wg < a.rows) ? r0 + a.rows_per_wg : a.rows;
+    const int64_t nch = a.cols / VE;
+    // Nothing read here depends on what this pass turns out to be: start the loads of the first
+    // rows, of both sign vectors, of the state and of the partial sums of c together, so that
+    // their latencies overlap instead of adding up.
+    Tile<TE, CPT, RB> ta;
+    tile_load<TE, CPT, RB>(ta, (const TE*)a.X, a.cols, r0, r1, nch, a.row_bits, a.rows, true);
+    const StateView st = view_state(a.level == 0 ? a.cur : a.next);
+    double cp = 0.0;
+    if (a.level == 0)
+        for (int i = threadIdx.x & (kWave - 1); i < a.ncparts; i += kWave) cp += a.cparts[i];
+    const uint64_t bcur = gather_bits<TE, CPT>(a.sign_cur, nch);
+    const uint64_t brng = gather_bits<TE, CPT>(a.sign_rng, nch);
     if (a.level == 0) {
-        const State st = *a.cur;
         Decision d;
-        if (!decide_level0(a, st, d)) {
+        if (!decide_level0(a, st, wave_sum(cp), d)) {
             if (blockIdx.x == 0 && threadIdx.x == 0) a.next->active = 0;
             return;
         }
-        level0_bookkeeping<TE>(a, st, d);
-        if (d.mode == PASS_UPDATE) {
-            rowpass_tiled_body<TE, CPT, RB, true, true>((TE*)a.X, a.rows, a.cols, a.rows_per_wg, a.sign_rng, a.sign_cur,
-                                                        a.row_bits, (TE)d.ck, (TE*)a.partials, a.u, a.fparts);
-        } else if (d.mode == PASS_START) {
-            rowpass_tiled_body<TE, CPT, RB, false, true>((TE*)a.X, a.rows, a.cols, a.rows_per_wg,
-                                                         st.t0_given ? a.sign_cur : a.sign_rng, a.sign_cur, a.row_bits,
-                                                         (TE)0, (TE*)a.partials, a.u, a.fparts);
+        if (d.mode == PASS_CONT) {
+            rowpass_tiled_body<TE, CPT, RB, false>(ta, (TE*)a.X, a.rows, a.cols, r0, r1, bcur, 0ull, a.row_bits, (TE)0,
+                                                   (TE*)a.partials, a.u, a.fparts);
         } else {
-            rowpass_tiled_body<TE, CPT, RB, false, false>((TE*)a.X, a.rows, a.cols, a.rows_per_wg, a.sign_cur,
-                                                          a.sign_cur, a.row_bits, (TE)0, (TE*)a.partials, a.u,
-                                                          a.fparts);
+            // a start pass is an update by zero: the remainder is rewritten unchanged and its squares summed
+            const bool upd = d.mode == PASS_UPDATE;
+            const uint64_t sumb = (upd || !st.t0_given) ? brng : bcur;
+            rowpass_tiled_body<TE, CPT, RB, true>(ta, (TE*)a.X, a.rows, a.cols, r0, r1, sumb, bcur, a.row_bits,
+                                                  upd ? (TE)d.ck : (TE)0, (TE*)a.partials, a.u, a.fparts);
         }
+        level0_bookkeeping<TE>(a, st, d);
     } else {
-        const State st = *a.next;
         if (!st.active) return;
-        rowpass_tiled_body<TE, CPT, RB, false, false>((TE*)a.X, a.rows, a.cols, a.rows_per_wg,
-                                                      st.sweep_rng ? a.sign_rng : a.sign_cur, a.sign_cur, a.row_bits,
-                                                      (TE)0, (TE*)a.partials, a.u, a.fparts);
+        rowpass_tiled_body<TE, CPT, RB, false>(ta, (TE*)a.X, a.rows, a.cols, r0, r1, st.sweep_rng ? brng : bcur, 0ull,
+                                               a.row_bits, (TE)0, (TE*)a.partials, a.u, a.fparts);
     }
 }
 
 // ------------------------------------------------------------------------------------------------
-// reduce: W[l] = sum over the partial rows, in f64 and in a fixed order.  One block per 64 columns.
+// reduce: W[l] = sum over the partial rows, in f64 and in a fixed order.  One block of 16 waves per
+// 64 columns; wave q adds the partial rows q, q+16, ... (16 independent loads in flight at a time),
+// then wave 0 adds the 16 wave sums in order.
+
+constexpr int kRedWaves = 16;
+constexpr int kRedBlock = kRedWaves * kWave;
 
 template <typename TA>
-__global__ void __launch_bounds__(kBlock) reduce_kernel(ReduceArgs a)
+__device__ __forceinline__ double column_sum(const TA* __restrict__ P, int nparts, int64_t cols, int64_t col,
+                                             double (*sh)[kWave])
 {
-    __shared__ double sh[kWavesPerBlock][kWave];
-    const State st = *a.next;
-    if (!st.active) return;
     const int lane = threadIdx.x & (kWave - 1);
     const int wv = threadIdx.x / kWave;
-    const int64_t col = (int64_t)blockIdx.x * kWave + lane;
-    const TA* P = (const TA*)a.partials;
-
     double s = 0.0;
-    if (col < a.cols) {
-        for (int p = wv; p < a.nparts; p += kWavesPerBlock) s += (double)P[(int64_t)p * a.cols + col];
+    if (col < cols) {
+        const TA* base = P + col;
+        int p = wv;
+        for (; p + 15 * kRedWaves < nparts; p += 16 * kRedWaves) {
+            TA tmp[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) tmp[i] = base[(int64_t)(p + i * kRedWaves) * cols];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) s += (double)tmp[i];
+        }
+        for (; p < nparts; p += kRedWaves) s += (double)base[(int64_t)p * cols];
     }
     sh[wv][lane] = s;
     __syncthreads();
+    double v = 0.0;
     if (wv == 0) {
-        double v = 0.0;
 #pragma unroll
-        for (int q = 0; q < kWavesPerBlock; ++q) v += sh[q][lane];
+        for (int q = 0; q < kRedWaves; ++q) v += sh[q][lane];
+    }
+    return v;
+}
+
+template <typename TA>
+__global__ void __launch_bounds__(kRedBlock) reduce_kernel(ReduceArgs a)
+{
+    __shared__ double sh[kRedWaves][kWave];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wv = threadIdx.x / kWave;
+    const int64_t col = (int64_t)blockIdx.x * kWave + lane;
+    const int64_t rwords = (a.rows + 63) / 64;
+    // Everything this block reads is independent of the state: start all loads, then look at it.
+    // (An inactive sweep reads valid, stale data and writes nothing.)
+    const State* sp = a.next;
+    const int32_t active = sp->active, norm_pending = sp->norm_pending;
+    const int64_t k = sp->k, w_target = sp->w_target;
+    const int64_t wd0 = (int64_t)blockIdx.x * kRedWaves + wv;
+    const int64_t i0 = wd0 * 64 + lane;
+    const double u0 = (wd0 < rwords && i0 < a.rows) ? a.u[i0] : 0.0;
+    double fp = 0.0;
+    if (a.final && blockIdx.x == 0 && wv == 1)
+        for (int i = lane; i < a.nfparts; i += kWave) fp += a.fparts[i];
+    const double v = column_sum<TA>((const TA*)a.partials, a.nparts, a.cols, col, sh);
+    if (!active) return;
+    if (wv == 0) {
         if (col < a.cols) a.W[col] = v;
         if (a.final) {
             // t = sgn(R^T s) packed from the ballot; c = sum |R^T s| (Algorithm 4 lines 6-7)
@@ -528,8 +654,11 @@ __global__ void __launch_bounds__(kBlock) reduce_kernel(ReduceArgs a)
         }
     }
     // s = sgn(u) for this level's mode, one word per wave-ballot
-    const int64_t rwords = (a.rows + 63) / 64;
-    for (int64_t wd = (int64_t)blockIdx.x * kWavesPerBlock + wv; wd < rwords; wd += (int64_t)gridDim.x * kWavesPerBlock) {
+    if (wd0 < rwords) {
+        const uint64_t word = __ballot(i0 < a.rows && u0 < 0.0);
+        if (lane == 0) a.row_bits[wd0] = word;
+    }
+    for (int64_t wd = wd0 + (int64_t)gridDim.x * kRedWaves; wd < rwords; wd += (int64_t)gridDim.x * kRedWaves) {
         const int64_t i = wd * 64 + lane;
         const uint64_t word = __ballot(i < a.rows && a.u[i] < 0.0);
         if (lane == 0) a.row_bits[wd] = word;
@@ -537,16 +666,19 @@ __global__ void __launch_bounds__(kBlock) reduce_kernel(ReduceArgs a)
     if (a.final) {
         // random start of the term after the current one, last mode (Algorithm 4 line 2)
         const int64_t cwords = (a.cols + 63) / 64;
-        for (int64_t wd = (int64_t)blockIdx.x * kBlock + threadIdx.x; wd < cwords; wd += (int64_t)gridDim.x * kBlock)
-            a.rng_last[wd] = rng_word_masked(a.seed, (uint64_t)st.k + 1, (uint32_t)a.last_mode, wd, a.cols);
-        if (blockIdx.x == 0 && wv == 0) {
-            double F = 0.0;
-            if (st.norm_pending) F = sum_fixed(a.fparts, a.nfparts);
-            if (lane == 0) {
-                if (st.norm_pending) a.trace[st.k] = sqrt(F);
-                State nx = st;
-                nx.done = (st.k >= st.w_target) ? 1 : 0;
-                *a.cur = nx;
+        for (int64_t wd = (int64_t)blockIdx.x * kRedBlock + threadIdx.x; wd < cwords; wd += (int64_t)gridDim.x * kRedBlock)
+            a.rng_last[wd] = rng_word_masked(a.seed, (uint64_t)k + 1, (uint32_t)a.last_mode, wd, a.cols);
+        if (blockIdx.x == 0 && wv == 1) {
+            const double F = wave_sum(fp);
+            if (lane == 0 && norm_pending) a.trace[k] = sqrt(F);
+            // cur <- next, word by word, with `done` set once the requested width is reached
+            constexpr int kWords = (int)(sizeof(State) / 4);
+            constexpr int kDoneWord = (int)(offsetof(State, done) / 4);
+            static_assert(sizeof(State) % 4 == 0 && kWords <= kWave, "state is copied by one wave");
+            if (lane < kWords) {
+                uint32_t wv32 = ((const uint32_t*)a.next)[lane];
+                if (lane == kDoneWord) wv32 = (k >= w_target) ? 1u : 0u;
+                ((uint32_t*)a.cur)[lane] = wv32;
             }
         }
     }
@@ -554,22 +686,15 @@ __global__ void __launch_bounds__(kBlock) reduce_kernel(ReduceArgs a)
 
 // Column half step on caller data: same reduction without any state.
 template <typename TA>
-__global__ void __launch_bounds__(kBlock)
+__global__ void __launch_bounds__(kRedBlock)
     reduce_plain_kernel(const TA* P, int nparts, int64_t cols, double* W, uint64_t* bits, double* cparts)
 {
-    __shared__ double sh[kWavesPerBlock][kWave];
+    __shared__ double sh[kRedWaves][kWave];
     const int lane = threadIdx.x & (kWave - 1);
     const int wv = threadIdx.x / kWave;
     const int64_t col = (int64_t)blockIdx.x * kWave + lane;
-    double s = 0.0;
-    if (col < cols)
-        for (int p = wv; p < nparts; p += kWavesPerBlock) s += (double)P[(int64_t)p * cols + col];
-    sh[wv][lane] = s;
-    __syncthreads();
+    const double v = column_sum<TA>(P, nparts, cols, col, sh);
     if (wv == 0) {
-        double v = 0.0;
-#pragma unroll
-        for (int q = 0; q < kWavesPerBlock; ++q) v += sh[q][lane];
         if (col < cols && W) W[col] = v;
         const uint64_t word = __ballot(col < cols && v < 0.0);
         const double cabs = wave_sum(col < cols ? fabs(v) : 0.0);
@@ -738,6 +863,55 @@ __global__ void __launch_bounds__(kBlock) rng_kernel(uint64_t seed, uint64_t ter
 }
 
 // ------------------------------------------------------------------------------------------------
+// plain streaming kernels: the measured ceiling the row pass is compared with, and the copy of
+// known size that calibrates the memory counters.
+
+__global__ void __launch_bounds__(kBlock) stream_read_kernel(const float4* __restrict__ x, int64_t n4, float* sink)
+{
+    float4 acc = {0.f, 0.f, 0.f, 0.f};
+    const int64_t stride = (int64_t)gridDim.x * kBlock;
+    int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    for (; i + 7 * stride < n4; i += 8 * stride) {
+        float4 v[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) v[q] = x[i + q * stride];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            acc.x += v[q].x;
+            acc.y += v[q].y;
+            acc.z += v[q].z;
+            acc.w += v[q].w;
+        }
+    }
+    for (; i < n4; i += stride) {
+        const float4 v = x[i];
+        acc.x += v.x;
+        acc.y += v.y;
+        acc.z += v.z;
+        acc.w += v.w;
+    }
+    if (acc.x + acc.y + acc.z + acc.w == 1.2345e38f) *sink = acc.x;  // keeps the loads alive
+}
+
+__global__ void __launch_bounds__(kBlock) stream_copy_kernel(const float4* __restrict__ x, float4* __restrict__ y, int64_t n4)
+{
+    const int64_t stride = (int64_t)gridDim.x * kBlock;
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n4; i += stride) y[i] = x[i];
+}
+
+hipError_t launch_stream_read(const void* x, int64_t bytes, int grid, float* sink, hipStream_t st)
+{
+    hipLaunchKernelGGL(stream_read_kernel, dim3(grid), dim3(kBlock), 0, st, (const float4*)x, bytes / 16, sink);
+    return hipGetLastError();
+}
+
+hipError_t launch_stream_copy(const void* x, void* y, int64_t bytes, int grid, hipStream_t st)
+{
+    hipLaunchKernelGGL(stream_copy_kernel, dim3(grid), dim3(kBlock), 0, st, (const float4*)x, (float4*)y, bytes / 16);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
 // launchers
 
 static int grid_for(int64_t items, int per_block, int cap)
@@ -813,8 +987,8 @@ hipError_t launch_rowpass(const RowPassArgs& a, scd_dtype dt, int grid, int vari
 hipError_t launch_reduce(const ReduceArgs& a, bool f32_partials, hipStream_t st)
 {
     const int grid = (int)((a.cols + kWave - 1) / kWave);
-    if (f32_partials) hipLaunchKernelGGL((reduce_kernel<float>), dim3(grid), dim3(kBlock), 0, st, a);
-    else hipLaunchKernelGGL((reduce_kernel<double>), dim3(grid), dim3(kBlock), 0, st, a);
+    if (f32_partials) hipLaunchKernelGGL((reduce_kernel<float>), dim3(grid), dim3(kRedBlock), 0, st, a);
+    else hipLaunchKernelGGL((reduce_kernel<double>), dim3(grid), dim3(kRedBlock), 0, st, a);
     return hipGetLastError();
 }
 
@@ -896,9 +1070,9 @@ hipError_t launch_reduce_plain(const void* partials, scd_dtype dt, int nparts, i
 {
     const int grid = (int)((cols + kWave - 1) / kWave);
     if (dt == SCD_F32)
-        hipLaunchKernelGGL((reduce_plain_kernel<float>), dim3(grid), dim3(kBlock), 0, st, (const float*)partials, nparts, cols, W, bits, cparts);
+        hipLaunchKernelGGL((reduce_plain_kernel<float>), dim3(grid), dim3(kRedBlock), 0, st, (const float*)partials, nparts, cols, W, bits, cparts);
     else
-        hipLaunchKernelGGL((reduce_plain_kernel<double>), dim3(grid), dim3(kBlock), 0, st, (const double*)partials, nparts, cols, W, bits, cparts);
+        hipLaunchKernelGGL((reduce_plain_kernel<double>), dim3(grid), dim3(kRedBlock), 0, st, (const double*)partials, nparts, cols, W, bits, cparts);
     return hipGetLastError();
 }
 

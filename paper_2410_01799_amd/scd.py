@@ -24,6 +24,7 @@ EXPORTS = [
     "scd_decompose", "scd_create", "scd_destroy", "scd_set_max_iters", "scd_step", "scd_run", "scd_step_from",
     "scd_width", "scd_results", "scd_remainder", "scd_set_remainder", "scd_row_signed_sum", "scd_col_signed_sum",
     "scd_expand", "scd_pack", "scd_unpack", "scd_rng_signs", "scd_strerror", "scd_last_hip_error", "scd_traffic",
+    "scd_probe_stream", "scd_profile_sweeps",
 ]
 
 
@@ -69,6 +70,8 @@ def lib() -> C.CDLL:
         L.scd_strerror.restype = C.c_char_p
         L.scd_last_hip_error.argtypes = []
         L.scd_traffic.argtypes = [vp, C.POINTER(C.c_double), pi64, pi64]
+        L.scd_profile_sweeps.argtypes = [vp, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+        L.scd_probe_stream.argtypes = [vp, vp, i64, C.c_int, C.c_int, vp, C.POINTER(C.c_double)]
         _lib = L
     return _lib
 
@@ -199,6 +202,16 @@ def scd_col_signed_sum(R: torch.Tensor, sbits: torch.Tensor):
     return v, t, c
 
 
+def scd_probe_stream(src: torch.Tensor, dst: Optional[torch.Tensor] = None, grid: int = 2048, reps: int = 20) -> float:
+    """Seconds per launch of the plain streaming read (dst None) or copy kernel over src's bytes."""
+    src = _dev(src, "src")
+    nbytes = src.numel() * src.element_size()
+    sec = C.c_double()
+    st = lib().scd_probe_stream(_ptr(src), _ptr(dst), nbytes, int(grid), int(reps), _stream(), C.byref(sec))
+    _check(st, "scd_probe_stream")
+    return sec.value
+
+
 # --------------------------------------------------------------------------- stateful context
 
 
@@ -271,6 +284,12 @@ class ScdContext:
         if tuple(R.shape) != self.shape or R.dtype != self.dtype:
             raise ValueError("remainder must have the shape and dtype of the input")
         _check(lib().scd_set_remainder(self._h, _ptr(R)), "scd_set_remainder")
+
+    def profile_sweeps(self, n: int):
+        """Average seconds of the row-pass launch and of the reduce launch over n further sweeps."""
+        a, b = C.c_double(), C.c_double()
+        _check(lib().scd_profile_sweeps(self._h, int(n), C.byref(a), C.byref(b)), "scd_profile_sweeps")
+        return a.value, b.value
 
     def traffic(self):
         b = C.c_double()
