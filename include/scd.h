@@ -52,7 +52,9 @@ typedef enum {
     SCD_EHIP = -3,       /* a HIP call failed; scd_last_hip_error() gives its code */
     SCD_EFULL = -4,      /* the context already holds w_capacity terms */
     SCD_ENONFINITE = -5, /* the input (or a remainder given to the context) holds NaN or Inf */
-    SCD_ENODEVICE = -6   /* no usable HIP device */
+    SCD_ENODEVICE = -6,  /* no usable HIP device */
+    SCD_ETIMEOUT = -7    /* a bounded device-side wait ran out (workgroups of a persistent launch were not all
+                            resident); the context refuses further steps until scd_set_remainder */
 } scd_status;
 
 #define SCD_MAX_ORDER 8
@@ -142,6 +144,13 @@ int scd_profile_sweeps(scd_ctx* ctx, int n, double* rowpass_seconds, double* red
  * copy of known size calibrates the memory counters of the profiler. */
 int scd_probe_stream(const void* src, void* dst, int64_t bytes, int grid, int reps, void* stream,
                      double* seconds);
+
+/* Latency of exchanging data between the workgroups of one persistent launch, for measurement only.
+ * which = 0: every workgroup publishes 256 tagged values per round and reads those of its `group`
+ * neighbours (the exchange the register-resident engine uses); which = 1: a counter barrier over the
+ * whole grid.  grid workgroups (a multiple of group, at most 1024) must all be resident at once, which
+ * the cooperative launch checks.  *seconds_per_round: host. */
+int scd_probe_exchange(int which, int grid, int group, int rounds, void* stream, double* seconds_per_round);
 
 #ifdef __cplusplus
 }

@@ -82,6 +82,15 @@ struct scd_ctx {
     KronArgs kron;
     int variant = 1;
     int batch = 64;
+    // register-resident engine
+    bool resident = false;          // shape and dtype fit, and not switched off
+    bool stream_stale = false;      // the launch-stream state lags behind the engine's progress
+    bool broken = false;            // an engine wait ran out: the remainder is no longer trustworthy
+    uint64_t* xbuf = nullptr;
+    ResidentResult* res_dev = nullptr;
+    ResidentResult* res_pin = nullptr;
+    uint32_t seq_u = 0, seq_v = 0;
+    int max_spin = 1 << 22;
     std::vector<void*> allocs;
 };
 
@@ -253,6 +262,67 @@ int check_dims(int order, const int64_t* dims, int64_t* total)
 
 bool dtype_ok(int dt) { return dt == SCD_F32 || dt == SCD_F64; }
 
+// Bring the launch-stream state (first alternation of term k done, ||R_k|| known) up to date after the
+// resident engine advanced the context.
+int resync_stream_state(scd_ctx* c)
+{
+    if (!c->stream_stale) return SCD_OK;
+    c->hs.w_target = c->hs.k;
+    c->hs.done = 0;
+    c->hs.j = 0;
+    c->hs.t0_given = 0;
+    c->hs.c_prev = -INFINITY;
+    SCD_TRY(write_state(c));
+    SCD_TRY(seed_current_term(c, 0, true));
+    SCD_TRY(launch_sweep(c));
+    SCD_TRY(read_state(c));
+    c->stream_stale = false;
+    return SCD_OK;
+}
+
+// n terms in one persistent launch with the remainder held in registers.
+int run_resident(scd_ctx* c, int64_t n)
+{
+    ResidentArgs a;
+    memset(&a, 0, sizeof(a));
+    a.R = (float*)c->R;
+    a.m = c->dims[0];
+    a.n = c->dims[1];
+    a.seed = c->seed;
+    a.k_start = c->hs.k;
+    a.w_target = c->hs.k + n;
+    a.max_iters = c->hs.max_iters;
+    a.max_spin = c->max_spin;
+    a.seq_u = c->seq_u;
+    a.seq_v = c->seq_v;
+    a.xbuf = c->xbuf;
+    a.S = c->out_signs[0];
+    a.T = c->out_signs[1];
+    a.c = (float*)c->c_out;
+    a.iters = c->iters;
+    a.trace = c->trace;
+    a.mw = (int32_t)words_for(c->dims[0]);
+    a.nw = (int32_t)words_for(c->dims[1]);
+    a.res = c->res_dev;
+    HIP_TRY(hipMemsetAsync(c->res_dev, 0, sizeof(ResidentResult), c->stream));
+    HIP_TRY(launch_resident(a, c->stream));
+    HIP_TRY(hipMemcpyAsync(c->res_pin, c->res_dev, sizeof(ResidentResult), hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(hipStreamSynchronize(c->stream));
+    const ResidentResult r = *c->res_pin;
+    if (r.err || r.k != a.w_target) {
+        c->broken = true;
+        return SCD_ETIMEOUT;
+    }
+    c->seq_u = r.seq_u;
+    c->seq_v = r.seq_v;
+    c->hs.k = r.k;
+    c->hs.passes += r.alternations;
+    c->hs.updates += r.updates;
+    if (r.warn) c->hs.warn = 1;
+    c->stream_stale = true;
+    return SCD_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -353,6 +423,15 @@ int scd_create(scd_ctx** out, const void* A, scd_dtype dt, int order, const int6
             CTRY(dev_alloc(c, (void**)&L.kron_rng, (size_t)words_for(L.cols) * 8));
         }
     }
+    c->resident = env_int("SCD_RESIDENT", 1) != 0 && resident_supported(dt, order, dims);
+    if (c->resident) {
+        const size_t xb = (size_t)4 * kResGrid * kResGrid * kResSlotWords * 8;
+        CTRY(dev_alloc(c, (void**)&c->xbuf, xb));
+        CHIP(hipMemsetAsync(c->xbuf, 0, xb, c->stream));
+        CTRY(dev_alloc(c, (void**)&c->res_dev, sizeof(ResidentResult)));
+        CHIP(hipHostMalloc((void**)&c->res_pin, sizeof(ResidentResult), hipHostMallocDefault));
+        c->max_spin = env_int("SCD_RESIDENT_MAX_SPIN", 1 << 22);
+    }
     c->ncparts = (int)words_for(dims[order - 1]);
     CTRY(dev_alloc(c, (void**)&c->cparts, (size_t)c->ncparts * 8));
     CHIP(hipMemsetAsync(c->cparts, 0, (size_t)c->ncparts * 8, c->stream));
@@ -383,6 +462,7 @@ void scd_destroy(scd_ctx* c)
     (void)hipStreamSynchronize(c->stream);
     for (void* p : c->allocs) (void)hipFree(p);
     if (c->pinned) (void)hipHostFree(c->pinned);
+    if (c->res_pin) (void)hipHostFree(c->res_pin);
     (void)hipGetLastError();
     delete c;
 }
@@ -397,8 +477,13 @@ int scd_set_max_iters(scd_ctx* c, int32_t max_iters)
 int scd_run(scd_ctx* c, int64_t n)
 {
     if (!c || n < 0) return SCD_EINVAL;
+    if (c->broken) return SCD_ETIMEOUT;
     if (n == 0) return c->hs.warn ? SCD_WMAXITER : SCD_OK;
     if (c->hs.k + n > c->w_capacity) return SCD_EFULL;
+    if (c->resident) {
+        SCD_TRY(run_resident(c, n));
+        return c->hs.warn ? SCD_WMAXITER : SCD_OK;
+    }
     c->hs.w_target = c->hs.k + n;
     c->hs.done = 0;
     SCD_TRY(write_state(c));
@@ -415,7 +500,9 @@ int scd_step_from(scd_ctx* c, const uint64_t* const* init_signs)
     if (!c || !init_signs) return SCD_EINVAL;
     for (int i = 1; i < c->order; ++i)
         if (!init_signs[i]) return SCD_EINVAL;
+    if (c->broken) return SCD_ETIMEOUT;
     if (c->hs.k + 1 > c->w_capacity) return SCD_EFULL;
+    SCD_TRY(resync_stream_state(c));
     for (int i = 1; i < c->order; ++i)
         HIP_TRY(hipMemcpyAsync(c->s_bits[i], init_signs[i], (size_t)words_for(c->dims[i]) * 8, hipMemcpyDeviceToDevice,
                                c->stream));
@@ -459,6 +546,7 @@ int scd_results(const scd_ctx* c, uint64_t* const* signs, void* cvec, double* fr
 int scd_remainder(const scd_ctx* c, void* R_out)
 {
     if (!c || !R_out) return SCD_EINVAL;
+    if (c->broken) return SCD_ETIMEOUT;
     HIP_TRY(hipMemcpyAsync(R_out, c->R, (size_t)c->total * c->esize, hipMemcpyDeviceToDevice, c->stream));
     HIP_TRY(hipStreamSynchronize(c->stream));
     return SCD_OK;
@@ -467,6 +555,8 @@ int scd_remainder(const scd_ctx* c, void* R_out)
 int scd_set_remainder(scd_ctx* c, const void* R_in)
 {
     if (!c || !R_in) return SCD_EINVAL;
+    c->stream_stale = false;  // the start pass below rebuilds the launch-stream state
+    c->broken = false;
     HIP_TRY(hipMemcpyAsync(c->R, R_in, (size_t)c->total * c->esize, hipMemcpyDeviceToDevice, c->stream));
     c->hs.w_target = c->hs.k;
     c->hs.done = 0;
@@ -496,7 +586,9 @@ int scd_traffic(const scd_ctx* c, double* bytes, int64_t* passes, int64_t* sweep
 int scd_profile_sweeps(scd_ctx* c, int n, double* rowpass_seconds, double* reduce_seconds)
 {
     if (!c || n < 1 || n > 4096 || !rowpass_seconds || !reduce_seconds) return SCD_EINVAL;
+    if (c->broken) return SCD_ETIMEOUT;
     if (c->hs.k >= c->w_capacity) return SCD_EFULL;
+    SCD_TRY(resync_stream_state(c));
     // keep the device loop running for the whole sample: aim at the capacity, restore nothing (the
     // terms found while sampling are ordinary terms)
     c->hs.w_target = c->w_capacity;
@@ -740,6 +832,50 @@ int scd_probe_stream(const void* src, void* dst, int64_t bytes, int grid, int re
     return rc;
 }
 
+int scd_probe_exchange(int which, int grid, int group, int rounds, void* stream, double* seconds_per_round)
+{
+    if (which < 0 || which > 1 || grid < 1 || grid > 1024 || group < 1 || grid % group || rounds < 1 ||
+        !seconds_per_round)
+        return SCD_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    uint64_t* buf = nullptr;
+    unsigned* flags = nullptr;  // [0] counter, [1] error
+    float* out = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    const size_t bufbytes = (size_t)2 * grid * 256 * 8;
+    hipError_t e = hipMalloc((void**)&buf, bufbytes);
+    if (e == hipSuccess) e = hipMalloc((void**)&flags, 8);
+    if (e == hipSuccess) e = hipMalloc((void**)&out, (size_t)grid * 4);
+    if (e == hipSuccess) e = hipMemsetAsync(buf, 0, bufbytes, st);
+    if (e == hipSuccess) e = hipMemsetAsync(flags, 0, 8, st);
+    if (e == hipSuccess) e = hipEventCreate(&e0);
+    if (e == hipSuccess) e = hipEventCreate(&e1);
+    if (e == hipSuccess) e = hipEventRecord(e0, st);
+    if (e == hipSuccess) e = launch_exchange_probe(which, grid, buf, flags, rounds, group, 1 << 20, flags + 1, out, st);
+    if (e == hipSuccess) e = hipEventRecord(e1, st);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    float ms = 0.f;
+    unsigned err[2] = {0, 0};
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    if (e == hipSuccess) e = hipMemcpy(err, flags, 8, hipMemcpyDeviceToHost);
+    int rc = SCD_OK;
+    if (e != hipSuccess) {
+        g_last_hip = (int)e;
+        (void)hipGetLastError();
+        rc = SCD_EHIP;
+    } else if (err[1]) {
+        rc = SCD_EINVAL;  // a bounded wait ran out: the workgroups were not all resident
+    } else {
+        *seconds_per_round = (double)ms * 1e-3 / rounds;
+    }
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    if (buf) (void)hipFree(buf);
+    if (flags) (void)hipFree(flags);
+    if (out) (void)hipFree(out);
+    return rc;
+}
+
 const char* scd_strerror(int code)
 {
     switch (code) {
@@ -751,6 +887,7 @@ const char* scd_strerror(int code)
         case SCD_EFULL: return "context is at its width capacity";
         case SCD_ENONFINITE: return "input holds NaN or Inf";
         case SCD_ENODEVICE: return "no HIP device";
+        case SCD_ETIMEOUT: return "a bounded device-side wait ran out; give the context a remainder again or destroy it";
         default: return "unknown status";
     }
 }

@@ -101,6 +101,41 @@ struct KronArgs {
     const State* next;
 };
 
+// Register-resident engine (scd_resident.hip): the whole remainder lives in the register files of a
+// 16 x 16 grid of co-resident workgroups for as many terms as requested.
+constexpr int kResGrid = 16;                       // workgroups per side
+constexpr int kResThreads = 512;
+constexpr int kResSlotWords = 512 + 8;             // exchange slot: up to 512 values + piggybacked scalars
+
+struct ResidentResult {
+    int64_t k;             // terms complete on exit
+    int64_t alternations;  // row phases executed
+    int64_t updates;
+    uint32_t seq_u, seq_v; // last exchange sequence numbers used
+    int32_t err;           // 1: a bounded wait ran out
+    int32_t warn;          // a term ended on max_iters
+};
+
+struct ResidentArgs {
+    float* R;
+    int64_t m, n;
+    uint64_t seed;
+    int64_t k_start, w_target;
+    int32_t max_iters, max_spin;
+    uint32_t seq_u, seq_v;   // sequence numbers already used by earlier launches
+    uint64_t* xbuf;          // [2 kinds][2 parities][256 workgroups][kResSlotWords]
+    uint64_t* S;
+    uint64_t* T;
+    float* c;
+    int32_t* iters;
+    double* trace;
+    int32_t mw, nw;
+    ResidentResult* res;
+};
+
+bool resident_supported(scd_dtype dt, int order, const int64_t* dims);
+hipError_t launch_resident(const ResidentArgs& a, hipStream_t st);
+
 // ---- launchers implemented in scd_kernels.hip ----------------------------------------------------
 hipError_t launch_rowpass(const RowPassArgs& a, scd_dtype dt, int grid, int variant, hipStream_t st);
 hipError_t launch_reduce(const ReduceArgs& a, bool f32_partials, hipStream_t st);
@@ -119,6 +154,8 @@ hipError_t launch_reduce_plain(const void* partials, scd_dtype dt, int nparts, i
 hipError_t launch_sum_parts(const double* parts, int n, double* out, hipStream_t st);
 hipError_t launch_stream_read(const void* x, int64_t bytes, int grid, float* sink, hipStream_t st);
 hipError_t launch_stream_copy(const void* x, void* y, int64_t bytes, int grid, hipStream_t st);
+hipError_t launch_exchange_probe(int which, int grid, uint64_t* buf, unsigned* counter, int rounds, int group,
+                                 int max_spin, unsigned* err, float* out, hipStream_t st);
 bool fast_rowpass_supported(scd_dtype dt, int64_t cols, int level);
 
 }  // namespace scd

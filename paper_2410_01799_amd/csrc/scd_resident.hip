@@ -1,0 +1,524 @@
+// Probes of workgroup-to-workgroup exchange latency inside one persistent launch (measurement only).
+#include "scd_device.h"
+
+namespace scd {
+
+__device__ __forceinline__ uint64_t tagged(float v, uint32_t tag)
+{
+    return ((uint64_t)tag << 32) | (uint64_t)__float_as_uint(v);
+}
+
+// Every workgroup publishes 256 tagged values per round and reads those of the `group` workgroups
+// it shares a group with; value and tag travel in one 8-byte store, so the data is its own flag.
+__global__ void __launch_bounds__(256) exchange_probe_kernel(uint64_t* buf, int rounds, int group, int max_spin,
+                                                            unsigned* err, float* out)
+{
+    const int g = blockIdx.x, tid = threadIdx.x;
+    const int g0 = (g / group) * group;
+    float carry = 0.f;
+    for (int r = 1; r <= rounds; ++r) {
+        uint64_t* mine = buf + ((size_t)(r & 1) * gridDim.x + g) * 256;
+        __hip_atomic_store(mine + tid, tagged(carry + (float)tid, (uint32_t)r), __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+        float s = 0.f;
+        for (int q0 = 0; q0 < group; q0 += 16) {
+            // all loads of a batch of 16 members are in flight together; stale ones are retried
+            uint64_t w[16];
+            const int nq = group - q0 < 16 ? group - q0 : 16;
+            unsigned pending = (nq == 16) ? 0xFFFFu : ((1u << nq) - 1u);
+            int spin = 0;
+            while (pending) {
+#pragma unroll
+                for (int q = 0; q < 16; ++q) {
+                    const uint64_t* theirs = buf + ((size_t)(r & 1) * gridDim.x + g0 + q0 + (q < nq ? q : 0)) * 256;
+                    if ((pending >> q) & 1u)
+                        w[q] = __hip_atomic_load(theirs + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+#pragma unroll
+                for (int q = 0; q < 16; ++q)
+                    if (((pending >> q) & 1u) && (uint32_t)(w[q] >> 32) == (uint32_t)r) pending &= ~(1u << q);
+                if (pending && ++spin > max_spin) {
+                    atomicExch(err, 1u);
+                    return;
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < 16; ++q)
+                if (q < nq) s += __uint_as_float((uint32_t)w[q]);
+        }
+        carry = s * 1e-3f;
+    }
+    if (tid == 0) out[g] = carry;
+}
+
+// Classic counter barrier over the whole grid, for comparison.
+__global__ void __launch_bounds__(256) barrier_probe_kernel(unsigned* counter, int rounds, int max_spin, unsigned* err,
+                                                           float* out)
+{
+    unsigned target = 0;
+    for (int r = 1; r <= rounds; ++r) {
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            __threadfence();
+            __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            target += gridDim.x;
+            int spin = 0;
+            while (__hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+                if (++spin > max_spin) {
+                    atomicExch(err, 1u);
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(1);
+            }
+            __threadfence();
+        }
+        __syncthreads();
+        if (*(volatile unsigned*)err) return;
+    }
+    if (threadIdx.x == 0) out[blockIdx.x] = (float)target;
+}
+
+hipError_t launch_exchange_probe(int which, int grid, uint64_t* buf, unsigned* counter, int rounds, int group,
+                                 int max_spin, unsigned* err, float* out, hipStream_t st)
+{
+    if (which == 0) {
+        void* args[] = {&buf, &rounds, &group, &max_spin, &err, &out};
+        return hipLaunchCooperativeKernel((const void*)exchange_probe_kernel, dim3(grid), dim3(256), args, 0, st);
+    }
+    void* args[] = {&counter, &rounds, &max_spin, &err, &out};
+    return hipLaunchCooperativeKernel((const void*)barrier_probe_kernel, dim3(grid), dim3(256), args, 0, st);
+}
+
+// ---- helpers of the engine (kept local to this file: the two translation units share no device code)
+
+__device__ __forceinline__ uint64_t mix64_res(uint64_t z)
+{
+    // SplitMix64 finaliser
+    z ^= z >> 30;
+    z *= 0xBF58476D1CE4E5B9ull;
+    z ^= z >> 27;
+    z *= 0x94D049BB133111EBull;
+    z ^= z >> 31;
+    return z;
+}
+
+__device__ __forceinline__ uint64_t rng_word_res(uint64_t seed, uint64_t term, uint32_t mode, uint64_t word)
+{
+    uint64_t h = mix64_res(seed ^ (0x9E3779B97F4A7C15ull * (term + 1)));
+    h = mix64_res(h + 0xD1B54A32D192ED03ull * ((uint64_t)mode + 1));
+    h = mix64_res(h + 0x8CB92BA72F3D8DD7ull * (word + 1));
+    return h;
+}
+
+__device__ __forceinline__ double wave_sum_res(double a)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) a += __shfl_xor(a, off, kWave);
+    return a;
+}
+
+
+// =================================================================================================
+// Register-resident engine.
+//
+// A 4096 x 4096 f32 remainder is 64 MiB; the 256 compute units of the chip hold 128 MiB of vector
+// registers.  Workgroup (pr, pc) of a 16 x 16 grid keeps block (pr, pc) of R in its registers for the
+// whole run, so an alternation of Algorithm 4 moves no matrix data at all: only 256 partial sums per
+// workgroup and phase travel through memory.
+//
+//   row phase   p_i = sum over the block's columns of +-R_il (signs t), published to the 16
+//               workgroups of the same block row; each adds the 16 partials in order -> u_i, s_i
+//   col phase   q_l = sum over the block's rows of +-R_il (signs s), published to the 16 workgroups
+//               of the same block column -> v_l, t_l, and this column block's share of c = sum |v_l|
+//
+// Exchange: value and sequence number travel in one 8-byte store (the datum is its own flag), read
+// back with loads that bypass the non-coherent caches; no counter, no fence.  Slots alternate by the
+// parity of the sequence number: a workgroup can only be one exchange ahead of the readers of its
+// slot, because finishing exchange e+1 needs data its readers publish after they have read e.
+// The sum of the 16 column-block shares of c rides on the next row-phase exchange, so the test of
+// Algorithm 4 line 8 is taken one phase late: the row phase already done with the final t is then
+// dropped.  ||R||_F^2 after an update travels the same way (block row sums, then the total).
+// Every wait is bounded; on expiry all workgroups leave and the host reports an error.
+
+__device__ __forceinline__ uint64_t* res_slot(const ResidentArgs& a, int kind, uint32_t seq, int wg)
+{
+    return a.xbuf + ((size_t)((kind * 2 + (int)(seq & 1u)) * (kResGrid * kResGrid) + wg)) * kResSlotWords;
+}
+
+__device__ __forceinline__ void res_publish(uint64_t* p, float v, uint32_t seq)
+{
+    __hip_atomic_store(p, ((uint64_t)seq << 32) | (uint64_t)__float_as_uint(v), __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ __forceinline__ void res_publish_f64(uint64_t* p, double v, uint32_t seq)
+{
+    const uint64_t b = (uint64_t)__double_as_longlong(v);
+    __hip_atomic_store(p, ((uint64_t)seq << 32) | (b & 0xFFFFFFFFull), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(p + 1, ((uint64_t)seq << 32) | (b >> 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Eight members' values of one element, all loads in flight together; stale ones are read again.
+__device__ __forceinline__ bool res_gather8(const uint64_t* base, size_t stride, uint32_t seq, int max_spin,
+                                            double& sum)
+{
+    uint64_t w[8];
+    unsigned pending = 0xFFu;
+    int spin = 0;
+    while (pending) {
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+            if ((pending >> q) & 1u) w[q] = __hip_atomic_load(base + q * stride, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+            if (((pending >> q) & 1u) && (uint32_t)(w[q] >> 32) == seq) pending &= ~(1u << q);
+        if (pending) {
+            if (++spin > max_spin) return false;
+            __builtin_amdgcn_s_sleep(1);
+        }
+    }
+    double s = 0.0;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) s += (double)__uint_as_float((uint32_t)w[q]);
+    sum = s;
+    return true;
+}
+
+__device__ __forceinline__ bool res_load_f64(const uint64_t* p, uint32_t seq, int max_spin, double& out)
+{
+    uint64_t lo = 0, hi = 0;
+    int spin = 0;
+    for (;;) {
+        lo = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        hi = __hip_atomic_load(p + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if ((uint32_t)(lo >> 32) == seq && (uint32_t)(hi >> 32) == seq) break;
+        if (++spin > max_spin) return false;
+        __builtin_amdgcn_s_sleep(1);
+    }
+    out = __longlong_as_double((long long)((hi << 32) | (lo & 0xFFFFFFFFull)));
+    return true;
+}
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+
+// the value of the neighbouring lane (lane ^ 1), for doubles
+__device__ __forceinline__ double dpp_swap1_f64(double v)
+{
+    const long long b = __double_as_longlong(v);
+    const int lo = __builtin_amdgcn_update_dpp(0, (int)(b & 0xFFFFFFFFll), 0xB1, 0xF, 0xF, true);
+    const int hi = __builtin_amdgcn_update_dpp(0, (int)(b >> 32), 0xB1, 0xF, 0xF, true);
+    return __longlong_as_double(((long long)hi << 32) | (long long)(unsigned)lo);
+}
+
+template <int TR, int TC>
+__global__ void __launch_bounds__(kResThreads) resident_kernel(ResidentArgs a)
+{
+    constexpr int P = kResGrid;
+    constexpr int BM = 32 * TR, BN = 16 * TC;  // block of this workgroup
+    static_assert(TR >= 2 && TR <= 16 && (TR % 2) == 0, "rows per thread");
+    static_assert(TC >= 4 && TC <= 32 && (TC % 4) == 0, "columns per thread");
+    static_assert(BM + 4 <= kResSlotWords && BN + 2 <= kResSlotWords, "slot size");
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int tr = tid >> 4, tc = tid & 15;  // 32 x 16 threads, each TR x TC elements
+    const int pr = blockIdx.x / P, pc = blockIdx.x % P;
+    const int wg = blockIdx.x;
+
+    __shared__ float lds_q[32][BN];
+    __shared__ uint8_t lds_s[2][BM];
+    __shared__ uint8_t lds_t[BN];
+    __shared__ double lds_red[kResThreads / 64];
+    __shared__ double lds_x[2][P];
+
+    // ---- load the block
+    float x[TR][TC];
+    {
+        const float* base = a.R + ((int64_t)pr * BM + tr * TR) * a.n + (int64_t)pc * BN + tc * TC;
+#pragma unroll
+        for (int r = 0; r < TR; ++r)
+#pragma unroll
+            for (int c4 = 0; c4 < TC / 4; ++c4) {
+                const float4 v = *(const float4*)(base + (int64_t)r * a.n + 4 * c4);
+                x[r][4 * c4 + 0] = v.x;
+                x[r][4 * c4 + 1] = v.y;
+                x[r][4 * c4 + 2] = v.z;
+                x[r][4 * c4 + 3] = v.w;
+            }
+    }
+
+    int64_t k = a.k_start;
+    int64_t alternations = 0, updates = 0;
+    uint32_t seq_u = a.seq_u, seq_v = a.seq_v;
+    int j = 0, warn = 0, cur = 0;
+    double c_prev = -INFINITY;
+    double cpart = 0.0;      // this column block's sum |v_l| of the last column phase
+    double fsq_block = 0.0;  // sum of squares of this block after the last update
+    double frow = 0.0;       // ... of this block row
+    int norm_stage = 0;      // 1: fsq_block to publish (row exchange); 2: frow to publish (col exchange)
+    int64_t norm_k = 0;
+    const double total = (double)a.m * (double)a.n;
+    bool need_t0 = true;
+
+    for (;;) {
+        if (k >= a.w_target && norm_stage == 0) break;
+        if (need_t0) {
+            // t_0 of term k from the keyed stream (Algorithm 4 line 2)
+            if (tid < BN) {
+                const int64_t col = (int64_t)pc * BN + tid;
+                lds_t[tid] = (uint8_t)((rng_word_res(a.seed, (uint64_t)k, 1u, (uint64_t)(col >> 6)) >> (col & 63)) & 1ull);
+            }
+            need_t0 = false;
+            __syncthreads();
+        }
+        // ================= row phase: u = R t (Algorithm 4 line 5)
+        uint32_t tm[TC];
+#pragma unroll
+        for (int c = 0; c < TC; ++c) tm[c] = (uint32_t)lds_t[tc * TC + c] << 31;
+        float p[TR];
+#pragma unroll
+        for (int r = 0; r < TR; ++r) {
+            float s = 0.f;
+#pragma unroll
+            for (int c = 0; c < TC; ++c) s += __uint_as_float(__float_as_uint(x[r][c]) ^ tm[c]);
+            // sum over the 16 lanes that share these rows (fixed order per lane)
+            s += dpp_f32<0xB1>(s);   // lane ^ 1
+            s += dpp_f32<0x4E>(s);   // lane ^ 2
+            s += dpp_f32<0x124>(s);  // row rotate 4
+            s += dpp_f32<0x128>(s);  // row rotate 8
+            p[r] = s;
+        }
+        ++seq_u;
+        ++alternations;
+        {
+            uint64_t* mine = res_slot(a, 0, seq_u, wg);
+            if (tc < TR) {
+                float v = p[0];
+#pragma unroll
+                for (int r = 1; r < TR; ++r) v = (tc == r) ? p[r] : v;
+                res_publish(mine + tr * TR + tc, v, seq_u);
+            }
+            if (tid == 0) {
+                res_publish_f64(mine + BM, cpart, seq_u);
+                res_publish_f64(mine + BM + 2, fsq_block, seq_u);
+            }
+        }
+        bool ok = true;
+        {
+            // gather: thread (row, half) adds eight members in order, the two halves are combined low first
+            const int row = tid >> 1, h = tid & 1;
+            if (row < BM) {
+                double half = 0.0;
+                ok = res_gather8(res_slot(a, 0, seq_u, pr * P + h * 8) + row, kResSlotWords, seq_u, a.max_spin, half);
+                const double other = dpp_swap1_f64(half);
+                const double u = h ? other + half : half + other;
+                if (h == 0) lds_s[cur ^ 1][row] = (u < 0.0) ? 1 : 0;
+            }
+            if (tid >= kResThreads - P) {
+                // piggybacked scalars of the 16 members (last 16 threads: not on the critical rows when BM < 256)
+                const int q = tid - (kResThreads - P);
+                double cp = 0.0, fq = 0.0;
+                const uint64_t* sl = res_slot(a, 0, seq_u, pr * P + q) + BM;
+                bool o2 = res_load_f64(sl, seq_u, a.max_spin, cp);
+                o2 = res_load_f64(sl + 2, seq_u, a.max_spin, fq) && o2;
+                lds_x[0][q] = cp;
+                lds_x[1][q] = fq;
+                ok = ok && o2;
+            }
+        }
+        if (__syncthreads_or(ok ? 0 : 1)) {
+            if (tid == 0) atomicExch((unsigned*)&a.res->err, 1u);
+            return;
+        }
+        double c_tot = 0.0, f_tot = 0.0;
+#pragma unroll
+        for (int q = 0; q < P; ++q) {
+            c_tot += lds_x[0][q];
+            f_tot += lds_x[1][q];
+        }
+        if (norm_stage == 1) {
+            frow = f_tot;
+            norm_stage = 2;
+        }
+        if (j > 0) {
+            const bool conv = (c_tot <= c_prev) || (j >= a.max_iters);
+            if (conv) {
+                // ---- the term is (c_tot, s_cur, t): append it (Algorithm 5 lines 7-9) and subtract it (line 10)
+                if (!(c_tot <= c_prev)) warn = 1;
+                const double ck = c_tot / total;
+                const float ckf = (float)ck;
+                if (pc == 0 && wv < BM / 64) {
+                    const uint64_t word = __ballot(lds_s[cur][wv * 64 + lane] != 0);
+                    if (lane == 0) a.S[k * a.mw + pr * (BM / 64) + wv] = word;
+                }
+                if (pr == 0 && wv < BN / 64) {
+                    const uint64_t word = __ballot(lds_t[wv * 64 + lane] != 0);
+                    if (lane == 0) a.T[k * a.nw + pc * (BN / 64) + wv] = word;
+                }
+                if (wg == 0 && tid == 0) {
+                    a.c[k] = ckf;
+                    a.iters[k] = j;
+                }
+                double f = 0.0;
+#pragma unroll
+                for (int r = 0; r < TR; ++r) {
+                    const uint32_t sr = (uint32_t)lds_s[cur][tr * TR + r] << 31;
+                    float fr = 0.f;
+#pragma unroll
+                    for (int c = 0; c < TC; ++c) {
+                        // R_il - ck s_i t_l: the signs choose +ck or -ck
+                        const float d = __uint_as_float(__float_as_uint(ckf) ^ sr ^ tm[c]);
+                        x[r][c] = x[r][c] - d;
+                        fr += x[r][c] * x[r][c];
+                    }
+                    f += (double)fr;
+                }
+                f = wave_sum_res(f);
+                if (lane == 0) lds_red[wv] = f;
+                __syncthreads();
+                double fb = 0.0;
+#pragma unroll
+                for (int q = 0; q < kResThreads / 64; ++q) fb += lds_red[q];
+                fsq_block = fb;
+                ++k;
+                ++updates;
+                norm_stage = 1;
+                norm_k = k;
+                j = 0;
+                c_prev = -INFINITY;
+                cpart = 0.0;
+                need_t0 = true;
+                __syncthreads();  // lds_t and lds_red are rewritten next
+                continue;
+            }
+            c_prev = c_tot;
+        }
+        cur ^= 1;  // s_j = sgn(u)
+
+        // ================= column phase: v = R^T s (Algorithm 4 line 6), c = sum |v| (line 7)
+        {
+            uint32_t sm[TR];
+#pragma unroll
+            for (int r = 0; r < TR; ++r) sm[r] = (uint32_t)lds_s[cur][tr * TR + r] << 31;
+#pragma unroll
+            for (int c4 = 0; c4 < TC / 4; ++c4) {
+                float qv[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    float s = 0.f;
+#pragma unroll
+                    for (int r = 0; r < TR; ++r) s += __uint_as_float(__float_as_uint(x[r][4 * c4 + e]) ^ sm[r]);
+                    qv[e] = s;
+                }
+                *(float4*)&lds_q[tr][tc * TC + 4 * c4] = make_float4(qv[0], qv[1], qv[2], qv[3]);
+            }
+        }
+        __syncthreads();
+        ++seq_v;
+        {
+            uint64_t* mine = res_slot(a, 1, seq_v, wg);
+            if (tid < BN) {
+                float s = 0.f;
+#pragma unroll
+                for (int q = 0; q < 32; ++q) s += lds_q[q][tid];
+                res_publish(mine + tid, s, seq_v);
+            }
+            if (tid == kResThreads - 1) res_publish_f64(mine + BN, frow, seq_v);
+        }
+        ok = true;
+        double absv = 0.0;
+        {
+            const int col = tid >> 1, h = tid & 1;
+            if (col < BN) {
+                double half = 0.0;
+                ok = res_gather8(res_slot(a, 1, seq_v, (h * 8) * P + pc) + col, (size_t)P * kResSlotWords, seq_v,
+                                 a.max_spin, half);
+                const double other = dpp_swap1_f64(half);
+                const double v = h ? other + half : half + other;
+                if (h == 0) {
+                    lds_t[col] = (v < 0.0) ? 1 : 0;
+                    absv = fabs(v);
+                }
+            }
+            if (tid >= kResThreads - P) {
+                const int q = tid - (kResThreads - P);
+                double fq = 0.0;
+                const bool o2 = res_load_f64(res_slot(a, 1, seq_v, q * P + pc) + BN, seq_v, a.max_spin, fq);
+                lds_x[1][q] = fq;
+                ok = ok && o2;
+            }
+        }
+        absv = wave_sum_res(absv);
+        if (lane == 0) lds_red[wv] = absv;
+        if (__syncthreads_or(ok ? 0 : 1)) {
+            if (tid == 0) atomicExch((unsigned*)&a.res->err, 1u);
+            return;
+        }
+        {
+            double cs = 0.0, ft = 0.0;
+#pragma unroll
+            for (int q = 0; q < kResThreads / 64; ++q) cs += lds_red[q];
+#pragma unroll
+            for (int q = 0; q < P; ++q) ft += lds_x[1][q];
+            cpart = cs;
+            if (norm_stage == 2) {
+                if (wg == 0 && tid == 0) a.trace[norm_k] = sqrt(ft);
+                norm_stage = 0;
+            }
+        }
+        ++j;
+        __syncthreads();  // lds_red / lds_x are rewritten in the next phase
+    }
+
+    // ---- write the block back
+    {
+        float* base = a.R + ((int64_t)pr * BM + tr * TR) * a.n + (int64_t)pc * BN + tc * TC;
+#pragma unroll
+        for (int r = 0; r < TR; ++r)
+#pragma unroll
+            for (int c4 = 0; c4 < TC / 4; ++c4)
+                *(float4*)(base + (int64_t)r * a.n + 4 * c4) =
+                    make_float4(x[r][4 * c4], x[r][4 * c4 + 1], x[r][4 * c4 + 2], x[r][4 * c4 + 3]);
+    }
+    if (wg == 0 && tid == 0) {
+        a.res->k = k;
+        a.res->alternations = alternations;
+        a.res->updates = updates;
+        a.res->seq_u = seq_u;
+        a.res->seq_v = seq_v;
+        a.res->warn = warn;
+    }
+}
+
+static bool resident_shape(int64_t m, int64_t n, int* tr, int* tc)
+{
+    if (m % (32 * kResGrid) || n % (16 * kResGrid)) return false;
+    const int64_t r = m / (32 * kResGrid), c = n / (16 * kResGrid);
+    if (r == 8 && c == 16) { *tr = 8; *tc = 16; return true; }   // 4096 x 4096
+    if (r == 2 && c == 16) { *tr = 2; *tc = 16; return true; }   // 1024 x 4096
+    if (r == 4 && c == 8) { *tr = 4; *tc = 8; return true; }     // 2048 x 2048
+    return false;
+}
+
+bool resident_supported(scd_dtype dt, int order, const int64_t* dims)
+{
+    int tr, tc;
+    return dt == SCD_F32 && order == 2 && resident_shape(dims[0], dims[1], &tr, &tc);
+}
+
+hipError_t launch_resident(const ResidentArgs& a, hipStream_t st)
+{
+    int tr = 0, tc = 0;
+    if (!resident_shape(a.m, a.n, &tr, &tc)) return hipErrorInvalidValue;
+    ResidentArgs args = a;
+    void* kargs[] = {&args};
+    const void* fn = nullptr;
+    if (tr == 8 && tc == 16) fn = (const void*)resident_kernel<8, 16>;
+    else if (tr == 2 && tc == 16) fn = (const void*)resident_kernel<2, 16>;
+    else fn = (const void*)resident_kernel<4, 8>;
+    return hipLaunchCooperativeKernel(fn, dim3(kResGrid * kResGrid), dim3(kResThreads), kargs, 0, st);
+}
+
+}  // namespace scd

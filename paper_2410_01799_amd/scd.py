@@ -18,13 +18,13 @@ _lib = None
 
 F32, F64 = 0, 1
 OK, WMAXITER = 0, 1
-EINVAL, ENOMEM, EHIP, EFULL, ENONFINITE, ENODEVICE = -1, -2, -3, -4, -5, -6
+EINVAL, ENOMEM, EHIP, EFULL, ENONFINITE, ENODEVICE, ETIMEOUT = -1, -2, -3, -4, -5, -6, -7
 
 EXPORTS = [
     "scd_decompose", "scd_create", "scd_destroy", "scd_set_max_iters", "scd_step", "scd_run", "scd_step_from",
     "scd_width", "scd_results", "scd_remainder", "scd_set_remainder", "scd_row_signed_sum", "scd_col_signed_sum",
     "scd_expand", "scd_pack", "scd_unpack", "scd_rng_signs", "scd_strerror", "scd_last_hip_error", "scd_traffic",
-    "scd_probe_stream", "scd_profile_sweeps",
+    "scd_probe_stream", "scd_profile_sweeps", "scd_probe_exchange",
 ]
 
 
@@ -71,6 +71,7 @@ def lib() -> C.CDLL:
         L.scd_last_hip_error.argtypes = []
         L.scd_traffic.argtypes = [vp, C.POINTER(C.c_double), pi64, pi64]
         L.scd_profile_sweeps.argtypes = [vp, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+        L.scd_probe_exchange.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, vp, C.POINTER(C.c_double)]
         L.scd_probe_stream.argtypes = [vp, vp, i64, C.c_int, C.c_int, vp, C.POINTER(C.c_double)]
         _lib = L
     return _lib
@@ -209,6 +210,14 @@ def scd_probe_stream(src: torch.Tensor, dst: Optional[torch.Tensor] = None, grid
     sec = C.c_double()
     st = lib().scd_probe_stream(_ptr(src), _ptr(dst), nbytes, int(grid), int(reps), _stream(), C.byref(sec))
     _check(st, "scd_probe_stream")
+    return sec.value
+
+
+def scd_probe_exchange(which: int, grid: int = 256, group: int = 16, rounds: int = 1000) -> float:
+    """Seconds per round of the in-kernel exchange probe (0: tagged data, 1: counter barrier)."""
+    sec = C.c_double()
+    _check(lib().scd_probe_exchange(int(which), int(grid), int(group), int(rounds), _stream(), C.byref(sec)),
+           "scd_probe_exchange")
     return sec.value
 
 

@@ -1,0 +1,119 @@
+"""The register-resident engine (whole remainder in the register files, one persistent launch) against
+the oracle and against the launch-stream path, on every shape it is built for."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from helpers import C_RTOL, CURVE_RTOL, ID_RTOL, to_np_bits
+from test_gpu_parity import lockstep_check
+
+pytestmark = pytest.mark.gpu
+
+SHAPES = [(1024, 4096), (2048, 2048), (4096, 4096)]
+
+
+@pytest.fixture(scope="module")
+def scd():
+    from paper_2410_01799_amd import scd as mod
+
+    mod.lib()
+    return mod
+
+
+def with_resident(flag):
+    os.environ["SCD_RESIDENT"] = "1" if flag else "0"
+
+
+@pytest.fixture(autouse=True)
+def restore_env():
+    yield
+    os.environ.pop("SCD_RESIDENT", None)
+
+
+def gauss(shape, seed):
+    return np.random.Generator(np.random.PCG64(seed)).standard_normal(shape).astype(np.float32)
+
+
+@pytest.mark.parametrize("m,n", SHAPES)
+def test_resident_matches_oracle_in_lockstep(scd, oracle, m, n):
+    w, seed = 10, 17
+    A = gauss((m, n), m + n)
+    with_resident(True)
+    res = scd.scd_decompose(torch.from_numpy(A).cuda(), w, seed)
+    S, T = to_np_bits(res["signs"][0]), to_np_bits(res["signs"][1])
+    c = res["c"].cpu().numpy().astype(np.float64)
+    trace = res["trace"].cpu().numpy()
+    iters = res["iters"].cpu().numpy()
+    np.testing.assert_allclose(trace[1:] ** 2, trace[:-1] ** 2 - m * n * c ** 2, rtol=ID_RTOL)
+    curve, _ = lockstep_check(oracle, A.astype(np.float64), seed, S, T, c, trace, iters, True)
+    np.testing.assert_allclose(trace, curve, rtol=2e-5)
+    np.testing.assert_allclose(trace / trace[0], curve / curve[0], rtol=CURVE_RTOL)
+    E = scd.scd_expand(res["signs"], res["c"], (m, n)).double()
+    resid = float((torch.from_numpy(A).cuda().double() - E).norm())
+    assert resid == pytest.approx(trace[-1], rel=1e-4)
+
+
+@pytest.mark.parametrize("m,n", SHAPES[:2])
+def test_resident_and_stream_paths_agree(scd, m, n):
+    A = torch.from_numpy(gauss((m, n), 5)).cuda()
+    with_resident(True)
+    a = scd.scd_decompose(A, 8, 3)
+    with_resident(False)
+    b = scd.scd_decompose(A, 8, 3)
+    ta, tb = a["trace"].cpu().numpy(), b["trace"].cpu().numpy()
+    np.testing.assert_allclose(ta / ta[0], tb / tb[0], rtol=CURVE_RTOL)
+    # same signs unless a near tie split the two summation orders: then the curves still agree (above)
+    if torch.equal(a["signs"][0], b["signs"][0]) and torch.equal(a["signs"][1], b["signs"][1]):
+        np.testing.assert_allclose(a["c"].cpu().numpy(), b["c"].cpu().numpy(), rtol=C_RTOL)
+        assert torch.equal(a["iters"], b["iters"])
+        np.testing.assert_allclose(ta, tb, rtol=1e-6)
+
+
+def test_resident_chunking_determinism_and_handover(scd):
+    m, n = 1024, 4096
+    A = torch.from_numpy(gauss((m, n), 9)).cuda()
+    with_resident(True)
+    one = scd.scd_decompose(A, 9, 4)
+    two = scd.scd_decompose(A, 9, 4)
+    for k in ("c", "trace", "iters"):
+        assert torch.equal(one[k], two[k])
+    with scd.ScdContext(A, 12, 4) as ctx:
+        ctx.step()
+        ctx.run(5)
+        ctx.step()
+        ctx.run(2)
+        assert ctx.width == 9
+        res = ctx.results()
+        R = ctx.remainder()
+        # hand-over to the launch-stream path: profiling sweeps continue the same decomposition
+        ctx.profile_sweeps(40)
+        k2 = ctx.width
+        res2 = ctx.results()
+    assert torch.equal(one["signs"][0], res["signs"][0]) and torch.equal(one["signs"][1], res["signs"][1])
+    assert torch.equal(one["c"], res["c"]) and torch.equal(one["trace"], res["trace"])
+    E = scd.scd_expand(res["signs"], res["c"], (m, n))
+    assert float((A - E - R).abs().max()) <= 2e-6 * float(A.abs().max())
+    assert k2 >= 9
+    tr = res2["trace"].cpu().numpy()
+    c2 = res2["c"].cpu().numpy().astype(np.float64)
+    np.testing.assert_allclose(tr[1:] ** 2, tr[:-1] ** 2 - m * n * c2 ** 2, rtol=ID_RTOL)
+
+
+def test_resident_iteration_cap(scd):
+    A = torch.from_numpy(gauss((2048, 2048), 2)).cuda()
+    with_resident(True)
+    with scd.ScdContext(A, 3, 1) as ctx:
+        ctx.set_max_iters(2)
+        assert ctx.run(3) == scd.WMAXITER
+        r = ctx.results()
+    assert r["iters"].cpu().tolist() == [2, 2, 2]
+    tr = r["trace"].cpu().numpy()
+    c = r["c"].cpu().numpy().astype(np.float64)
+    np.testing.assert_allclose(tr[1:] ** 2, tr[:-1] ** 2 - 2048 * 2048 * c ** 2, rtol=ID_RTOL)
+
+
+def test_exchange_probe_runs(scd):
+    t = scd.scd_probe_exchange(0, 256, 16, 200)
+    assert 0 < t < 1e-3
