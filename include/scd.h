@@ -131,6 +131,15 @@ int scd_last_hip_error(void);        /* hipError_t of the most recent SCD_EHIP o
  * of passes (launches) they took: the counters behind the bandwidth figures.  host pointers. */
 int scd_traffic(const scd_ctx* ctx, double* bytes, int64_t* passes, int64_t* sweeps);
 
+/* Which engine scd_run uses for this context: 0 = a stream of launches that re-read the remainder from
+ * memory every alternation (any shape); 1 = one persistent launch that keeps the whole remainder in
+ * the register files of a 16 x 16 grid of workgroups (f32 matrices of 1024x4096, 2048x2048, 4096x4096;
+ * switched off by the environment variable SCD_RESIDENT=0).  For engine 1 also the duration of the
+ * most recent launch by HIP events on the context's stream and its algorithmic bytes: (alternations +
+ * updates) * bytes of the remainder, what a streaming pass per alternation would move.  host pointers,
+ * each may be NULL. */
+int scd_engine(const scd_ctx* ctx, int* engine, double* last_launch_seconds, double* last_launch_bytes);
+
 /* Measurement: run n (<= 4096) further sweeps of the greedy loop with a HIP event before and after
  * each kernel of the pass over the remainder; returns the average duration of the row-pass launch
  * and of the reduce launch that follows it (host pointers, seconds).  The terms found meanwhile are

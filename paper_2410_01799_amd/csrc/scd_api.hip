@@ -6,6 +6,7 @@
 // wait for the host.  The host only reads the state back once per batch of sweeps to see whether
 // the requested number of terms is reached.
 #include <math.h>
+#include <stdio.h>
 #include <stdlib.h>
 #include <string.h>
 
@@ -91,6 +92,9 @@ struct scd_ctx {
     ResidentResult* res_pin = nullptr;
     uint32_t seq_u = 0, seq_v = 0;
     int max_spin = 1 << 22;
+    hipEvent_t ev0 = nullptr, ev1 = nullptr;  // around the engine's launch
+    double last_launch_seconds = 0.0;
+    double last_launch_bytes = 0.0;
     std::vector<void*> allocs;
 };
 
@@ -293,6 +297,7 @@ int run_resident(scd_ctx* c, int64_t n)
     a.w_target = c->hs.k + n;
     a.max_iters = c->hs.max_iters;
     a.max_spin = c->max_spin;
+    a.poll_delay = env_int("SCD_RESIDENT_POLL_DELAY", 16);
     a.seq_u = c->seq_u;
     a.seq_v = c->seq_v;
     a.xbuf = c->xbuf;
@@ -305,14 +310,26 @@ int run_resident(scd_ctx* c, int64_t n)
     a.nw = (int32_t)words_for(c->dims[1]);
     a.res = c->res_dev;
     HIP_TRY(hipMemsetAsync(c->res_dev, 0, sizeof(ResidentResult), c->stream));
+    HIP_TRY(hipEventRecord(c->ev0, c->stream));
     HIP_TRY(launch_resident(a, c->stream));
+    HIP_TRY(hipEventRecord(c->ev1, c->stream));
     HIP_TRY(hipMemcpyAsync(c->res_pin, c->res_dev, sizeof(ResidentResult), hipMemcpyDeviceToHost, c->stream));
     HIP_TRY(hipStreamSynchronize(c->stream));
     const ResidentResult r = *c->res_pin;
+    {
+        float ms = 0.f;
+        HIP_TRY(hipEventElapsedTime(&ms, c->ev0, c->ev1));
+        c->last_launch_seconds = (double)ms * 1e-3;
+        // one read of R per alternation, one write per update (what a streaming implementation must move)
+        c->last_launch_bytes = ((double)r.alternations + (double)r.updates) * (double)c->total * (double)c->esize;
+    }
     if (r.err || r.k != a.w_target) {
         c->broken = true;
         return SCD_ETIMEOUT;
     }
+    if (env_int("SCD_RESIDENT_VERBOSE", 0))
+        fprintf(stderr, "[scd resident] terms %lld alternations %lld re-reads %lld\n", (long long)n,
+                (long long)r.alternations, (long long)r.spins);
     c->seq_u = r.seq_u;
     c->seq_v = r.seq_v;
     c->hs.k = r.k;
@@ -431,6 +448,8 @@ int scd_create(scd_ctx** out, const void* A, scd_dtype dt, int order, const int6
         CTRY(dev_alloc(c, (void**)&c->res_dev, sizeof(ResidentResult)));
         CHIP(hipHostMalloc((void**)&c->res_pin, sizeof(ResidentResult), hipHostMallocDefault));
         c->max_spin = env_int("SCD_RESIDENT_MAX_SPIN", 1 << 22);
+        CHIP(hipEventCreate(&c->ev0));
+        CHIP(hipEventCreate(&c->ev1));
     }
     c->ncparts = (int)words_for(dims[order - 1]);
     CTRY(dev_alloc(c, (void**)&c->cparts, (size_t)c->ncparts * 8));
@@ -463,6 +482,8 @@ void scd_destroy(scd_ctx* c)
     for (void* p : c->allocs) (void)hipFree(p);
     if (c->pinned) (void)hipHostFree(c->pinned);
     if (c->res_pin) (void)hipHostFree(c->res_pin);
+    if (c->ev0) (void)hipEventDestroy(c->ev0);
+    if (c->ev1) (void)hipEventDestroy(c->ev1);
     (void)hipGetLastError();
     delete c;
 }
@@ -570,6 +591,15 @@ int scd_set_remainder(scd_ctx* c, const void* R_in)
     double f = 0.0;
     HIP_TRY(hipMemcpy(&f, c->trace + c->hs.k, sizeof(double), hipMemcpyDeviceToHost));
     if (!isfinite(f)) return SCD_ENONFINITE;
+    return SCD_OK;
+}
+
+int scd_engine(const scd_ctx* c, int* engine, double* last_launch_seconds, double* last_launch_bytes)
+{
+    if (!c) return SCD_EINVAL;
+    if (engine) *engine = c->resident ? 1 : 0;
+    if (last_launch_seconds) *last_launch_seconds = c->last_launch_seconds;
+    if (last_launch_bytes) *last_launch_bytes = c->last_launch_bytes;
     return SCD_OK;
 }
 
@@ -834,7 +864,7 @@ int scd_probe_stream(const void* src, void* dst, int64_t bytes, int grid, int re
 
 int scd_probe_exchange(int which, int grid, int group, int rounds, void* stream, double* seconds_per_round)
 {
-    if (which < 0 || which > 1 || grid < 1 || grid > 1024 || group < 1 || grid % group || rounds < 1 ||
+    if (which < 0 || which > 1 || grid < 1 || grid > 1024 || (group & 0xFFFF) < 1 || grid % (group & 0xFFFF) || rounds < 1 ||
         !seconds_per_round)
         return SCD_EINVAL;
     hipStream_t st = (hipStream_t)stream;

@@ -114,6 +114,7 @@ struct ResidentResult {
     uint32_t seq_u, seq_v; // last exchange sequence numbers used
     int32_t err;           // 1: a bounded wait ran out
     int32_t warn;          // a term ended on max_iters
+    int64_t spins;         // re-reads of stale exchange data by thread 0 of workgroup 0 (diagnostic)
 };
 
 struct ResidentArgs {
@@ -122,6 +123,7 @@ struct ResidentArgs {
     uint64_t seed;
     int64_t k_start, w_target;
     int32_t max_iters, max_spin;
+    int32_t poll_delay;      // s_sleep units between publishing and the first read of the neighbours' data
     uint32_t seq_u, seq_v;   // sequence numbers already used by earlier launches
     uint64_t* xbuf;          // [2 kinds][2 parities][256 workgroups][kResSlotWords]
     uint64_t* S;

@@ -14,8 +14,11 @@ __global__ void __launch_bounds__(256) exchange_probe_kernel(uint64_t* buf, int 
                                                             unsigned* err, float* out)
 {
     const int g = blockIdx.x, tid = threadIdx.x;
+    const int nvals = (group >> 16) ? (group >> 16) : 256;  // values each workgroup publishes per round
+    group &= 0xFFFF;
     const int g0 = (g / group) * group;
     float carry = 0.f;
+    if (tid >= nvals) return;
     for (int r = 1; r <= rounds; ++r) {
         uint64_t* mine = buf + ((size_t)(r & 1) * gridDim.x + g) * 256;
         __hip_atomic_store(mine + tid, tagged(carry + (float)tid, (uint32_t)r), __ATOMIC_RELAXED,
@@ -140,9 +143,23 @@ __device__ __forceinline__ double wave_sum_res(double a)
 // dropped.  ||R||_F^2 after an update travels the same way (block row sums, then the total).
 // Every wait is bounded; on expiry all workgroups leave and the host reports an error.
 
+// word offset of the slot of workgroup `wg` for exchange `seq` of kind 0 (rows) or 1 (columns)
+__device__ __forceinline__ uint32_t res_slot_off(int kind, uint32_t seq, int wg)
+{
+    return (uint32_t)(((kind * 2 + (int)(seq & 1u)) * (kResGrid * kResGrid) + wg) * kResSlotWords);
+}
 __device__ __forceinline__ uint64_t* res_slot(const ResidentArgs& a, int kind, uint32_t seq, int wg)
 {
-    return a.xbuf + ((size_t)((kind * 2 + (int)(seq & 1u)) * (kResGrid * kResGrid) + wg)) * kResSlotWords;
+    return a.xbuf + res_slot_off(kind, seq, wg);
+}
+
+__device__ __forceinline__ double uniform_f64(double v)
+{
+    // the value is the same in every lane: keep it in scalar registers
+    const long long b = __double_as_longlong(v);
+    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)(b & 0xFFFFFFFFll));
+    const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)((unsigned long long)b >> 32));
+    return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
 }
 
 __device__ __forceinline__ void res_publish(uint64_t* p, float v, uint32_t seq)
@@ -158,24 +175,52 @@ __device__ __forceinline__ void res_publish_f64(uint64_t* p, double v, uint32_t 
     __hip_atomic_store(p + 1, ((uint64_t)seq << 32) | (b >> 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Eight members' values of one element, all loads in flight together; stale ones are read again.
-__device__ __forceinline__ bool res_gather8(const uint64_t* base, size_t stride, uint32_t seq, int max_spin,
-                                            double& sum)
+// Eight members' values of one element plus the two piggybacked doubles of one member (four more
+// words), all twelve loads in flight together.  If any word is still from an earlier exchange, all
+// are read again (re-reads are rare once the first read is delayed a little).
+__device__ __forceinline__ bool res_gather8_x2(const uint64_t* xbuf, uint32_t off, uint32_t stride, uint32_t xoff,
+                                               uint32_t seq, int max_spin, double& sum, double& x0, double& x1,
+                                               int& spin)
+{
+    uint64_t w[12];
+    for (;;) {
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+            w[q] = __hip_atomic_load(xbuf + (off + q * stride), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            w[8 + q] = __hip_atomic_load(xbuf + (xoff + q), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        bool fresh = true;
+#pragma unroll
+        for (int q = 0; q < 12; ++q) fresh = fresh && ((uint32_t)(w[q] >> 32) == seq);
+        if (fresh) break;
+        if (++spin > max_spin) return false;
+        __builtin_amdgcn_s_sleep(1);
+    }
+    double s = 0.0;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) s += (double)__uint_as_float((uint32_t)w[q]);
+    sum = s;
+    x0 = __longlong_as_double((long long)((w[9] << 32) | (w[8] & 0xFFFFFFFFull)));
+    x1 = __longlong_as_double((long long)((w[11] << 32) | (w[10] & 0xFFFFFFFFull)));
+    return true;
+}
+
+// Eight members' values of one element, all loads in flight together.
+__device__ __forceinline__ bool res_gather8(const uint64_t* xbuf, uint32_t off, uint32_t stride, uint32_t seq,
+                                            int max_spin, double& sum, int& spin)
 {
     uint64_t w[8];
-    unsigned pending = 0xFFu;
-    int spin = 0;
-    while (pending) {
+    for (;;) {
 #pragma unroll
         for (int q = 0; q < 8; ++q)
-            if ((pending >> q) & 1u) w[q] = __hip_atomic_load(base + q * stride, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            w[q] = __hip_atomic_load(xbuf + (off + q * stride), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        bool fresh = true;
 #pragma unroll
-        for (int q = 0; q < 8; ++q)
-            if (((pending >> q) & 1u) && (uint32_t)(w[q] >> 32) == seq) pending &= ~(1u << q);
-        if (pending) {
-            if (++spin > max_spin) return false;
-            __builtin_amdgcn_s_sleep(1);
-        }
+        for (int q = 0; q < 8; ++q) fresh = fresh && ((uint32_t)(w[q] >> 32) == seq);
+        if (fresh) break;
+        if (++spin > max_spin) return false;
+        __builtin_amdgcn_s_sleep(1);
     }
     double s = 0.0;
 #pragma unroll
@@ -214,6 +259,22 @@ __device__ __forceinline__ double dpp_swap1_f64(double v)
     return __longlong_as_double(((long long)hi << 32) | (long long)(unsigned)lo);
 }
 
+// v[l] + v[l ^ 16] and v[l] + v[l ^ 32] by the row-swap instructions of gfx950 (no LDS traffic):
+// swapping the odd rows of one copy with the even rows of another leaves the two partners of every
+// lane in the two results, in the same order for both partners.
+__device__ __forceinline__ float sum_xor16(float v)
+{
+    const unsigned b = __float_as_uint(v);
+    const auto r = __builtin_amdgcn_permlane16_swap(b, b, false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+__device__ __forceinline__ float sum_xor32(float v)
+{
+    const unsigned b = __float_as_uint(v);
+    const auto r = __builtin_amdgcn_permlane32_swap(b, b, false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 template <int TR, int TC>
 __global__ void __launch_bounds__(kResThreads) resident_kernel(ResidentArgs a)
 {
@@ -221,13 +282,13 @@ __global__ void __launch_bounds__(kResThreads) resident_kernel(ResidentArgs a)
     constexpr int BM = 32 * TR, BN = 16 * TC;  // block of this workgroup
     static_assert(TR >= 2 && TR <= 16 && (TR % 2) == 0, "rows per thread");
     static_assert(TC >= 4 && TC <= 32 && (TC % 4) == 0, "columns per thread");
-    static_assert(BM + 4 <= kResSlotWords && BN + 2 <= kResSlotWords, "slot size");
+    static_assert(BM + 4 <= kResSlotWords && BN + 4 <= kResSlotWords, "slot size");
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int tr = tid >> 4, tc = tid & 15;  // 32 x 16 threads, each TR x TC elements
     const int pr = blockIdx.x / P, pc = blockIdx.x % P;
     const int wg = blockIdx.x;
 
-    __shared__ float lds_q[32][BN];
+    __shared__ float lds_q[kResThreads / 64][BN];
     __shared__ uint8_t lds_s[2][BM];
     __shared__ uint8_t lds_t[BN];
     __shared__ double lds_red[kResThreads / 64];
@@ -250,7 +311,7 @@ __global__ void __launch_bounds__(kResThreads) resident_kernel(ResidentArgs a)
     }
 
     int64_t k = a.k_start;
-    int64_t alternations = 0, updates = 0;
+    int alternations = 0, updates = 0;
     uint32_t seq_u = a.seq_u, seq_v = a.seq_v;
     int j = 0, warn = 0, cur = 0;
     double c_prev = -INFINITY;
@@ -261,6 +322,7 @@ __global__ void __launch_bounds__(kResThreads) resident_kernel(ResidentArgs a)
     int64_t norm_k = 0;
     const double total = (double)a.m * (double)a.n;
     bool need_t0 = true;
+    int spin = 0, spins = 0;
 
     for (;;) {
         if (k >= a.w_target && norm_stage == 0) break;
@@ -274,15 +336,18 @@ __global__ void __launch_bounds__(kResThreads) resident_kernel(ResidentArgs a)
             __syncthreads();
         }
         // ================= row phase: u = R t (Algorithm 4 line 5)
-        uint32_t tm[TC];
+        // The signs enter as +-1.0 multipliers of a fused multiply-add: x * (+-1) is exact, so each step
+        // rounds exactly like the sign-flip-and-add of Section 3.4, in one instruction instead of two
+        // (this engine is bound by vector instructions and latency, not by memory).
+        float tf[TC];
 #pragma unroll
-        for (int c = 0; c < TC; ++c) tm[c] = (uint32_t)lds_t[tc * TC + c] << 31;
+        for (int c = 0; c < TC; ++c) tf[c] = __uint_as_float(0x3F800000u | ((uint32_t)lds_t[tc * TC + c] << 31));
         float p[TR];
 #pragma unroll
         for (int r = 0; r < TR; ++r) {
             float s = 0.f;
 #pragma unroll
-            for (int c = 0; c < TC; ++c) s += __uint_as_float(__float_as_uint(x[r][c]) ^ tm[c]);
+            for (int c = 0; c < TC; ++c) s = __builtin_fmaf(x[r][c], tf[c], s);
             // sum over the 16 lanes that share these rows (fixed order per lane)
             s += dpp_f32<0xB1>(s);   // lane ^ 1
             s += dpp_f32<0x4E>(s);   // lane ^ 2
@@ -305,39 +370,45 @@ __global__ void __launch_bounds__(kResThreads) resident_kernel(ResidentArgs a)
                 res_publish_f64(mine + BM + 2, fsq_block, seq_u);
             }
         }
+        for (int d = 0; d < a.poll_delay; ++d) __builtin_amdgcn_s_sleep(1);
         bool ok = true;
         {
-            // gather: thread (row, half) adds eight members in order, the two halves are combined low first
+            // gather: thread (row, half) adds eight members in order, the two halves are combined low
+            // first.  The last wave also fetches the piggybacked scalars (lane & 15 = member), in the
+            // same batch of loads; threads past the block's rows read a valid row and drop it.
             const int row = tid >> 1, h = tid & 1;
-            if (row < BM) {
-                double half = 0.0;
-                ok = res_gather8(res_slot(a, 0, seq_u, pr * P + h * 8) + row, kResSlotWords, seq_u, a.max_spin, half);
-                const double other = dpp_swap1_f64(half);
-                const double u = h ? other + half : half + other;
-                if (h == 0) lds_s[cur ^ 1][row] = (u < 0.0) ? 1 : 0;
+            const int rowc = row < BM ? row : BM - 1;
+            const uint32_t off = res_slot_off(0, seq_u, pr * P + h * 8) + (uint32_t)rowc;
+            double half = 0.0;
+            if (wv == kResThreads / 64 - 1) {
+                double x0 = 0.0, x1 = 0.0;
+                ok = res_gather8_x2(a.xbuf, off, kResSlotWords, res_slot_off(0, seq_u, pr * P + (lane & 15)) + BM, seq_u,
+                                    a.max_spin, half, x0, x1, spin);
+                if (lane < P) {
+                    lds_x[0][lane] = x0;
+                    lds_x[1][lane] = x1;
+                }
+            } else {
+                ok = res_gather8(a.xbuf, off, kResSlotWords, seq_u, a.max_spin, half, spin);
             }
-            if (tid >= kResThreads - P) {
-                // piggybacked scalars of the 16 members (last 16 threads: not on the critical rows when BM < 256)
-                const int q = tid - (kResThreads - P);
-                double cp = 0.0, fq = 0.0;
-                const uint64_t* sl = res_slot(a, 0, seq_u, pr * P + q) + BM;
-                bool o2 = res_load_f64(sl, seq_u, a.max_spin, cp);
-                o2 = res_load_f64(sl + 2, seq_u, a.max_spin, fq) && o2;
-                lds_x[0][q] = cp;
-                lds_x[1][q] = fq;
-                ok = ok && o2;
-            }
+            const double other = dpp_swap1_f64(half);
+            const double u = h ? other + half : half + other;
+            if (h == 0 && row < BM) lds_s[cur ^ 1][row] = (u < 0.0) ? 1 : 0;
         }
         if (__syncthreads_or(ok ? 0 : 1)) {
             if (tid == 0) atomicExch((unsigned*)&a.res->err, 1u);
             return;
         }
+        spins += spin;
+        spin = 0;
         double c_tot = 0.0, f_tot = 0.0;
-#pragma unroll
+#pragma unroll 2
         for (int q = 0; q < P; ++q) {
             c_tot += lds_x[0][q];
             f_tot += lds_x[1][q];
         }
+        c_tot = uniform_f64(c_tot);
+        f_tot = uniform_f64(f_tot);
         if (norm_stage == 1) {
             frow = f_tot;
             norm_stage = 2;
@@ -369,7 +440,7 @@ __global__ void __launch_bounds__(kResThreads) resident_kernel(ResidentArgs a)
 #pragma unroll
                     for (int c = 0; c < TC; ++c) {
                         // R_il - ck s_i t_l: the signs choose +ck or -ck
-                        const float d = __uint_as_float(__float_as_uint(ckf) ^ sr ^ tm[c]);
+                        const float d = __uint_as_float(__float_as_uint(ckf) ^ sr ^ (__float_as_uint(tf[c]) & 0x80000000u));
                         x[r][c] = x[r][c] - d;
                         fr += x[r][c] * x[r][c];
                     }
@@ -379,9 +450,9 @@ __global__ void __launch_bounds__(kResThreads) resident_kernel(ResidentArgs a)
                 if (lane == 0) lds_red[wv] = f;
                 __syncthreads();
                 double fb = 0.0;
-#pragma unroll
+#pragma unroll 2
                 for (int q = 0; q < kResThreads / 64; ++q) fb += lds_red[q];
-                fsq_block = fb;
+                fsq_block = uniform_f64(fb);
                 ++k;
                 ++updates;
                 norm_stage = 1;
@@ -399,9 +470,9 @@ __global__ void __launch_bounds__(kResThreads) resident_kernel(ResidentArgs a)
 
         // ================= column phase: v = R^T s (Algorithm 4 line 6), c = sum |v| (line 7)
         {
-            uint32_t sm[TR];
+            float sf[TR];
 #pragma unroll
-            for (int r = 0; r < TR; ++r) sm[r] = (uint32_t)lds_s[cur][tr * TR + r] << 31;
+            for (int r = 0; r < TR; ++r) sf[r] = __uint_as_float(0x3F800000u | ((uint32_t)lds_s[cur][tr * TR + r] << 31));
 #pragma unroll
             for (int c4 = 0; c4 < TC / 4; ++c4) {
                 float qv[4];
@@ -409,10 +480,11 @@ __global__ void __launch_bounds__(kResThreads) resident_kernel(ResidentArgs a)
                 for (int e = 0; e < 4; ++e) {
                     float s = 0.f;
 #pragma unroll
-                    for (int r = 0; r < TR; ++r) s += __uint_as_float(__float_as_uint(x[r][4 * c4 + e]) ^ sm[r]);
-                    qv[e] = s;
+                    for (int r = 0; r < TR; ++r) s = __builtin_fmaf(x[r][4 * c4 + e], sf[r], s);
+                    // the four thread rows of this wave hold the same columns 16 lanes apart
+                    qv[e] = sum_xor32(sum_xor16(s));
                 }
-                *(float4*)&lds_q[tr][tc * TC + 4 * c4] = make_float4(qv[0], qv[1], qv[2], qv[3]);
+                if (lane < 16) *(float4*)&lds_q[wv][tc * TC + 4 * c4] = make_float4(qv[0], qv[1], qv[2], qv[3]);
             }
         }
         __syncthreads();
@@ -422,32 +494,35 @@ __global__ void __launch_bounds__(kResThreads) resident_kernel(ResidentArgs a)
             if (tid < BN) {
                 float s = 0.f;
 #pragma unroll
-                for (int q = 0; q < 32; ++q) s += lds_q[q][tid];
+                for (int q = 0; q < kResThreads / 64; ++q) s += lds_q[q][tid];
                 res_publish(mine + tid, s, seq_v);
             }
-            if (tid == kResThreads - 1) res_publish_f64(mine + BN, frow, seq_v);
+            if (tid == kResThreads - 1) {
+                res_publish_f64(mine + BN, frow, seq_v);
+                res_publish_f64(mine + BN + 2, 0.0, seq_v);
+            }
         }
+        for (int d = 0; d < a.poll_delay; ++d) __builtin_amdgcn_s_sleep(1);
         ok = true;
         double absv = 0.0;
         {
             const int col = tid >> 1, h = tid & 1;
-            if (col < BN) {
-                double half = 0.0;
-                ok = res_gather8(res_slot(a, 1, seq_v, (h * 8) * P + pc) + col, (size_t)P * kResSlotWords, seq_v,
-                                 a.max_spin, half);
-                const double other = dpp_swap1_f64(half);
-                const double v = h ? other + half : half + other;
-                if (h == 0) {
-                    lds_t[col] = (v < 0.0) ? 1 : 0;
-                    absv = fabs(v);
-                }
+            const int colc = col < BN ? col : BN - 1;
+            const uint32_t off = res_slot_off(1, seq_v, (h * 8) * P + pc) + (uint32_t)colc;
+            double half = 0.0;
+            if (wv == kResThreads / 64 - 1) {
+                double x0 = 0.0, x1 = 0.0;
+                ok = res_gather8_x2(a.xbuf, off, P * kResSlotWords, res_slot_off(1, seq_v, (lane & 15) * P + pc) + BN,
+                                    seq_v, a.max_spin, half, x0, x1, spin);
+                if (lane < P) lds_x[1][lane] = x0;
+            } else {
+                ok = res_gather8(a.xbuf, off, P * kResSlotWords, seq_v, a.max_spin, half, spin);
             }
-            if (tid >= kResThreads - P) {
-                const int q = tid - (kResThreads - P);
-                double fq = 0.0;
-                const bool o2 = res_load_f64(res_slot(a, 1, seq_v, q * P + pc) + BN, seq_v, a.max_spin, fq);
-                lds_x[1][q] = fq;
-                ok = ok && o2;
+            const double other = dpp_swap1_f64(half);
+            const double v = h ? other + half : half + other;
+            if (h == 0 && col < BN) {
+                lds_t[col] = (v < 0.0) ? 1 : 0;
+                absv = fabs(v);
             }
         }
         absv = wave_sum_res(absv);
@@ -458,17 +533,20 @@ __global__ void __launch_bounds__(kResThreads) resident_kernel(ResidentArgs a)
         }
         {
             double cs = 0.0, ft = 0.0;
-#pragma unroll
+#pragma unroll 2
             for (int q = 0; q < kResThreads / 64; ++q) cs += lds_red[q];
-#pragma unroll
+#pragma unroll 2
             for (int q = 0; q < P; ++q) ft += lds_x[1][q];
-            cpart = cs;
+            cpart = uniform_f64(cs);
+            ft = uniform_f64(ft);
             if (norm_stage == 2) {
                 if (wg == 0 && tid == 0) a.trace[norm_k] = sqrt(ft);
                 norm_stage = 0;
             }
         }
         ++j;
+        spins += spin;
+        spin = 0;
         __syncthreads();  // lds_red / lds_x are rewritten in the next phase
     }
 
@@ -489,6 +567,7 @@ __global__ void __launch_bounds__(kResThreads) resident_kernel(ResidentArgs a)
         a.res->seq_u = seq_u;
         a.res->seq_v = seq_v;
         a.res->warn = warn;
+        a.res->spins = spins;
     }
 }
 

@@ -24,7 +24,7 @@ EXPORTS = [
     "scd_decompose", "scd_create", "scd_destroy", "scd_set_max_iters", "scd_step", "scd_run", "scd_step_from",
     "scd_width", "scd_results", "scd_remainder", "scd_set_remainder", "scd_row_signed_sum", "scd_col_signed_sum",
     "scd_expand", "scd_pack", "scd_unpack", "scd_rng_signs", "scd_strerror", "scd_last_hip_error", "scd_traffic",
-    "scd_probe_stream", "scd_profile_sweeps", "scd_probe_exchange",
+    "scd_probe_stream", "scd_profile_sweeps", "scd_probe_exchange", "scd_engine",
 ]
 
 
@@ -71,6 +71,7 @@ def lib() -> C.CDLL:
         L.scd_last_hip_error.argtypes = []
         L.scd_traffic.argtypes = [vp, C.POINTER(C.c_double), pi64, pi64]
         L.scd_profile_sweeps.argtypes = [vp, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+        L.scd_engine.argtypes = [vp, C.POINTER(C.c_int), C.POINTER(C.c_double), C.POINTER(C.c_double)]
         L.scd_probe_exchange.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, vp, C.POINTER(C.c_double)]
         L.scd_probe_stream.argtypes = [vp, vp, i64, C.c_int, C.c_int, vp, C.POINTER(C.c_double)]
         _lib = L
@@ -299,6 +300,12 @@ class ScdContext:
         a, b = C.c_double(), C.c_double()
         _check(lib().scd_profile_sweeps(self._h, int(n), C.byref(a), C.byref(b)), "scd_profile_sweeps")
         return a.value, b.value
+
+    def engine(self):
+        """dict(engine=0 launch stream | 1 register-resident, last_launch_seconds, last_launch_bytes)."""
+        e, s_, b = C.c_int(), C.c_double(), C.c_double()
+        _check(lib().scd_engine(self._h, C.byref(e), C.byref(s_), C.byref(b)), "scd_engine")
+        return dict(engine=int(e.value), last_launch_seconds=s_.value, last_launch_bytes=b.value)
 
     def traffic(self):
         b = C.c_double()

@@ -92,7 +92,9 @@ def test_profile_and_traffic_counters(scd):
         k = ctx.width
         res = ctx.results()
     assert 0 < a < 1e-3 and 0 < b < 1e-3
-    assert t1["passes"] - t0["passes"] == 64
+    # 64 sampled passes, plus one start pass when the register-resident engine ran the first terms and
+    # the launch-stream state had to be rebuilt for the sampling
+    assert t1["passes"] - t0["passes"] in (64, 65)
     it = res["iters"].cpu().numpy()
     # passes so far = alternations of the finished terms + those of the term in progress
     assert it.sum() <= t1["passes"] <= it.sum() + 4096
