@@ -4,8 +4,9 @@
 A step is one whole greedy decomposition (every hot-path stage: start, row passes, reductions,
 termination, fused updates, appends) of the headline workload: a 4096x4096 f32 matrix with i.i.d.
 N(0,1) entries taken to width 8192.  The input is resident in HBM before the timed region.
-Prints ONE JSON line: terms/s, plus the roofline of the dominant kernel (the row pass) and the CPU
-oracle timed on a bounded sample of the same workload.
+Prints ONE JSON line: terms/s, plus the roofline of the dominant kernel (the persistent register-resident
+kernel, or the row pass of the launch-stream engine with --engine stream) and the CPU oracle timed on a
+bounded sample of the same workload.
 """
 from __future__ import annotations
 
@@ -21,6 +22,10 @@ if str(ROOT) not in sys.path:
     sys.path.insert(0, str(ROOT))
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+# HBM/fabric bytes measured with rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE (two runs, each scaled by the
+# plain copy kernel of known size); figures and commands in profiles/memory_traffic_f32_4096x4096_pmc.txt
+RESIDENT_TRAFFIC_PER_ROW_PHASE = 6.06e6   # bytes per alternation of resident_kernel<8,16> (4096x4096 f32)
+STREAM_TRAFFIC_PER_LAUNCH = 68.7e6        # bytes per launch of rowpass_tiled_kernel<float,4,4> (4096x4096 f32)
 
 
 def cpu_baseline(A64, seed: int, budget_s: float):
@@ -50,7 +55,14 @@ def main() -> int:
     ap.add_argument("--width", type=int, default=8192, help="terms per decomposition (headline: 8192)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the CPU oracle leg (0 = skip)")
     ap.add_argument("--profile-sweeps", type=int, default=512)
+    ap.add_argument("--engine", choices=["auto", "stream"], default="auto",
+                    help="auto: register-resident engine when the shape fits; stream: one launch per pass")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="only run the plain copy kernel (64 MiB, 20+1 launches): the known-size reference "
+                         "for scaling the profiler's FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
+    if args.engine == "stream":
+        os.environ["SCD_RESIDENT"] = "0"
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
         return 2
@@ -63,6 +75,14 @@ def main() -> int:
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     scd.lib()
     torch.cuda.set_device(0)
+    if args.calibrate:
+        src = torch.randn(16 * 1024 * 1024, device="cuda")
+        dst = torch.empty_like(src)
+        sec = scd.scd_probe_stream(src, dst, 2048, 20)
+        print(json.dumps({"calibrate": "stream_copy_kernel", "bytes_read_per_launch": src.numel() * 4,
+                          "bytes_written_per_launch": src.numel() * 4, "launches": 21,
+                          "us_per_launch": round(sec * 1e6, 2)}))
+        return 0
     m = n = args.size
     w, seed = args.width, 2
     A64 = workloads.gaussian_matrix(m, n, seed, np.float64)
@@ -110,7 +130,8 @@ def main() -> int:
         achieved = bpl / sec / 1e9
         roof = {"bound": "hbm", "kernel": "resident_kernel<8,16> (one launch per decomposition)",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": round(RESIDENT_TRAFFIC_PER_ROW_PHASE * bpl / (m * n * esize)) if (m, n) == (4096, 4096) else None,
                 "bytes_per_launch": round(bpl), "launch_us": round(sec * 1e6, 1),
                 "us_per_alternation": round(sec * 1e6 / (bpl / (m * n * esize)), 3),
                 "note": "remainder held in registers: algorithmic bytes are what a streaming pass per "
@@ -128,7 +149,8 @@ def main() -> int:
         achieved = bytes_per_launch / rowpass_s / 1e9
         roof = {"bound": "hbm", "kernel": "rowpass_tiled_kernel<float,4,4>",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": round(STREAM_TRAFFIC_PER_LAUNCH) if (m, n) == (4096, 4096) else None,
                 "bytes_per_launch": round(bytes_per_launch), "launch_us": round(rowpass_s * 1e6, 3),
                 "reduce_launch_us": round(reduce_s * 1e6, 3),
                 "measured_stream_read_gbs": round(m * n * esize / stream_s / 1e9, 1)}

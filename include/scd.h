@@ -157,8 +157,9 @@ int scd_probe_stream(const void* src, void* dst, int64_t bytes, int grid, int re
 /* Latency of exchanging data between the workgroups of one persistent launch, for measurement only.
  * which = 0: every workgroup publishes 256 tagged values per round and reads those of its `group`
  * neighbours (the exchange the register-resident engine uses); which = 1: a counter barrier over the
- * whole grid.  grid workgroups (a multiple of group, at most 1024) must all be resident at once, which
- * the cooperative launch checks.  *seconds_per_round: host. */
+ * whole grid.  grid workgroups (a multiple of group, at most 1024; keep it at most the number of
+ * compute units) must all be resident at once; every wait is bounded and SCD_EINVAL is returned when
+ * one runs out.  *seconds_per_round: host. */
 int scd_probe_exchange(int which, int grid, int group, int rounds, void* stream, double* seconds_per_round);
 
 #ifdef __cplusplus

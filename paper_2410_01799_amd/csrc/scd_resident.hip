@@ -84,12 +84,11 @@ __global__ void __launch_bounds__(256) barrier_probe_kernel(unsigned* counter, i
 hipError_t launch_exchange_probe(int which, int grid, uint64_t* buf, unsigned* counter, int rounds, int group,
                                  int max_spin, unsigned* err, float* out, hipStream_t st)
 {
-    if (which == 0) {
-        void* args[] = {&buf, &rounds, &group, &max_spin, &err, &out};
-        return hipLaunchCooperativeKernel((const void*)exchange_probe_kernel, dim3(grid), dim3(256), args, 0, st);
-    }
-    void* args[] = {&counter, &rounds, &max_spin, &err, &out};
-    return hipLaunchCooperativeKernel((const void*)barrier_probe_kernel, dim3(grid), dim3(256), args, 0, st);
+    if (which == 0)
+        hipLaunchKernelGGL(exchange_probe_kernel, dim3(grid), dim3(256), 0, st, buf, rounds, group, max_spin, err, out);
+    else
+        hipLaunchKernelGGL(barrier_probe_kernel, dim3(grid), dim3(256), 0, st, counter, rounds, max_spin, err, out);
+    return hipGetLastError();
 }
 
 // ---- helpers of the engine (kept local to this file: the two translation units share no device code)
@@ -587,17 +586,31 @@ bool resident_supported(scd_dtype dt, int order, const int64_t* dims)
     return dt == SCD_F32 && order == 2 && resident_shape(dims[0], dims[1], &tr, &tc);
 }
 
+template <int TR, int TC>
+static hipError_t launch_resident_t(const ResidentArgs& a, hipStream_t st)
+{
+    // All 256 workgroups must be resident at once.  One workgroup of 512 threads fits every compute
+    // unit (checked here against the occupancy the runtime reports); an ordinary launch on an idle
+    // device then places them all, and every wait in the kernel is bounded in case it does not.
+    int dev = 0, per_cu = 0;
+    hipDeviceProp_t prop;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipGetDeviceProperties(&prop, dev);
+    if (e == hipSuccess)
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, resident_kernel<TR, TC>, kResThreads, 0);
+    if (e != hipSuccess) return e;
+    if ((int64_t)per_cu * prop.multiProcessorCount < kResGrid * kResGrid) return hipErrorCooperativeLaunchTooLarge;
+    hipLaunchKernelGGL((resident_kernel<TR, TC>), dim3(kResGrid * kResGrid), dim3(kResThreads), 0, st, a);
+    return hipGetLastError();
+}
+
 hipError_t launch_resident(const ResidentArgs& a, hipStream_t st)
 {
     int tr = 0, tc = 0;
     if (!resident_shape(a.m, a.n, &tr, &tc)) return hipErrorInvalidValue;
-    ResidentArgs args = a;
-    void* kargs[] = {&args};
-    const void* fn = nullptr;
-    if (tr == 8 && tc == 16) fn = (const void*)resident_kernel<8, 16>;
-    else if (tr == 2 && tc == 16) fn = (const void*)resident_kernel<2, 16>;
-    else fn = (const void*)resident_kernel<4, 8>;
-    return hipLaunchCooperativeKernel(fn, dim3(kResGrid * kResGrid), dim3(kResThreads), kargs, 0, st);
+    if (tr == 8 && tc == 16) return launch_resident_t<8, 16>(a, st);
+    if (tr == 2 && tc == 16) return launch_resident_t<2, 16>(a, st);
+    return launch_resident_t<4, 8>(a, st);
 }
 
 }  // namespace scd
