@@ -421,7 +421,6 @@ __device__ __forceinline__ void tile_process(Tile<TE, CPT, RB>& t, TE* __restric
             const bool rok = FULL || (rb + r < r1);
             const int64_t rowc = rok ? rb + r : r1 - 1;
             const uint32_t sold = (t.rowsign >> r) & 1u;
-            TE f = 0;
 #pragma unroll
             for (int e = 0; e < NE; ++e) {
                 const uint32_t neg = sold ^ (uint32_t)((updb >> e) & 1ull);
@@ -444,9 +443,9 @@ __device__ __forceinline__ void tile_process(Tile<TE, CPT, RB>& t, TE* __restric
                     }
                 }
             }
+            // squares in f64: large entries must not overflow, small ones must not vanish
 #pragma unroll
-            for (int e = 0; e < NE; ++e) f += t.x[r][e] * t.x[r][e];
-            fsq += (double)f;
+            for (int e = 0; e < NE; ++e) fsq += (double)t.x[r][e] * (double)t.x[r][e];
         }
         TE p = 0;
 #pragma unroll

@@ -435,15 +435,13 @@ __global__ void __launch_bounds__(kResThreads) resident_kernel(ResidentArgs a)
 #pragma unroll
                 for (int r = 0; r < TR; ++r) {
                     const uint32_t sr = (uint32_t)lds_s[cur][tr * TR + r] << 31;
-                    float fr = 0.f;
 #pragma unroll
                     for (int c = 0; c < TC; ++c) {
                         // R_il - ck s_i t_l: the signs choose +ck or -ck
                         const float d = __uint_as_float(__float_as_uint(ckf) ^ sr ^ (__float_as_uint(tf[c]) & 0x80000000u));
                         x[r][c] = x[r][c] - d;
-                        fr += x[r][c] * x[r][c];
+                        f += (double)x[r][c] * (double)x[r][c];
                     }
-                    f += (double)fr;
                 }
                 f = wave_sum_res(f);
                 if (lane == 0) lds_red[wv] = f;
