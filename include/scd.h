@@ -132,12 +132,15 @@ int scd_last_hip_error(void);        /* hipError_t of the most recent SCD_EHIP o
 int scd_traffic(const scd_ctx* ctx, double* bytes, int64_t* passes, int64_t* sweeps);
 
 /* Which engine scd_run uses for this context: 0 = a stream of launches that re-read the remainder from
- * memory every alternation (any shape); 1 = one persistent launch that keeps the whole remainder in
- * the register files of a 16 x 16 grid of workgroups (f32 matrices of 1024x4096, 2048x2048, 4096x4096;
- * switched off by the environment variable SCD_RESIDENT=0).  For engine 1 also the duration of the
- * most recent launch by HIP events on the context's stream and its algorithmic bytes: (alternations +
- * updates) * bytes of the remainder, what a streaming pass per alternation would move.  host pointers,
- * each may be NULL. */
+ * memory every alternation (any shape, dtype, order); 1 = one persistent launch that keeps the whole
+ * remainder in the register files of a 16 x 16 grid of workgroups (f32 matrices of 1024x4096, 2048x2048,
+ * 4096x4096; switched off by the environment variable SCD_RESIDENT=0); 2 = one persistent launch that
+ * caches R t and R^T s and updates them from the flipped signs only (Section 3.1; f32/f64 matrices with
+ * 8 <= m, n <= 65536 whose rows and columns are multiples of 16 bytes; keeps a transposed copy of the
+ * remainder; switched off by SCD_SPARSE=0).  For engines 1 and 2 also the duration of the most recent
+ * launch by HIP events on the context's stream and its dense-equivalent bytes: (alternations + updates)
+ * * bytes of the remainder, what a streaming pass per alternation would move.  host pointers, each may
+ * be NULL. */
 int scd_engine(const scd_ctx* ctx, int* engine, double* last_launch_seconds, double* last_launch_bytes);
 
 /* Measurement: run n (<= 4096) further sweeps of the greedy loop with a HIP event before and after

@@ -9,7 +9,8 @@ from pathlib import Path
 
 PKG = Path(__file__).resolve().parent
 ROOT = PKG.parent
-SRC = [PKG / "csrc" / "scd_kernels.hip", PKG / "csrc" / "scd_resident.hip", PKG / "csrc" / "scd_api.hip"]
+SRC = [PKG / "csrc" / "scd_kernels.hip", PKG / "csrc" / "scd_resident.hip", PKG / "csrc" / "scd_sparse.hip",
+       PKG / "csrc" / "scd_api.hip"]
 LIB = PKG / "libscd.so"
 
 FLAGS = [

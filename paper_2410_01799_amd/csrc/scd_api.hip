@@ -92,6 +92,14 @@ struct scd_ctx {
     ResidentResult* res_pin = nullptr;
     uint32_t seq_u = 0, seq_v = 0;
     int max_spin = 1 << 22;
+    // sparse engine
+    bool sparse = false;
+    bool rt_stale = true;           // RT does not mirror R (R was changed by the launch-stream kernels)
+    void* RT = nullptr;
+    uint64_t* xbuf_sp = nullptr;
+    uint32_t seq_sp = 0;
+    int rs = 0, cs = 0;
+    int64_t flips = 0;
     hipEvent_t ev0 = nullptr, ev1 = nullptr;  // around the engine's launch
     double last_launch_seconds = 0.0;
     double last_launch_bytes = 0.0;
@@ -270,6 +278,7 @@ bool dtype_ok(int dt) { return dt == SCD_F32 || dt == SCD_F64; }
 // resident engine advanced the context.
 int resync_stream_state(scd_ctx* c)
 {
+    c->rt_stale = true;  // the caller is about to let the launch-stream kernels change R
     if (!c->stream_stale) return SCD_OK;
     c->hs.w_target = c->hs.k;
     c->hs.done = 0;
@@ -281,6 +290,67 @@ int resync_stream_state(scd_ctx* c)
     SCD_TRY(launch_sweep(c));
     SCD_TRY(read_state(c));
     c->stream_stale = false;
+    return SCD_OK;
+}
+
+// n terms in one persistent launch that updates the cached products from the flipped signs only.
+int run_sparse(scd_ctx* c, int64_t n)
+{
+    if (c->rt_stale) {
+        HIP_TRY(launch_transpose(c->R, c->RT, c->dt, c->dims[0], c->dims[1], c->stream));
+        c->rt_stale = false;
+    }
+    SparseArgs a;
+    memset(&a, 0, sizeof(a));
+    a.R = c->R;
+    a.RT = c->RT;
+    a.m = c->dims[0];
+    a.n = c->dims[1];
+    a.seed = c->seed;
+    a.k_start = c->hs.k;
+    a.w_target = c->hs.k + n;
+    a.max_iters = c->hs.max_iters;
+    a.max_spin = c->max_spin;
+    a.poll_delay = env_int("SCD_SPARSE_POLL_DELAY", 16);
+    a.seq = c->seq_sp;
+    a.xbuf = c->xbuf_sp;
+    a.S = c->out_signs[0];
+    a.T = c->out_signs[1];
+    a.c = c->c_out;
+    a.iters = c->iters;
+    a.trace = c->trace;
+    a.mw = (int32_t)words_for(c->dims[0]);
+    a.nw = (int32_t)words_for(c->dims[1]);
+    a.rs = c->rs;
+    a.cs = c->cs;
+    a.res = c->res_dev;
+    HIP_TRY(hipMemsetAsync(c->res_dev, 0, sizeof(ResidentResult), c->stream));
+    HIP_TRY(hipEventRecord(c->ev0, c->stream));
+    HIP_TRY(launch_sparse(a, c->dt, c->stream));
+    HIP_TRY(hipEventRecord(c->ev1, c->stream));
+    HIP_TRY(hipMemcpyAsync(c->res_pin, c->res_dev, sizeof(ResidentResult), hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(hipStreamSynchronize(c->stream));
+    const ResidentResult r = *c->res_pin;
+    {
+        float ms = 0.f;
+        HIP_TRY(hipEventElapsedTime(&ms, c->ev0, c->ev1));
+        c->last_launch_seconds = (double)ms * 1e-3;
+        c->last_launch_bytes = ((double)r.alternations + (double)r.updates) * (double)c->total * (double)c->esize;
+    }
+    if (r.err || r.k != a.w_target) {
+        c->broken = true;
+        return SCD_ETIMEOUT;
+    }
+    if (env_int("SCD_RESIDENT_VERBOSE", 0))
+        fprintf(stderr, "[scd sparse] terms %lld alternations %lld flips %lld re-reads %lld\n", (long long)n,
+                (long long)r.alternations, (long long)r.flips, (long long)r.spins);
+    c->seq_sp = r.seq_u;
+    c->flips += r.flips;
+    c->hs.k = r.k;
+    c->hs.passes += r.alternations;
+    c->hs.updates += r.updates;
+    if (r.warn) c->hs.warn = 1;
+    c->stream_stale = true;
     return SCD_OK;
 }
 
@@ -451,6 +521,25 @@ int scd_create(scd_ctx** out, const void* A, scd_dtype dt, int order, const int6
         CHIP(hipEventCreate(&c->ev0));
         CHIP(hipEventCreate(&c->ev1));
     }
+    c->sparse = !c->resident && env_int("SCD_SPARSE", 1) != 0 && sparse_supported(dt, order, dims, &c->rs, &c->cs);
+    if (c->sparse) {
+        // the transpose doubles the footprint: without room for it the launch-stream engine serves
+        hipError_t e = hipMalloc(&c->RT, (size_t)total * c->esize);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            c->RT = nullptr;
+            c->sparse = false;
+        } else {
+            c->allocs.push_back(c->RT);
+            CTRY(dev_alloc(c, (void**)&c->xbuf_sp, sparse_xbuf_bytes()));
+            CHIP(hipMemsetAsync(c->xbuf_sp, 0, sparse_xbuf_bytes(), c->stream));
+            CTRY(dev_alloc(c, (void**)&c->res_dev, sizeof(ResidentResult)));
+            CHIP(hipHostMalloc((void**)&c->res_pin, sizeof(ResidentResult), hipHostMallocDefault));
+            c->max_spin = env_int("SCD_RESIDENT_MAX_SPIN", 1 << 22);
+            CHIP(hipEventCreate(&c->ev0));
+            CHIP(hipEventCreate(&c->ev1));
+        }
+    }
     c->ncparts = (int)words_for(dims[order - 1]);
     CTRY(dev_alloc(c, (void**)&c->cparts, (size_t)c->ncparts * 8));
     CHIP(hipMemsetAsync(c->cparts, 0, (size_t)c->ncparts * 8, c->stream));
@@ -501,8 +590,8 @@ int scd_run(scd_ctx* c, int64_t n)
     if (c->broken) return SCD_ETIMEOUT;
     if (n == 0) return c->hs.warn ? SCD_WMAXITER : SCD_OK;
     if (c->hs.k + n > c->w_capacity) return SCD_EFULL;
-    if (c->resident) {
-        SCD_TRY(run_resident(c, n));
+    if (c->resident || c->sparse) {
+        SCD_TRY(c->resident ? run_resident(c, n) : run_sparse(c, n));
         return c->hs.warn ? SCD_WMAXITER : SCD_OK;
     }
     c->hs.w_target = c->hs.k + n;
@@ -577,6 +666,7 @@ int scd_set_remainder(scd_ctx* c, const void* R_in)
 {
     if (!c || !R_in) return SCD_EINVAL;
     c->stream_stale = false;  // the start pass below rebuilds the launch-stream state
+    c->rt_stale = true;
     c->broken = false;
     HIP_TRY(hipMemcpyAsync(c->R, R_in, (size_t)c->total * c->esize, hipMemcpyDeviceToDevice, c->stream));
     c->hs.w_target = c->hs.k;
@@ -597,7 +687,7 @@ int scd_set_remainder(scd_ctx* c, const void* R_in)
 int scd_engine(const scd_ctx* c, int* engine, double* last_launch_seconds, double* last_launch_bytes)
 {
     if (!c) return SCD_EINVAL;
-    if (engine) *engine = c->resident ? 1 : 0;
+    if (engine) *engine = c->resident ? 1 : (c->sparse ? 2 : 0);
     if (last_launch_seconds) *last_launch_seconds = c->last_launch_seconds;
     if (last_launch_bytes) *last_launch_bytes = c->last_launch_bytes;
     return SCD_OK;

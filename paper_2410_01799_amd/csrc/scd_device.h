@@ -115,6 +115,7 @@ struct ResidentResult {
     int32_t err;           // 1: a bounded wait ran out
     int32_t warn;          // a term ended on max_iters
     int64_t spins;         // re-reads of stale exchange data by thread 0 of workgroup 0 (diagnostic)
+    int64_t flips;         // sparse engine: sign changes processed (rows + columns)
 };
 
 struct ResidentArgs {
@@ -137,6 +138,35 @@ struct ResidentArgs {
 
 bool resident_supported(scd_dtype dt, int order, const int64_t* dims);
 hipError_t launch_resident(const ResidentArgs& a, hipStream_t st);
+
+// Sparse engine (scd_sparse.hip): cached products updated from the flipped signs only; keeps R and its
+// transpose in HBM.
+constexpr int kSpGrid = 256;  // workgroups of the persistent launch
+
+struct SparseArgs {
+    void* R;                 // m x n
+    void* RT;                // n x m, the transpose, kept in step with R
+    int64_t m, n;
+    uint64_t seed;
+    int64_t k_start, w_target;
+    int32_t max_iters, max_spin;
+    int32_t poll_delay;
+    uint32_t seq;            // exchange sequence numbers already used
+    uint64_t* xbuf;          // sparse_xbuf_bytes()
+    uint64_t* S;
+    uint64_t* T;
+    void* c;
+    int32_t* iters;
+    double* trace;
+    int32_t mw, nw;
+    int32_t rs, cs;          // rows / columns owned per workgroup (multiples of 8)
+    ResidentResult* res;
+};
+
+bool sparse_supported(scd_dtype dt, int order, const int64_t* dims, int* rs, int* cs);
+size_t sparse_xbuf_bytes();
+hipError_t launch_sparse(const SparseArgs& a, scd_dtype dt, hipStream_t st);
+hipError_t launch_transpose(const void* in, void* out, scd_dtype dt, int64_t rows, int64_t cols, hipStream_t st);
 
 // ---- launchers implemented in scd_kernels.hip ----------------------------------------------------
 hipError_t launch_rowpass(const RowPassArgs& a, scd_dtype dt, int grid, int variant, hipStream_t st);

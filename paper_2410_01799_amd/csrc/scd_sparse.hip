@@ -1,0 +1,607 @@
+// Cached, sparsified alternation (Section 3.1 of arXiv 2410.01799) as one persistent launch.
+//
+// After the first alternation of a term only a few signs change per alternation, so
+//     R t_j     = R t_{j-1}     + 2 * sum over flipped columns l of t_j[l] * R[:, l]
+//     R^T s_j   = R^T s_{j-1}   + 2 * sum over flipped rows    i of s_j[i] * R[i, :]
+// and an alternation touches a few per cent of the matrix instead of all of it.  The paper keeps the
+// matrix and its transpose so that both kinds of slices are contiguous; so does this engine (R and RT
+// in HBM, both updated when a term is subtracted).
+//
+// 256 workgroups, one per compute unit.  Workgroup g owns the slice I_g of the rows (its entries of
+// u = R t) and the slice J_g of the columns (its entries of v = R^T s), in f64.
+//   term start   dense: rows I_g of R   -> subtract the finished term (Algorithm 5 line 10), ||R||^2,
+//                        u = R t_0; all-gather of s;   rows J_g of RT -> subtract, v = R^T s; all-gather of t
+//   afterwards   sparse: u[I_g] += 2 sum_f +-RT[l_f][I_g]; all-gather of s;
+//                        v[J_g] += 2 sum_f +-R[i_f][J_g];  all-gather of t and of the shares of c
+// The all-gather is the tagged exchange of the register-resident engine (one 8-byte relaxed
+// agent-scope store per word: 32 payload bits + 32-bit sequence number; readers poll with loads that
+// bypass the non-coherent caches; slots alternate by sequence parity; every wait is bounded).
+// Flipped indices are compacted in ascending order and added in a fixed order: results are
+// bit-identical from run to run.
+#include "scd_device.h"
+
+namespace scd {
+
+namespace {
+
+constexpr int kSpThreads = 512;
+constexpr int kSpWaves = kSpThreads / kWave;
+constexpr int kSpPayload = 16;                    // payload words per slot (32 sign bits each)
+constexpr int kSpSlot = kSpPayload + 4;           // + two doubles as four tagged halves
+constexpr int kSpListCap = 32 * kSpThreads;       // flips handled per compaction round: one 32-bit word per thread
+constexpr int kSpMaxItems = (kSpGrid * kSpSlot + kSpThreads - 1) / kSpThreads;
+
+__device__ __forceinline__ uint64_t sp_mix64(uint64_t z)
+{
+    // SplitMix64 finaliser
+    z ^= z >> 30;
+    z *= 0xBF58476D1CE4E5B9ull;
+    z ^= z >> 27;
+    z *= 0x94D049BB133111EBull;
+    z ^= z >> 31;
+    return z;
+}
+
+__device__ __forceinline__ uint64_t sp_rng_word(uint64_t seed, uint64_t term, uint32_t mode, uint64_t word)
+{
+    uint64_t h = sp_mix64(seed ^ (0x9E3779B97F4A7C15ull * (term + 1)));
+    h = sp_mix64(h + 0xD1B54A32D192ED03ull * ((uint64_t)mode + 1));
+    h = sp_mix64(h + 0x8CB92BA72F3D8DD7ull * (word + 1));
+    return h;
+}
+
+__device__ __forceinline__ double sp_wave_sum(double a)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) a += __shfl_xor(a, off, kWave);
+    return a;
+}
+
+__device__ __forceinline__ uint32_t sp_bits4(const uint32_t* bits, int64_t col)
+{
+    // the bits of `col .. col+3` (col is a multiple of 4, so they sit in one word)
+    return (bits[col >> 5] >> (col & 31)) & 0xFu;
+}
+
+template <typename TE>
+struct SpVec;
+template <>
+struct SpVec<float> {
+    typedef float4 type;
+    static constexpr int N = 4;
+};
+template <>
+struct SpVec<double> {
+    typedef double2 type;
+    static constexpr int N = 2;
+};
+
+__device__ __forceinline__ float sp_flip(float x, uint32_t neg) { return __uint_as_float(__float_as_uint(x) ^ (neg << 31)); }
+__device__ __forceinline__ double sp_flip(double x, uint32_t neg)
+{
+    return __longlong_as_double(__double_as_longlong(x) ^ ((long long)neg << 63));
+}
+
+// Shared-memory carve-up of one workgroup.
+struct SpShared {
+    uint32_t* sA;      // sign bits of the rows, two buffers (current / other)
+    uint32_t* sB;
+    uint32_t* tA;      // sign bits of the columns
+    uint32_t* tB;
+    uint16_t* list;    // compacted flips of one round: index within the round | new sign << 15
+    double* accu;      // u on I_g
+    double* accv;      // v on J_g
+    double* red;       // [kSpThreads] partial sums of the sparse accumulation / per-wave scratch
+    uint32_t* scal;    // [2][kSpGrid][2] gathered scalars (lo, hi halves)
+    int* scan;         // [kSpWaves + 1]
+};
+
+// Dense pass over `nrows` consecutive rows of Y (row length ld, a multiple of 16 bytes): optionally
+// subtract ck * rowsign * colsign, sum the squares, and form the signed row sums with `sumbits`.
+template <typename TE>
+__device__ void sp_dense_rows(TE* __restrict__ Y, int64_t ld, int64_t row0, int nrows, bool upd,
+                              const uint32_t* rowbits_upd, const uint32_t* colbits_upd, TE ck,
+                              const uint32_t* colbits_sum, double* acc, double& fsq_out, double* red)
+{
+    constexpr int VE = SpVec<TE>::N;
+    constexpr int RB = 4;
+    typedef typename SpVec<TE>::type V;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
+    const int64_t nch = ld / VE;
+    double fsq = 0.0;
+    for (int rb = 0; rb < nrows; rb += RB) {
+        double ps[RB];
+        uint32_t sr[RB];
+        V* rowp[RB];
+#pragma unroll
+        for (int r = 0; r < RB; ++r) {
+            const int rr = rb + r < nrows ? rb + r : nrows - 1;
+            const int64_t row = row0 + rr;
+            ps[r] = 0.0;
+            sr[r] = upd ? ((rowbits_upd[row >> 5] >> (row & 31)) & 1u) : 0u;
+            rowp[r] = (V*)(Y + row * ld);
+        }
+        for (int64_t c = tid; c < nch; c += kSpThreads) {
+            const int64_t col = c * VE;
+            const uint32_t bsum = sp_bits4(colbits_sum, col & ~3ll) >> (col & 3);
+            const uint32_t bupd = upd ? (sp_bits4(colbits_upd, col & ~3ll) >> (col & 3)) : 0u;
+            V v[RB];
+#pragma unroll
+            for (int r = 0; r < RB; ++r) v[r] = rowp[r][c];
+#pragma unroll
+            for (int r = 0; r < RB; ++r) {
+                if (rb + r >= nrows) continue;
+                TE x[VE];
+                if constexpr (VE == 4) {
+                    x[0] = v[r].x; x[1] = v[r].y; x[2] = v[r].z; x[3] = v[r].w;
+                } else {
+                    x[0] = v[r].x; x[1] = v[r].y;
+                }
+                if (upd) {
+#pragma unroll
+                    for (int e = 0; e < VE; ++e) x[e] = x[e] - sp_flip(ck, sr[r] ^ ((bupd >> e) & 1u));
+                    V o;
+                    if constexpr (VE == 4) o = V{x[0], x[1], x[2], x[3]};
+                    else o = V{x[0], x[1]};
+                    rowp[r][c] = o;
+#pragma unroll
+                    for (int e = 0; e < VE; ++e) fsq += (double)x[e] * (double)x[e];
+                }
+#pragma unroll
+                for (int e = 0; e < VE; ++e) ps[r] += (double)sp_flip(x[e], (bsum >> e) & 1u);
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < RB; ++r) ps[r] = sp_wave_sum(ps[r]);
+        __syncthreads();  // `red` may still be read from the previous batch
+        if (lane == 0) {
+#pragma unroll
+            for (int r = 0; r < RB; ++r) red[wv * RB + r] = ps[r];
+        }
+        __syncthreads();
+        if (tid < RB && rb + tid < nrows) {
+            double s = 0.0;
+            for (int q = 0; q < kSpWaves; ++q) s += red[q * RB + tid];
+            acc[rb + tid] = s;
+        }
+    }
+    // squares: per-wave sums, then in wave order
+    fsq = sp_wave_sum(fsq);
+    __syncthreads();
+    if (lane == 0) red[wv] = fsq;
+    __syncthreads();
+    double f = 0.0;
+    for (int q = 0; q < kSpWaves; ++q) f += red[q];
+    fsq_out = f;
+    __syncthreads();
+}
+
+// acc[e] += 2 * sum over the indices i whose sign changed (cur xor prev) of sign_cur(i) * Y[i][off + e],
+// e < len.  Flipped indices are compacted in ascending order, one 32-bit word of sign bits per thread
+// and round, and every thread adds its share of the list in order.
+template <typename TE>
+__device__ void sp_accumulate_flips(const TE* __restrict__ Y, int64_t ld, int64_t off, int len, const uint32_t* cur,
+                                    const uint32_t* prev, int64_t nbits, double* acc, SpShared& sh, int64_t& nflips)
+{
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
+    int slp = 16;
+    while (slp < len) slp <<= 1;  // lanes per flip: power of two >= len (len <= kSpThreads)
+    const int Q = kSpThreads / slp;
+    const int e = tid & (slp - 1), q = tid / slp;
+    const bool active = e < len;
+    const TE* ycol = Y + off + e;
+    double part = 0.0;
+    const int64_t nwords = (nbits + 31) >> 5;
+    for (int64_t w0 = 0; w0 < nwords; w0 += kSpThreads) {
+        // ---- compaction of this round's flips
+        const int64_t wi = w0 + tid;
+        const uint32_t cw = wi < nwords ? cur[wi] : 0u;
+        const uint32_t x = wi < nwords ? (cw ^ prev[wi]) : 0u;
+        const int cnt = __popc(x);
+        int incl = cnt;
+#pragma unroll
+        for (int d = 1; d < kWave; d <<= 1) {
+            const int o = __shfl_up(incl, d, kWave);
+            if (lane >= d) incl += o;
+        }
+        __syncthreads();  // the list and the scan cells of the previous round are free
+        if (lane == kWave - 1) sh.scan[wv + 1] = incl;
+        __syncthreads();
+        int base = 0;
+        for (int i = 0; i < wv; ++i) base += sh.scan[i + 1];
+        int total = 0;
+        for (int i = 0; i < kSpWaves; ++i) total += sh.scan[i + 1];
+        int pos = base + incl - cnt;
+        uint32_t bits = x;
+        while (bits) {
+            const int b = __ffs(bits) - 1;
+            bits &= bits - 1;
+            sh.list[pos++] = (uint16_t)((tid * 32 + b) | (((cw >> b) & 1u) << 15));
+        }
+        __syncthreads();
+        nflips += total;
+        // ---- gather: thread (e, q) takes flips q, q+Q, ... ; four loads in flight
+        if (active) {
+            const int64_t ibase = w0 * 32;
+            int f = q;
+            for (; f + 3 * Q < total; f += 4 * Q) {
+                uint16_t en[4];
+                TE val[4];
+#pragma unroll
+                for (int z = 0; z < 4; ++z) en[z] = sh.list[f + z * Q];
+#pragma unroll
+                for (int z = 0; z < 4; ++z) val[z] = ycol[(ibase + (en[z] & 0x3FFF)) * ld];
+#pragma unroll
+                for (int z = 0; z < 4; ++z) part += (double)sp_flip(val[z], (uint32_t)(en[z] >> 15));
+            }
+            for (; f < total; f += Q) {
+                const uint16_t en = sh.list[f];
+                part += (double)sp_flip(ycol[(ibase + (en & 0x3FFF)) * ld], (uint32_t)(en >> 15));
+            }
+        }
+    }
+    __syncthreads();
+    sh.red[tid] = part;
+    __syncthreads();
+    if (tid < len) {
+        double s = 0.0;
+        for (int z = 0; z < Q; ++z) s += sh.red[z * slp + tid];
+        acc[tid] += 2.0 * s;
+    }
+    __syncthreads();
+}
+
+__device__ __forceinline__ void sp_store_tagged(uint64_t* p, uint32_t v, uint32_t seq)
+{
+    __hip_atomic_store(p, ((uint64_t)seq << 32) | (uint64_t)v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Publish this workgroup's slice of sign bits (taken from acc < 0) and two scalars, then read every
+// workgroup's: the full bit vector lands in `dest`, the scalars in sh.scal.  Returns false on time-out.
+// `fence`: this exchange also hands over ordinary data (the rows of R or RT this workgroup has just
+// rewritten): the writes are released to the whole device before anything is published, and the
+// caches are invalidated after the gather, because the L2 of one XCD does not see another's writes.
+__device__ bool sp_exchange(const SparseArgs& a, uint32_t seq, const double* acc, int len, int slice, int64_t total_bits,
+                            double sc0, double sc1, uint32_t* dest, SpShared& sh, int& spins, bool fence)
+{
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
+    const int g = blockIdx.x;
+    if (fence) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+        __syncthreads();
+    }
+    uint64_t* mine = a.xbuf + ((size_t)(seq & 1u) * kSpGrid + g) * kSpSlot;
+    const int words = (slice + 31) >> 5;  // payload words every workgroup publishes
+    // ---- publish: one ballot per 64 slice entries
+    for (int b = wv * kWave; b < slice; b += kSpThreads) {
+        const int e = b + lane;
+        const uint64_t bal = __ballot(e < len && acc[e] < 0.0);
+        if (lane == 0) {
+            sp_store_tagged(mine + (b >> 5), (uint32_t)bal, seq);
+            if (b + 32 < slice) sp_store_tagged(mine + (b >> 5) + 1, (uint32_t)(bal >> 32), seq);
+        }
+    }
+    if (tid == kSpThreads - 1) {
+        const uint64_t b0 = (uint64_t)__double_as_longlong(sc0), b1 = (uint64_t)__double_as_longlong(sc1);
+        sp_store_tagged(mine + kSpPayload + 0, (uint32_t)b0, seq);
+        sp_store_tagged(mine + kSpPayload + 1, (uint32_t)(b0 >> 32), seq);
+        sp_store_tagged(mine + kSpPayload + 2, (uint32_t)b1, seq);
+        sp_store_tagged(mine + kSpPayload + 3, (uint32_t)(b1 >> 32), seq);
+    }
+    for (int d = 0; d < a.poll_delay; ++d) __builtin_amdgcn_s_sleep(1);
+    // ---- gather: (words + 4) items from each of the kSpGrid members, spread over the threads
+    const int per = words + 4;
+    const int items = kSpGrid * per;
+    uint64_t w[kSpMaxItems];
+    const uint64_t* xb = a.xbuf + (size_t)(seq & 1u) * kSpGrid * kSpSlot;
+    bool ok = true;
+    int spin = 0;
+    for (;;) {
+        bool fresh = true;
+#pragma unroll
+        for (int it = 0; it < kSpMaxItems; ++it) {
+            const int idx = tid + it * kSpThreads;
+            if (idx < items) {
+                const int mem = idx / per, k = idx - mem * per;
+                const int word = k < words ? k : kSpPayload + (k - words);
+                w[it] = __hip_atomic_load(xb + (size_t)mem * kSpSlot + word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+#pragma unroll
+        for (int it = 0; it < kSpMaxItems; ++it) {
+            const int idx = tid + it * kSpThreads;
+            if (idx < items) fresh = fresh && ((uint32_t)(w[it] >> 32) == seq);
+        }
+        if (fresh) break;
+        if (++spin > a.max_spin) {
+            ok = false;
+            break;
+        }
+        __builtin_amdgcn_s_sleep(1);
+    }
+    spins += spin;
+    if (fence) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    if (ok) {
+        uint8_t* dbytes = (uint8_t*)dest;
+        const int sbytes = slice >> 3;                      // bytes of one member's slice (slice is a multiple of 8)
+        const int64_t tbytes = (total_bits + 7) >> 3;
+#pragma unroll
+        for (int it = 0; it < kSpMaxItems; ++it) {
+            const int idx = tid + it * kSpThreads;
+            if (idx < items) {
+                const int mem = idx / per, k = idx - mem * per;
+                const uint32_t v = (uint32_t)w[it];
+                if (k < words) {
+                    const int64_t b0 = (int64_t)mem * sbytes + 4 * k;
+#pragma unroll
+                    for (int b = 0; b < 4; ++b)
+                        if (4 * k + b < sbytes && b0 + b < tbytes) dbytes[b0 + b] = (uint8_t)(v >> (8 * b));
+                } else {
+                    const int z = k - words;  // 0,1: first scalar lo/hi; 2,3: second
+                    sh.scal[((z >> 1) * kSpGrid + mem) * 2 + (z & 1)] = v;
+                }
+            }
+        }
+    }
+    return !__syncthreads_or(ok ? 0 : 1);
+}
+
+// Sum of one gathered scalar over the members, in a fixed order; every thread gets the same bits.
+__device__ double sp_sum_scalar(const SpShared& sh, int which, double* scratch)
+{
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    if (tid < kWave) {
+        double s = 0.0;
+        for (int g = lane; g < kSpGrid; g += kWave) {
+            const uint32_t lo = sh.scal[(which * kSpGrid + g) * 2], hi = sh.scal[(which * kSpGrid + g) * 2 + 1];
+            s += __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
+        }
+        s = sp_wave_sum(s);
+        if (lane == 0) scratch[0] = s;
+    }
+    __syncthreads();
+    const double r = scratch[0];
+    __syncthreads();
+    return r;
+}
+
+template <typename TE>
+__global__ void __launch_bounds__(kSpThreads) sparse_kernel(SparseArgs a)
+{
+    extern __shared__ __align__(16) unsigned char sp_lds[];
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
+    const int g = blockIdx.x;
+    const int64_t m = a.m, n = a.n;
+    const int64_t mwords32 = (m + 31) >> 5, nwords32 = (n + 31) >> 5;
+
+    SpShared sh;
+    {
+        size_t o = 0;
+        auto take = [&](size_t bytes) {
+            unsigned char* p = sp_lds + o;
+            o += (bytes + 15) & ~(size_t)15;
+            return p;
+        };
+        sh.sA = (uint32_t*)take((size_t)mwords32 * 4 + 8);
+        sh.sB = (uint32_t*)take((size_t)mwords32 * 4 + 8);
+        sh.tA = (uint32_t*)take((size_t)nwords32 * 4 + 8);
+        sh.tB = (uint32_t*)take((size_t)nwords32 * 4 + 8);
+        sh.list = (uint16_t*)take((size_t)kSpListCap * 2);
+        sh.accu = (double*)take((size_t)kSpThreads * 8);
+        sh.accv = (double*)take((size_t)kSpThreads * 8);
+        sh.red = (double*)take((size_t)kSpThreads * 8);
+        sh.scal = (uint32_t*)take((size_t)2 * kSpGrid * 2 * 4);
+        sh.scan = (int*)take((size_t)(kSpWaves + 1) * 4);
+    }
+    for (int64_t i = tid; i < mwords32 + 2; i += kSpThreads) {
+        sh.sA[i] = 0;
+        sh.sB[i] = 0;
+    }
+    for (int64_t i = tid; i < nwords32 + 2; i += kSpThreads) {
+        sh.tA[i] = 0;
+        sh.tB[i] = 0;
+    }
+    __syncthreads();
+    uint32_t *s_cur = sh.sA, *s_oth = sh.sB, *t_cur = sh.tA, *t_oth = sh.tB;
+
+    const int rs = a.rs, cs = a.cs;
+    const int64_t i0 = (int64_t)g * rs < m ? (int64_t)g * rs : m;
+    const int rlen = (int)((i0 + rs < m ? i0 + rs : m) - i0);
+    const int64_t j0 = (int64_t)g * cs < n ? (int64_t)g * cs : n;
+    const int clen = (int)((j0 + cs < n ? j0 + cs : n) - j0);
+    TE* R = (TE*)a.R;
+    TE* RT = (TE*)a.RT;
+    const double total = (double)m * (double)n;
+
+    int64_t k = a.k_start;
+    uint32_t seq = a.seq;
+    int alternations = 0, updates = 0, warn = 0, spins = 0;
+    int64_t flips = 0;
+    bool pending = false;  // a finished term waits to be subtracted
+    double ck = 0.0;
+
+    for (;;) {
+        if (k >= a.w_target && !pending) break;
+        // ================= start of term k (dense): subtract the finished term, first alternation
+        // t_0 from the keyed stream (Algorithm 4 line 2), into the other column buffer
+        for (int64_t i = tid; i < nwords32; i += kSpThreads) {
+            uint32_t v = (uint32_t)(sp_rng_word(a.seed, (uint64_t)k, 1u, (uint64_t)(i >> 1)) >> (32 * (i & 1)));
+            const int64_t rem = n - i * 32;
+            if (rem < 32) v &= (1u << rem) - 1u;
+            t_oth[i] = v;
+        }
+        __syncthreads();
+        const TE ckt = (TE)ck;
+        double fsq = 0.0, dummy = 0.0;
+        // rows I_g of R: R <- R - ck s t^T (Algorithm 5 line 10), squares, u = R t_0 (Algorithm 4 line 5)
+        if (rlen > 0) sp_dense_rows<TE>(R, n, i0, rlen, pending, s_cur, t_cur, ckt, t_oth, sh.accu, fsq, sh.red);
+        const bool was_pending = pending;
+        if (!sp_exchange(a, ++seq, sh.accu, rlen, rs, m, fsq, 0.0, s_oth, sh, spins, was_pending)) {
+            if (tid == 0) atomicExch((unsigned*)&a.res->err, 1u);
+            return;
+        }
+        ++alternations;
+        if (pending) {
+            const double F = sp_sum_scalar(sh, 0, sh.red);
+            if (g == 0 && tid == 0) a.trace[k] = sqrt(F);
+        }
+        // rows J_g of RT (columns of R): same update, v = R^T s_1 (Algorithm 4 line 6)
+        const bool last = k >= a.w_target;
+        if (clen > 0 && (pending || !last))
+            sp_dense_rows<TE>(RT, m, j0, clen, pending, t_cur, s_cur, ckt, s_oth, sh.accv, dummy, sh.red);
+        if (pending) ++updates;
+        pending = false;
+        if (last) break;
+        // the old term's signs are dead: s_cur <- s_1, t_cur <- t_0
+        {
+            uint32_t* z = s_cur; s_cur = s_oth; s_oth = z;
+            z = t_cur; t_cur = t_oth; t_oth = z;
+        }
+        int j = 0;
+        double c_prev = -INFINITY;
+        bool handover = was_pending;  // RT was rewritten: the next exchange carries the fences
+        for (;;) {
+            // ---- finish the column half: t = sgn(v), c = sum |v| (Algorithm 4 lines 6-7), all-gather
+            double cabs = (tid < clen) ? fabs(sh.accv[tid]) : 0.0;
+            cabs = sp_wave_sum(cabs);
+            __syncthreads();
+            if (lane == 0) sh.red[wv] = cabs;
+            __syncthreads();
+            double cpart = 0.0;
+            for (int q = 0; q < kSpWaves; ++q) cpart += sh.red[q];
+            __syncthreads();
+            if (!sp_exchange(a, ++seq, sh.accv, clen, cs, n, cpart, 0.0, t_oth, sh, spins, handover)) {
+                if (tid == 0) atomicExch((unsigned*)&a.res->err, 1u);
+                return;
+            }
+            handover = false;
+            {
+                uint32_t* z = t_cur; t_cur = t_oth; t_oth = z;  // t_cur = t_j, t_oth = t_{j-1}
+            }
+            ++j;
+            const double c = sp_sum_scalar(sh, 0, sh.red);
+            // ---- Algorithm 4 line 8
+            if (c <= c_prev || j >= a.max_iters) {
+                if (!(c <= c_prev)) warn = 1;
+                ck = c / total;
+                if (g == 0) {
+                    for (int p = tid; p < a.mw; p += kSpThreads)
+                        a.S[k * a.mw + p] = (uint64_t)s_cur[2 * p] | ((uint64_t)(2 * p + 1 < mwords32 ? s_cur[2 * p + 1] : 0u) << 32);
+                    if (tid == 0) {
+                        ((TE*)a.c)[k] = (TE)ck;
+                        a.iters[k] = j;
+                    }
+                }
+                if (g == 1 % kSpGrid) {
+                    for (int p = tid; p < a.nw; p += kSpThreads)
+                        a.T[k * a.nw + p] = (uint64_t)t_cur[2 * p] | ((uint64_t)(2 * p + 1 < nwords32 ? t_cur[2 * p + 1] : 0u) << 32);
+                }
+                pending = true;
+                ++k;
+                break;
+            }
+            c_prev = c;
+            // ---- row half, sparse: u += 2 sum over flipped columns (rows of RT), s = sgn(u), all-gather
+            sp_accumulate_flips<TE>(RT, m, i0, rlen, t_cur, t_oth, n, sh.accu, sh, flips);
+            if (!sp_exchange(a, ++seq, sh.accu, rlen, rs, m, 0.0, 0.0, s_oth, sh, spins, false)) {
+                if (tid == 0) atomicExch((unsigned*)&a.res->err, 1u);
+                return;
+            }
+            {
+                uint32_t* z = s_cur; s_cur = s_oth; s_oth = z;  // s_cur = s_{j+1}
+            }
+            ++alternations;
+            // ---- column half, sparse: v += 2 sum over flipped rows (rows of R)
+            sp_accumulate_flips<TE>(R, n, j0, clen, s_cur, s_oth, m, sh.accv, sh, flips);
+        }
+    }
+    if (g == 0 && tid == 0) {
+        a.res->k = k;
+        a.res->alternations = alternations;
+        a.res->updates = updates;
+        a.res->seq_u = seq;
+        a.res->seq_v = seq;
+        a.res->warn = warn;
+        a.res->spins = spins;
+        a.res->flips = flips;
+    }
+}
+
+// out (cols x rows) = in^T (rows x cols), 32 x 32 tiles through LDS
+template <typename TE>
+__global__ void __launch_bounds__(256) transpose_kernel(const TE* __restrict__ in, TE* __restrict__ out, int64_t rows,
+                                                        int64_t cols)
+{
+    __shared__ TE tile[32][33];
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
+    const int64_t c0 = (int64_t)blockIdx.x * 32, r0 = (int64_t)blockIdx.y * 32;
+    for (int i = ty; i < 32; i += 8)
+        if (r0 + i < rows && c0 + tx < cols) tile[i][tx] = in[(r0 + i) * cols + c0 + tx];
+    __syncthreads();
+    for (int i = ty; i < 32; i += 8)
+        if (c0 + i < cols && r0 + tx < rows) out[(c0 + i) * rows + r0 + tx] = tile[tx][i];
+}
+
+size_t sparse_lds_bytes(int64_t m, int64_t n)
+{
+    auto al = [](size_t b) { return (b + 15) & ~(size_t)15; };
+    const size_t mw = (size_t)((m + 31) >> 5), nw = (size_t)((n + 31) >> 5);
+    return 2 * al(mw * 4 + 8) + 2 * al(nw * 4 + 8) + al((size_t)kSpListCap * 2) + 3 * al((size_t)kSpThreads * 8) +
+           al((size_t)2 * kSpGrid * 2 * 4) + al((size_t)(kSpWaves + 1) * 4);
+}
+
+}  // namespace
+
+bool sparse_supported(scd_dtype dt, int order, const int64_t* dims, int* rs, int* cs)
+{
+    if (order != 2) return false;
+    const int64_t m = dims[0], n = dims[1];
+    const int ve = dt == SCD_F32 ? 4 : 2;
+    if (m % ve || n % ve) return false;               // rows of R and of RT start on 16-byte boundaries
+    if (m > 65536 || n > 65536 || m < 8 || n < 8) return false;
+    const int r = (int)(8 * ((m + 8 * kSpGrid - 1) / (8 * kSpGrid)));
+    const int c = (int)(8 * ((n + 8 * kSpGrid - 1) / (8 * kSpGrid)));
+    if (r > kSpThreads || c > kSpThreads) return false;
+    if (r > 32 * kSpPayload || c > 32 * kSpPayload) return false;
+    if (sparse_lds_bytes(m, n) > 150 * 1024) return false;
+    if (rs) *rs = r;
+    if (cs) *cs = c;
+    return true;
+}
+
+size_t sparse_xbuf_bytes() { return (size_t)2 * kSpGrid * kSpSlot * 8; }
+
+hipError_t launch_transpose(const void* in, void* out, scd_dtype dt, int64_t rows, int64_t cols, hipStream_t st)
+{
+    dim3 grid((unsigned)((cols + 31) / 32), (unsigned)((rows + 31) / 32));
+    if (dt == SCD_F32)
+        hipLaunchKernelGGL((transpose_kernel<float>), grid, dim3(256), 0, st, (const float*)in, (float*)out, rows, cols);
+    else
+        hipLaunchKernelGGL((transpose_kernel<double>), grid, dim3(256), 0, st, (const double*)in, (double*)out, rows, cols);
+    return hipGetLastError();
+}
+
+template <typename TE>
+static hipError_t launch_sparse_t(const SparseArgs& a, hipStream_t st)
+{
+    const size_t lds = sparse_lds_bytes(a.m, a.n);
+    hipError_t e = hipFuncSetAttribute((const void*)sparse_kernel<TE>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    int dev = 0, per_cu = 0;
+    hipDeviceProp_t prop;
+    e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipGetDeviceProperties(&prop, dev);
+    if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, sparse_kernel<TE>, kSpThreads, lds);
+    if (e != hipSuccess) return e;
+    // all workgroups must be resident at once (every wait in the kernel is bounded in case they are not)
+    if ((int64_t)per_cu * prop.multiProcessorCount < kSpGrid) return hipErrorCooperativeLaunchTooLarge;
+    hipLaunchKernelGGL((sparse_kernel<TE>), dim3(kSpGrid), dim3(kSpThreads), lds, st, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_sparse(const SparseArgs& a, scd_dtype dt, hipStream_t st)
+{
+    return dt == SCD_F32 ? launch_sparse_t<float>(a, st) : launch_sparse_t<double>(a, st);
+}
+
+}  // namespace scd

@@ -30,13 +30,16 @@ def scd():
 
 @pytest.fixture(params=[1, 0], ids=["tiled", "generic"])
 def variant(request):
-    old = os.environ.get("SCD_ROWPASS_VARIANT")
-    os.environ["SCD_ROWPASS_VARIANT"] = str(request.param)
+    """The launch-stream engine with either row-pass kernel (the persistent engines switched off)."""
+    keys = {"SCD_ROWPASS_VARIANT": str(request.param), "SCD_RESIDENT": "0", "SCD_SPARSE": "0"}
+    old = {k: os.environ.get(k) for k in keys}
+    os.environ.update(keys)
     yield request.param
-    if old is None:
-        os.environ.pop("SCD_ROWPASS_VARIANT", None)
-    else:
-        os.environ["SCD_ROWPASS_VARIANT"] = old
+    for k, v in old.items():
+        if v is None:
+            os.environ.pop(k, None)
+        else:
+            os.environ[k] = v
 
 
 def gauss(shape, seed, dtype=np.float32):
@@ -249,10 +252,12 @@ def test_two_runs_are_bit_identical(scd):
 def test_tiled_and_generic_kernels_agree(scd):
     A = dev(gauss((384, 1024), 12))
     out = []
+    os.environ["SCD_SPARSE"] = "0"
     for v in ("1", "0"):
         os.environ["SCD_ROWPASS_VARIANT"] = v
         out.append(scd.scd_decompose(A, 10, 3))
     os.environ.pop("SCD_ROWPASS_VARIANT")
+    os.environ.pop("SCD_SPARSE")
     np.testing.assert_allclose(out[0]["trace"].cpu().numpy(), out[1]["trace"].cpu().numpy(), rtol=1e-5)
 
 
