@@ -46,6 +46,39 @@ def cpu_baseline(A64, seed: int, budget_s: float):
                        f"{float(res['iters'].mean()):.1f} alternations/term)")
 
 
+def layer_mode(args, scd, workloads, torch, np) -> int:
+    """Seconds per decoder layer at 50 % of the bf16 size (workload 3): every matrix decomposed to its
+    Table 2 width, input resident in HBM before its timer starts."""
+    rows, total_s, total_terms = [], 0.0, 0
+    for name, M, wfull, seed in workloads.config3():
+        A = torch.from_numpy(M).cuda()
+        w = max(1, int(round(wfull * args.layer_fraction)))
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        with scd.ScdContext(A, w, seed) as ctx:
+            ctx.run(w)
+            res = ctx.results()
+            eng = ctx.engine()["engine"]
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        tr = res["trace"].cpu().numpy()
+        it = res["iters"].cpu().numpy()
+        est = dt * wfull / w
+        rows.append({"matrix": name, "shape": list(M.shape), "width": wfull, "terms_run": w, "seconds": round(dt, 3),
+                     "seconds_full_width": round(est, 3), "terms_per_s": round(w / dt, 1),
+                     "alternations_per_term": round(float(it.mean()), 2),
+                     "relative_error": round(float(tr[-1] / tr[0]), 5),
+                     "engine": ["launch-stream", "register-resident", "sparse"][eng]})
+        total_s += est
+        total_terms += wfull
+        del A
+    print(json.dumps({"metric": "seconds per Mistral-7B-shaped decoder layer at 50% of bf16 size", "value": round(total_s, 2),
+                      "unit": "s/layer", "n_gpus": 1, "higher_is_better": False, "dtype": "f32", "data": "synthetic",
+                      "extrapolated": args.layer_fraction < 1.0, "terms": total_terms,
+                      "terms_per_s": round(total_terms / total_s, 1), "matrices": rows}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -57,6 +90,12 @@ def main() -> int:
     ap.add_argument("--profile-sweeps", type=int, default=512)
     ap.add_argument("--engine", choices=["auto", "stream"], default="auto",
                     help="auto: register-resident engine when the shape fits; stream: one launch per pass")
+    ap.add_argument("--layer", action="store_true",
+                    help="instead of the headline: decompose one synthetic Mistral-7B-shaped decoder layer (7 "
+                         "matrices, each to 50 %% of its bf16 footprint) and print seconds per layer")
+    ap.add_argument("--layer-fraction", type=float, default=1.0,
+                    help="with --layer: run only this fraction of every matrix's width (the rest is extrapolated "
+                         "and the line says so)")
     ap.add_argument("--calibrate", action="store_true",
                     help="only run the plain copy kernel (64 MiB, 20+1 launches): the known-size reference "
                          "for scaling the profiler's FETCH_SIZE / WRITE_SIZE counters")
@@ -83,6 +122,8 @@ def main() -> int:
                           "bytes_written_per_launch": src.numel() * 4, "launches": 21,
                           "us_per_launch": round(sec * 1e6, 2)}))
         return 0
+    if args.layer:
+        return layer_mode(args, scd, workloads, torch, np)
     m = n = args.size
     w, seed = args.width, 2
     A64 = workloads.gaussian_matrix(m, n, seed, np.float64)

@@ -136,8 +136,9 @@ int scd_traffic(const scd_ctx* ctx, double* bytes, int64_t* passes, int64_t* swe
  * remainder in the register files of a 16 x 16 grid of workgroups (f32 matrices of 1024x4096, 2048x2048,
  * 4096x4096; switched off by the environment variable SCD_RESIDENT=0); 2 = one persistent launch that
  * caches R t and R^T s and updates them from the flipped signs only (Section 3.1; f32/f64 matrices with
- * 8 <= m, n <= 65536 whose rows and columns are multiples of 16 bytes; keeps a transposed copy of the
- * remainder; switched off by SCD_SPARSE=0).  For engines 1 and 2 also the duration of the most recent
+ * 8 <= m, n <= 65536 whose rows and columns are multiples of 16 bytes and whose remainder takes at
+ * least 48 MiB (SCD_SPARSE_MIN_MIB); keeps a transposed copy of the remainder; switched off by
+ * SCD_SPARSE=0).  For engines 1 and 2 also the duration of the most recent
  * launch by HIP events on the context's stream and its dense-equivalent bytes: (alternations + updates)
  * * bytes of the remainder, what a streaming pass per alternation would move.  host pointers, each may
  * be NULL. */

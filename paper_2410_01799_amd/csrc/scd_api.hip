@@ -323,6 +323,7 @@ int run_sparse(scd_ctx* c, int64_t n)
     a.nw = (int32_t)words_for(c->dims[1]);
     a.rs = c->rs;
     a.cs = c->cs;
+    a.profile = env_int("SCD_RESIDENT_VERBOSE", 0);
     a.res = c->res_dev;
     HIP_TRY(hipMemsetAsync(c->res_dev, 0, sizeof(ResidentResult), c->stream));
     HIP_TRY(hipEventRecord(c->ev0, c->stream));
@@ -342,8 +343,10 @@ int run_sparse(scd_ctx* c, int64_t n)
         return SCD_ETIMEOUT;
     }
     if (env_int("SCD_RESIDENT_VERBOSE", 0))
-        fprintf(stderr, "[scd sparse] terms %lld alternations %lld flips %lld re-reads %lld\n", (long long)n,
-                (long long)r.alternations, (long long)r.flips, (long long)r.spins);
+        fprintf(stderr, "[scd sparse] terms %lld alternations %lld flips %lld re-reads %lld; us: dense %.0f, t-exchange %.0f, "
+                        "decide %.0f, u-update %.0f, s-exchange %.0f, v-update %.0f\n", (long long)n,
+                (long long)r.alternations, (long long)r.flips, (long long)r.spins, r.ticks[0] * 0.01, r.ticks[1] * 0.01,
+                r.ticks[2] * 0.01, r.ticks[3] * 0.01, r.ticks[4] * 0.01, r.ticks[5] * 0.01);
     c->seq_sp = r.seq_u;
     c->flips += r.flips;
     c->hs.k = r.k;
@@ -521,7 +524,11 @@ int scd_create(scd_ctx** out, const void* A, scd_dtype dt, int order, const int6
         CHIP(hipEventCreate(&c->ev0));
         CHIP(hipEventCreate(&c->ev1));
     }
-    c->sparse = !c->resident && env_int("SCD_SPARSE", 1) != 0 && sparse_supported(dt, order, dims, &c->rs, &c->cs);
+    // The sparse engine pays about 15 us per alternation whatever the size, the launch-stream engine one
+    // pass over the remainder: the former wins from about 48 MiB on (SCD_SPARSE_MIN_MIB moves the line).
+    const double mib = (double)total * (double)c->esize / (1024.0 * 1024.0);
+    c->sparse = !c->resident && env_int("SCD_SPARSE", 1) != 0 && mib >= (double)env_int("SCD_SPARSE_MIN_MIB", 48) &&
+                sparse_supported(dt, order, dims, &c->rs, &c->cs);
     if (c->sparse) {
         // the transpose doubles the footprint: without room for it the launch-stream engine serves
         hipError_t e = hipMalloc(&c->RT, (size_t)total * c->esize);

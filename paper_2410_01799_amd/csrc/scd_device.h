@@ -116,6 +116,7 @@ struct ResidentResult {
     int32_t warn;          // a term ended on max_iters
     int64_t spins;         // re-reads of stale exchange data by thread 0 of workgroup 0 (diagnostic)
     int64_t flips;         // sparse engine: sign changes processed (rows + columns)
+    int64_t ticks[6];      // sparse engine, profile mode: 100 MHz ticks of workgroup 0 per phase
 };
 
 struct ResidentArgs {
@@ -160,6 +161,7 @@ struct SparseArgs {
     double* trace;
     int32_t mw, nw;
     int32_t rs, cs;          // rows / columns owned per workgroup (multiples of 8)
+    int32_t profile;         // 1: workgroup 0 times its phases
     ResidentResult* res;
 };
 

@@ -27,9 +27,12 @@ namespace {
 constexpr int kSpThreads = 512;
 constexpr int kSpWaves = kSpThreads / kWave;
 constexpr int kSpPayload = 16;                    // payload words per slot (32 sign bits each)
-constexpr int kSpSlot = kSpPayload + 4;           // + two doubles as four tagged halves
+constexpr int kSpSlotUsed = kSpPayload + 4;       // + two doubles as four tagged halves
+// Every workgroup reads every slot: slots 4 KB apart land on different memory channels, so that the
+// 256 x 256 reads of one exchange do not queue up at a handful of them.
+constexpr int kSpSlot = 512;
 constexpr int kSpListCap = 32 * kSpThreads;       // flips handled per compaction round: one 32-bit word per thread
-constexpr int kSpMaxItems = (kSpGrid * kSpSlot + kSpThreads - 1) / kSpThreads;
+constexpr int kSpMaxItems = (kSpGrid * kSpSlotUsed + kSpThreads - 1) / kSpThreads;
 
 __device__ __forceinline__ uint64_t sp_mix64(uint64_t z)
 {
@@ -419,6 +422,15 @@ __global__ void __launch_bounds__(kSpThreads) sparse_kernel(SparseArgs a)
     int64_t flips = 0;
     bool pending = false;  // a finished term waits to be subtracted
     double ck = 0.0;
+    const bool prof = a.profile && g == 0 && tid == 0;
+    int64_t tick[6] = {0, 0, 0, 0, 0, 0};
+    uint64_t tk = prof ? wall_clock64() : 0;
+#define SP_TICK(i)                              \
+    if (prof) {                                 \
+        const uint64_t now = wall_clock64();    \
+        tick[i] += (int64_t)(now - tk);         \
+        tk = now;                               \
+    }
 
     for (;;) {
         if (k >= a.w_target && !pending) break;
@@ -451,6 +463,7 @@ __global__ void __launch_bounds__(kSpThreads) sparse_kernel(SparseArgs a)
             sp_dense_rows<TE>(RT, m, j0, clen, pending, t_cur, s_cur, ckt, s_oth, sh.accv, dummy, sh.red);
         if (pending) ++updates;
         pending = false;
+        SP_TICK(0)
         if (last) break;
         // the old term's signs are dead: s_cur <- s_1, t_cur <- t_0
         {
@@ -479,6 +492,7 @@ __global__ void __launch_bounds__(kSpThreads) sparse_kernel(SparseArgs a)
                 uint32_t* z = t_cur; t_cur = t_oth; t_oth = z;  // t_cur = t_j, t_oth = t_{j-1}
             }
             ++j;
+            SP_TICK(1)
             const double c = sp_sum_scalar(sh, 0, sh.red);
             // ---- Algorithm 4 line 8
             if (c <= c_prev || j >= a.max_iters) {
@@ -502,17 +516,21 @@ __global__ void __launch_bounds__(kSpThreads) sparse_kernel(SparseArgs a)
             }
             c_prev = c;
             // ---- row half, sparse: u += 2 sum over flipped columns (rows of RT), s = sgn(u), all-gather
+            SP_TICK(2)
             sp_accumulate_flips<TE>(RT, m, i0, rlen, t_cur, t_oth, n, sh.accu, sh, flips);
+            SP_TICK(3)
             if (!sp_exchange(a, ++seq, sh.accu, rlen, rs, m, 0.0, 0.0, s_oth, sh, spins, false)) {
                 if (tid == 0) atomicExch((unsigned*)&a.res->err, 1u);
                 return;
             }
+            SP_TICK(4)
             {
                 uint32_t* z = s_cur; s_cur = s_oth; s_oth = z;  // s_cur = s_{j+1}
             }
             ++alternations;
             // ---- column half, sparse: v += 2 sum over flipped rows (rows of R)
             sp_accumulate_flips<TE>(R, n, j0, clen, s_cur, s_oth, m, sh.accv, sh, flips);
+            SP_TICK(5)
         }
     }
     if (g == 0 && tid == 0) {
@@ -524,6 +542,7 @@ __global__ void __launch_bounds__(kSpThreads) sparse_kernel(SparseArgs a)
         a.res->warn = warn;
         a.res->spins = spins;
         a.res->flips = flips;
+        for (int i = 0; i < 6; ++i) a.res->ticks[i] = tick[i];
     }
 }
 

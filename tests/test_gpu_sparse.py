@@ -22,11 +22,12 @@ def scd():
 
 @pytest.fixture(autouse=True)
 def engines():
-    os.environ["SCD_RESIDENT"] = "0"   # so that the sparse engine also serves the resident engine's shapes
+    os.environ["SCD_RESIDENT"] = "0"        # so that the sparse engine also serves the resident engine's shapes
+    os.environ["SCD_SPARSE_MIN_MIB"] = "0"  # ... and matrices below the size from which it pays off
     os.environ.pop("SCD_SPARSE", None)
     yield
-    os.environ.pop("SCD_RESIDENT", None)
-    os.environ.pop("SCD_SPARSE", None)
+    for k in ("SCD_RESIDENT", "SCD_SPARSE", "SCD_SPARSE_MIN_MIB"):
+        os.environ.pop(k, None)
 
 
 def gauss(shape, seed, dtype=np.float32):
