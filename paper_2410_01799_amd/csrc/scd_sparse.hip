@@ -227,7 +227,17 @@ __device__ void sp_accumulate_flips(const TE* __restrict__ Y, int64_t ld, int64_
         if (active) {
             const int64_t ibase = w0 * 32;
             int f = q;
-            for (; f + 3 * Q < total; f += 4 * Q) {
+            for (; f + 7 * Q < total; f += 8 * Q) {
+                uint16_t en[8];
+                TE val[8];
+#pragma unroll
+                for (int z = 0; z < 8; ++z) en[z] = sh.list[f + z * Q];
+#pragma unroll
+                for (int z = 0; z < 8; ++z) val[z] = ycol[(ibase + (en[z] & 0x3FFF)) * ld];
+#pragma unroll
+                for (int z = 0; z < 8; ++z) part += (double)sp_flip(val[z], (uint32_t)(en[z] >> 15));
+            }
+            if (f + 3 * Q < total) {
                 uint16_t en[4];
                 TE val[4];
 #pragma unroll
@@ -236,6 +246,19 @@ __device__ void sp_accumulate_flips(const TE* __restrict__ Y, int64_t ld, int64_
                 for (int z = 0; z < 4; ++z) val[z] = ycol[(ibase + (en[z] & 0x3FFF)) * ld];
 #pragma unroll
                 for (int z = 0; z < 4; ++z) part += (double)sp_flip(val[z], (uint32_t)(en[z] >> 15));
+                f += 4 * Q;
+            }
+            {
+                // the last (at most three) flips of this thread, loaded together
+                uint16_t en[3];
+                TE val[3];
+#pragma unroll
+                for (int z = 0; z < 3; ++z) en[z] = f + z * Q < total ? sh.list[f + z * Q] : (uint16_t)0;
+#pragma unroll
+                for (int z = 0; z < 3; ++z) val[z] = f + z * Q < total ? ycol[(ibase + (en[z] & 0x3FFF)) * ld] : (TE)0;
+#pragma unroll
+                for (int z = 0; z < 3; ++z) part += (double)sp_flip(val[z], (uint32_t)(en[z] >> 15));
+                f += 3 * Q;
             }
             for (; f < total; f += Q) {
                 const uint16_t en = sh.list[f];
