@@ -228,21 +228,6 @@ __device__ __forceinline__ bool res_gather8(const uint64_t* xbuf, uint32_t off, 
     return true;
 }
 
-__device__ __forceinline__ bool res_load_f64(const uint64_t* p, uint32_t seq, int max_spin, double& out)
-{
-    uint64_t lo = 0, hi = 0;
-    int spin = 0;
-    for (;;) {
-        lo = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        hi = __hip_atomic_load(p + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if ((uint32_t)(lo >> 32) == seq && (uint32_t)(hi >> 32) == seq) break;
-        if (++spin > max_spin) return false;
-        __builtin_amdgcn_s_sleep(1);
-    }
-    out = __longlong_as_double((long long)((hi << 32) | (lo & 0xFFFFFFFFull)));
-    return true;
-}
-
 template <int CTRL>
 __device__ __forceinline__ float dpp_f32(float v)
 {
