@@ -79,7 +79,32 @@ def test_layer_shapes_prefix(scd, oracle, m, n):
     from paper_2410_01799_amd import workloads
 
     A = workloads.weight_like_matrix(m, n, 300)
-    run_case(scd, oracle, A, seed=300, w_check=2, w_total=6)
+    run_case(scd, oracle, A, seed=300, w_check=2, w_total=40)
+
+
+def test_image_tensor_full_size_first_term(scd, oracle):
+    """Workload 4 at its real shape (4000 x 3000 x 3): the first term against Algorithm 12 of the oracle, the
+    following ones by the identity and the expansion."""
+    from paper_2410_01799_amd import workloads
+
+    a = workloads.image_like_tensor(blobs=24)
+    N = a.size
+    ad = torch.from_numpy(a).cuda()
+    res = scd.scd_decompose(ad, 5, 4)
+    c = res["c"].cpu().numpy().astype(np.float64)
+    tr = res["trace"].cpu().numpy()
+    # the first term removes 98 % of the energy (the mean level): the identity is a difference of large
+    # numbers there, and its tolerance is relative to ||R_k||^2, the minuend (c is stored in f32)
+    assert np.all(np.abs(tr[1:] ** 2 - (tr[:-1] ** 2 - N * c ** 2)) <= ID_RTOL * tr[:-1] ** 2)
+    s0 = [oracle.rng_signs(4, 0, i, d) for i, d in enumerate(a.shape)]
+    g = oracle.axial_greedy_cut(a.astype(np.float64), s0)
+    if g["margin"].min() >= 10 * TIE_TOL:
+        for i in range(3):
+            assert np.array_equal(to_np_bits(res["signs"][i])[0], g["signs"][i])
+        assert c[0] == pytest.approx(g["c"] / N, rel=C_RTOL)
+        assert int(res["iters"][0]) == g["iters"]
+    E = scd.scd_expand(res["signs"], res["c"], a.shape)
+    assert float((ad.double() - E.double()).norm()) == pytest.approx(tr[-1], rel=1e-4)
 
 
 def test_profile_and_traffic_counters(scd):
