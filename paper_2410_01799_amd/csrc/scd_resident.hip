@@ -174,56 +174,58 @@ __device__ __forceinline__ void res_publish_f64(uint64_t* p, double v, uint32_t 
     __hip_atomic_store(p + 1, ((uint64_t)seq << 32) | (b >> 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Eight members' values of one element plus the two piggybacked doubles of one member (four more
-// words), all twelve loads in flight together.  If any word is still from an earlier exchange, all
+// H members' values of one element (one half of a group of 2H) plus the two piggybacked doubles of one
+// member (four more words), all loads in flight together.  If any word is still from an earlier exchange, all
 // are read again (re-reads are rare once the first read is delayed a little).
-__device__ __forceinline__ bool res_gather8_x2(const uint64_t* xbuf, uint32_t off, uint32_t stride, uint32_t xoff,
-                                               uint32_t seq, int max_spin, double& sum, double& x0, double& x1,
-                                               int& spin)
+template <int H>
+__device__ __forceinline__ bool res_gather_x2(const uint64_t* xbuf, uint32_t off, uint32_t stride, uint32_t xoff,
+                                              uint32_t seq, int max_spin, double& sum, double& x0, double& x1,
+                                              int& spin)
 {
-    uint64_t w[12];
+    uint64_t w[H + 4];
     for (;;) {
 #pragma unroll
-        for (int q = 0; q < 8; ++q)
+        for (int q = 0; q < H; ++q)
             w[q] = __hip_atomic_load(xbuf + (off + q * stride), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
         for (int q = 0; q < 4; ++q)
-            w[8 + q] = __hip_atomic_load(xbuf + (xoff + q), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            w[H + q] = __hip_atomic_load(xbuf + (xoff + q), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         bool fresh = true;
 #pragma unroll
-        for (int q = 0; q < 12; ++q) fresh = fresh && ((uint32_t)(w[q] >> 32) == seq);
+        for (int q = 0; q < H + 4; ++q) fresh = fresh && ((uint32_t)(w[q] >> 32) == seq);
         if (fresh) break;
         if (++spin > max_spin) return false;
         __builtin_amdgcn_s_sleep(1);
     }
     double s = 0.0;
 #pragma unroll
-    for (int q = 0; q < 8; ++q) s += (double)__uint_as_float((uint32_t)w[q]);
+    for (int q = 0; q < H; ++q) s += (double)__uint_as_float((uint32_t)w[q]);
     sum = s;
-    x0 = __longlong_as_double((long long)((w[9] << 32) | (w[8] & 0xFFFFFFFFull)));
-    x1 = __longlong_as_double((long long)((w[11] << 32) | (w[10] & 0xFFFFFFFFull)));
+    x0 = __longlong_as_double((long long)((w[H + 1] << 32) | (w[H] & 0xFFFFFFFFull)));
+    x1 = __longlong_as_double((long long)((w[H + 3] << 32) | (w[H + 2] & 0xFFFFFFFFull)));
     return true;
 }
 
-// Eight members' values of one element, all loads in flight together.
-__device__ __forceinline__ bool res_gather8(const uint64_t* xbuf, uint32_t off, uint32_t stride, uint32_t seq,
-                                            int max_spin, double& sum, int& spin)
+// H members' values of one element, all loads in flight together.
+template <int H>
+__device__ __forceinline__ bool res_gather(const uint64_t* xbuf, uint32_t off, uint32_t stride, uint32_t seq,
+                                           int max_spin, double& sum, int& spin)
 {
-    uint64_t w[8];
+    uint64_t w[H];
     for (;;) {
 #pragma unroll
-        for (int q = 0; q < 8; ++q)
+        for (int q = 0; q < H; ++q)
             w[q] = __hip_atomic_load(xbuf + (off + q * stride), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         bool fresh = true;
 #pragma unroll
-        for (int q = 0; q < 8; ++q) fresh = fresh && ((uint32_t)(w[q] >> 32) == seq);
+        for (int q = 0; q < H; ++q) fresh = fresh && ((uint32_t)(w[q] >> 32) == seq);
         if (fresh) break;
         if (++spin > max_spin) return false;
         __builtin_amdgcn_s_sleep(1);
     }
     double s = 0.0;
 #pragma unroll
-    for (int q = 0; q < 8; ++q) s += (double)__uint_as_float((uint32_t)w[q]);
+    for (int q = 0; q < H; ++q) s += (double)__uint_as_float((uint32_t)w[q]);
     sum = s;
     return true;
 }
@@ -259,10 +261,11 @@ __device__ __forceinline__ float sum_xor32(float v)
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-template <int TR, int TC>
+template <int TR, int TC, int P>
 __global__ void __launch_bounds__(kResThreads) resident_kernel(ResidentArgs a)
 {
-    constexpr int P = kResGrid;
+    constexpr int H = P / 2;  // members per half of an exchange group
+    static_assert(P == 4 || P == 8 || P == 16, "grid side");
     constexpr int BM = 32 * TR, BN = 16 * TC;  // block of this workgroup
     static_assert(TR >= 2 && TR <= 16 && (TR % 2) == 0, "rows per thread");
     static_assert(TC >= 4 && TC <= 32 && (TC % 4) == 0, "columns per thread");
@@ -358,22 +361,22 @@ __global__ void __launch_bounds__(kResThreads) resident_kernel(ResidentArgs a)
         bool ok = true;
         {
             // gather: thread (row, half) adds eight members in order, the two halves are combined low
-            // first.  The last wave also fetches the piggybacked scalars (lane & 15 = member), in the
+            // first.  The last wave also fetches the piggybacked scalars (lane mod P = member), in the
             // same batch of loads; threads past the block's rows read a valid row and drop it.
             const int row = tid >> 1, h = tid & 1;
             const int rowc = row < BM ? row : BM - 1;
-            const uint32_t off = res_slot_off(0, seq_u, pr * P + h * 8) + (uint32_t)rowc;
+            const uint32_t off = res_slot_off(0, seq_u, pr * P + h * H) + (uint32_t)rowc;
             double half = 0.0;
             if (wv == kResThreads / 64 - 1) {
                 double x0 = 0.0, x1 = 0.0;
-                ok = res_gather8_x2(a.xbuf, off, kResSlotWords, res_slot_off(0, seq_u, pr * P + (lane & 15)) + BM, seq_u,
-                                    a.max_spin, half, x0, x1, spin);
+                ok = res_gather_x2<H>(a.xbuf, off, kResSlotWords, res_slot_off(0, seq_u, pr * P + (lane & (P - 1))) + BM,
+                                      seq_u, a.max_spin, half, x0, x1, spin);
                 if (lane < P) {
                     lds_x[0][lane] = x0;
                     lds_x[1][lane] = x1;
                 }
             } else {
-                ok = res_gather8(a.xbuf, off, kResSlotWords, seq_u, a.max_spin, half, spin);
+                ok = res_gather<H>(a.xbuf, off, kResSlotWords, seq_u, a.max_spin, half, spin);
             }
             const double other = dpp_swap1_f64(half);
             const double u = h ? other + half : half + other;
@@ -490,15 +493,15 @@ __global__ void __launch_bounds__(kResThreads) resident_kernel(ResidentArgs a)
         {
             const int col = tid >> 1, h = tid & 1;
             const int colc = col < BN ? col : BN - 1;
-            const uint32_t off = res_slot_off(1, seq_v, (h * 8) * P + pc) + (uint32_t)colc;
+            const uint32_t off = res_slot_off(1, seq_v, (h * H) * P + pc) + (uint32_t)colc;
             double half = 0.0;
             if (wv == kResThreads / 64 - 1) {
                 double x0 = 0.0, x1 = 0.0;
-                ok = res_gather8_x2(a.xbuf, off, P * kResSlotWords, res_slot_off(1, seq_v, (lane & 15) * P + pc) + BN,
-                                    seq_v, a.max_spin, half, x0, x1, spin);
+                ok = res_gather_x2<H>(a.xbuf, off, P * kResSlotWords, res_slot_off(1, seq_v, (lane & (P - 1)) * P + pc) + BN,
+                                      seq_v, a.max_spin, half, x0, x1, spin);
                 if (lane < P) lds_x[1][lane] = x0;
             } else {
-                ok = res_gather8(a.xbuf, off, P * kResSlotWords, seq_v, a.max_spin, half, spin);
+                ok = res_gather<H>(a.xbuf, off, P * kResSlotWords, seq_v, a.max_spin, half, spin);
             }
             const double other = dpp_swap1_f64(half);
             const double v = h ? other + half : half + other;
@@ -553,26 +556,34 @@ __global__ void __launch_bounds__(kResThreads) resident_kernel(ResidentArgs a)
     }
 }
 
-static bool resident_shape(int64_t m, int64_t n, int* tr, int* tc)
+// Grid side and thread tile for a shape the engine is built for: m = P * 32 * TR, n = P * 16 * TC.
+static bool resident_shape(int64_t m, int64_t n, int* p, int* tr, int* tc)
 {
-    if (m % (32 * kResGrid) || n % (16 * kResGrid)) return false;
-    const int64_t r = m / (32 * kResGrid), c = n / (16 * kResGrid);
-    if (r == 8 && c == 16) { *tr = 8; *tc = 16; return true; }   // 4096 x 4096
-    if (r == 2 && c == 16) { *tr = 2; *tc = 16; return true; }   // 1024 x 4096
-    if (r == 4 && c == 8) { *tr = 4; *tc = 8; return true; }     // 2048 x 2048
+    static const int table[][5] = {
+        // m, n, P, TR, TC
+        {4096, 4096, 16, 8, 16}, {1024, 4096, 16, 2, 16}, {2048, 2048, 16, 4, 8},
+        {1024, 1024, 8, 4, 8},   {512, 512, 8, 2, 4},     {256, 256, 4, 2, 4},
+    };
+    for (const auto& e : table)
+        if (m == e[0] && n == e[1]) {
+            *p = e[2];
+            *tr = e[3];
+            *tc = e[4];
+            return true;
+        }
     return false;
 }
 
 bool resident_supported(scd_dtype dt, int order, const int64_t* dims)
 {
-    int tr, tc;
-    return dt == SCD_F32 && order == 2 && resident_shape(dims[0], dims[1], &tr, &tc);
+    int p, tr, tc;
+    return dt == SCD_F32 && order == 2 && resident_shape(dims[0], dims[1], &p, &tr, &tc);
 }
 
-template <int TR, int TC>
+template <int TR, int TC, int P>
 static hipError_t launch_resident_t(const ResidentArgs& a, hipStream_t st)
 {
-    // All 256 workgroups must be resident at once.  One workgroup of 512 threads fits every compute
+    // All P x P workgroups must be resident at once.  One workgroup of 512 threads fits every compute
     // unit (checked here against the occupancy the runtime reports); an ordinary launch on an idle
     // device then places them all, and every wait in the kernel is bounded in case it does not.
     int dev = 0, per_cu = 0;
@@ -580,20 +591,23 @@ static hipError_t launch_resident_t(const ResidentArgs& a, hipStream_t st)
     hipError_t e = hipGetDevice(&dev);
     if (e == hipSuccess) e = hipGetDeviceProperties(&prop, dev);
     if (e == hipSuccess)
-        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, resident_kernel<TR, TC>, kResThreads, 0);
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, resident_kernel<TR, TC, P>, kResThreads, 0);
     if (e != hipSuccess) return e;
-    if ((int64_t)per_cu * prop.multiProcessorCount < kResGrid * kResGrid) return hipErrorCooperativeLaunchTooLarge;
-    hipLaunchKernelGGL((resident_kernel<TR, TC>), dim3(kResGrid * kResGrid), dim3(kResThreads), 0, st, a);
+    if ((int64_t)per_cu * prop.multiProcessorCount < P * P) return hipErrorCooperativeLaunchTooLarge;
+    hipLaunchKernelGGL((resident_kernel<TR, TC, P>), dim3(P * P), dim3(kResThreads), 0, st, a);
     return hipGetLastError();
 }
 
 hipError_t launch_resident(const ResidentArgs& a, hipStream_t st)
 {
-    int tr = 0, tc = 0;
-    if (!resident_shape(a.m, a.n, &tr, &tc)) return hipErrorInvalidValue;
-    if (tr == 8 && tc == 16) return launch_resident_t<8, 16>(a, st);
-    if (tr == 2 && tc == 16) return launch_resident_t<2, 16>(a, st);
-    return launch_resident_t<4, 8>(a, st);
+    int p = 0, tr = 0, tc = 0;
+    if (!resident_shape(a.m, a.n, &p, &tr, &tc)) return hipErrorInvalidValue;
+    if (p == 16 && tr == 8) return launch_resident_t<8, 16, 16>(a, st);
+    if (p == 16 && tr == 2) return launch_resident_t<2, 16, 16>(a, st);
+    if (p == 16 && tr == 4) return launch_resident_t<4, 8, 16>(a, st);
+    if (p == 8 && tr == 4) return launch_resident_t<4, 8, 8>(a, st);
+    if (p == 8 && tr == 2) return launch_resident_t<2, 4, 8>(a, st);
+    return launch_resident_t<2, 4, 4>(a, st);
 }
 
 }  // namespace scd

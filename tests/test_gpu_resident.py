@@ -11,7 +11,7 @@ from test_gpu_parity import lockstep_check
 
 pytestmark = pytest.mark.gpu
 
-SHAPES = [(1024, 4096), (2048, 2048), (4096, 4096)]
+SHAPES = [(1024, 4096), (2048, 2048), (4096, 4096), (256, 256), (512, 512), (1024, 1024)]
 
 
 @pytest.fixture(scope="module")
@@ -55,7 +55,7 @@ def test_resident_matches_oracle_in_lockstep(scd, oracle, m, n):
     assert resid == pytest.approx(trace[-1], rel=1e-4)
 
 
-@pytest.mark.parametrize("m,n", SHAPES[:2])
+@pytest.mark.parametrize("m,n", SHAPES[:2] + SHAPES[3:])
 def test_resident_and_stream_paths_agree(scd, m, n):
     A = torch.from_numpy(gauss((m, n), 5)).cuda()
     with_resident(True)
