@@ -48,33 +48,75 @@ def cpu_baseline(A64, seed: int, budget_s: float):
 
 def layer_mode(args, scd, workloads, torch, np) -> int:
     """Seconds per decoder layer at 50 % of the bf16 size (workload 3): every matrix decomposed to its
-    Table 2 width, input resident in HBM before its timer starts."""
-    rows, total_s, total_terms = [], 0.0, 0
+    Table 2 width, all inputs resident in HBM before the timer starts.  With --concurrency K the seven
+    matrices are taken from a queue (largest first) by K host threads, each decomposition on its own
+    stream and on 256/K compute units; the figure is the wall time of the whole layer."""
+    import threading
+
+    K = args.concurrency
+    share = 0 if K == 1 else 256 // K
+    jobs = []
     for name, M, wfull, seed in workloads.config3():
-        A = torch.from_numpy(M).cuda()
-        w = max(1, int(round(wfull * args.layer_fraction)))
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        with scd.ScdContext(A, w, seed) as ctx:
-            ctx.run(w)
-            res = ctx.results()
-            eng = ctx.engine()["engine"]
-        torch.cuda.synchronize()
-        dt = time.perf_counter() - t0
-        tr = res["trace"].cpu().numpy()
-        it = res["iters"].cpu().numpy()
-        est = dt * wfull / w
-        rows.append({"matrix": name, "shape": list(M.shape), "width": wfull, "terms_run": w, "seconds": round(dt, 3),
-                     "seconds_full_width": round(est, 3), "terms_per_s": round(w / dt, 1),
-                     "alternations_per_term": round(float(it.mean()), 2),
-                     "relative_error": round(float(tr[-1] / tr[0]), 5),
-                     "engine": ["launch-stream", "register-resident", "sparse"][eng]})
-        total_s += est
-        total_terms += wfull
-        del A
+        jobs.append(dict(name=name, A=torch.from_numpy(M).cuda(), shape=list(M.shape), wfull=wfull, seed=seed,
+                         w=max(1, int(round(wfull * args.layer_fraction)))))
+    order = sorted(range(len(jobs)), key=lambda i: -jobs[i]["wfull"] * jobs[i]["shape"][0] * jobs[i]["shape"][1])
+    rows, lock, errors = [None] * len(jobs), threading.Lock(), []
+
+    def worker():
+        torch.cuda.set_device(0)
+        stream = torch.cuda.Stream() if K > 1 else torch.cuda.current_stream()
+        with torch.cuda.stream(stream):
+            while True:
+                with lock:
+                    if not order or errors:
+                        return
+                    i = order.pop(0)
+                j = jobs[i]
+                try:
+                    t0 = time.perf_counter()
+                    with scd.ScdContext(j["A"], j["w"], j["seed"]) as ctx:
+                        if share:
+                            ctx.set_workgroups(share)
+                        step = j["w"] if K == 1 else 1024
+                        for k in range(0, j["w"], step):
+                            ctx.run(min(step, j["w"] - k))
+                        res = ctx.results()
+                        eng = ctx.engine()["engine"]
+                        stream.synchronize()
+                        dt = time.perf_counter() - t0
+                except Exception as err:  # noqa: BLE001 - reported by the main thread
+                    with lock:
+                        errors.append((j["name"], repr(err)))
+                    return
+                tr = res["trace"].cpu().numpy()
+                it = res["iters"].cpu().numpy()
+                rows[i] = {"matrix": j["name"], "shape": j["shape"], "width": j["wfull"], "terms_run": j["w"],
+                           "seconds": round(dt, 3), "terms_per_s": round(j["w"] / dt, 1),
+                           "alternations_per_term": round(float(it.mean()), 2),
+                           "relative_error": round(float(tr[-1] / tr[0]), 5),
+                           "engine": ["launch-stream", "register-resident", "sparse"][eng]}
+
+    torch.cuda.synchronize()
+    t_begin = time.perf_counter()
+    if K == 1:
+        worker()
+    else:
+        threads = [threading.Thread(target=worker) for _ in range(K)]
+        for t in threads:
+            t.start()
+        for t in threads:
+            t.join()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t_begin
+    if errors:
+        print(f"layer run failed: {errors}", file=sys.stderr)
+        return 1
+    total_terms = sum(j["wfull"] for j in jobs)
+    total_s = wall / args.layer_fraction
     print(json.dumps({"metric": "seconds per Mistral-7B-shaped decoder layer at 50% of bf16 size", "value": round(total_s, 2),
                       "unit": "s/layer", "n_gpus": 1, "higher_is_better": False, "dtype": "f32", "data": "synthetic",
-                      "extrapolated": args.layer_fraction < 1.0, "terms": total_terms,
+                      "extrapolated": args.layer_fraction < 1.0, "terms": total_terms, "concurrency": K,
+                      "compute_units_per_matrix": share or 256,
                       "terms_per_s": round(total_terms / total_s, 1), "matrices": rows}))
     return 0
 
@@ -96,6 +138,8 @@ def main() -> int:
     ap.add_argument("--layer-fraction", type=float, default=1.0,
                     help="with --layer: run only this fraction of every matrix's width (the rest is extrapolated "
                          "and the line says so)")
+    ap.add_argument("--concurrency", type=int, default=4, choices=[1, 2, 4, 8],
+                    help="with --layer: matrices decomposed side by side, each on 256/K compute units")
     ap.add_argument("--calibrate", action="store_true",
                     help="only run the plain copy kernel (64 MiB, 20+1 launches): the known-size reference "
                          "for scaling the profiler's FETCH_SIZE / WRITE_SIZE counters")

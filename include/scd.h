@@ -83,6 +83,17 @@ void scd_destroy(scd_ctx* ctx);
 /* Iteration cap of Algorithm 4's loop (the paper's loop is unbounded); default SCD_DEFAULT_MAX_ITERS. */
 int scd_set_max_iters(scd_ctx* ctx, int32_t max_iters);
 
+/* Share of the device for this context: its persistent launches take at most `workgroups` workgroups
+ * (one per compute unit; 16 or more, rounded down to a power of two; 0 = the whole device, the default).
+ * The matrices of a model are decomposed independently of one another (Section 4.2), and one greedy
+ * decomposition is bound by the latency of its alternations, not by bandwidth: contexts with a share,
+ * driven from different host threads on different streams, run side by side and fill each other's
+ * waits.  The library serialises persistent launches of one process that would not fit together.
+ * The results of a context do not depend on what runs beside it; they may differ in near-tie signs
+ * from those of another share (the summation order follows the number of workgroups).
+ * Call it between runs, never while another thread uses the context.  May allocate (SCD_ENOMEM). */
+int scd_set_workgroups(scd_ctx* ctx, int workgroups);
+
 /* Advance exactly one term (Algorithm 5 lines 6-10): greedy cut from the keyed random start of the
  * current term, append (s, t, c), update the remainder, record ||R||_F. */
 int scd_step(scd_ctx* ctx);

@@ -10,6 +10,8 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <condition_variable>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -99,6 +101,9 @@ struct scd_ctx {
     uint64_t* xbuf_sp = nullptr;
     uint32_t seq_sp = 0;
     int rs = 0, cs = 0;
+    int sp_grid = kSpGrid;          // workgroups of the sparse engine's launch
+    int share = 0;                  // most workgroups a persistent launch may take (0: the whole device)
+    int cus = 256;                  // compute units of the device
     int64_t flips = 0;
     hipEvent_t ev0 = nullptr, ev1 = nullptr;  // around the engine's launch
     double last_launch_seconds = 0.0;
@@ -293,6 +298,88 @@ int resync_stream_state(scd_ctx* c)
     return SCD_OK;
 }
 
+// Persistent launches of different contexts (host threads, streams) share the device: each needs all of
+// its workgroups resident at once, one per compute unit, so a launch waits here until that many compute
+// units are free of other persistent launches of this process.
+std::mutex g_slots_mutex;
+std::condition_variable g_slots_cv;
+int g_slots_in_use = 0;
+
+struct SlotLease {
+    int n = 0;
+    void acquire(int want, int capacity)
+    {
+        if (want > capacity) want = capacity;  // the occupancy check of the launcher has the last word
+        std::unique_lock<std::mutex> lk(g_slots_mutex);
+        g_slots_cv.wait(lk, [&] { return g_slots_in_use + want <= capacity; });
+        g_slots_in_use += want;
+        n = want;
+    }
+    ~SlotLease()
+    {
+        if (!n) return;
+        {
+            std::lock_guard<std::mutex> lk(g_slots_mutex);
+            g_slots_in_use -= n;
+        }
+        g_slots_cv.notify_all();
+    }
+};
+
+// Which engine serves this context, and its buffers (allocated once, kept until scd_destroy).
+int setup_engines(scd_ctx* c)
+{
+    const int limit = c->share > 0 ? c->share : c->cus;
+    c->resident = env_int("SCD_RESIDENT", 1) != 0 && resident_supported(c->dt, c->order, c->dims) &&
+                  resident_workgroups(c->dims) <= limit;
+    c->sparse = false;
+    if (!c->resident && env_int("SCD_SPARSE", 1) != 0) {
+        // The sparse engine pays about 15 us per alternation whatever the size, the launch-stream engine
+        // one pass over the remainder: the former wins from about 48 MiB on (SCD_SPARSE_MIN_MIB moves the
+        // line).  A context that was given a share of the device runs side by side with others, which
+        // hides exactly that latency: it takes the sparse engine at any size.
+        const double mib = (double)c->total * (double)c->esize / (1024.0 * 1024.0);
+        int grid = kSpGrid;
+        while (grid > limit) grid >>= 1;
+        const bool big = c->share > 0 || mib >= (double)env_int("SCD_SPARSE_MIN_MIB", 48);
+        if (big && grid >= 1 && sparse_supported(c->dt, c->order, c->dims, grid, &c->rs, &c->cs)) {
+            c->sparse = true;
+            c->sp_grid = grid;
+        }
+    }
+    auto hip_ok = [](hipError_t e) {
+        if (e == hipSuccess) return true;
+        g_last_hip = (int)e;
+        (void)hipGetLastError();
+        return false;
+    };
+    if (c->sparse && !c->RT) {
+        // the transpose doubles the footprint: without room for it the launch-stream engine serves
+        if (hipMalloc(&c->RT, (size_t)c->total * c->esize) != hipSuccess) {
+            (void)hipGetLastError();
+            c->RT = nullptr;
+            c->sparse = false;
+        } else {
+            c->allocs.push_back(c->RT);
+            c->rt_stale = true;
+            SCD_TRY(dev_alloc(c, (void**)&c->xbuf_sp, sparse_xbuf_bytes()));
+            if (!hip_ok(hipMemsetAsync(c->xbuf_sp, 0, sparse_xbuf_bytes(), c->stream))) return SCD_EHIP;
+        }
+    }
+    if (c->resident && !c->xbuf) {
+        const size_t xb = (size_t)4 * kResGrid * kResGrid * kResSlotWords * 8;
+        SCD_TRY(dev_alloc(c, (void**)&c->xbuf, xb));
+        if (!hip_ok(hipMemsetAsync(c->xbuf, 0, xb, c->stream))) return SCD_EHIP;
+    }
+    if ((c->resident || c->sparse) && !c->res_dev) {
+        SCD_TRY(dev_alloc(c, (void**)&c->res_dev, sizeof(ResidentResult)));
+        if (!hip_ok(hipHostMalloc((void**)&c->res_pin, sizeof(ResidentResult), hipHostMallocDefault))) return SCD_EHIP;
+        c->max_spin = env_int("SCD_RESIDENT_MAX_SPIN", 1 << 22);
+        if (!hip_ok(hipEventCreate(&c->ev0)) || !hip_ok(hipEventCreate(&c->ev1))) return SCD_EHIP;
+    }
+    return SCD_OK;
+}
+
 // n terms in one persistent launch that updates the cached products from the flipped signs only.
 int run_sparse(scd_ctx* c, int64_t n)
 {
@@ -323,8 +410,11 @@ int run_sparse(scd_ctx* c, int64_t n)
     a.nw = (int32_t)words_for(c->dims[1]);
     a.rs = c->rs;
     a.cs = c->cs;
+    a.grid = c->sp_grid;
     a.profile = env_int("SCD_RESIDENT_VERBOSE", 0);
     a.res = c->res_dev;
+    SlotLease lease;
+    lease.acquire(a.grid, c->cus);
     HIP_TRY(hipMemsetAsync(c->res_dev, 0, sizeof(ResidentResult), c->stream));
     HIP_TRY(hipEventRecord(c->ev0, c->stream));
     HIP_TRY(launch_sparse(a, c->dt, c->stream));
@@ -382,6 +472,8 @@ int run_resident(scd_ctx* c, int64_t n)
     a.mw = (int32_t)words_for(c->dims[0]);
     a.nw = (int32_t)words_for(c->dims[1]);
     a.res = c->res_dev;
+    SlotLease lease;
+    lease.acquire(resident_workgroups(c->dims), c->cus);
     HIP_TRY(hipMemsetAsync(c->res_dev, 0, sizeof(ResidentResult), c->stream));
     HIP_TRY(hipEventRecord(c->ev0, c->stream));
     HIP_TRY(launch_resident(a, c->stream));
@@ -513,40 +605,8 @@ int scd_create(scd_ctx** out, const void* A, scd_dtype dt, int order, const int6
             CTRY(dev_alloc(c, (void**)&L.kron_rng, (size_t)words_for(L.cols) * 8));
         }
     }
-    c->resident = env_int("SCD_RESIDENT", 1) != 0 && resident_supported(dt, order, dims);
-    if (c->resident) {
-        const size_t xb = (size_t)4 * kResGrid * kResGrid * kResSlotWords * 8;
-        CTRY(dev_alloc(c, (void**)&c->xbuf, xb));
-        CHIP(hipMemsetAsync(c->xbuf, 0, xb, c->stream));
-        CTRY(dev_alloc(c, (void**)&c->res_dev, sizeof(ResidentResult)));
-        CHIP(hipHostMalloc((void**)&c->res_pin, sizeof(ResidentResult), hipHostMallocDefault));
-        c->max_spin = env_int("SCD_RESIDENT_MAX_SPIN", 1 << 22);
-        CHIP(hipEventCreate(&c->ev0));
-        CHIP(hipEventCreate(&c->ev1));
-    }
-    // The sparse engine pays about 15 us per alternation whatever the size, the launch-stream engine one
-    // pass over the remainder: the former wins from about 48 MiB on (SCD_SPARSE_MIN_MIB moves the line).
-    const double mib = (double)total * (double)c->esize / (1024.0 * 1024.0);
-    c->sparse = !c->resident && env_int("SCD_SPARSE", 1) != 0 && mib >= (double)env_int("SCD_SPARSE_MIN_MIB", 48) &&
-                sparse_supported(dt, order, dims, &c->rs, &c->cs);
-    if (c->sparse) {
-        // the transpose doubles the footprint: without room for it the launch-stream engine serves
-        hipError_t e = hipMalloc(&c->RT, (size_t)total * c->esize);
-        if (e != hipSuccess) {
-            (void)hipGetLastError();
-            c->RT = nullptr;
-            c->sparse = false;
-        } else {
-            c->allocs.push_back(c->RT);
-            CTRY(dev_alloc(c, (void**)&c->xbuf_sp, sparse_xbuf_bytes()));
-            CHIP(hipMemsetAsync(c->xbuf_sp, 0, sparse_xbuf_bytes(), c->stream));
-            CTRY(dev_alloc(c, (void**)&c->res_dev, sizeof(ResidentResult)));
-            CHIP(hipHostMalloc((void**)&c->res_pin, sizeof(ResidentResult), hipHostMallocDefault));
-            c->max_spin = env_int("SCD_RESIDENT_MAX_SPIN", 1 << 22);
-            CHIP(hipEventCreate(&c->ev0));
-            CHIP(hipEventCreate(&c->ev1));
-        }
-    }
+    c->cus = cus;
+    CTRY(setup_engines(c));
     c->ncparts = (int)words_for(dims[order - 1]);
     CTRY(dev_alloc(c, (void**)&c->cparts, (size_t)c->ncparts * 8));
     CHIP(hipMemsetAsync(c->cparts, 0, (size_t)c->ncparts * 8, c->stream));
@@ -589,6 +649,15 @@ int scd_set_max_iters(scd_ctx* c, int32_t max_iters)
     if (!c || max_iters < 1) return SCD_EINVAL;
     c->hs.max_iters = max_iters;
     return write_state(c);
+}
+
+int scd_set_workgroups(scd_ctx* c, int workgroups)
+{
+    if (!c || workgroups < 0) return SCD_EINVAL;
+    if (workgroups != 0 && workgroups < 16) return SCD_EINVAL;
+    if (c->broken) return SCD_ETIMEOUT;
+    c->share = workgroups >= c->cus ? 0 : workgroups;
+    return setup_engines(c);
 }
 
 int scd_run(scd_ctx* c, int64_t n)

@@ -138,11 +138,12 @@ struct ResidentArgs {
 };
 
 bool resident_supported(scd_dtype dt, int order, const int64_t* dims);
+int resident_workgroups(const int64_t* dims);  // workgroups of the launch for a supported shape
 hipError_t launch_resident(const ResidentArgs& a, hipStream_t st);
 
 // Sparse engine (scd_sparse.hip): cached products updated from the flipped signs only; keeps R and its
 // transpose in HBM.
-constexpr int kSpGrid = 256;  // workgroups of the persistent launch
+constexpr int kSpGrid = 256;  // most workgroups of the persistent launch
 
 struct SparseArgs {
     void* R;                 // m x n
@@ -161,11 +162,12 @@ struct SparseArgs {
     double* trace;
     int32_t mw, nw;
     int32_t rs, cs;          // rows / columns owned per workgroup (multiples of 8)
+    int32_t grid;            // workgroups of this launch (power of two, at most kSpGrid)
     int32_t profile;         // 1: workgroup 0 times its phases
     ResidentResult* res;
 };
 
-bool sparse_supported(scd_dtype dt, int order, const int64_t* dims, int* rs, int* cs);
+bool sparse_supported(scd_dtype dt, int order, const int64_t* dims, int grid, int* rs, int* cs);
 size_t sparse_xbuf_bytes();
 hipError_t launch_sparse(const SparseArgs& a, scd_dtype dt, hipStream_t st);
 hipError_t launch_transpose(const void* in, void* out, scd_dtype dt, int64_t rows, int64_t cols, hipStream_t st);

@@ -580,6 +580,12 @@ bool resident_supported(scd_dtype dt, int order, const int64_t* dims)
     return dt == SCD_F32 && order == 2 && resident_shape(dims[0], dims[1], &p, &tr, &tc);
 }
 
+int resident_workgroups(const int64_t* dims)
+{
+    int p = 0, tr, tc;
+    return resident_shape(dims[0], dims[1], &p, &tr, &tc) ? p * p : 0;
+}
+
 template <int TR, int TC, int P>
 static hipError_t launch_resident_t(const ResidentArgs& a, hipStream_t st)
 {

@@ -7,8 +7,9 @@
 // matrix and its transpose so that both kinds of slices are contiguous; so does this engine (R and RT
 // in HBM, both updated when a term is subtracted).
 //
-// 256 workgroups, one per compute unit.  Workgroup g owns the slice I_g of the rows (its entries of
-// u = R t) and the slice J_g of the columns (its entries of v = R^T s), in f64.
+// G workgroups (a power of two up to 256, one per compute unit: the whole device by default, a share
+// of it when several decompositions run side by side).  Workgroup g owns the slice I_g of the rows
+// (its entries of u = R t) and the slice J_g of the columns (its entries of v = R^T s), in f64.
 //   term start   dense: rows I_g of R   -> subtract the finished term (Algorithm 5 line 10), ||R||^2,
 //                        u = R t_0; all-gather of s;   rows J_g of RT -> subtract, v = R^T s; all-gather of t
 //   afterwards   sparse: u[I_g] += 2 sum_f +-RT[l_f][I_g]; all-gather of s;
@@ -315,9 +316,9 @@ __device__ bool sp_exchange(const SparseArgs& a, uint32_t seq, const double* acc
         sp_store_tagged(mine + kSpPayload + 3, (uint32_t)(b1 >> 32), seq);
     }
     for (int d = 0; d < a.poll_delay; ++d) __builtin_amdgcn_s_sleep(1);
-    // ---- gather: (words + 4) items from each of the kSpGrid members, spread over the threads
+    // ---- gather: (words + 4) items from each of the a.grid members, spread over the threads
     const int per = words + 4;
-    const int items = kSpGrid * per;
+    const int items = a.grid * per;
     uint64_t w[kSpMaxItems];
     const uint64_t* xb = a.xbuf + (size_t)(seq & 1u) * kSpGrid * kSpSlot;
     bool ok = true;
@@ -373,12 +374,12 @@ __device__ bool sp_exchange(const SparseArgs& a, uint32_t seq, const double* acc
 }
 
 // Sum of one gathered scalar over the members, in a fixed order; every thread gets the same bits.
-__device__ double sp_sum_scalar(const SpShared& sh, int which, double* scratch)
+__device__ double sp_sum_scalar(const SpShared& sh, int which, double* scratch, int grid)
 {
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     if (tid < kWave) {
         double s = 0.0;
-        for (int g = lane; g < kSpGrid; g += kWave) {
+        for (int g = lane; g < grid; g += kWave) {
             const uint32_t lo = sh.scal[(which * kSpGrid + g) * 2], hi = sh.scal[(which * kSpGrid + g) * 2 + 1];
             s += __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
         }
@@ -477,7 +478,7 @@ __global__ void __launch_bounds__(kSpThreads) sparse_kernel(SparseArgs a)
         }
         ++alternations;
         if (pending) {
-            const double F = sp_sum_scalar(sh, 0, sh.red);
+            const double F = sp_sum_scalar(sh, 0, sh.red, a.grid);
             if (g == 0 && tid == 0) a.trace[k] = sqrt(F);
         }
         // rows J_g of RT (columns of R): same update, v = R^T s_1 (Algorithm 4 line 6)
@@ -516,7 +517,7 @@ __global__ void __launch_bounds__(kSpThreads) sparse_kernel(SparseArgs a)
             }
             ++j;
             SP_TICK(1)
-            const double c = sp_sum_scalar(sh, 0, sh.red);
+            const double c = sp_sum_scalar(sh, 0, sh.red, a.grid);
             // ---- Algorithm 4 line 8
             if (c <= c_prev || j >= a.max_iters) {
                 if (!(c <= c_prev)) warn = 1;
@@ -529,7 +530,7 @@ __global__ void __launch_bounds__(kSpThreads) sparse_kernel(SparseArgs a)
                         a.iters[k] = j;
                     }
                 }
-                if (g == 1 % kSpGrid) {
+                if (g == (a.grid > 1 ? 1 : 0)) {
                     for (int p = tid; p < a.nw; p += kSpThreads)
                         a.T[k * a.nw + p] = (uint64_t)t_cur[2 * p] | ((uint64_t)(2 * p + 1 < nwords32 ? t_cur[2 * p + 1] : 0u) << 32);
                 }
@@ -594,20 +595,21 @@ size_t sparse_lds_bytes(int64_t m, int64_t n)
 
 }  // namespace
 
-bool sparse_supported(scd_dtype dt, int order, const int64_t* dims, int* rs, int* cs)
+bool sparse_supported(scd_dtype dt, int order, const int64_t* dims, int grid, int* rs, int* cs)
 {
     if (order != 2) return false;
+    if (grid < 1 || grid > kSpGrid || (grid & (grid - 1))) return false;
     const int64_t m = dims[0], n = dims[1];
     const int ve = dt == SCD_F32 ? 4 : 2;
     if (m % ve || n % ve) return false;               // rows of R and of RT start on 16-byte boundaries
     if (m > 65536 || n > 65536 || m < 8 || n < 8) return false;
-    const int r = (int)(8 * ((m + 8 * kSpGrid - 1) / (8 * kSpGrid)));
-    const int c = (int)(8 * ((n + 8 * kSpGrid - 1) / (8 * kSpGrid)));
+    const int64_t r = 8 * ((m + 8 * grid - 1) / (8 * grid));  // slice of the rows / columns per workgroup
+    const int64_t c = 8 * ((n + 8 * grid - 1) / (8 * grid));
     if (r > kSpThreads || c > kSpThreads) return false;
     if (r > 32 * kSpPayload || c > 32 * kSpPayload) return false;
     if (sparse_lds_bytes(m, n) > 150 * 1024) return false;
-    if (rs) *rs = r;
-    if (cs) *cs = c;
+    if (rs) *rs = (int)r;
+    if (cs) *cs = (int)c;
     return true;
 }
 
@@ -636,8 +638,9 @@ static hipError_t launch_sparse_t(const SparseArgs& a, hipStream_t st)
     if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, sparse_kernel<TE>, kSpThreads, lds);
     if (e != hipSuccess) return e;
     // all workgroups must be resident at once (every wait in the kernel is bounded in case they are not)
-    if ((int64_t)per_cu * prop.multiProcessorCount < kSpGrid) return hipErrorCooperativeLaunchTooLarge;
-    hipLaunchKernelGGL((sparse_kernel<TE>), dim3(kSpGrid), dim3(kSpThreads), lds, st, a);
+    if (a.grid < 1 || a.grid > kSpGrid) return hipErrorInvalidValue;
+    if ((int64_t)per_cu * prop.multiProcessorCount < a.grid) return hipErrorCooperativeLaunchTooLarge;
+    hipLaunchKernelGGL((sparse_kernel<TE>), dim3(a.grid), dim3(kSpThreads), lds, st, a);
     return hipGetLastError();
 }
 

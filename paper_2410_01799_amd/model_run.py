@@ -12,6 +12,7 @@ from __future__ import annotations
 import argparse
 import json
 import sys
+import threading
 import time
 from pathlib import Path
 
@@ -36,47 +37,104 @@ def device_weight_like(m: int, n: int, seed: int, kind: str) -> torch.Tensor:
     return G.bfloat16().float().contiguous()   # bf16-representable values, stored as f32
 
 
+def decompose_one(e: dict, share: int, chunk: int) -> dict:
+    """One matrix of the manifest on the current stream; returns its result row."""
+    m, n = e["m"], e["n"]
+    A = device_weight_like(m, n, e["seed"], e["kind"])
+    w = e["widths"]["1/2"]
+    torch.cuda.current_stream().synchronize()
+    t0 = time.perf_counter()
+    with scd.ScdContext(A, w, e["seed"]) as ctx:
+        if share:
+            ctx.set_workgroups(share)
+        # launches of bounded length: a thread that frees device memory waits for the launches in flight
+        # on every stream, so nobody should hold the device for tens of seconds
+        for k in range(0, w, chunk):
+            ctx.run(min(chunk, w - k))
+        res = ctx.results()
+        eng = ctx.engine()["engine"]
+        torch.cuda.current_stream().synchronize()
+        dt = time.perf_counter() - t0
+    tr = res["trace"].double()
+    c = res["c"].double()
+    ident = ((tr[1:] ** 2 - (tr[:-1] ** 2 - m * n * c ** 2)).abs() / tr[:-1] ** 2).max().item()
+    rel = {p: float(tr[e["widths"][p]] / tr[0]) for p in ("1/4", "3/8", "1/2")}
+    return dict(index=e["index"], name=e["name"], m=m, n=n, seed=e["seed"], width=w, seconds=round(dt, 3),
+                terms_per_s=round(w / dt, 1), alternations_per_term=round(float(res["iters"].float().mean()), 2),
+                rel_err=rel, identity_max_violation=ident, engine=eng, share=share or 256)
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--start", type=int, default=0)
     ap.add_argument("--stop", type=int, default=226)
     ap.add_argument("--out", type=str, required=True)
-    ap.add_argument("--budget-seconds", type=float, default=1e9, help="stop before a matrix that would overrun")
+    ap.add_argument("--budget-seconds", type=float, default=1e9, help="take no new matrix that would overrun")
+    ap.add_argument("--concurrency", type=int, default=1, choices=[1, 2, 4, 8],
+                    help="matrices decomposed side by side, each on 256/K compute units (the matrices of a model "
+                         "are independent, and one decomposition is latency-bound)")
+    ap.add_argument("--chunk", type=int, default=1024, help="terms per launch when matrices run side by side")
     args = ap.parse_args()
     man = workloads.config5_manifest()
+    for i, e in enumerate(man):
+        e["index"] = i
+    todo = list(range(args.start, min(args.stop, len(man))))
     out = Path(args.out)
     out.parent.mkdir(parents=True, exist_ok=True)
+    K = args.concurrency
+    share = 0 if K == 1 else 256 // K
+    chunk = 1 << 30 if K == 1 else args.chunk
+    lock = threading.Lock()
     t_begin = time.perf_counter()
-    last = 0.0
+    cost: dict = {}      # (m, n) -> seconds the last matrix of that shape took
+    failures = []
+    scd.lib()
+    torch.cuda.set_device(0)
     with out.open("a") as fh:
-        for idx in range(args.start, min(args.stop, len(man))):
-            if time.perf_counter() - t_begin + 1.2 * last > args.budget_seconds:
-                break
-            e = man[idx]
-            m, n = e["m"], e["n"]
-            A = device_weight_like(m, n, e["seed"], e["kind"])
-            w = e["widths"]["1/2"]
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            with scd.ScdContext(A, w, e["seed"]) as ctx:
-                ctx.run(w)
-                res = ctx.results()
-                eng = ctx.engine()["engine"]
-            torch.cuda.synchronize()
-            dt = time.perf_counter() - t0
-            last = dt
-            tr = res["trace"].double()
-            c = res["c"].double()
-            ident = ((tr[1:] ** 2 - (tr[:-1] ** 2 - m * n * c ** 2)).abs() / tr[:-1] ** 2).max().item()
-            rel = {p: float(tr[e["widths"][p]] / tr[0]) for p in ("1/4", "3/8", "1/2")}
-            row = dict(index=idx, name=e["name"], m=m, n=n, seed=e["seed"], width=w, seconds=round(dt, 3),
-                       terms_per_s=round(w / dt, 1), alternations_per_term=round(float(res["iters"].float().mean()), 2),
-                       rel_err=rel, identity_max_violation=ident, engine=eng)
-            fh.write(json.dumps(row) + "\n")
-            fh.flush()
-            print(f"[{idx}] {e['name']} {m}x{n} w={w}: {dt:.1f} s, {w / dt:.0f} terms/s, rel err 1/4 {rel['1/4']:.4f} "
-                  f"3/8 {rel['3/8']:.4f} 1/2 {rel['1/2']:.4f}", flush=True)
-            del A, res
+        def worker():
+            torch.cuda.set_device(0)
+            stream = torch.cuda.Stream() if K > 1 else torch.cuda.current_stream()
+            with torch.cuda.stream(stream):
+                while True:
+                    with lock:
+                        if not todo or failures:
+                            return
+                        e = man[todo[0]]
+                        guess = cost.get((e["m"], e["n"]), 0.0)
+                        if time.perf_counter() - t_begin + 1.2 * guess > args.budget_seconds:
+                            return
+                        todo.pop(0)
+                    try:
+                        row = decompose_one(e, share, chunk)
+                    except Exception as err:  # noqa: BLE001 - reported by the main thread
+                        with lock:
+                            failures.append((e["index"], repr(err)))
+                        return
+                    with lock:
+                        cost[(e["m"], e["n"])] = row["seconds"]
+                        fh.write(json.dumps(row) + "\n")
+                        fh.flush()
+                        rel = row["rel_err"]
+                        print(f"[{row['index']}] {row['name']} {row['m']}x{row['n']} w={row['width']}: "
+                              f"{row['seconds']:.1f} s, {row['terms_per_s']:.0f} terms/s, rel err 1/4 {rel['1/4']:.4f} "
+                              f"3/8 {rel['3/8']:.4f} 1/2 {rel['1/2']:.4f}", flush=True)
+
+        if K == 1:
+            worker()
+        else:
+            threads = [threading.Thread(target=worker) for _ in range(K)]
+            for t in threads:
+                t.start()
+            for t in threads:
+                t.join()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t_begin
+        fh.write(json.dumps(dict(summary=True, start=args.start, next_index=todo[0] if todo else None,
+                                 concurrency=K, wall_seconds=round(wall, 2))) + "\n")
+    print(f"wall {wall:.1f} s, next index {todo[0] if todo else None}", flush=True)
+    if failures:
+        print(f"failed: {failures}", file=sys.stderr)
+        return 1
     return 0
 
 

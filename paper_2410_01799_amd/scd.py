@@ -24,7 +24,7 @@ EXPORTS = [
     "scd_decompose", "scd_create", "scd_destroy", "scd_set_max_iters", "scd_step", "scd_run", "scd_step_from",
     "scd_width", "scd_results", "scd_remainder", "scd_set_remainder", "scd_row_signed_sum", "scd_col_signed_sum",
     "scd_expand", "scd_pack", "scd_unpack", "scd_rng_signs", "scd_strerror", "scd_last_hip_error", "scd_traffic",
-    "scd_probe_stream", "scd_profile_sweeps", "scd_probe_exchange", "scd_engine",
+    "scd_probe_stream", "scd_profile_sweeps", "scd_probe_exchange", "scd_engine", "scd_set_workgroups",
 ]
 
 
@@ -53,6 +53,7 @@ def lib() -> C.CDLL:
         L.scd_destroy.argtypes = [vp]
         L.scd_destroy.restype = None
         L.scd_set_max_iters.argtypes = [vp, i32]
+        L.scd_set_workgroups.argtypes = [vp, C.c_int]
         L.scd_step.argtypes = [vp]
         L.scd_run.argtypes = [vp, i64]
         L.scd_step_from.argtypes = [vp, pvp]
@@ -258,6 +259,11 @@ class ScdContext:
 
     def set_max_iters(self, n: int):
         _check(lib().scd_set_max_iters(self._h, int(n)), "scd_set_max_iters")
+
+    def set_workgroups(self, n: int):
+        """Share of the device (workgroups of the persistent launches; 0 = all): lets several contexts,
+        each on its own stream and host thread, run side by side."""
+        _check(lib().scd_set_workgroups(self._h, int(n)), "scd_set_workgroups")
 
     def step(self) -> int:
         return _check(lib().scd_step(self._h), "scd_step")

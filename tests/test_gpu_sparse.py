@@ -34,10 +34,12 @@ def gauss(shape, seed, dtype=np.float32):
     return np.random.Generator(np.random.PCG64(seed)).standard_normal(shape).astype(dtype)
 
 
-def run_and_check(scd, oracle, A, w, seed):
+def run_and_check(scd, oracle, A, w, seed, share=0):
     m, n = A.shape
     Ad = torch.from_numpy(A).cuda()
     with scd.ScdContext(Ad, w, seed) as ctx:
+        if share:
+            ctx.set_workgroups(share)
         assert ctx.engine()["engine"] == 2
         ctx.run(w)
         res = ctx.results()
@@ -131,3 +133,93 @@ def test_sparse_iteration_cap_and_set_remainder(scd):
     tr = r["trace"].cpu().numpy()
     c = r["c"].cpu().numpy().astype(np.float64)
     np.testing.assert_allclose(tr[1:] ** 2, tr[:-1] ** 2 - 512 * 512 * c ** 2, rtol=ID_RTOL)
+
+
+# ---- a share of the device per context (several decompositions side by side)
+
+@pytest.mark.parametrize("m,n,w,share", [(1000, 4096, 10, 64), (2052, 516, 10, 128), (256, 256, 16, 16),
+                                         (4096, 4096, 6, 32), (100, 76, 12, 100)])
+def test_share_matches_oracle(scd, oracle, m, n, w, share):
+    run_and_check(scd, oracle, gauss((m, n), m + n + share), w, 13, share)
+
+
+def test_share_f64_and_large(scd, oracle):
+    from paper_2410_01799_amd import workloads
+
+    run_and_check(scd, oracle, gauss((1026, 770), 3, np.float64), 8, 2, 64)
+    run_and_check(scd, oracle, workloads.weight_like_matrix(14336, 4096, 301), 3, 301, 64)
+
+
+def test_share_limits_and_engine_choice(scd):
+    os.environ.pop("SCD_RESIDENT", None)
+    os.environ.pop("SCD_SPARSE_MIN_MIB", None)
+    A = torch.from_numpy(gauss((4096, 4096), 1)).cuda()
+    with scd.ScdContext(A, 4, 1) as ctx:
+        assert ctx.engine()["engine"] == 1            # the whole device: register-resident
+        ctx.run(2)
+        ctx.set_workgroups(64)                        # its 256 workgroups do not fit a share of 64
+        assert ctx.engine()["engine"] == 2
+        ctx.run(2)
+        res = ctx.results()
+        with pytest.raises(scd.ScdError):
+            ctx.set_workgroups(8)
+        with pytest.raises(scd.ScdError):
+            ctx.set_workgroups(-1)
+        ctx.set_workgroups(0)
+        assert ctx.engine()["engine"] == 1
+    tr = res["trace"].cpu().numpy()
+    c = res["c"].cpu().numpy().astype(np.float64)
+    np.testing.assert_allclose(tr[1:] ** 2, tr[:-1] ** 2 - 4096 * 4096 * c ** 2, rtol=ID_RTOL)
+    B = torch.from_numpy(gauss((256, 256), 2)).cuda()
+    with scd.ScdContext(B, 4, 1) as ctx:
+        ctx.set_workgroups(64)
+        assert ctx.engine()["engine"] == 1            # 4 x 4 workgroups fit
+    # a tensor has no persistent engine: the share is accepted and changes nothing
+    Tn = torch.from_numpy(gauss((20, 30, 3), 3)).cuda()
+    with scd.ScdContext(Tn, 4, 1) as ctx:
+        ctx.set_workgroups(64)
+        assert ctx.engine()["engine"] == 0
+        ctx.run(4)
+
+
+def test_contexts_side_by_side_reproduce_their_solo_runs(scd):
+    import threading
+
+    shapes = [(2048, 1024), (1024, 4096), (1536, 1536), (4096, 1024)]
+    mats = [torch.from_numpy(gauss(sh, 40 + i)).cuda() for i, sh in enumerate(shapes)]
+    w = 24
+
+    def one(i, out):
+        torch.cuda.set_device(0)
+        st = torch.cuda.Stream()
+        with torch.cuda.stream(st):
+            with scd.ScdContext(mats[i], w, 100 + i) as ctx:
+                ctx.set_workgroups(64)
+                assert ctx.engine()["engine"] == 2
+                for _ in range(3):
+                    ctx.run(w // 3)
+                out[i] = ctx.results()
+            st.synchronize()
+
+    solo = [None] * len(mats)
+    for i in range(len(mats)):
+        one(i, solo)
+    together = [None] * len(mats)
+    errors = []
+
+    def guarded(i):
+        try:
+            one(i, together)
+        except Exception as e:  # noqa: BLE001 - reported below, in the main thread
+            errors.append((i, repr(e)))
+
+    threads = [threading.Thread(target=guarded, args=(i,)) for i in range(len(mats))]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    torch.cuda.synchronize()
+    assert not errors, errors
+    for a, b in zip(solo, together):
+        assert torch.equal(a["signs"][0], b["signs"][0]) and torch.equal(a["signs"][1], b["signs"][1])
+        assert torch.equal(a["c"], b["c"]) and torch.equal(a["trace"], b["trace"]) and torch.equal(a["iters"], b["iters"])
