@@ -12,6 +12,8 @@
  *   - Section 5.1, Algorithm 12 AXIAL GREEDY CUT           -> scdo_axial_greedy_cut
  *   - Section 5.2, Algorithm 13 TENSOR GREEDY DECOMPOSITION-> scdo_tensor_decompose
  *   - Section 2.2 / 5.2 definition  a - r_w = sum_j c_j s_j -> scdo_expand
+ *   - Section 6.1 (Question A) product of the decomposition with a vector, without expanding it
+ *                                                          -> scdo_apply
  *   - Section 2.2 signed cut norm (max over sign vectors)  -> scdo_bruteforce_signed_cut_norm
  *   - Section 3.1 sign bitsets (a 1 bit stands for -1)     -> scdo_pack / scdo_unpack
  *
@@ -474,6 +476,30 @@ void scdo_expand(int order, const int64_t* dims, int64_t w, const uint64_t* cons
         out[pos] = acc;
         ++pos;
     } while (next_index(order, dims, idx));
+}
+
+/* ---------------------------------------------------------------- product with a vector (Section 6.1) */
+
+/*
+ * y = (sum_{j<w} c_j s_j t_j^T) x          (transpose == 0:  x has n entries, y has m)
+ * y = (sum_{j<w} c_j s_j t_j^T)^T x        (transpose != 0:  x has m entries, y has n)
+ * straight from the factors: z_j = c_j <t_j, x>, then y = sum_j z_j s_j with the terms added in
+ * the order j = 0..w-1 (for the transpose the two sign vectors trade places).
+ */
+void scdo_apply(int64_t m, int64_t n, int64_t w, const uint64_t* S, const uint64_t* T, const double* c,
+                int transpose, const double* x, double* y)
+{
+    const uint64_t* in_bits = transpose ? S : T;
+    const uint64_t* out_bits = transpose ? T : S;
+    int64_t nin = transpose ? m : n, nout = transpose ? n : m;
+    int64_t win = words_for(nin), wout = words_for(nout);
+    for (int64_t i = 0; i < nout; ++i) y[i] = 0.0;
+    for (int64_t j = 0; j < w; ++j) {
+        double z = 0.0;
+        for (int64_t l = 0; l < nin; ++l) z += sign_at(in_bits + j * win, l) * x[l];
+        z *= c[j];
+        for (int64_t i = 0; i < nout; ++i) y[i] += sign_at(out_bits + j * wout, i) * z;
+    }
 }
 
 /* ---------------------------------------------------------------- brute force (Section 2.2, 3.1) */

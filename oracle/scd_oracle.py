@@ -71,6 +71,7 @@ def _load():
                                         C.POINTER(vp), _f64p, _f64p, vp, vp, vp]
     L.scdo_tensor_decompose.restype = C.c_int
     L.scdo_expand.argtypes = [C.c_int, _i64p, C.c_int64, C.POINTER(vp), _f64p, _f64p]
+    L.scdo_apply.argtypes = [C.c_int64, C.c_int64, C.c_int64, _u64p, _u64p, _f64p, C.c_int, _f64p, _f64p]
     L.scdo_bruteforce_signed_cut_norm.argtypes = [_f64p, C.c_int64, C.c_int64, C.POINTER(C.c_uint64)]
     L.scdo_bruteforce_signed_cut_norm.restype = C.c_double
     _lib = L
@@ -265,6 +266,15 @@ def expand(signs, c, dims) -> np.ndarray:
     out = np.empty(int(np.prod(dims)), dtype=np.float64)
     _load().scdo_expand(len(dims), dims, c.size, _ptrs(sg), c, out)
     return out.reshape(tuple(int(d) for d in dims))
+
+
+def apply(S, T, c, m: int, n: int, x, transpose: bool = False) -> np.ndarray:
+    """(sum_j c_j s_j t_j^T) x, or the transposed matrix times x, from the packed factors (Section 6.1)."""
+    S, T, c, x = _u64(S), _u64(T), _f64(c).ravel(), _f64(x).ravel()
+    assert x.size == (m if transpose else n)
+    y = np.empty(n if transpose else m, dtype=np.float64)
+    _load().scdo_apply(m, n, c.size, S, T, c, 1 if transpose else 0, x, y)
+    return y
 
 
 def bruteforce_signed_cut_norm(A):

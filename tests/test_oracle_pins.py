@@ -228,6 +228,53 @@ def test_expand_order_and_rounding(oracle):
     assert np.array_equal(E, ref)
 
 
+# ------------------------------------------------------------------ product with a vector (Section 6.1)
+
+
+def test_apply_is_the_dense_product(oracle):
+    # The packed product equals (sum_j c_j s_j t_j^T) x formed with dense +-1 vectors and numpy's matmul;
+    # the transposed form equals the transposed matrix times x.  Ragged sizes: tails of both bitsets count.
+    rs = np.random.default_rng(21)
+    for (m, n, w) in [(9, 70, 40), (130, 65, 7), (64, 128, 1), (5, 3, 0)]:
+        S = np.array([bits_of(np.sign(rs.standard_normal(m))) for _ in range(w)]).reshape(w, (m + 63) // 64)
+        T = np.array([bits_of(np.sign(rs.standard_normal(n))) for _ in range(w)]).reshape(w, (n + 63) // 64)
+        c = rs.standard_normal(w)
+        M = np.zeros((m, n))
+        for j in range(w):
+            M += c[j] * np.outer(dense(S[j], m), dense(T[j], n))
+        x, xt = rs.standard_normal(n), rs.standard_normal(m)
+        np.testing.assert_allclose(oracle.apply(S, T, c, m, n, x), M @ x, rtol=0, atol=1e-12 * max(1.0, np.abs(M).sum()))
+        np.testing.assert_allclose(oracle.apply(S, T, c, m, n, xt, transpose=True), M.T @ xt, rtol=0,
+                                   atol=1e-12 * max(1.0, np.abs(M).sum()))
+
+
+def test_apply_one_term_closed_form_and_adjoint(oracle):
+    # w = 1: y = c <t, x> s exactly.  Any w: <y', A x> = <A^T y', x> (the two forms are adjoint).
+    rs = np.random.default_rng(22)
+    m, n = 67, 190
+    s, t = np.sign(rs.standard_normal(m)), np.sign(rs.standard_normal(n))
+    x = rs.integers(-8, 9, n).astype(np.float64)            # small integers: every sum is exact
+    y = oracle.apply(bits_of(s)[None, :], bits_of(t)[None, :], np.array([0.375]), m, n, x)
+    assert np.array_equal(y, 0.375 * float(t @ x) * s)
+    w = 25
+    S = np.array([bits_of(np.sign(rs.standard_normal(m))) for _ in range(w)])
+    T = np.array([bits_of(np.sign(rs.standard_normal(n))) for _ in range(w)])
+    c = rs.standard_normal(w)
+    xv, yv = rs.standard_normal(n), rs.standard_normal(m)
+    lhs = yv @ oracle.apply(S, T, c, m, n, xv)
+    rhs = oracle.apply(S, T, c, m, n, yv, transpose=True) @ xv
+    assert lhs == pytest.approx(rhs, rel=1e-12)
+
+
+def test_apply_agrees_with_a_decomposition_and_its_remainder(oracle):
+    # (A - R_w) x = sum_j c_j s_j <t_j, x> for the factors the decomposition itself returns (Section 1, definition).
+    A = rng_matrix(40, 72, 23)
+    res = oracle.decompose(A, 12, 9, want_remainder=True)
+    x = np.random.default_rng(24).standard_normal(72)
+    y = oracle.apply(res["S"], res["T"], res["c"], 40, 72, x)
+    np.testing.assert_allclose(y, (A - res["R"]) @ x, rtol=0, atol=1e-12 * np.abs(A).sum())
+
+
 # ------------------------------------------------------------------ printed values
 
 
