@@ -129,6 +129,23 @@ int scd_col_signed_sum(const void* R, scd_dtype dt, int64_t m, int64_t n, const 
 int scd_expand(const uint64_t* const* signs, const void* c, scd_dtype dt, int order, const int64_t* dims,
                int64_t w, void* stream, void* out);
 
+/* Product of a matrix decomposition with a vector, straight from the packed factors, without expanding
+ * the matrix (Section 6.1, Question A):
+ *   transpose == 0:  y = (sum_{j<w} c_j s_j t_j^T) x      x: n entries, y: m entries
+ *   transpose != 0:  y = (sum_{j<w} c_j s_j t_j^T)^T x    x: m entries, y: n entries
+ * computed as z_j = c_j <t_j, x> and y = sum_j z_j s_j, every sum in f64 in a fixed order, y rounded once
+ * to dt.  S, T: device, term-major bitsets as scd_decompose writes them (w * ceil(m/64) and
+ * w * ceil(n/64) words, padding bits 0); c, x, y: device, dtype dt; x and y must not overlap.
+ * nvec >= 1 vectors are taken one after the other: x is nvec rows of the input length, y nvec rows of the
+ * output length.  workspace: device, at least scd_apply_workspace_bytes(m, n, w) bytes, 8-byte aligned,
+ * owned by the caller and free again on return; the call allocates nothing and is synchronous on stream.
+ * w == 0 gives y = 0.  SCD_EINVAL on null pointers, negative sizes, m or n above 2^31, a workspace that
+ * is too small. */
+size_t scd_apply_workspace_bytes(int64_t m, int64_t n, int64_t w);
+int scd_apply(const uint64_t* S, const uint64_t* T, const void* c, scd_dtype dt, int64_t m, int64_t n, int64_t w,
+              int transpose, const void* x, int64_t nvec, void* y, void* workspace, size_t workspace_bytes,
+              void* stream);
+
 /* ---- bitsets (Section 3.1) -------------------------------------------------------------------- */
 int scd_pack(const void* values, scd_dtype dt, int64_t n, void* stream, uint64_t* bits);   /* x < 0 -> 1 */
 int scd_unpack(const uint64_t* bits, int64_t n, scd_dtype dt, void* stream, void* values); /* 1 -> -1.0 */

@@ -966,6 +966,39 @@ int scd_expand(const uint64_t* const* signs, const void* cvec, scd_dtype dt, int
     return SCD_OK;
 }
 
+size_t scd_apply_workspace_bytes(int64_t m, int64_t n, int64_t w)
+{
+    if (m < 0 || n < 0 || w < 0) return 0;
+    // either direction: the larger of the two layouts
+    ApplyPlan a, b;
+    apply_plan(n, m, w, &a);
+    apply_plan(m, n, w, &b);
+    return a.bytes > b.bytes ? a.bytes : b.bytes;
+}
+
+int scd_apply(const uint64_t* S, const uint64_t* T, const void* c, scd_dtype dt, int64_t m, int64_t n, int64_t w,
+              int transpose, const void* x, int64_t nvec, void* y, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!dtype_ok(dt) || m < 0 || n < 0 || w < 0 || nvec < 0) return SCD_EINVAL;
+    if (m > (1ll << 31) || n > (1ll << 31)) return SCD_EINVAL;
+    const int64_t nin = transpose ? m : n, nout = transpose ? n : m;
+    if (nvec == 0 || nout == 0) return SCD_OK;
+    if (!y || !workspace || ((uintptr_t)workspace & 7u)) return SCD_EINVAL;
+    if (w > 0 && nin > 0 && (!S || !T || !c || !x)) return SCD_EINVAL;
+    ApplyPlan pl;
+    apply_plan(nin, nout, w, &pl);
+    if (workspace_bytes < pl.bytes) return SCD_EINVAL;
+    const size_t es = dt == SCD_F32 ? 4 : 8;
+    hipStream_t st = (hipStream_t)stream;
+    for (int64_t v = 0; v < nvec; ++v) {
+        HIP_TRY(launch_apply(transpose ? S : T, transpose ? T : S, c, dt, nin, nout, w,
+                             x ? (const char*)x + (size_t)v * (size_t)nin * es : nullptr,
+                             (char*)y + (size_t)v * (size_t)nout * es, workspace, st));
+    }
+    HIP_TRY(hipStreamSynchronize(st));
+    return SCD_OK;
+}
+
 int scd_pack(const void* values, scd_dtype dt, int64_t n, void* stream, uint64_t* bits)
 {
     if (!values || !bits || !dtype_ok(dt) || n < 0) return SCD_EINVAL;

@@ -1,0 +1,245 @@
+// Product of a signed cut decomposition with a vector, straight from the packed factors
+// (Section 6.1 of arXiv 2410.01799, Question A):
+//     y = (sum_j c_j s_j t_j^T) x = sum_j z_j s_j,    z_j = c_j <t_j, x>.
+// The matrix is never expanded: the kernels read the w (m + n) / 8 bytes of sign bits once and do one
+// select and one add per bit.
+//
+// Both passes have the same inner step: a wave owns 64 consecutive entries (one per lane), takes a
+// 64-bit word of sign bits that is the same for all its lanes (fetched by one lane, broadcast through a
+// scalar register), turns bit `lane` into a multiplier +-1.0 and adds with one fused multiply-add in f64 (the product with +-1 is exact, so each
+// step rounds like the sign-flip-and-add of Section 3.4).
+//   inner pass  lanes = 64 entries of x, kept in registers for a chunk of 4096 entries; for every term
+//               the wave adds its 64 words and reduces across the lanes -> <t_j, x> per chunk
+//   outer pass  lanes = 64 entries of y; z_j = c_j * (sum of the chunk parts, in order) is formed on the
+//               way in, and for every term of its split the wave adds +-z_j
+//   reduce      y = sum of the splits, in order, rounded once to the output type
+// Every sum has a fixed order: results are bit-identical from run to run.
+#include "scd_device.h"
+
+namespace scd {
+
+namespace {
+
+constexpr int kApChunkWords = 64;   // words of sign bits per lane-resident chunk of x (4096 entries)
+constexpr int kApInnerWaves = 4;    // waves per workgroup of the inner pass
+constexpr int kApOuterWaves = 8;    // waves per workgroup of the outer pass: 8 adjacent words = one 64-byte line
+
+__device__ __forceinline__ double ap_wave_sum(double a)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) a += __shfl_xor(a, off, kWave);
+    return a;
+}
+
+// +-1.0 for lane `lane` from bit `lane` of a wave-uniform word (a 1 bit stands for -1)
+__device__ __forceinline__ double ap_sign(uint64_t word)
+{
+    const int hi = __builtin_amdgcn_inverse_ballot_w64(word) ? (int)0xBFF00000 : (int)0x3FF00000;
+    return __hiloint2double(hi, 0);
+}
+
+// word `p` of a lane-distributed row of sign bits (lane p holds word p), as a wave-uniform value
+__device__ __forceinline__ uint64_t ap_word(uint64_t lane_word, int p)
+{
+    const uint32_t lo = __builtin_amdgcn_readlane((uint32_t)lane_word, p);
+    const uint32_t hi = __builtin_amdgcn_readlane((uint32_t)(lane_word >> 32), p);
+    return ((uint64_t)hi << 32) | lo;
+}
+
+constexpr int kApDepth = 4;  // rows of sign bits in flight per wave
+
+template <typename TE>
+__global__ void __launch_bounds__(kApInnerWaves* kWave)
+    apply_inner_kernel(const uint64_t* __restrict__ bits, int64_t nw, int64_t w, const TE* __restrict__ x, int64_t n,
+                       double* __restrict__ part, int terms_per_wave)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int64_t chunk = blockIdx.y;
+    const int64_t p0 = chunk * kApChunkWords;
+    const int nwc = (int)(nw - p0 < kApChunkWords ? nw - p0 : kApChunkWords);  // words of this chunk
+    double xr[kApChunkWords];
+#pragma unroll
+    for (int p = 0; p < kApChunkWords; ++p) {
+        // unconditional loads (all in flight together); entries past the end count as zero
+        const int64_t l = (p0 + p) * 64 + lane;
+        const TE v = x[l < n ? l : n - 1];
+        xr[p] = l < n ? (double)v : 0.0;
+    }
+    const int64_t j0 = ((int64_t)blockIdx.x * kApInnerWaves + wv) * terms_per_wave;
+    const int64_t j1 = j0 + terms_per_wave < w ? j0 + terms_per_wave : w;
+    if (j0 >= j1) return;
+    // Lane p fetches word p of a term's row (one coalesced load per term), kApDepth terms ahead.  Loads
+    // are unconditional: terms past the end re-read the last one, lanes past the end of the row read its
+    // first word (the entries of x there are zero, so any valid word will do).
+    const int64_t lw = p0 + (lane < nwc ? lane : 0);
+    uint64_t buf[kApDepth];
+#pragma unroll
+    for (int d = 0; d < kApDepth; ++d) {
+        const int64_t jn = j0 + d < j1 ? j0 + d : j1 - 1;
+        buf[d] = bits[jn * nw + lw];
+    }
+    for (int64_t j = j0; j < j1; j += kApDepth) {
+#pragma unroll
+        for (int d = 0; d < kApDepth; ++d) {
+            const uint64_t row = buf[d];
+            const int64_t jn = j + kApDepth + d < j1 ? j + kApDepth + d : j1 - 1;
+            buf[d] = bits[jn * nw + lw];
+            if (j + d < j1) {
+                // four independent chains: a dependent f64 add would wait for the one before it
+                double a4[4] = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+                for (int p = 0; p < kApChunkWords; ++p) a4[p & 3] = __builtin_fma(xr[p], ap_sign(ap_word(row, p)), a4[p & 3]);
+                double acc = (a4[0] + a4[1]) + (a4[2] + a4[3]);
+                acc = ap_wave_sum(acc);
+                if (lane == 0) part[chunk * w + j + d] = acc;
+            }
+        }
+    }
+}
+
+// Outer pass.  Wave (p, split) owns the 64 output entries of word p and the terms of its split; lane q
+// fetches word p of term (tile + q) and forms z of that term (the scale step: c times the chunk parts in
+// order); z goes through a wave-private strip of LDS so that every lane can read every term's value.
+template <typename TE>
+__global__ void __launch_bounds__(kApOuterWaves* kWave)
+    apply_outer_kernel(const uint64_t* __restrict__ bits, int64_t mw, int64_t w, const double* __restrict__ part, int chunks,
+                       const TE* __restrict__ c, int64_t terms_per_split, double* __restrict__ ypart)
+{
+    __shared__ double zs[kApOuterWaves][2][kWave];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int64_t p = (int64_t)blockIdx.x * kApOuterWaves + wv;  // word of the output this wave owns
+    if (p >= mw) return;                                           // (no workgroup-wide barrier below)
+    const int64_t split = blockIdx.y;
+    const int64_t j0 = split * terms_per_split;
+    const int64_t j1 = j0 + terms_per_split < w ? j0 + terms_per_split : w;
+    auto fetch = [&](int64_t tile, uint64_t& word, double& z) {
+        // unconditional loads; terms past the end re-read the last one and count as z = 0
+        const int64_t j = tile + lane;
+        const int64_t jc = j < j1 ? j : j1 - 1;
+        word = bits[jc * mw + p];
+        double s = 0.0;
+        for (int q = 0; q < chunks; ++q) s += part[(int64_t)q * w + jc];
+        z = j < j1 ? (double)c[jc] * s : 0.0;
+    };
+    double a4[4] = {0.0, 0.0, 0.0, 0.0};
+    if (j0 < j1) {
+        // two tiles of 64 terms in flight ahead of the one being added
+        uint64_t word_a, word_b;
+        double z_a, z_b;
+        fetch(j0, word_a, z_a);
+        fetch(j0 + kWave < j1 ? j0 + kWave : j0, word_b, z_b);
+        int b = 0;
+        for (int64_t tile = j0; tile < j1; tile += kWave, b ^= 1) {
+            const uint64_t word = word_a;
+            zs[wv][b][lane] = z_a;
+            word_a = word_b;
+            z_a = z_b;
+            fetch(tile + 2 * kWave < j1 ? tile + 2 * kWave : tile, word_b, z_b);
+            // the strip is written and read by this wave only: LDS operations of one wave complete in order
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll 16
+            for (int q = 0; q < kWave; ++q) a4[q & 3] = __builtin_fma(zs[wv][b][q], ap_sign(ap_word(word, q)), a4[q & 3]);
+        }
+    }
+    ypart[split * (mw * 64) + p * 64 + lane] = (a4[0] + a4[1]) + (a4[2] + a4[3]);
+}
+
+// y = sum of the splits in order, rounded once.  64 entries per workgroup; the splits are cut into four
+// runs that are added side by side (their loads in flight together) and joined in order.
+template <typename TE>
+__global__ void __launch_bounds__(256)
+    apply_reduce_kernel(const double* __restrict__ ypart, int splits, int64_t mpad, int64_t m, TE* __restrict__ y)
+{
+    __shared__ double run[4][64];
+    const int r = threadIdx.x & 63, g = threadIdx.x >> 6;
+    const int64_t i = (int64_t)blockIdx.x * 64 + r;
+    const int per = (splits + 3) / 4;
+    const int q0 = g * per, q1 = q0 + per < splits ? q0 + per : splits;
+    double s = 0.0;
+    if (i < mpad) {
+        int q = q0;
+        for (; q + 4 <= q1; q += 4) {
+            const double a0 = ypart[(int64_t)q * mpad + i], a1 = ypart[(int64_t)(q + 1) * mpad + i];
+            const double a2 = ypart[(int64_t)(q + 2) * mpad + i], a3 = ypart[(int64_t)(q + 3) * mpad + i];
+            s = (((s + a0) + a1) + a2) + a3;
+        }
+        for (; q < q1; ++q) s += ypart[(int64_t)q * mpad + i];
+    }
+    run[g][r] = s;
+    __syncthreads();
+    if (g == 0 && i < m) y[i] = (TE)(((run[0][r] + run[1][r]) + run[2][r]) + run[3][r]);
+}
+
+}  // namespace
+
+void apply_plan(int64_t nin, int64_t nout, int64_t w, ApplyPlan* pl)
+{
+    const int64_t win = (nin + 63) / 64, wout = (nout + 63) / 64;
+    pl->chunks = (int)((win + kApChunkWords - 1) / kApChunkWords);
+    if (pl->chunks < 1) pl->chunks = 1;
+    // inner pass: enough waves to fill the device, enough terms per wave to pay for loading its chunk of x
+    int64_t tpw = (w * pl->chunks + 4095) / 4096;
+    if (tpw < 8) tpw = 8;
+    if (tpw > 64) tpw = 64;
+    pl->terms_per_wave = (int)tpw;
+    // outer pass: one wave per word of the output and split of the terms
+    int64_t splits = wout > 0 ? (4096 + wout - 1) / wout : 1;
+    if (splits > 64) splits = 64;
+    while (splits > 1 && (w + splits - 1) / splits < 32) --splits;
+    if (splits < 1) splits = 1;
+    pl->terms_per_split = (w + splits - 1) / splits;
+    if (pl->terms_per_split < 1) pl->terms_per_split = 1;
+    pl->splits = (int)((w + pl->terms_per_split - 1) / pl->terms_per_split);
+    if (pl->splits < 1) pl->splits = 1;
+    pl->off_part = 0;
+    pl->off_ypart = pl->off_part + (size_t)pl->chunks * (size_t)w * 8;
+    pl->bytes = pl->off_ypart + (size_t)pl->splits * (size_t)wout * 64 * 8;
+    if (pl->bytes < 8) pl->bytes = 8;
+}
+
+hipError_t launch_apply(const uint64_t* in_bits, const uint64_t* out_bits, const void* c, scd_dtype dt, int64_t nin,
+                        int64_t nout, int64_t w, const void* x, void* y, void* workspace, hipStream_t st)
+{
+    ApplyPlan pl;
+    apply_plan(nin, nout, w, &pl);
+    const int64_t win = (nin + 63) / 64, wout = (nout + 63) / 64;
+    double* part = (double*)((char*)workspace + pl.off_part);
+    double* ypart = (double*)((char*)workspace + pl.off_ypart);
+    if (nout == 0) return hipSuccess;
+    if (w == 0 || nin == 0) {
+        // the empty sum: a reduce over no splits writes zeros
+        const unsigned g0 = (unsigned)((nout + 63) / 64);
+        if (dt == SCD_F32)
+            hipLaunchKernelGGL((apply_reduce_kernel<float>), dim3(g0), dim3(256), 0, st, ypart, 0, wout * 64, nout, (float*)y);
+        else
+            hipLaunchKernelGGL((apply_reduce_kernel<double>), dim3(g0), dim3(256), 0, st, ypart, 0, wout * 64, nout, (double*)y);
+        return hipGetLastError();
+    }
+    const int64_t waves = (w + pl.terms_per_wave - 1) / pl.terms_per_wave;
+    dim3 gi((unsigned)((waves + kApInnerWaves - 1) / kApInnerWaves), (unsigned)pl.chunks);
+    if (dt == SCD_F32)
+        hipLaunchKernelGGL((apply_inner_kernel<float>), gi, dim3(kApInnerWaves * kWave), 0, st, in_bits, win, w, (const float*)x,
+                           nin, part, pl.terms_per_wave);
+    else
+        hipLaunchKernelGGL((apply_inner_kernel<double>), gi, dim3(kApInnerWaves * kWave), 0, st, in_bits, win, w,
+                           (const double*)x, nin, part, pl.terms_per_wave);
+    dim3 go((unsigned)((wout + kApOuterWaves - 1) / kApOuterWaves), (unsigned)pl.splits);
+    if (dt == SCD_F32)
+        hipLaunchKernelGGL((apply_outer_kernel<float>), go, dim3(kApOuterWaves * kWave), 0, st, out_bits, wout, w, part,
+                           pl.chunks, (const float*)c, pl.terms_per_split, ypart);
+    else
+        hipLaunchKernelGGL((apply_outer_kernel<double>), go, dim3(kApOuterWaves * kWave), 0, st, out_bits, wout, w, part,
+                           pl.chunks, (const double*)c, pl.terms_per_split, ypart);
+    const unsigned gr = (unsigned)((nout + 63) / 64);
+    if (dt == SCD_F32)
+        hipLaunchKernelGGL((apply_reduce_kernel<float>), dim3(gr), dim3(256), 0, st, ypart, pl.splits, wout * 64, nout, (float*)y);
+    else
+        hipLaunchKernelGGL((apply_reduce_kernel<double>), dim3(gr), dim3(256), 0, st, ypart, pl.splits, wout * 64, nout, (double*)y);
+    return hipGetLastError();
+}
+
+}  // namespace scd

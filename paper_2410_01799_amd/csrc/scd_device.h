@@ -172,6 +172,18 @@ size_t sparse_xbuf_bytes();
 hipError_t launch_sparse(const SparseArgs& a, scd_dtype dt, hipStream_t st);
 hipError_t launch_transpose(const void* in, void* out, scd_dtype dt, int64_t rows, int64_t cols, hipStream_t st);
 
+// ---- product with a vector from the packed factors (scd_apply.hip) ---------------------------------
+struct ApplyPlan {
+    int chunks;               // chunks of 4096 input entries
+    int terms_per_wave;       // inner pass
+    int splits;               // outer pass: parts the terms are split into
+    int64_t terms_per_split;
+    size_t off_part, off_ypart, bytes;  // workspace layout
+};
+void apply_plan(int64_t nin, int64_t nout, int64_t w, ApplyPlan* pl);
+hipError_t launch_apply(const uint64_t* in_bits, const uint64_t* out_bits, const void* c, scd_dtype dt, int64_t nin,
+                        int64_t nout, int64_t w, const void* x, void* y, void* workspace, hipStream_t st);
+
 // ---- launchers implemented in scd_kernels.hip ----------------------------------------------------
 hipError_t launch_rowpass(const RowPassArgs& a, scd_dtype dt, int grid, int variant, hipStream_t st);
 hipError_t launch_reduce(const ReduceArgs& a, bool f32_partials, hipStream_t st);

@@ -25,6 +25,7 @@ EXPORTS = [
     "scd_width", "scd_results", "scd_remainder", "scd_set_remainder", "scd_row_signed_sum", "scd_col_signed_sum",
     "scd_expand", "scd_pack", "scd_unpack", "scd_rng_signs", "scd_strerror", "scd_last_hip_error", "scd_traffic",
     "scd_probe_stream", "scd_profile_sweeps", "scd_probe_exchange", "scd_engine", "scd_set_workgroups",
+    "scd_apply", "scd_apply_workspace_bytes",
 ]
 
 
@@ -54,6 +55,9 @@ def lib() -> C.CDLL:
         L.scd_destroy.restype = None
         L.scd_set_max_iters.argtypes = [vp, i32]
         L.scd_set_workgroups.argtypes = [vp, C.c_int]
+        L.scd_apply_workspace_bytes.argtypes = [i64, i64, i64]
+        L.scd_apply_workspace_bytes.restype = C.c_size_t
+        L.scd_apply.argtypes = [vp, vp, vp, C.c_int, i64, i64, i64, C.c_int, vp, i64, vp, vp, C.c_size_t, vp]
         L.scd_step.argtypes = [vp]
         L.scd_run.argtypes = [vp, i64]
         L.scd_step_from.argtypes = [vp, pvp]
@@ -160,6 +164,32 @@ def scd_expand(signs: Sequence[torch.Tensor], c: torch.Tensor, dims: Sequence[in
     st = lib().scd_expand(_ptr_array(list(signs)), _ptr(c), _dt(c), len(dims), _dims(dims), w, _stream(), _ptr(out))
     _check(st, "scd_expand")
     return out
+
+
+def scd_apply(S: torch.Tensor, T: torch.Tensor, c: torch.Tensor, m: int, n: int, x: torch.Tensor,
+              transpose: bool = False, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """(sum_j c_j s_j t_j^T) x, or the transposed matrix times x, from the packed factors; x may hold
+    several vectors as rows.  dtype of c."""
+    c = _dev(c, "c")
+    S, T = _dev(S, "S"), _dev(T, "T")
+    x = _dev(x, "x")
+    if x.dtype != c.dtype:
+        raise TypeError("x and c must have the same dtype")
+    w = int(c.numel())
+    nin, nout = (m, n) if transpose else (n, m)
+    single = x.dim() == 1
+    x2 = x.reshape(1, -1) if single else x
+    if x2.dim() != 2 or x2.shape[1] != nin:
+        raise ValueError(f"x must have {nin} entries per vector")
+    nvec = int(x2.shape[0])
+    need = int(lib().scd_apply_workspace_bytes(int(m), int(n), w))
+    if workspace is None:
+        workspace = torch.empty((need + 7) // 8, dtype=torch.float64, device=c.device)
+    y = torch.empty((nvec, nout), dtype=c.dtype, device=c.device)
+    st = lib().scd_apply(_ptr(S), _ptr(T), _ptr(c), _dt(c), int(m), int(n), w, 1 if transpose else 0, _ptr(x2), nvec,
+                         _ptr(y), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream())
+    _check(st, "scd_apply")
+    return y[0] if single else y
 
 
 def scd_pack(values: torch.Tensor) -> torch.Tensor:
