@@ -121,6 +121,44 @@ def layer_mode(args, scd, workloads, torch, np) -> int:
     return 0
 
 
+def apply_mode(args, scd, torch) -> int:
+    """Microseconds per product of a decomposition with a vector, straight from the packed factors
+    (Section 6.1), on random factors of the layer shapes at their 50 % widths; a plain f32 matrix-vector
+    product of the same shape (torch) is timed beside it.  Wall-clock per product includes the host's three
+    launches; the kernels' own durations are in profiles/."""
+    rows = []
+    L = scd.lib()
+    for (m, n, w) in [(4096, 4096, 16320), (1024, 4096, 6512), (14336, 4096, 25442)]:
+        g = torch.Generator(device="cuda")
+        g.manual_seed(m + n)
+        S = torch.randint(-2 ** 62, 2 ** 62, (w, (m + 63) // 64), device="cuda", generator=g)
+        T = torch.randint(-2 ** 62, 2 ** 62, (w, (n + 63) // 64), device="cuda", generator=g)
+        c = torch.randn(w, device="cuda", generator=g)
+        reps = 20
+        X = torch.randn(reps, n, device="cuda", generator=g)
+        ws = torch.empty(L.scd_apply_workspace_bytes(m, n, w) // 8 + 1, dtype=torch.float64, device="cuda")
+        scd.scd_apply(S, T, c, m, n, X, workspace=ws)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        scd.scd_apply(S, T, c, m, n, X, workspace=ws)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / reps
+        A = torch.randn(m, n, device="cuda", generator=g)
+        A @ X[0]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for r in range(reps):
+            A @ X[r]
+        torch.cuda.synchronize()
+        dg = (time.perf_counter() - t0) / reps
+        bits = w * ((m + 63) // 64 + (n + 63) // 64) * 8
+        rows.append({"shape": [m, n], "width": w, "us_per_product": round(dt * 1e6, 1), "sign_bit_bytes": bits,
+                     "sign_bits_gbs": round(bits / dt / 1e9, 1), "dense_f32_matvec_us": round(dg * 1e6, 1)})
+    print(json.dumps({"metric": "microseconds per packed product y = (sum_j c_j s_j t_j^T) x", "unit": "us", "n_gpus": 1,
+                      "dtype": "f32 in/out, f64 sums", "data": "synthetic", "products": rows}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -140,6 +178,9 @@ def main() -> int:
                          "and the line says so)")
     ap.add_argument("--concurrency", type=int, default=4, choices=[1, 2, 4, 8],
                     help="with --layer: matrices decomposed side by side, each on 256/K compute units")
+    ap.add_argument("--apply", action="store_true",
+                    help="instead of the headline: time the product of a decomposition with a vector from the "
+                         "packed factors (scd_apply) on the layer shapes")
     ap.add_argument("--calibrate", action="store_true",
                     help="only run the plain copy kernel (64 MiB, 20+1 launches): the known-size reference "
                          "for scaling the profiler's FETCH_SIZE / WRITE_SIZE counters")
@@ -168,6 +209,8 @@ def main() -> int:
         return 0
     if args.layer:
         return layer_mode(args, scd, workloads, torch, np)
+    if args.apply:
+        return apply_mode(args, scd, torch)
     m = n = args.size
     w, seed = args.width, 2
     A64 = workloads.gaussian_matrix(m, n, seed, np.float64)

@@ -9,6 +9,7 @@
  *   - Section 3.1, Algorithm 4  GREEDY SIGNED CUT          -> scdo_greedy_signed_cut
  *   - Section 3.2, Algorithm 5  GREEDY DECOMPOSITION       -> scdo_decompose
  *   - Section 3.2, Frobenius identity                      -> checked by the tests, not used here
+ *   - Section 3.3, Algorithm 6  LEAST SQUARES DECOMPOSITION-> scdo_lsq_coefficients, scdo_lsq_decompose
  *   - Section 5.1, Algorithm 12 AXIAL GREEDY CUT           -> scdo_axial_greedy_cut
  *   - Section 5.2, Algorithm 13 TENSOR GREEDY DECOMPOSITION-> scdo_tensor_decompose
  *   - Section 2.2 / 5.2 definition  a - r_w = sum_j c_j s_j -> scdo_expand
@@ -295,6 +296,113 @@ int scdo_decompose(const double* A, int64_t m, int64_t n, int64_t w, uint64_t se
         trace[k + 1] = sqrt(scdo_fro2(R, m, n));
     }
     if (R_out) memcpy(R_out, R, bytes);
+    free(R);
+    return capped;
+}
+
+/* ---------------------------------------------------------------- Algorithm 6 (Section 3.3) */
+
+/*
+ * c = argmin || A - sum_{j<k} c_j s_j t_j^T ||_F  (Algorithm 6 line 9) by the normal equations of
+ * Section 3.3:  G c = b,  G_ij = <s_i t_i^T, s_j t_j^T>_F,  b_i = <s_i t_i^T, A>_F.  Every inner
+ * product is the sum over all entries, written out.  G is solved by Gaussian elimination with partial
+ * pivoting.  Returns 0, or 1 if G is singular to working precision (repeated terms).
+ */
+int scdo_lsq_coefficients(const double* A, int64_t m, int64_t n, int64_t k, const uint64_t* S,
+                          const uint64_t* T, double* c)
+{
+    int64_t mw = words_for(m), nw = words_for(n);
+    double* G;
+    double* b;
+    int singular = 0;
+    if (k == 0) return 0;
+    G = (double*)malloc(sizeof(double) * (size_t)k * (size_t)k);
+    b = (double*)malloc(sizeof(double) * (size_t)k);
+    for (int64_t a = 0; a < k; ++a) {
+        double acc = 0.0;
+        for (int64_t i = 0; i < m; ++i)
+            for (int64_t l = 0; l < n; ++l)
+                acc += sign_at(S + a * mw, i) * sign_at(T + a * nw, l) * A[i * n + l];
+        b[a] = acc;
+        for (int64_t q = 0; q <= a; ++q) {
+            double g = 0.0;
+            for (int64_t i = 0; i < m; ++i) {
+                double si = sign_at(S + a * mw, i) * sign_at(S + q * mw, i);
+                for (int64_t l = 0; l < n; ++l) g += si * sign_at(T + a * nw, l) * sign_at(T + q * nw, l);
+            }
+            G[a * k + q] = g;
+            G[q * k + a] = g;
+        }
+    }
+    for (int64_t col = 0; col < k; ++col) {
+        int64_t piv = col;
+        for (int64_t r = col + 1; r < k; ++r)
+            if (fabs(G[r * k + col]) > fabs(G[piv * k + col])) piv = r;
+        if (fabs(G[piv * k + col]) < 1e-9 * (double)m * (double)n) {
+            singular = 1;
+            break;
+        }
+        if (piv != col) {
+            for (int64_t q = 0; q < k; ++q) {
+                double tmp = G[col * k + q];
+                G[col * k + q] = G[piv * k + q];
+                G[piv * k + q] = tmp;
+            }
+            double tb = b[col];
+            b[col] = b[piv];
+            b[piv] = tb;
+        }
+        for (int64_t r = col + 1; r < k; ++r) {
+            double f = G[r * k + col] / G[col * k + col];
+            for (int64_t q = col; q < k; ++q) G[r * k + q] -= f * G[col * k + q];
+            b[r] -= f * b[col];
+        }
+    }
+    if (!singular) {
+        for (int64_t r = k - 1; r >= 0; --r) {
+            double acc = b[r];
+            for (int64_t q = r + 1; q < k; ++q) acc -= G[r * k + q] * c[q];
+            c[r] = acc / G[r * k + r];
+        }
+    }
+    free(G);
+    free(b);
+    return singular;
+}
+
+/*
+ * LEAST SQUARES DECOMPOSITION.  Term k: R_k = A - S_k diag(c_k) T_k^T (line 5, read with the "A -" that
+ * the caption's "orthogonal complement of A" requires), greedy signed cut of R_k from the keyed random
+ * start of term k (line 6; its value is discarded), append (lines 7-8), new coefficients for ALL terms
+ * (line 9).  c gets the final coefficients c_w; trace[k] = ||A - S_k diag(c_k) T_k^T||_F, k = 0..w.
+ * Returns the number of terms whose cut hit max_iters, or -1 if the normal equations became singular.
+ */
+int scdo_lsq_decompose(const double* A, int64_t m, int64_t n, int64_t w, uint64_t seed, int32_t max_iters,
+                       uint64_t* S, uint64_t* T, double* c, double* trace, int32_t* iters, double* margins)
+{
+    int64_t mw = words_for(m), nw = words_for(n);
+    size_t bytes = sizeof(double) * (size_t)m * (size_t)n;
+    double* R = (double*)malloc(bytes);
+    int capped = 0;
+    memcpy(R, A, bytes);
+    trace[0] = sqrt(scdo_fro2(R, m, n));
+    for (int64_t k = 0; k < w; ++k) {
+        uint64_t* sk = S + k * mw;
+        uint64_t* tk = T + k * nw;
+        double cu;
+        int32_t it;
+        scdo_rng_signs(seed, (uint64_t)k, 1, n, tk);
+        capped += scdo_greedy_signed_cut(R, m, n, tk, sk, &cu, max_iters, &it, NULL,
+                                         margins ? margins + 2 * k : NULL);
+        if (iters) iters[k] = it;
+        if (scdo_lsq_coefficients(A, m, n, k + 1, S, T, c)) {
+            free(R);
+            return -1;
+        }
+        memcpy(R, A, bytes);
+        for (int64_t j = 0; j <= k; ++j) scdo_rank1_update(R, m, n, c[j], S + j * mw, T + j * nw);
+        trace[k + 1] = sqrt(scdo_fro2(R, m, n));
+    }
     free(R);
     return capped;
 }

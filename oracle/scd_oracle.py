@@ -71,6 +71,11 @@ def _load():
                                         C.POINTER(vp), _f64p, _f64p, vp, vp, vp]
     L.scdo_tensor_decompose.restype = C.c_int
     L.scdo_expand.argtypes = [C.c_int, _i64p, C.c_int64, C.POINTER(vp), _f64p, _f64p]
+    L.scdo_lsq_coefficients.argtypes = [_f64p, C.c_int64, C.c_int64, C.c_int64, _u64p, _u64p, _f64p]
+    L.scdo_lsq_coefficients.restype = C.c_int
+    L.scdo_lsq_decompose.argtypes = [_f64p, C.c_int64, C.c_int64, C.c_int64, C.c_uint64, C.c_int32, _u64p, _u64p,
+                                     _f64p, _f64p, C.c_void_p, C.c_void_p]
+    L.scdo_lsq_decompose.restype = C.c_int
     L.scdo_apply.argtypes = [C.c_int64, C.c_int64, C.c_int64, _u64p, _u64p, _f64p, C.c_int, _f64p, _f64p]
     L.scdo_bruteforce_signed_cut_norm.argtypes = [_f64p, C.c_int64, C.c_int64, C.POINTER(C.c_uint64)]
     L.scdo_bruteforce_signed_cut_norm.restype = C.c_double
@@ -200,6 +205,35 @@ def decompose(A, w: int, seed: int, max_iters: int = DEFAULT_MAX_ITERS, want_rem
     if want_remainder:
         out["R"] = R
     return out
+
+
+def lsq_coefficients(A, S, T) -> np.ndarray:
+    """argmin_c ||A - sum_j c_j s_j t_j^T||_F for given sign vectors (Algorithm 6 line 9, Section 3.3)."""
+    A = _f64(A)
+    m, n = A.shape
+    S, T = _u64(S).reshape(-1, words(m)), _u64(T).reshape(-1, words(n))
+    k = S.shape[0]
+    c = np.zeros(k, dtype=np.float64)
+    if _load().scdo_lsq_coefficients(A, m, n, k, S, T, c):
+        raise np.linalg.LinAlgError("normal equations singular")
+    return c
+
+
+def lsq_decompose(A, w: int, seed: int, max_iters: int = DEFAULT_MAX_ITERS):
+    """Algorithm 6.  Returns dict(S, T, c (final, all terms), trace, iters, margins, capped)."""
+    A = _f64(A)
+    m, n = A.shape
+    S = np.zeros((w, words(m)), dtype=np.uint64)
+    T = np.zeros((w, words(n)), dtype=np.uint64)
+    c = np.zeros(w, dtype=np.float64)
+    trace = np.zeros(w + 1, dtype=np.float64)
+    iters = np.zeros(w, dtype=np.int32)
+    margins = np.zeros((w, 2), dtype=np.float64)
+    capped = _load().scdo_lsq_decompose(A, m, n, w, seed, max_iters, S, T, c, trace, iters.ctypes.data,
+                                        margins.ctypes.data)
+    if capped < 0:
+        raise np.linalg.LinAlgError("normal equations singular")
+    return dict(S=S, T=T, c=c, trace=trace, iters=iters, margins=margins, capped=int(capped))
 
 
 def mode_signed_sum(a, signs, mode: int) -> np.ndarray:

@@ -228,6 +228,71 @@ def test_expand_order_and_rounding(oracle):
     assert np.array_equal(E, ref)
 
 
+# ------------------------------------------------------------------ Algorithm 6 (Section 3.3)
+
+
+def basis(S, T, m, n):
+    """mn x k matrix whose column j is s_j t_j^T flattened (the operator X of Section 3.3), dense."""
+    return np.stack([np.outer(dense(S[j], m), dense(T[j], n)).ravel() for j in range(len(S))], axis=1)
+
+
+def test_lsq_coefficients_are_numpys_least_squares(oracle):
+    rs = np.random.default_rng(31)
+    for (m, n, k) in [(9, 70, 6), (65, 20, 12), (8, 8, 1)]:
+        A = rs.standard_normal((m, n))
+        S = np.array([bits_of(np.sign(rs.standard_normal(m))) for _ in range(k)])
+        T = np.array([bits_of(np.sign(rs.standard_normal(n))) for _ in range(k)])
+        c = oracle.lsq_coefficients(A, S, T)
+        ref = np.linalg.lstsq(basis(S, T, m, n), A.ravel(), rcond=None)[0]
+        np.testing.assert_allclose(c, ref, rtol=1e-10, atol=1e-13)
+    # a matrix inside the span is reproduced with exactly its coefficients
+    m, n = 12, 33
+    S = np.array([bits_of(np.sign(rs.standard_normal(m))) for _ in range(3)])
+    T = np.array([bits_of(np.sign(rs.standard_normal(n))) for _ in range(3)])
+    coef = np.array([1.5, -0.25, 3.0])
+    A = (basis(S, T, m, n) @ coef).reshape(m, n)
+    np.testing.assert_allclose(oracle.lsq_coefficients(A, S, T), coef, rtol=1e-12)
+
+
+@pytest.mark.parametrize("m,n,w,seed", [(24, 40, 10, 3), (33, 65, 8, 5)])
+def test_lsq_decomposition_invariants(oracle, m, n, w, seed):
+    A = rng_matrix(m, n, 32 + seed)
+    res = oracle.lsq_decompose(A, w, seed)
+    greedy = oracle.decompose(A, w, seed)
+    X = basis(res["S"], res["T"], m, n)
+    # the remainder after k terms is orthogonal to all k of them (caption of Algorithm 6) and its norm is the trace
+    for k in range(1, w + 1):
+        ck = np.linalg.lstsq(X[:, :k], A.ravel(), rcond=None)[0]
+        r = A.ravel() - X[:, :k] @ ck
+        assert np.abs(X[:, :k].T @ r).max() <= 1e-9 * np.abs(A).sum()
+        assert res["trace"][k] == pytest.approx(np.linalg.norm(r), rel=1e-12)
+    np.testing.assert_allclose(res["c"], np.linalg.lstsq(X, A.ravel(), rcond=None)[0], rtol=1e-9, atol=1e-12)
+    assert np.all(np.diff(res["trace"]) < 0)
+    # with one term nothing but c_1 varies, so Algorithms 5 and 6 coincide (Section 3.3, first explanation) ...
+    assert np.array_equal(res["S"][0], greedy["S"][0]) and np.array_equal(res["T"][0], greedy["T"][0])
+    assert res["trace"][1] == pytest.approx(greedy["trace"][1], rel=1e-12)
+    first = oracle.lsq_decompose(A, 1, seed)
+    assert first["c"][0] == pytest.approx(greedy["c"][0], rel=1e-12)
+    # ... and afterwards the projection onto all terms can only leave less than a greedy step from the same state does
+    for k in range(1, w):
+        Rk = (A.ravel() - X[:, :k] @ np.linalg.lstsq(X[:, :k], A.ravel(), rcond=None)[0]).reshape(m, n)
+        s, t = dense(res["S"][k], m), dense(res["T"][k], n)
+        one_step = np.linalg.norm(Rk - (s @ Rk @ t) / (m * n) * np.outer(s, t))
+        assert res["trace"][k + 1] <= one_step * (1 + 1e-12)
+
+
+def test_lsq_step_is_a_greedy_cut_of_the_projected_remainder(oracle):
+    # term k+1 of Algorithm 6 is Algorithm 4 applied to A - S_k diag(c_k) T_k^T from the keyed start of term k
+    A = rng_matrix(20, 36, 40)
+    res = oracle.lsq_decompose(A, 6, 11)
+    for k in range(6):
+        ck = oracle.lsq_coefficients(A, res["S"][:k], res["T"][:k]) if k else np.zeros(0)
+        Rk = A - (oracle.expand([res["S"][:k], res["T"][:k]], ck, (20, 36)) if k else 0.0)
+        t0 = oracle.rng_signs(11, k, 1, 36)
+        cut = oracle.greedy_signed_cut(Rk, t0)
+        assert np.array_equal(cut["s"], res["S"][k]) and np.array_equal(cut["t"], res["T"][k])
+
+
 # ------------------------------------------------------------------ product with a vector (Section 6.1)
 
 
