@@ -53,12 +53,15 @@ typedef enum {
     SCD_EFULL = -4,      /* the context already holds w_capacity terms */
     SCD_ENONFINITE = -5, /* the input (or a remainder given to the context) holds NaN or Inf */
     SCD_ENODEVICE = -6,  /* no usable HIP device */
-    SCD_ETIMEOUT = -7    /* a bounded device-side wait ran out (workgroups of a persistent launch were not all
+    SCD_ETIMEOUT = -7,   /* a bounded device-side wait ran out (workgroups of a persistent launch were not all
                             resident); the context refuses further steps until scd_set_remainder */
+    SCD_ESINGULAR = -8   /* scd_lsq_decompose: a new term lies in the span of the earlier ones (normal equations
+                            singular to working precision) */
 } scd_status;
 
 #define SCD_MAX_ORDER 8
 #define SCD_DEFAULT_MAX_ITERS 4096
+#define SCD_LSQ_MAX_WIDTH 4096
 
 typedef struct scd_ctx scd_ctx; /* opaque: remainder, scratch, outputs so far, position in the random stream */
 
@@ -128,6 +131,20 @@ int scd_col_signed_sum(const void* R, scd_dtype dt, int64_t m, int64_t n, const 
  * result is reproducible bit for bit.  signs: host array of `order` device pointers. */
 int scd_expand(const uint64_t* const* signs, const void* c, scd_dtype dt, int order, const int64_t* dims,
                int64_t w, void* stream, void* out);
+
+/* ---- least squares decomposition (Algorithm 6, Section 3.3) --------------------------------------
+ * For k = 0..w-1: greedy signed cut (Algorithm 4) of R_k = A - S_k diag(c_k) T_k^T from the keyed random start
+ * of term k, append its (s, t), then refit ALL coefficients: c_{k+1} = argmin ||A - S_{k+1} diag(c) T_{k+1}^T||_F
+ * by the normal equations of Section 3.3 (Gram matrix from popcounts of the bitsets, Cholesky factor grown by a
+ * row per term, f64).  The remainder is kept implicit, A is not modified.  Matrices only.
+ * A: device, m x n row-major of dt.  S, T: device out, term-major bitsets as in scd_decompose.  c: device out,
+ * w values of dt: the FINAL coefficients c_w of all terms (they are direct coefficients of s_j t_j^T, like the
+ * normalised c of scd_decompose).  fro_trace: device out, w + 1 doubles, ||A - S_k diag(c_k) T_k^T||_F for
+ * k = 0..w.  iters: device out, optional.  w <= SCD_LSQ_MAX_WIDTH (the factor takes 8 w^2 bytes).
+ * Allocates its work space on the device and frees it before returning; synchronous on stream.
+ * Returns SCD_OK, SCD_WMAXITER, or SCD_EINVAL / SCD_ENOMEM / SCD_EHIP / SCD_ENONFINITE / SCD_ESINGULAR. */
+int scd_lsq_decompose(const void* A, scd_dtype dt, int64_t m, int64_t n, int64_t w, uint64_t seed, int32_t max_iters,
+                      void* stream, uint64_t* S, uint64_t* T, void* c, double* fro_trace, int32_t* iters);
 
 /* Product of a matrix decomposition with a vector, straight from the packed factors, without expanding
  * the matrix (Section 6.1, Question A):

@@ -9,7 +9,7 @@ from pathlib import Path
 
 PKG = Path(__file__).resolve().parent
 ROOT = PKG.parent
-SRC = [PKG / "csrc" / "scd_kernels.hip", PKG / "csrc" / "scd_resident.hip", PKG / "csrc" / "scd_sparse.hip", PKG / "csrc" / "scd_apply.hip",
+SRC = [PKG / "csrc" / "scd_kernels.hip", PKG / "csrc" / "scd_resident.hip", PKG / "csrc" / "scd_sparse.hip", PKG / "csrc" / "scd_apply.hip", PKG / "csrc" / "scd_lsq.hip",
        PKG / "csrc" / "scd_api.hip"]
 LIB = PKG / "libscd.so"
 

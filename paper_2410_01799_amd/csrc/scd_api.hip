@@ -966,6 +966,133 @@ int scd_expand(const uint64_t* const* signs, const void* cvec, scd_dtype dt, int
     return SCD_OK;
 }
 
+// ---------------------------------------------------------------------------------------------- Algorithm 6
+
+int scd_lsq_decompose(const void* A, scd_dtype dt, int64_t m, int64_t n, int64_t w, uint64_t seed, int32_t max_iters,
+                      void* stream, uint64_t* S, uint64_t* T, void* cvec, double* fro_trace, int32_t* iters)
+{
+    if (!A || !dtype_ok(dt) || m < 1 || n < 1 || w < 0 || w > SCD_LSQ_MAX_WIDTH || max_iters < 1) return SCD_EINVAL;
+    if (!fro_trace || (w > 0 && (!S || !T || !cvec))) return SCD_EINVAL;
+    if (m > (1ll << 31) || n > (1ll << 31)) return SCD_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    const int64_t mw = words_for(m), nw = words_for(n);
+    const size_t es = dt == SCD_F32 ? 4 : 8;
+    int rpw, grid;
+    halfstep_geometry(m, &rpw, &grid);
+    const int nsq = 256;
+    const int64_t wl = w > 0 ? w : 1;
+
+    std::vector<void*> bufs;
+    double* host = nullptr;  // pinned: [0] cut value, [1] b of the current pair, [2] right-hand side to upload
+    int rc = SCD_OK;
+    auto alloc = [&](void** p, size_t bytes) {
+        if (hipMalloc(p, bytes ? bytes : 8) != hipSuccess) {
+            (void)hipGetLastError();
+            *p = nullptr;
+            return false;
+        }
+        bufs.push_back(*p);
+        return true;
+    };
+    double *uA = nullptr, *vA = nullptr, *e = nullptr, *ga = nullptr, *gb = nullptr, *absp = nullptr, *dotp = nullptr;
+    double *scal = nullptr, *L = nullptr, *yv = nullptr, *c = nullptr, *work = nullptr, *bvec = nullptr, *cparts = nullptr;
+    double* sq = nullptr;
+    void* partials = nullptr;
+    uint64_t *sb = nullptr, *tb = nullptr;
+    int* status = nullptr;
+    std::vector<int32_t> it_host((size_t)wl, 0);
+    bool ok = alloc((void**)&uA, (size_t)m * 8) && alloc((void**)&vA, (size_t)n * 8) && alloc((void**)&e, (size_t)wl * 8) &&
+              alloc((void**)&ga, (size_t)wl * 8) && alloc((void**)&gb, (size_t)wl * 8) && alloc((void**)&absp, (size_t)nw * 8) &&
+              alloc((void**)&dotp, (size_t)nw * 8) && alloc((void**)&scal, 16) && alloc((void**)&L, (size_t)wl * wl * 8) &&
+              alloc((void**)&yv, (size_t)wl * 8) && alloc((void**)&c, (size_t)wl * 8) && alloc((void**)&work, (size_t)wl * 8) &&
+              alloc((void**)&bvec, (size_t)wl * 8) && alloc((void**)&cparts, (size_t)nw * 8) &&
+              alloc((void**)&sq, (size_t)nsq * 8) && alloc(&partials, (size_t)grid * (size_t)n * es) &&
+              alloc((void**)&sb, (size_t)mw * 8) && alloc((void**)&tb, (size_t)nw * 8) && alloc((void**)&status, 4);
+    if (ok && hipHostMalloc((void**)&host, 4 * sizeof(double), hipHostMallocDefault) != hipSuccess) {
+        (void)hipGetLastError();
+        host = nullptr;
+        ok = false;
+    }
+    auto cleanup = [&](int code) {
+        (void)hipStreamSynchronize(st);
+        for (void* p : bufs) (void)hipFree(p);
+        if (host) (void)hipHostFree(host);
+        (void)hipGetLastError();
+        return code;
+    };
+    if (!ok) return cleanup(SCD_ENOMEM);
+#define LQ(expr)                              \
+    do {                                      \
+        hipError_t _e = (expr);               \
+        if (_e != hipSuccess) {               \
+            g_last_hip = (int)_e;             \
+            (void)hipGetLastError();          \
+            return cleanup(SCD_EHIP);         \
+        }                                     \
+    } while (0)
+
+    LQ(hipMemsetAsync(status, 0, 4, st));
+    // ||A||_F^2
+    LQ(launch_lsq_sumsq(A, dt, m * n, sq, nsq, st));
+    LQ(launch_lsq_sum2(sq, nullptr, nsq, scal, st));
+    LQ(hipMemcpyAsync(host, scal, 16, hipMemcpyDeviceToHost, st));
+    LQ(hipStreamSynchronize(st));
+    const double fro0sq = host[0];
+    if (!isfinite(fro0sq)) return cleanup(SCD_ENONFINITE);
+    {
+        const double f0 = sqrt(fro0sq);
+        host[2] = f0;
+        LQ(hipMemcpyAsync(fro_trace, host + 2, 8, hipMemcpyHostToDevice, st));
+        LQ(hipStreamSynchronize(st));
+    }
+    for (int64_t k = 0; k < w; ++k) {
+        // Algorithm 4 on the implicit remainder, from the keyed random start of term k (Algorithm 6 line 6)
+        LQ(launch_rng(seed, (uint64_t)k, 1u, n, tb, st));
+        double c_prev = -INFINITY, bnew = 0.0;
+        int32_t j = 0;
+        for (;;) {
+            // s = sgn(A t - S (c o T^T t))
+            LQ(launch_halfstep(A, dt, m, n, rpw, grid, 1, tb, nullptr, nullptr, uA, st));
+            LQ(launch_lsq_dots(T, k, nw, n, tb, c, e, st));
+            LQ(launch_lsq_correct(S, k, mw, m, e, uA, sb, nullptr, nullptr, st));
+            // t = sgn(A^T s - T (c o S^T s)), cut value sum |.|, and <t, A^T s> = <s, A t>
+            LQ(launch_halfstep(A, dt, m, n, rpw, grid, 0, nullptr, sb, partials, nullptr, st));
+            LQ(launch_reduce_plain(partials, dt, grid, n, vA, nullptr, cparts, st));
+            LQ(launch_lsq_dots(S, k, mw, m, sb, c, e, st));
+            LQ(launch_lsq_correct(T, k, nw, n, e, vA, tb, absp, dotp, st));
+            LQ(launch_lsq_sum2(absp, dotp, nw, scal, st));
+            LQ(hipMemcpyAsync(host, scal, 16, hipMemcpyDeviceToHost, st));
+            LQ(hipStreamSynchronize(st));
+            ++j;
+            const double cut = host[0];
+            bnew = host[1];
+            if (!isfinite(cut)) return cleanup(SCD_ENONFINITE);
+            if (cut <= c_prev || j >= max_iters) {
+                if (!(cut <= c_prev)) rc = SCD_WMAXITER;
+                break;
+            }
+            c_prev = cut;
+        }
+        it_host[(size_t)k] = j;
+        // append (lines 7-8) and refit every coefficient (line 9)
+        LQ(hipMemcpyAsync(S + k * mw, sb, (size_t)mw * 8, hipMemcpyDeviceToDevice, st));
+        LQ(hipMemcpyAsync(T + k * nw, tb, (size_t)nw * 8, hipMemcpyDeviceToDevice, st));
+        host[2] = bnew;
+        LQ(hipMemcpyAsync(bvec + k, host + 2, 8, hipMemcpyHostToDevice, st));
+        LQ(launch_lsq_dots(S, k, mw, m, sb, nullptr, ga, st));
+        LQ(launch_lsq_dots(T, k, nw, n, tb, nullptr, gb, st));
+        LQ(launch_lsq_solve(L, wl, k, ga, gb, (double)m * (double)n, bvec, yv, c, work, fro0sq, fro_trace + k + 1, status, st));
+        LQ(hipMemcpyAsync(host + 3, status, 4, hipMemcpyDeviceToHost, st));
+        LQ(hipStreamSynchronize(st));  // host[2] is reused by the next term
+        if (*(const int*)(host + 3) != 0) return cleanup(SCD_ESINGULAR);
+    }
+    LQ(launch_lsq_cast(c, w, dt, cvec, st));
+    if (iters && w > 0) LQ(hipMemcpyAsync(iters, it_host.data(), (size_t)w * 4, hipMemcpyHostToDevice, st));
+    LQ(hipStreamSynchronize(st));
+#undef LQ
+    return cleanup(rc);
+}
+
 size_t scd_apply_workspace_bytes(int64_t m, int64_t n, int64_t w)
 {
     if (m < 0 || n < 0 || w < 0) return 0;
@@ -1117,6 +1244,7 @@ const char* scd_strerror(int code)
         case SCD_ENONFINITE: return "input holds NaN or Inf";
         case SCD_ENODEVICE: return "no HIP device";
         case SCD_ETIMEOUT: return "a bounded device-side wait ran out; give the context a remainder again or destroy it";
+        case SCD_ESINGULAR: return "a new term lies in the span of the earlier ones: normal equations singular";
         default: return "unknown status";
     }
 }

@@ -184,6 +184,18 @@ void apply_plan(int64_t nin, int64_t nout, int64_t w, ApplyPlan* pl);
 hipError_t launch_apply(const uint64_t* in_bits, const uint64_t* out_bits, const void* c, scd_dtype dt, int64_t nin,
                         int64_t nout, int64_t w, const void* x, void* y, void* workspace, hipStream_t st);
 
+// ---- least squares decomposition, Algorithm 6 (scd_lsq.hip) -----------------------------------------
+hipError_t launch_lsq_dots(const uint64_t* bits, int64_t k, int64_t nw, int64_t len, const uint64_t* vec, const double* coef,
+                           double* out, hipStream_t st);
+hipError_t launch_lsq_correct(const uint64_t* bits, int64_t k, int64_t mw, int64_t m, const double* e, const double* base,
+                              uint64_t* out_bits, double* abs_parts, double* dot_parts, hipStream_t st);
+hipError_t launch_lsq_sum2(const double* a, const double* b, int64_t n, double* out, hipStream_t st);
+hipError_t launch_lsq_sumsq(const void* A, scd_dtype dt, int64_t total, double* parts, int nparts, hipStream_t st);
+hipError_t launch_lsq_cast(const double* c, int64_t k, scd_dtype dt, void* out, hipStream_t st);
+hipError_t launch_lsq_solve(double* L, int64_t ld, int64_t k, const double* ga, const double* gb, double diag,
+                            const double* bvec, double* yv, double* c, double* work, double fro0sq, double* trace_out,
+                            int* status, hipStream_t st);
+
 // ---- launchers implemented in scd_kernels.hip ----------------------------------------------------
 hipError_t launch_rowpass(const RowPassArgs& a, scd_dtype dt, int grid, int variant, hipStream_t st);
 hipError_t launch_reduce(const ReduceArgs& a, bool f32_partials, hipStream_t st);

@@ -1,0 +1,127 @@
+"""Least squares decomposition (Algorithm 6, Section 3.3) on the GPU against the oracle, in lockstep: the
+coefficients of Algorithm 6 are a function of (A, S_k, T_k) alone, so for every term the oracle refits them
+for the GPU's own sign vectors, forms the remainder in f64 and repeats the greedy cut from the keyed start."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from helpers import C_RTOL, TIE_TOL, dense, to_np_bits
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def scd():
+    from paper_2410_01799_amd import scd as mod
+
+    mod.lib()
+    return mod
+
+
+def gauss(shape, seed, dtype=np.float32):
+    return np.random.Generator(np.random.PCG64(seed)).standard_normal(shape).astype(dtype)
+
+
+def run_and_check(scd, oracle, A, w, seed):
+    m, n = A.shape
+    f32 = A.dtype == np.float32
+    A64 = A.astype(np.float64)
+    res = scd.scd_lsq_decompose(torch.from_numpy(A).cuda(), w, seed)
+    assert res["status"] == 0
+    S, T = to_np_bits(res["signs"][0]), to_np_bits(res["signs"][1])
+    c = res["c"].cpu().numpy().astype(np.float64)
+    trace = res["trace"].cpu().numpy()
+    iters = res["iters"].cpu().numpy()
+    rtol_norm = 2e-6 if f32 else 1e-10   # f32: the column pass keeps its partial sums in f32
+    assert trace[0] == pytest.approx(np.linalg.norm(A64), rel=1e-12)
+    adopted = 0
+    for k in range(w):
+        ck = oracle.lsq_coefficients(A64, S[:k], T[:k]) if k else np.zeros(0)
+        Rk = A64 - (oracle.expand([S[:k], T[:k]], ck, (m, n)) if k else 0.0)
+        assert trace[k] == pytest.approx(np.linalg.norm(Rk), rel=rtol_norm), f"trace[{k}]"
+        g = oracle.greedy_signed_cut(Rk, oracle.rng_signs(seed, k, 1, n))
+        if np.array_equal(g["s"], S[k]) and np.array_equal(g["t"], T[k]):
+            assert iters[k] == g["iters"], f"term {k}: iteration count"
+        else:
+            # the only rounding on the GPU side is the f32 partial sums of the column pass (f32 input)
+            # and the order of f64 sums; a different outcome needs a near tie in the oracle's run
+            assert g["margin"].min() < (10 * TIE_TOL if f32 else 1e-9), \
+                f"term {k}: signs differ although the oracle's margin is {g['margin'].min():.2e}"
+            adopted += 1
+        # padding bits clear
+        if m % 64:
+            assert int(S[k][-1]) >> (m % 64) == 0
+        if n % 64:
+            assert int(T[k][-1]) >> (n % 64) == 0
+    cw = oracle.lsq_coefficients(A64, S, T)
+    np.testing.assert_allclose(c, cw, rtol=C_RTOL if f32 else 1e-9, atol=1e-7 * np.abs(cw).max())
+    Rw = A64 - oracle.expand([S, T], cw, (m, n))
+    assert trace[w] == pytest.approx(np.linalg.norm(Rw), rel=rtol_norm)
+    # the remainder is orthogonal to every term (caption of Algorithm 6)
+    for j in range(w):
+        assert abs(dense(S[j], m) @ Rw @ dense(T[j], n)) <= 1e-9 * np.abs(A64).sum()
+    assert np.all(np.diff(trace) < 0)
+    return res, adopted
+
+
+@pytest.mark.parametrize("m,n,w,dtype", [(256, 256, 40, np.float32), (256, 256, 24, np.float64), (100, 76, 20, np.float32),
+                                         (65, 130, 12, np.float64), (8, 8, 6, np.float32), (1030, 520, 16, np.float32),
+                                         (64, 4100, 10, np.float32)])
+def test_lsq_matches_oracle_in_lockstep(scd, oracle, m, n, w, dtype):
+    run_and_check(scd, oracle, gauss((m, n), 7 * m + n, dtype), w, 3)
+
+
+def test_lsq_free_run_and_first_term(scd, oracle):
+    A = gauss((96, 160), 5, np.float64)
+    res, adopted = run_and_check(scd, oracle, A, 16, 9)
+    free = oracle.lsq_decompose(A, 16, 9)
+    if adopted == 0:
+        assert np.array_equal(to_np_bits(res["signs"][0]), free["S"]) and np.array_equal(to_np_bits(res["signs"][1]), free["T"])
+        np.testing.assert_allclose(res["trace"].cpu().numpy(), free["trace"], rtol=1e-10)
+        np.testing.assert_allclose(res["c"].cpu().numpy(), free["c"], rtol=1e-8, atol=1e-12)
+    # one term: nothing but c_1 varies, Algorithms 5 and 6 coincide (Section 3.3)
+    one = scd.scd_lsq_decompose(torch.from_numpy(A).cuda(), 1, 9)
+    greedy = scd.scd_decompose(torch.from_numpy(A).cuda(), 1, 9)
+    assert torch.equal(one["signs"][0], greedy["signs"][0]) and torch.equal(one["signs"][1], greedy["signs"][1])
+    assert float(one["c"][0]) == pytest.approx(float(greedy["c"][0]), rel=1e-12)
+    assert float(one["trace"][1]) == pytest.approx(float(greedy["trace"][1]), rel=1e-10)
+
+
+def test_lsq_is_no_worse_than_greedy_on_structured_input(scd):
+    # an image-like matrix (smooth, strongly correlated terms): refitting all coefficients helps
+    from paper_2410_01799_amd import workloads
+
+    a = workloads.image_like_tensor(240, 320, 1, blobs=40, seed=400)[:, :, 0].astype(np.float32).copy()
+    A = torch.from_numpy(a).cuda()
+    w = 48
+    ls = scd.scd_lsq_decompose(A, w, 2)
+    gr = scd.scd_decompose(A, w, 2)
+    assert float(ls["trace"][w]) <= float(gr["trace"][w]) * (1 + 1e-9)
+    E = scd.scd_expand(ls["signs"], ls["c"], a.shape).double()
+    assert float((A.double() - E).norm()) == pytest.approx(float(ls["trace"][w]), rel=1e-4)
+
+
+def test_lsq_edges_and_errors(scd):
+    A = torch.from_numpy(gauss((70, 50), 1)).cuda()
+    r0 = scd.scd_lsq_decompose(A, 0, 1)
+    assert r0["c"].numel() == 0 and float(r0["trace"][0]) == pytest.approx(float(A.double().norm()), rel=1e-12)
+    with pytest.raises(scd.ScdError) as e:
+        scd.scd_lsq_decompose(A, 4097, 1)
+    assert e.value.code == -1
+    bad = A.clone()
+    bad[3, 4] = float("nan")
+    with pytest.raises(scd.ScdError) as e:
+        scd.scd_lsq_decompose(bad, 2, 1)
+    assert e.value.code == -5
+    # the zero matrix: every cut returns the all-ones vectors, so the second term repeats the first
+    with pytest.raises(scd.ScdError) as e:
+        scd.scd_lsq_decompose(torch.zeros(40, 72, device="cuda"), 3, 1)
+    assert e.value.code == -8
+    # iteration cap: a warning status, results still consistent
+    capped = scd.scd_lsq_decompose(A, 3, 1, max_iters=1)
+    assert capped["status"] == 1 and torch.all(capped["iters"] == 1)
+    one = scd.scd_lsq_decompose(A, 3, 1)
+    two = scd.scd_lsq_decompose(A, 3, 1)
+    assert torch.equal(one["c"], two["c"]) and torch.equal(one["trace"], two["trace"])   # bit-identical reruns
