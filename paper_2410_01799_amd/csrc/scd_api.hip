@@ -670,6 +670,7 @@ int scd_run(scd_ctx* c, int64_t n)
         SCD_TRY(c->resident ? run_resident(c, n) : run_sparse(c, n));
         return c->hs.warn ? SCD_WMAXITER : SCD_OK;
     }
+    SCD_TRY(resync_stream_state(c));  // a persistent engine may have advanced the context before it lost its share
     c->hs.w_target = c->hs.k + n;
     c->hs.done = 0;
     SCD_TRY(write_state(c));

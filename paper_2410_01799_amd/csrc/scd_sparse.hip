@@ -33,6 +33,7 @@ constexpr int kSpSlotUsed = kSpPayload + 4;       // + two doubles as four tagge
 // 256 x 256 reads of one exchange do not queue up at a handful of them.
 constexpr int kSpSlot = 512;
 constexpr int kSpListCap = 32 * kSpThreads;       // flips handled per compaction round: one 32-bit word per thread
+constexpr size_t kSpMaxLds = 150 * 1024;          // most dynamic LDS a launch may ask for
 constexpr int kSpMaxItems = (kSpGrid * kSpSlotUsed + kSpThreads - 1) / kSpThreads;
 
 __device__ __forceinline__ uint64_t sp_mix64(uint64_t z)
@@ -607,7 +608,7 @@ bool sparse_supported(scd_dtype dt, int order, const int64_t* dims, int grid, in
     const int64_t c = 8 * ((n + 8 * grid - 1) / (8 * grid));
     if (r > kSpThreads || c > kSpThreads) return false;
     if (r > 32 * kSpPayload || c > 32 * kSpPayload) return false;
-    if (sparse_lds_bytes(m, n) > 150 * 1024) return false;
+    if (sparse_lds_bytes(m, n) > kSpMaxLds) return false;
     if (rs) *rs = (int)r;
     if (cs) *cs = (int)c;
     return true;
@@ -629,7 +630,10 @@ template <typename TE>
 static hipError_t launch_sparse_t(const SparseArgs& a, hipStream_t st)
 {
     const size_t lds = sparse_lds_bytes(a.m, a.n);
-    hipError_t e = hipFuncSetAttribute((const void*)sparse_kernel<TE>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (lds > kSpMaxLds) return hipErrorInvalidValue;
+    // always the same ceiling, whatever this launch needs: launches from several host threads set it too
+    hipError_t e = hipFuncSetAttribute((const void*)sparse_kernel<TE>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)kSpMaxLds);
     if (e != hipSuccess) return e;
     int dev = 0, per_cu = 0;
     hipDeviceProp_t prop;

@@ -117,3 +117,30 @@ def test_resident_iteration_cap(scd):
 def test_exchange_probe_runs(scd):
     t = scd.scd_probe_exchange(0, 256, 16, 200)
     assert 0 < t < 1e-3
+
+
+def test_a_context_that_loses_its_share_continues_on_the_launch_stream(scd):
+    m = n = 1024
+    A = torch.from_numpy(gauss((m, n), 21)).cuda()
+    os.environ["SCD_SPARSE"] = "0"
+    try:
+        with_resident(True)
+        with scd.ScdContext(A, 8, 6) as ctx:
+            assert ctx.engine()["engine"] == 1
+            ctx.run(4)
+            ctx.set_workgroups(16)            # the 8 x 8 grid no longer fits, the sparse engine is switched off
+            assert ctx.engine()["engine"] == 0
+            ctx.run(4)
+            mixed = ctx.results()
+            R = ctx.remainder()
+        whole = scd.scd_decompose(A, 8, 6)
+    finally:
+        os.environ.pop("SCD_SPARSE", None)
+    tr = mixed["trace"].cpu().numpy()
+    c = mixed["c"].cpu().numpy().astype(np.float64)
+    np.testing.assert_allclose(tr[1:] ** 2, tr[:-1] ** 2 - m * n * c ** 2, rtol=ID_RTOL)
+    tw = whole["trace"].cpu().numpy()
+    np.testing.assert_allclose(tr / tr[0], tw / tw[0], rtol=CURVE_RTOL)
+    assert torch.equal(mixed["c"][:4], whole["c"][:4])
+    E = scd.scd_expand(mixed["signs"], mixed["c"], (m, n))
+    assert float((A - E - R).abs().max()) <= 2e-6 * float(A.abs().max())
