@@ -310,6 +310,35 @@ def main() -> int:
                 "reduce_launch_us": round(reduce_s * 1e6, 3),
                 "measured_stream_read_gbs": round(m * n * esize / stream_s / 1e9, 1)}
 
+    # Bytes the paper's own scheme would move for this run (Section 3.1's cached products, Section 3.2's
+    # delayed update): dense first alternation of a term (R once for u, once for v), then one row of R per
+    # changed row sign and one column per changed column sign, plus the update amortised over 32 terms.
+    # The sign changes are counted by the sparse engine on the first terms of the same decomposition.
+    sample_terms = min(w, 128)
+    saved = {k: os.environ.get(k) for k in ("SCD_RESIDENT", "SCD_SPARSE_MIN_MIB")}
+    os.environ["SCD_RESIDENT"] = "0"
+    os.environ["SCD_SPARSE_MIN_MIB"] = "0"
+    try:
+        with scd.ScdContext(A, sample_terms, seed) as ctx:
+            useful = None
+            if ctx.engine()["engine"] == 2:
+                ctx.run(sample_terms)
+                fl = ctx.sparse_flips()
+                per_term = (2.0 * m * n * esize + esize * (n * fl["rows"] + m * fl["cols"]) / sample_terms
+                            + 2.0 * m * n * esize / 32.0)
+                useful = {"bytes_per_term": round(per_term), "row_sign_changes_per_term": round(fl["rows"] / sample_terms, 1),
+                          "col_sign_changes_per_term": round(fl["cols"] / sample_terms, 1),
+                          "gbs": round(per_term * terms_per_s / 1e9, 1),
+                          "frac": round(per_term * terms_per_s / 1e9 / HBM_PEAK_GBS, 4),
+                          "sample": f"sign changes counted on the first {sample_terms} terms"}
+    finally:
+        for k, v in saved.items():
+            if v is None:
+                os.environ.pop(k, None)
+            else:
+                os.environ[k] = v
+    roof["useful_bytes"] = useful
+
     out = {
         "metric": f"signed-cut terms/s on {m}x{n} f32 (w={w})",
         "value": round(terms_per_s, 2),

@@ -172,6 +172,12 @@ int scd_rng_signs(uint64_t seed, uint64_t term, uint32_t mode, int64_t n, void* 
 /* ---- diagnostics ------------------------------------------------------------------------------ */
 const char* scd_strerror(int code);
 int scd_last_hip_error(void);        /* hipError_t of the most recent SCD_EHIP on this thread */
+/* Sparse engine only (zeros otherwise): how many row signs and column signs changed after the first
+ * alternation of their term, summed over the terms run so far.  Section 3.1's cached products re-read one
+ * row of R per changed row sign and one column per changed column sign: these counts give the bytes the
+ * paper's own method moves (host pointers, may be NULL). */
+int scd_sparse_flips(const scd_ctx* ctx, int64_t* row_flips, int64_t* col_flips);
+
 /* Algorithmic bytes the row-pass kernels of this context have read+written so far and the number
  * of passes (launches) they took: the counters behind the bandwidth figures.  host pointers. */
 int scd_traffic(const scd_ctx* ctx, double* bytes, int64_t* passes, int64_t* sweeps);

@@ -104,7 +104,7 @@ struct scd_ctx {
     int sp_grid = kSpGrid;          // workgroups of the sparse engine's launch
     int share = 0;                  // most workgroups a persistent launch may take (0: the whole device)
     int cus = 256;                  // compute units of the device
-    int64_t flips = 0;
+    int64_t flips = 0, flips_rows = 0;  // column / row signs that changed after the first alternation of their term
     hipEvent_t ev0 = nullptr, ev1 = nullptr;  // around the engine's launch
     double last_launch_seconds = 0.0;
     double last_launch_bytes = 0.0;
@@ -435,10 +435,11 @@ int run_sparse(scd_ctx* c, int64_t n)
     if (env_int("SCD_RESIDENT_VERBOSE", 0))
         fprintf(stderr, "[scd sparse] terms %lld alternations %lld flips %lld re-reads %lld; us: dense %.0f, t-exchange %.0f, "
                         "decide %.0f, u-update %.0f, s-exchange %.0f, v-update %.0f\n", (long long)n,
-                (long long)r.alternations, (long long)r.flips, (long long)r.spins, r.ticks[0] * 0.01, r.ticks[1] * 0.01,
+                (long long)r.alternations, (long long)(r.flips + r.flips_rows), (long long)r.spins, r.ticks[0] * 0.01, r.ticks[1] * 0.01,
                 r.ticks[2] * 0.01, r.ticks[3] * 0.01, r.ticks[4] * 0.01, r.ticks[5] * 0.01);
     c->seq_sp = r.seq_u;
     c->flips += r.flips;
+    c->flips_rows += r.flips_rows;
     c->hs.k = r.k;
     c->hs.passes += r.alternations;
     c->hs.updates += r.updates;
@@ -767,6 +768,14 @@ int scd_engine(const scd_ctx* c, int* engine, double* last_launch_seconds, doubl
     if (engine) *engine = c->resident ? 1 : (c->sparse ? 2 : 0);
     if (last_launch_seconds) *last_launch_seconds = c->last_launch_seconds;
     if (last_launch_bytes) *last_launch_bytes = c->last_launch_bytes;
+    return SCD_OK;
+}
+
+int scd_sparse_flips(const scd_ctx* c, int64_t* row_flips, int64_t* col_flips)
+{
+    if (!c) return SCD_EINVAL;
+    if (row_flips) *row_flips = c->flips_rows;
+    if (col_flips) *col_flips = c->flips;
     return SCD_OK;
 }
 

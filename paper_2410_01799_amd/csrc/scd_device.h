@@ -115,7 +115,8 @@ struct ResidentResult {
     int32_t err;           // 1: a bounded wait ran out
     int32_t warn;          // a term ended on max_iters
     int64_t spins;         // re-reads of stale exchange data by thread 0 of workgroup 0 (diagnostic)
-    int64_t flips;         // sparse engine: sign changes processed (rows + columns)
+    int64_t flips;         // sparse engine: column signs that changed (each costs one column of R)
+    int64_t flips_rows;    // sparse engine: row signs that changed (each costs one row of R)
     int64_t ticks[6];      // sparse engine, profile mode: 100 MHz ticks of workgroup 0 per phase
 };
 

@@ -444,7 +444,7 @@ __global__ void __launch_bounds__(kSpThreads) sparse_kernel(SparseArgs a)
     int64_t k = a.k_start;
     uint32_t seq = a.seq;
     int alternations = 0, updates = 0, warn = 0, spins = 0;
-    int64_t flips = 0;
+    int64_t flips = 0, flips_rows = 0;
     bool pending = false;  // a finished term waits to be subtracted
     double ck = 0.0;
     const bool prof = a.profile && g == 0 && tid == 0;
@@ -554,7 +554,7 @@ __global__ void __launch_bounds__(kSpThreads) sparse_kernel(SparseArgs a)
             }
             ++alternations;
             // ---- column half, sparse: v += 2 sum over flipped rows (rows of R)
-            sp_accumulate_flips<TE>(R, n, j0, clen, s_cur, s_oth, m, sh.accv, sh, flips);
+            sp_accumulate_flips<TE>(R, n, j0, clen, s_cur, s_oth, m, sh.accv, sh, flips_rows);
             SP_TICK(5)
         }
     }
@@ -567,6 +567,7 @@ __global__ void __launch_bounds__(kSpThreads) sparse_kernel(SparseArgs a)
         a.res->warn = warn;
         a.res->spins = spins;
         a.res->flips = flips;
+        a.res->flips_rows = flips_rows;
         for (int i = 0; i < 6; ++i) a.res->ticks[i] = tick[i];
     }
 }

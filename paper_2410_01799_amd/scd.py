@@ -25,7 +25,7 @@ EXPORTS = [
     "scd_width", "scd_results", "scd_remainder", "scd_set_remainder", "scd_row_signed_sum", "scd_col_signed_sum",
     "scd_expand", "scd_pack", "scd_unpack", "scd_rng_signs", "scd_strerror", "scd_last_hip_error", "scd_traffic",
     "scd_probe_stream", "scd_profile_sweeps", "scd_probe_exchange", "scd_engine", "scd_set_workgroups",
-    "scd_apply", "scd_apply_workspace_bytes", "scd_lsq_decompose",
+    "scd_apply", "scd_apply_workspace_bytes", "scd_lsq_decompose", "scd_sparse_flips",
 ]
 
 
@@ -55,6 +55,7 @@ def lib() -> C.CDLL:
         L.scd_destroy.restype = None
         L.scd_set_max_iters.argtypes = [vp, i32]
         L.scd_set_workgroups.argtypes = [vp, C.c_int]
+        L.scd_sparse_flips.argtypes = [vp, pi64, pi64]
         L.scd_lsq_decompose.argtypes = [vp, C.c_int, i64, i64, i64, C.c_uint64, i32, vp, vp, vp, vp, vp, vp]
         L.scd_apply_workspace_bytes.argtypes = [i64, i64, i64]
         L.scd_apply_workspace_bytes.restype = C.c_size_t
@@ -308,6 +309,12 @@ class ScdContext:
 
     def set_max_iters(self, n: int):
         _check(lib().scd_set_max_iters(self._h, int(n)), "scd_set_max_iters")
+
+    def sparse_flips(self) -> dict:
+        """Row and column signs that changed after the first alternation of their term (sparse engine)."""
+        r, cl = C.c_int64(), C.c_int64()
+        _check(lib().scd_sparse_flips(self._h, C.byref(r), C.byref(cl)), "scd_sparse_flips")
+        return dict(rows=int(r.value), cols=int(cl.value))
 
     def set_workgroups(self, n: int):
         """Share of the device (workgroups of the persistent launches; 0 = all): lets several contexts,

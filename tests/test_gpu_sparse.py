@@ -223,3 +223,20 @@ def test_contexts_side_by_side_reproduce_their_solo_runs(scd):
     for a, b in zip(solo, together):
         assert torch.equal(a["signs"][0], b["signs"][0]) and torch.equal(a["signs"][1], b["signs"][1])
         assert torch.equal(a["c"], b["c"]) and torch.equal(a["trace"], b["trace"]) and torch.equal(a["iters"], b["iters"])
+
+
+def test_sparse_flip_counts(scd):
+    A = torch.from_numpy(gauss((512, 1024), 77)).cuda()
+    with scd.ScdContext(A, 6, 3) as ctx:
+        assert ctx.engine()["engine"] == 2
+        assert ctx.sparse_flips() == dict(rows=0, cols=0)
+        ctx.run(6)
+        fl = ctx.sparse_flips()
+        alts = int(ctx.results()["iters"].sum())
+    # every alternation after a term's first changes at least one sign of each kind (else it would have stopped
+    # one earlier, or be the last), and never more than all of them
+    assert 0 < fl["rows"] <= 512 * alts and 0 < fl["cols"] <= 1024 * alts
+    os.environ["SCD_SPARSE"] = "0"
+    with scd.ScdContext(A, 2, 3) as ctx:
+        ctx.run(2)
+        assert ctx.sparse_flips() == dict(rows=0, cols=0)
