@@ -98,6 +98,165 @@ __global__ void __launch_bounds__(kApInnerWaves* kWave)
     }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Inner pass on the matrix cores (f32 x).  <t_j, x> for many terms j is a dense contraction of a +-1
+// matrix with x, so it belongs on MFMA; what keeps it exact is fixed point.  Per chunk of 4096 entries
+// x is scaled by a power of two so that |x| 2^s < 2^30, rounded to integers and cut into four balanced
+// base-256 digits (int8).  v_mfma_i32_4x4x4_16B_i8 multiplies, in each of its 16 blocks, 4 terms x 4
+// entries of signs (int8 +-1, expanded from a nibble of the bitset by a 16-entry table) with 4 entries x
+// 4 digits: the four digit columns use the whole instruction, the products and the int32 sums are exact,
+// and the digits are recombined in f64.  The only rounding is the fixed point itself: at most
+// max|x| 2^-30 per entry of the chunk, below the resolution of the f32 input for all but entries more
+// than 64 times smaller than the largest.
+// Operand layout of the instruction (lane l, block l / 4): A = row (l % 4) of the block's 4 x 4 sign
+// matrix (4 bytes along the contraction), B = column (l % 4) of its 4 x 4 digit matrix (4 bytes along the
+// contraction), D register r = element (row r, column l % 4).  Lane = term, so A comes from the lane's
+// own row of sign bits; the digit matrix is the same for every block.
+typedef int ap_int4 __attribute__((ext_vector_type(4)));
+
+constexpr int kApMfmaWaves = 8;                      // waves per workgroup: each takes 8 of the chunk's 64 words
+constexpr int kApTileWords = kApChunkWords / kApMfmaWaves;  // words of a row per wave (64 bytes per term)
+constexpr int kApTilePitch = kApTileWords + 1;       // LDS pitch in words: rows 72 bytes apart
+static_assert(kApTileWords == 8, "staging below assumes 8 words per wave");
+
+// part[chunk * w + j] = <t_j, x> restricted to the chunk: each wave forms the sum over its 512 entries, the
+// eight are joined in wave order through LDS
+__global__ void __launch_bounds__(kApMfmaWaves* kWave)
+    apply_inner_mfma_kernel(const uint64_t* __restrict__ bits, int64_t nw, int64_t w, const float* __restrict__ x, int64_t n,
+                            double* __restrict__ part, int tiles_per_wg)
+{
+    __shared__ int xd[kApChunkWords * 16 * 4];                    // [group of 4 entries][digit]: 4 packed int8
+    __shared__ int lut[16];                                       // nibble -> 4 packed int8 signs
+    __shared__ uint64_t tile[kApMfmaWaves][kWave * kApTilePitch];  // per wave: 64 terms x 8 words
+    __shared__ float redmax[kApMfmaWaves];
+    __shared__ double wsum[kApMfmaWaves][kWave];
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int wv = __builtin_amdgcn_readfirstlane(tid / kWave);
+    const int64_t chunk = blockIdx.y;
+    const int64_t p0 = chunk * kApChunkWords;
+    const int nwc = (int)(nw - p0 < kApChunkWords ? nw - p0 : kApChunkWords);
+
+    // the first tile of sign bits is requested before anything else: its latency hides behind the fixed point
+    const int pw = wv * kApTileWords;  // first word of this wave within the chunk
+    uint64_t stage[8];
+    auto fetch = [&](int64_t jbase) {
+        // lane l fetches word (l % 8) of terms (l / 8) + 8 r: every load reads 8 rows x 64 bytes
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            int64_t j = jbase + (lane >> 3) + 8 * r;
+            j = j < w ? j : w - 1;
+            int p = pw + (lane & 7);
+            p = p < nwc ? p : nwc - 1;
+            stage[r] = bits[j * nw + p0 + p];
+        }
+    };
+    fetch((int64_t)blockIdx.x * tiles_per_wg * kWave);
+
+    // ---- fixed point of this chunk of x: thread t owns the groups of four entries t and t + 512
+    float xv[2][4];
+    float amax = 0.f;
+    bool finite = true;
+#pragma unroll
+    for (int r = 0; r < 2; ++r)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int64_t l = p0 * 64 + 4 * (tid + 512 * r) + k;
+            const float v = x[l < n ? l : n - 1];
+            xv[r][k] = l < n ? v : 0.f;
+            finite = finite && (fabsf(xv[r][k]) <= 3.0e38f);
+            amax = fmaxf(amax, fabsf(xv[r][k]));
+        }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off, kWave));
+    if (tid < 16) {
+        uint32_t v = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) v |= (((tid >> k) & 1) ? 0xFFu : 0x01u) << (8 * k);
+        lut[tid] = (int)v;
+    }
+    if (lane == 0) redmax[wv] = amax;
+    const bool all_finite = !__syncthreads_or(finite ? 0 : 1);
+    amax = 0.f;
+#pragma unroll
+    for (int q = 0; q < kApMfmaWaves; ++q) amax = fmaxf(amax, redmax[q]);
+    int ex = 0;
+    if (amax > 0.f) (void)frexpf(amax, &ex);  // amax < 2^ex
+    const int sh = 30 - ex;
+    const double scale = ldexp(1.0, sh), inv_scale = ldexp(1.0, -sh);
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+        uint32_t dig[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            int q = all_finite ? (int)rint((double)xv[r][k] * scale) : 0;
+#pragma unroll
+            for (int jd = 0; jd < 3; ++jd) {
+                const int d = (int)(int8_t)(q & 0xFF);
+                dig[jd] |= (uint32_t)(d & 0xFF) << (8 * k);
+                q = (q - d) >> 8;
+            }
+            dig[3] |= (uint32_t)(q & 0xFF) << (8 * k);
+        }
+        const int g = tid + 512 * r;
+#pragma unroll
+        for (int jd = 0; jd < 4; ++jd) xd[g * 4 + jd] = (int)dig[jd];
+    }
+    __syncthreads();
+
+    uint64_t* mytile = tile[wv];
+    const int jd = lane & 3;
+    const double digit_weight = (double)(1u << (8 * jd));
+    double* mypart = part + chunk * w;
+    for (int t = 0; t < tiles_per_wg; ++t) {
+        const int64_t jbase = ((int64_t)blockIdx.x * tiles_per_wg + t) * kWave;
+        if (jbase >= w) break;
+        ap_int4 acc0 = {0, 0, 0, 0}, acc1 = {0, 0, 0, 0};
+        if (pw < nwc) {
+#pragma unroll
+            for (int r = 0; r < 8; ++r) mytile[((lane >> 3) + 8 * r) * kApTilePitch + (lane & 7)] = stage[r];
+            if (t + 1 < tiles_per_wg && jbase + kWave < w) fetch(jbase + kWave);  // the next 64 terms, during the products
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+            for (int pp = 0; pp < kApTileWords; ++pp) {
+                if (pw + pp < nwc) {
+                    const uint64_t word = mytile[lane * kApTilePitch + pp];
+                    const uint32_t half[2] = {(uint32_t)word, (uint32_t)(word >> 32)};
+                    const int* xg = xd + ((pw + pp) * 16) * 4 + jd;
+#pragma unroll
+                    for (int q = 0; q < 16; ++q) {
+                        const uint32_t hw = half[q >> 3];
+                        const int s4 = 4 * (q & 7);
+                        const uint32_t off = s4 >= 2 ? ((hw >> (s4 - 2)) & 0x3Cu) : ((hw << 2) & 0x3Cu);
+                        const int a = *(const int*)((const char*)lut + off);
+                        if (q & 1) acc1 = __builtin_amdgcn_mfma_i32_4x4x4i8(a, xg[q * 4], acc1, 0, 0, 0);
+                        else acc0 = __builtin_amdgcn_mfma_i32_4x4x4i8(a, xg[q * 4], acc0, 0, 0, 0);
+                    }
+                }
+            }
+            __builtin_amdgcn_wave_barrier();  // the tile is rewritten for the next 64 terms
+        }
+        // D register i = term jbase + 4 (lane / 4) + i, digit (lane % 4): recombine the digits (exact in f64)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            double v = (double)(acc0[i] + acc1[i]) * digit_weight;
+            v += __shfl_xor(v, 1, kWave);
+            v += __shfl_xor(v, 2, kWave);
+            if (jd == 0) wsum[wv][4 * (lane >> 2) + i] = v;
+        }
+        __syncthreads();  // (every wave of the workgroup runs the same tiles)
+        if (wv == 0) {
+            double tot = 0.0;
+#pragma unroll
+            for (int q = 0; q < kApMfmaWaves; ++q) tot += wsum[q][lane];
+            const int64_t j = jbase + lane;
+            if (j < w) mypart[j] = all_finite ? tot * inv_scale : __longlong_as_double(0x7FF8000000000000ll);
+        }
+        __syncthreads();  // wsum is rewritten for the next tile
+    }
+}
+
 // Outer pass.  Wave (p, split) owns the 64 output entries of word p and the terms of its split; lane q
 // fetches word p of term (tile + q) and forms z of that term (the scale step: c times the chunk parts in
 // order); z goes through a wave-private strip of LDS so that every lane can read every term's value.
@@ -119,8 +278,8 @@ __global__ void __launch_bounds__(kApOuterWaves* kWave)
         const int64_t j = tile + lane;
         const int64_t jc = j < j1 ? j : j1 - 1;
         word = bits[jc * mw + p];
-        double s = 0.0;
-        for (int q = 0; q < chunks; ++q) s += part[(int64_t)q * w + jc];
+        double s = part[jc];
+        for (int q = 1; q < chunks; ++q) s += part[(int64_t)q * w + jc];
         z = j < j1 ? (double)c[jc] * s : 0.0;
     };
     double a4[4] = {0.0, 0.0, 0.0, 0.0};
@@ -196,7 +355,8 @@ void apply_plan(int64_t nin, int64_t nout, int64_t w, ApplyPlan* pl)
     pl->splits = (int)((w + pl->terms_per_split - 1) / pl->terms_per_split);
     if (pl->splits < 1) pl->splits = 1;
     pl->off_part = 0;
-    pl->off_ypart = pl->off_part + (size_t)pl->chunks * (size_t)w * 8;
+    pl->parts = pl->chunks;  // slices of <t_j, x> the inner pass writes per term
+    pl->off_ypart = pl->off_part + (size_t)pl->parts * (size_t)w * 8;
     pl->bytes = pl->off_ypart + (size_t)pl->splits * (size_t)wout * 64 * 8;
     if (pl->bytes < 8) pl->bytes = 8;
 }
@@ -221,19 +381,25 @@ hipError_t launch_apply(const uint64_t* in_bits, const uint64_t* out_bits, const
     }
     const int64_t waves = (w + pl.terms_per_wave - 1) / pl.terms_per_wave;
     dim3 gi((unsigned)((waves + kApInnerWaves - 1) / kApInnerWaves), (unsigned)pl.chunks);
-    if (dt == SCD_F32)
-        hipLaunchKernelGGL((apply_inner_kernel<float>), gi, dim3(kApInnerWaves * kWave), 0, st, in_bits, win, w, (const float*)x,
-                           nin, part, pl.terms_per_wave);
-    else
+    if (dt == SCD_F32) {
+        // one workgroup per tile of 64 terms (eight waves split the chunk's words); several tiles per
+        // workgroup once there are enough of them, to pay for the fixed point less often
+        const int64_t tiles = (w + kWave - 1) / kWave;
+        int tpw = (int)((tiles * pl.chunks + 1023) / 1024);
+        if (tpw < 1) tpw = 1;
+        const int64_t wgs = (tiles + tpw - 1) / tpw;
+        hipLaunchKernelGGL(apply_inner_mfma_kernel, dim3((unsigned)wgs, (unsigned)pl.chunks), dim3(kApMfmaWaves * kWave), 0, st,
+                           in_bits, win, w, (const float*)x, nin, part, tpw);
+    } else
         hipLaunchKernelGGL((apply_inner_kernel<double>), gi, dim3(kApInnerWaves * kWave), 0, st, in_bits, win, w,
                            (const double*)x, nin, part, pl.terms_per_wave);
     dim3 go((unsigned)((wout + kApOuterWaves - 1) / kApOuterWaves), (unsigned)pl.splits);
     if (dt == SCD_F32)
         hipLaunchKernelGGL((apply_outer_kernel<float>), go, dim3(kApOuterWaves * kWave), 0, st, out_bits, wout, w, part,
-                           pl.chunks, (const float*)c, pl.terms_per_split, ypart);
+                           pl.parts, (const float*)c, pl.terms_per_split, ypart);
     else
         hipLaunchKernelGGL((apply_outer_kernel<double>), go, dim3(kApOuterWaves * kWave), 0, st, out_bits, wout, w, part,
-                           pl.chunks, (const double*)c, pl.terms_per_split, ypart);
+                           pl.parts, (const double*)c, pl.terms_per_split, ypart);
     const unsigned gr = (unsigned)((nout + 63) / 64);
     if (dt == SCD_F32)
         hipLaunchKernelGGL((apply_reduce_kernel<float>), dim3(gr), dim3(256), 0, st, ypart, pl.splits, wout * 64, nout, (float*)y);

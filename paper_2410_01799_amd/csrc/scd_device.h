@@ -176,6 +176,7 @@ hipError_t launch_transpose(const void* in, void* out, scd_dtype dt, int64_t row
 // ---- product with a vector from the packed factors (scd_apply.hip) ---------------------------------
 struct ApplyPlan {
     int chunks;               // chunks of 4096 input entries
+    int parts;                // slices of <t_j, x> per term that the inner pass writes
     int terms_per_wave;       // inner pass
     int splits;               // outer pass: parts the terms are split into
     int64_t terms_per_split;

@@ -46,10 +46,16 @@ def check(scd, oracle, m, n, w, seed, dtype, transpose, nvec=1):
     y = y.cpu().numpy().astype(np.float64)
     for v in range(nvec):
         ref = oracle.apply(S, T, c.astype(np.float64), m, n, x[v].astype(np.float64), transpose=transpose)
-        # both sides add the same exactly representable terms in f64, in different orders; the GPU result
-        # is then rounded once to the output type
-        zabs = float(np.abs(c.astype(np.float64)).sum() * np.abs(x[v].astype(np.float64)).sum())
-        tol = 1e-13 * zabs + (2.0 ** -23 if dtype == np.float32 else 0.0) * np.abs(ref)
+        # f64 path: both sides add the same exactly representable terms in f64, in different orders.
+        # f32 path: <t_j, x> is formed in fixed point on the matrix cores: x is rounded to 30 bits below the
+        # largest entry of its chunk of 4096 (at most max|x| 2^-30 per entry, exact sums afterwards), the rest
+        # is f64; the result is rounded once to f32.  The roundings are independent, so their sum over a row is
+        # of the order sqrt(n) of them; 4 sqrt(n) is far above that and far below what a lost digit would cost.
+        c64, x64 = c.astype(np.float64), x[v].astype(np.float64)
+        zabs = float(np.abs(c64).sum() * np.abs(x64).sum())
+        tol = 1e-13 * zabs
+        if dtype == np.float32:
+            tol = tol + 4.0 * np.sqrt(nin) * float(np.abs(x64).max()) * 2.0 ** -30 * float(np.abs(c64).sum()) + 2.0 ** -23 * np.abs(ref)
         assert np.all(np.abs(y[v] - ref) <= tol + 1e-300), (m, n, w, transpose, float(np.abs(y[v] - ref).max()))
 
 
