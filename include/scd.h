@@ -150,8 +150,10 @@ int scd_lsq_decompose(const void* A, scd_dtype dt, int64_t m, int64_t n, int64_t
  * the matrix (Section 6.1, Question A):
  *   transpose == 0:  y = (sum_{j<w} c_j s_j t_j^T) x      x: n entries, y: m entries
  *   transpose != 0:  y = (sum_{j<w} c_j s_j t_j^T)^T x    x: m entries, y: n entries
- * computed as z_j = c_j <t_j, x> and y = sum_j z_j s_j, every sum in f64 in a fixed order, y rounded once
- * to dt.  S, T: device, term-major bitsets as scd_decompose writes them (w * ceil(m/64) and
+ * computed as z_j = c_j <t_j, x> and y = sum_j z_j s_j, every sum in a fixed order, y rounded once to dt.
+ * dt = SCD_F64: all sums in f64.  dt = SCD_F32: <t_j, x> is formed in block fixed point (each chunk of 4096
+ * entries of x scaled by a power of two and rounded to integers below 2^30: at most max|x| 2^-30 per entry,
+ * exact integer sums afterwards), the rest in f64.  Non-finite entries of x give NaN.  S, T: device, term-major bitsets as scd_decompose writes them (w * ceil(m/64) and
  * w * ceil(n/64) words, padding bits 0); c, x, y: device, dtype dt; x and y must not overlap.
  * nvec >= 1 vectors are taken one after the other: x is nvec rows of the input length, y nvec rows of the
  * output length.  workspace: device, at least scd_apply_workspace_bytes(m, n, w) bytes, 8-byte aligned,

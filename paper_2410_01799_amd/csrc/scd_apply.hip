@@ -4,12 +4,12 @@
 // The matrix is never expanded: the kernels read the w (m + n) / 8 bytes of sign bits once and do one
 // select and one add per bit.
 //
-// Both passes have the same inner step: a wave owns 64 consecutive entries (one per lane), takes a
-// 64-bit word of sign bits that is the same for all its lanes (fetched by one lane, broadcast through a
-// scalar register), turns bit `lane` into a multiplier +-1.0 and adds with one fused multiply-add in f64 (the product with +-1 is exact, so each
-// step rounds like the sign-flip-and-add of Section 3.4).
-//   inner pass  lanes = 64 entries of x, kept in registers for a chunk of 4096 entries; for every term
-//               the wave adds its 64 words and reduces across the lanes -> <t_j, x> per chunk
+// On the vector units (inner pass for f64, outer pass) the step is: a wave owns 64 consecutive entries (one
+// per lane), takes a 64-bit word of sign bits that is the same for all its lanes (fetched by one lane,
+// broadcast through a scalar register), turns bit `lane` into a multiplier +-1.0 and adds with one fused
+// multiply-add in f64 (the product with +-1 is exact, so each step rounds like the sign-flip-and-add of
+// Section 3.4).  The inner pass for f32 runs on the matrix cores in fixed point (see there).
+//   inner pass  <t_j, x> per chunk of 4096 entries
 //   outer pass  lanes = 64 entries of y; z_j = c_j * (sum of the chunk parts, in order) is formed on the
 //               way in, and for every term of its split the wave adds +-z_j
 //   reduce      y = sum of the splits, in order, rounded once to the output type

@@ -67,6 +67,24 @@ def test_apply_matches_oracle(scd, oracle, m, n, w, dtype):
     check(scd, oracle, m, n, w, m + 3 * n + w + 7, dtype, True)
 
 
+def test_apply_scales_of_x(scd, oracle):
+    # the fixed point follows the scale of x: tiny, huge and mixed-magnitude vectors
+    m, n, w = 200, 4100, 50
+    S, T, c = random_factors(m, n, w, 21, np.float32)
+    rs = np.random.Generator(np.random.PCG64(22))
+    for scale in (1e-30, 1e30):
+        x = (rs.standard_normal(n) * scale).astype(np.float32)
+        y = scd.scd_apply(dev_bits(S), dev_bits(T), torch.from_numpy(c).cuda(), m, n, torch.from_numpy(x).cuda())
+        ref = oracle.apply(S, T, c.astype(np.float64), m, n, x.astype(np.float64))
+        tol = 4.0 * np.sqrt(n) * float(np.abs(x).max()) * 2.0 ** -30 * float(np.abs(c).sum()) + 2.0 ** -23 * np.abs(ref)
+        assert np.all(np.abs(y.cpu().numpy().astype(np.float64) - ref) <= tol)
+    x = (rs.standard_normal(n) * 10.0 ** rs.uniform(-6, 0, n)).astype(np.float32)
+    y = scd.scd_apply(dev_bits(S), dev_bits(T), torch.from_numpy(c).cuda(), m, n, torch.from_numpy(x).cuda())
+    ref = oracle.apply(S, T, c.astype(np.float64), m, n, x.astype(np.float64))
+    tol = 4.0 * np.sqrt(n) * float(np.abs(x).max()) * 2.0 ** -30 * float(np.abs(c).sum()) + 2.0 ** -23 * np.abs(ref)
+    assert np.all(np.abs(y.cpu().numpy().astype(np.float64) - ref) <= tol)
+
+
 def test_apply_several_vectors_and_empty_sum(scd, oracle):
     check(scd, oracle, 300, 200, 40, 5, np.float32, False, nvec=3)
     check(scd, oracle, 300, 200, 40, 6, np.float64, True, nvec=2)
@@ -118,3 +136,16 @@ def test_apply_rejects_bad_arguments(scd):
     assert L.scd_apply(p(Sd), p(Td), p(cd), 0, 128, 128, 4, 0, p(x), 1, p(y), p(ws), need, st) == 0
     with pytest.raises(ValueError):
         scd.scd_apply(Sd, Td, cd, 128, 128, torch.zeros(100, device="cuda"))
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+def test_apply_non_finite_input_gives_nan(scd, dtype):
+    S, T, c = random_factors(130, 200, 9, 3, dtype)
+    x = np.ones(200, dtype=dtype)
+    x[77] = np.inf
+    y = scd.scd_apply(dev_bits(S), dev_bits(T), torch.from_numpy(c).cuda(), 130, 200, torch.from_numpy(x).cuda())
+    assert bool(torch.isnan(y).all())
+    # zeros and a tiny vector pass through the fixed point unharmed
+    z = scd.scd_apply(dev_bits(S), dev_bits(T), torch.from_numpy(c).cuda(), 130, 200,
+                      torch.zeros(200, dtype=torch.from_numpy(c).dtype, device="cuda"))
+    assert float(z.abs().max()) == 0.0
