@@ -182,6 +182,33 @@ def lsq_mode(args, scd, workloads, torch, np) -> int:
     return 0
 
 
+def oracle_mode(args, workloads, np) -> int:
+    """The CPU oracle (plain f64, as it stands) timed on fixed prefixes of the workloads, with one thread and
+    with all host cores: terms/s to quote beside the GPU figures.  No GPU work."""
+    from oracle import scd_oracle as oracle
+
+    oracle.build()
+    all_cores = oracle.get_threads()
+    cases = [("config 1: 256x256 N(0,1)", workloads.gaussian_matrix(256, 256, 1, np.float64), 64, 64, 1),
+             ("config 2: 4096x4096 N(0,1)", workloads.gaussian_matrix(4096, 4096, 2, np.float64), 2, 32, 2),
+             ("config 3: 14336x4096 weight-like", workloads.weight_like_matrix(14336, 4096, 300).astype(np.float64), 1, 8, 300)]
+    rows = []
+    for name, A, terms_one, terms_all, seed in cases:
+        row = {"workload": name}
+        for label, threads, terms in (("one_thread", 1, terms_one), ("all_cores", all_cores, terms_all)):
+            oracle.set_threads(threads)
+            t0 = time.perf_counter()
+            res = oracle.decompose(A, terms, seed)
+            dt = time.perf_counter() - t0
+            row[label] = {"threads": threads, "terms": terms, "seconds": round(dt, 2), "terms_per_s": round(terms / dt, 3),
+                          "alternations_per_term": round(float(res["iters"].mean()), 1)}
+        rows.append(row)
+    oracle.set_threads(all_cores)
+    print(json.dumps({"metric": "CPU oracle terms/s (f64, first terms of each workload)", "unit": "terms/s", "kind": "oracle",
+                      "host_cores": all_cores, "runs": rows}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -206,6 +233,8 @@ def main() -> int:
                          "packed factors (scd_apply) on the layer shapes")
     ap.add_argument("--lsq", action="store_true",
                     help="instead of the headline: time the least squares decomposition (Algorithm 6)")
+    ap.add_argument("--oracle-timing", action="store_true",
+                    help="only time the CPU oracle (one thread, all cores) on prefixes of workloads 1-3")
     ap.add_argument("--calibrate", action="store_true",
                     help="only run the plain copy kernel (64 MiB, 20+1 launches): the known-size reference "
                          "for scaling the profiler's FETCH_SIZE / WRITE_SIZE counters")
@@ -217,6 +246,11 @@ def main() -> int:
         return 2
 
     import numpy as np
+
+    if args.oracle_timing:
+        from paper_2410_01799_amd import workloads as wl
+
+        return oracle_mode(args, wl, np)
     import torch
 
     from paper_2410_01799_amd import scd, workloads
