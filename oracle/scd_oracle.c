@@ -12,6 +12,8 @@
  *   - Section 3.3, Algorithm 6  LEAST SQUARES DECOMPOSITION-> scdo_lsq_coefficients, scdo_lsq_decompose
  *   - Section 5.1, Algorithm 12 AXIAL GREEDY CUT           -> scdo_axial_greedy_cut
  *   - Section 5.2, Algorithm 13 TENSOR GREEDY DECOMPOSITION-> scdo_tensor_decompose
+ *   - Section 5.3, Algorithm 14 TENSOR LEAST SQUARES       -> scdo_tensor_lsq_coefficients,
+ *                                                             scdo_tensor_lsq_decompose
  *   - Section 2.2 / 5.2 definition  a - r_w = sum_j c_j s_j -> scdo_expand
  *   - Section 6.1 (Question A) product of the decomposition with a vector, without expanding it
  *                                                          -> scdo_apply
@@ -555,6 +557,124 @@ int scdo_tensor_decompose(const double* a, int order, const int64_t* dims, int64
         trace[k + 1] = sqrt(scdo_fro2(r, 1, N));
     }
     if (r_out) memcpy(r_out, r, bytes);
+    free(r);
+    return capped;
+}
+
+/* ---------------------------------------------------------------- Algorithm 14 (Section 5.3) */
+
+/* Gaussian elimination with partial pivoting on the k x k system G c = b (G, b are overwritten).
+ * Returns 1 if a pivot falls below tol. */
+static int solve_dense(double* G, double* b, int64_t k, double tol, double* c)
+{
+    for (int64_t col = 0; col < k; ++col) {
+        int64_t piv = col;
+        for (int64_t r = col + 1; r < k; ++r)
+            if (fabs(G[r * k + col]) > fabs(G[piv * k + col])) piv = r;
+        if (fabs(G[piv * k + col]) < tol) return 1;
+        if (piv != col) {
+            for (int64_t q = 0; q < k; ++q) {
+                double tmp = G[col * k + q];
+                G[col * k + q] = G[piv * k + q];
+                G[piv * k + q] = tmp;
+            }
+            double tb = b[col];
+            b[col] = b[piv];
+            b[piv] = tb;
+        }
+        for (int64_t r = col + 1; r < k; ++r) {
+            double f = G[r * k + col] / G[col * k + col];
+            for (int64_t q = col; q < k; ++q) G[r * k + q] -= f * G[col * k + q];
+            b[r] -= f * b[col];
+        }
+    }
+    for (int64_t r = k - 1; r >= 0; --r) {
+        double acc = b[r];
+        for (int64_t q = r + 1; q < k; ++q) acc -= G[r * k + q] * c[q];
+        c[r] = acc / G[r * k + r];
+    }
+    return 0;
+}
+
+/*
+ * c = argmin || a - sum_{j<k} c_j (tensor product of term j's sign vectors) ||_2  (Algorithm 14 line 8),
+ * by the normal equations as in Section 3.3: G_ij = <S_i, S_j>, b_i = <S_i, a>, every inner product summed
+ * over all entries of the tensor.  signs[i]: k * ceil(dims[i]/64) words, term-major.
+ */
+int scdo_tensor_lsq_coefficients(const double* a, int order, const int64_t* dims, int64_t k,
+                                 const uint64_t* const* signs, double* c)
+{
+    int64_t N = total_size(order, dims);
+    int64_t nw[SCDO_MAX_ORDER];
+    double* G;
+    double* b;
+    int singular;
+    if (k == 0) return 0;
+    for (int i = 0; i < order; ++i) nw[i] = words_for(dims[i]);
+    G = (double*)malloc(sizeof(double) * (size_t)k * (size_t)k);
+    b = (double*)malloc(sizeof(double) * (size_t)k);
+    for (int64_t p = 0; p < k; ++p) {
+        const uint64_t* sp[SCDO_MAX_ORDER];
+        for (int i = 0; i < order; ++i) sp[i] = signs[i] + p * nw[i];
+        b[p] = scdo_tensor_inner(a, order, dims, sp);
+        for (int64_t q = 0; q <= p; ++q) {
+            int64_t idx[SCDO_MAX_ORDER] = {0};
+            double g = 0.0;
+            if (N > 0) do {
+                double sg = 1.0;
+                for (int i = 0; i < order; ++i)
+                    sg *= sign_at(sp[i], idx[i]) * sign_at(signs[i] + q * nw[i], idx[i]);
+                g += sg;
+            } while (next_index(order, dims, idx));
+            G[p * k + q] = g;
+            G[q * k + p] = g;
+        }
+    }
+    singular = solve_dense(G, b, k, 1e-9 * (double)N, c);
+    free(G);
+    free(b);
+    return singular;
+}
+
+/*
+ * TENSOR LEAST SQUARES.  Term k: r_k = a - S_k c_k (line 4), axial greedy cut of r_k from the keyed
+ * random start of term k (line 5, every mode drawn as in Algorithm 13), append (lines 6-7), new
+ * coefficients for all terms (line 8).  Outputs as scdo_tensor_decompose, with c the final coefficients.
+ * Returns the number of capped terms, or -1 if the normal equations became singular.
+ */
+int scdo_tensor_lsq_decompose(const double* a, int order, const int64_t* dims, int64_t w, uint64_t seed,
+                              int32_t max_iters, uint64_t* const* signs_out, double* c, double* trace,
+                              int32_t* iters, double* margins)
+{
+    int64_t N = total_size(order, dims);
+    size_t bytes = sizeof(double) * (size_t)N;
+    double* r = (double*)malloc(bytes ? bytes : 8);
+    uint64_t* cur[SCDO_MAX_ORDER];
+    int capped = 0;
+    memcpy(r, a, bytes);
+    trace[0] = sqrt(scdo_fro2(r, 1, N));
+    for (int64_t k = 0; k < w; ++k) {
+        double cu;
+        int32_t it;
+        for (int i = 0; i < order; ++i) {
+            cur[i] = signs_out[i] + k * words_for(dims[i]);
+            scdo_rng_signs(seed, (uint64_t)k, (uint32_t)i, dims[i], cur[i]);
+        }
+        capped += scdo_axial_greedy_cut(r, order, dims, cur, &cu, max_iters, &it, NULL,
+                                        margins ? margins + order * k : NULL);
+        if (iters) iters[k] = it;
+        if (scdo_tensor_lsq_coefficients(a, order, dims, k + 1, (const uint64_t* const*)signs_out, c)) {
+            free(r);
+            return -1;
+        }
+        memcpy(r, a, bytes);
+        for (int64_t j = 0; j <= k; ++j) {
+            const uint64_t* sj[SCDO_MAX_ORDER];
+            for (int i = 0; i < order; ++i) sj[i] = signs_out[i] + j * words_for(dims[i]);
+            scdo_tensor_update(r, order, dims, c[j], sj);
+        }
+        trace[k + 1] = sqrt(scdo_fro2(r, 1, N));
+    }
     free(r);
     return capped;
 }

@@ -76,6 +76,11 @@ def _load():
     L.scdo_lsq_decompose.argtypes = [_f64p, C.c_int64, C.c_int64, C.c_int64, C.c_uint64, C.c_int32, _u64p, _u64p,
                                      _f64p, _f64p, C.c_void_p, C.c_void_p]
     L.scdo_lsq_decompose.restype = C.c_int
+    L.scdo_tensor_lsq_coefficients.argtypes = [_f64p, C.c_int, _i64p, C.c_int64, C.POINTER(vp), _f64p]
+    L.scdo_tensor_lsq_coefficients.restype = C.c_int
+    L.scdo_tensor_lsq_decompose.argtypes = [_f64p, C.c_int, _i64p, C.c_int64, C.c_uint64, C.c_int32, C.POINTER(vp), _f64p,
+                                            _f64p, C.c_void_p, C.c_void_p]
+    L.scdo_tensor_lsq_decompose.restype = C.c_int
     L.scdo_apply.argtypes = [C.c_int64, C.c_int64, C.c_int64, _u64p, _u64p, _f64p, C.c_int, _f64p, _f64p]
     L.scdo_bruteforce_signed_cut_norm.argtypes = [_f64p, C.c_int64, C.c_int64, C.POINTER(C.c_uint64)]
     L.scdo_bruteforce_signed_cut_norm.restype = C.c_double
@@ -290,6 +295,34 @@ def tensor_decompose(a, w: int, seed: int, max_iters: int = DEFAULT_MAX_ITERS, w
     if want_remainder:
         out["r"] = r
     return out
+
+
+def tensor_lsq_coefficients(a, signs) -> np.ndarray:
+    """argmin_c ||a - sum_j c_j (tensor product of term j's sign vectors)||_2 (Algorithm 14 line 8)."""
+    a = _f64(a)
+    dims = np.asarray(a.shape, dtype=np.int64)
+    sg = [_u64(s).reshape(-1, words(d)) for s, d in zip(signs, a.shape)]
+    k = sg[0].shape[0]
+    c = np.zeros(k, dtype=np.float64)
+    if _load().scdo_tensor_lsq_coefficients(a.reshape(-1), a.ndim, dims, k, _ptrs(sg), c):
+        raise np.linalg.LinAlgError("normal equations singular")
+    return c
+
+
+def tensor_lsq_decompose(a, w: int, seed: int, max_iters: int = DEFAULT_MAX_ITERS):
+    """Algorithm 14.  Returns dict(signs, c (final, all terms), trace, iters, margins, capped)."""
+    a = _f64(a)
+    dims = np.asarray(a.shape, dtype=np.int64)
+    sg = [np.zeros((w, words(d)), dtype=np.uint64) for d in a.shape]
+    c = np.zeros(w, dtype=np.float64)
+    trace = np.zeros(w + 1, dtype=np.float64)
+    iters = np.zeros(w, dtype=np.int32)
+    margins = np.zeros((w, a.ndim), dtype=np.float64)
+    capped = _load().scdo_tensor_lsq_decompose(a.reshape(-1), a.ndim, dims, w, seed, max_iters, _ptrs(sg), c, trace,
+                                               iters.ctypes.data, margins.ctypes.data)
+    if capped < 0:
+        raise np.linalg.LinAlgError("normal equations singular")
+    return dict(signs=sg, c=c, trace=trace, iters=iters, margins=margins, capped=int(capped))
 
 
 def expand(signs, c, dims) -> np.ndarray:

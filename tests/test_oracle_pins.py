@@ -293,6 +293,55 @@ def test_lsq_step_is_a_greedy_cut_of_the_projected_remainder(oracle):
         assert np.array_equal(cut["s"], res["S"][k]) and np.array_equal(cut["t"], res["T"][k])
 
 
+# ------------------------------------------------------------------ Algorithm 14 (Section 5.3)
+
+
+def tensor_basis(signs, shape):
+    """prod(shape) x k matrix whose column j is the tensor product of term j's sign vectors, flattened."""
+    cols = []
+    for j in range(len(signs[0])):
+        t = np.ones(())
+        for i, d in enumerate(shape):
+            t = np.multiply.outer(t, dense(signs[i][j], d))
+        cols.append(t.ravel())
+    return np.stack(cols, axis=1)
+
+
+@pytest.mark.parametrize("shape,w,seed", [((6, 9, 3), 7, 2), ((5, 4, 3, 2), 5, 4), ((70, 5, 3), 6, 6)])
+def test_tensor_lsq_invariants(oracle, shape, w, seed):
+    a = np.random.default_rng(50 + seed).standard_normal(shape)
+    res = oracle.tensor_lsq_decompose(a, w, seed)
+    X = tensor_basis(res["signs"], shape)
+    for k in range(1, w + 1):
+        ck = np.linalg.lstsq(X[:, :k], a.ravel(), rcond=None)[0]
+        r = a.ravel() - X[:, :k] @ ck
+        assert np.abs(X[:, :k].T @ r).max() <= 1e-9 * np.abs(a).sum()          # orthogonal to every term
+        assert res["trace"][k] == pytest.approx(np.linalg.norm(r), rel=1e-12)
+    np.testing.assert_allclose(res["c"], np.linalg.lstsq(X, a.ravel(), rcond=None)[0], rtol=1e-9, atol=1e-12)
+    np.testing.assert_allclose(oracle.tensor_lsq_coefficients(a, res["signs"]), res["c"], rtol=1e-12, atol=1e-15)
+    assert np.all(np.diff(res["trace"]) < 0)
+    # the first term is Algorithm 13's first term (only its own coefficient varies)
+    greedy = oracle.tensor_decompose(a, 1, seed)
+    for i in range(len(shape)):
+        assert np.array_equal(res["signs"][i][0], greedy["signs"][i][0])
+    assert res["trace"][1] == pytest.approx(greedy["trace"][1], rel=1e-12)
+    # term k+1 is the axial cut of a - S_k c_k from the keyed start of term k
+    for k in range(w):
+        sk = [s[:k] for s in res["signs"]]
+        rk = a - (oracle.expand(sk, oracle.tensor_lsq_coefficients(a, sk), shape) if k else 0.0)
+        start = [oracle.rng_signs(seed, k, i, d) for i, d in enumerate(shape)]
+        cut = oracle.axial_greedy_cut(rk, start)
+        for i in range(len(shape)):
+            assert np.array_equal(cut["signs"][i], res["signs"][i][k])
+
+
+def test_order2_tensor_lsq_is_the_matrix_lsq(oracle):
+    A = rng_matrix(18, 70, 61)
+    S = np.array([bits_of(np.sign(np.random.default_rng(62 + j).standard_normal(18))) for j in range(5)])
+    T = np.array([bits_of(np.sign(np.random.default_rng(72 + j).standard_normal(70))) for j in range(5)])
+    np.testing.assert_allclose(oracle.tensor_lsq_coefficients(A, [S, T]), oracle.lsq_coefficients(A, S, T), rtol=1e-12)
+
+
 # ------------------------------------------------------------------ product with a vector (Section 6.1)
 
 
