@@ -146,6 +146,15 @@ int scd_expand(const uint64_t* const* signs, const void* c, scd_dtype dt, int or
 int scd_lsq_decompose(const void* A, scd_dtype dt, int64_t m, int64_t n, int64_t w, uint64_t seed, int32_t max_iters,
                       void* stream, uint64_t* S, uint64_t* T, void* c, double* fro_trace, int32_t* iters);
 
+/* The same for a tensor of order 2..SCD_MAX_ORDER (Algorithm 14, Section 5.3): axial greedy cut (Algorithm 12) of
+ * a - S_k c_k from the keyed random start of term k, then all coefficients refitted.  dims: host array; A: device,
+ * row-major, last mode fastest; signs: host array of `order` device pointers, term-major bitsets as in
+ * scd_decompose; the other arguments and the status codes as above.  Every mode step makes its own pass over the
+ * tensor (the remainder is implicit, so no contracted copy can be reused): meant for small and medium tensors. */
+int scd_lsq_decompose_tensor(const void* A, scd_dtype dt, int order, const int64_t* dims, int64_t w, uint64_t seed,
+                             int32_t max_iters, void* stream, uint64_t* const* signs, void* c, double* fro_trace,
+                             int32_t* iters);
+
 /* Product of a matrix decomposition with a vector, straight from the packed factors, without expanding
  * the matrix (Section 6.1, Question A):
  *   transpose == 0:  y = (sum_{j<w} c_j s_j t_j^T) x      x: n entries, y: m entries

@@ -976,24 +976,48 @@ int scd_expand(const uint64_t* const* signs, const void* cvec, scd_dtype dt, int
     return SCD_OK;
 }
 
-// ---------------------------------------------------------------------------------------------- Algorithm 6
+// ---------------------------------------------------------------------------------------------- Algorithms 6 and 14
 
-int scd_lsq_decompose(const void* A, scd_dtype dt, int64_t m, int64_t n, int64_t w, uint64_t seed, int32_t max_iters,
-                      void* stream, uint64_t* S, uint64_t* T, void* cvec, double* fro_trace, int32_t* iters)
+int scd_lsq_decompose_tensor(const void* A, scd_dtype dt, int order, const int64_t* dims, int64_t w, uint64_t seed,
+                             int32_t max_iters, void* stream, uint64_t* const* signs, void* cvec, double* fro_trace,
+                             int32_t* iters)
 {
-    if (!A || !dtype_ok(dt) || m < 1 || n < 1 || w < 0 || w > SCD_LSQ_MAX_WIDTH || max_iters < 1) return SCD_EINVAL;
-    if (!fro_trace || (w > 0 && (!S || !T || !cvec))) return SCD_EINVAL;
-    if (m > (1ll << 31) || n > (1ll << 31)) return SCD_EINVAL;
+    int64_t total = 0;
+    if (!A || !dtype_ok(dt) || w < 0 || w > SCD_LSQ_MAX_WIDTH || max_iters < 1 || !fro_trace) return SCD_EINVAL;
+    SCD_TRY(check_dims(order, dims, &total));
+    if (w > 0 && (!signs || !cvec)) return SCD_EINVAL;
+    for (int i = 0; i < order; ++i) {
+        if (w > 0 && !signs[i]) return SCD_EINVAL;
+        if (dims[i] > (1ll << 31)) return SCD_EINVAL;
+    }
     hipStream_t st = (hipStream_t)stream;
-    const int64_t mw = words_for(m), nw = words_for(n);
     const size_t es = dt == SCD_F32 ? 4 : 8;
-    int rpw, grid;
-    halfstep_geometry(m, &rpw, &grid);
-    const int nsq = 256;
     const int64_t wl = w > 0 ? w : 1;
+    const int nsq = 256;
+    // mode i sees the tensor as (outer_i) x n_i x (inner_i), last mode fastest
+    int64_t outer[SCD_MAX_ORDER], inner[SCD_MAX_ORDER], nwords[SCD_MAX_ORDER];
+    int64_t max_dim = 1, max_w = 1, max_kron = 1, max_part = 1, max_words = 1;
+    for (int i = 0; i < order; ++i) {
+        outer[i] = 1;
+        inner[i] = 1;
+        for (int q = 0; q < i; ++q) outer[i] *= dims[q];
+        for (int q = i + 1; q < order; ++q) inner[i] *= dims[q];
+        nwords[i] = words_for(dims[i]);
+        if (dims[i] > max_dim) max_dim = dims[i];
+        if (nwords[i] > max_words) max_words = nwords[i];
+        if (i > 0) {
+            const int64_t wcols = dims[i] * inner[i];
+            if (wcols > max_w) max_w = wcols;
+            int rpw, grid;
+            halfstep_geometry(outer[i], &rpw, &grid);
+            if ((int64_t)grid * wcols > max_part) max_part = (int64_t)grid * wcols;
+            if (outer[i] > max_kron) max_kron = outer[i];
+        }
+        if (inner[i] > max_kron) max_kron = inner[i];
+    }
 
     std::vector<void*> bufs;
-    double* host = nullptr;  // pinned: [0] cut value, [1] b of the current pair, [2] right-hand side to upload
+    double* host = nullptr;  // pinned: [0] cut value, [1] b of the current term, [2] upload slot, [3] status
     int rc = SCD_OK;
     auto alloc = [&](void** p, size_t bytes) {
         if (hipMalloc(p, bytes ? bytes : 8) != hipSuccess) {
@@ -1004,20 +1028,23 @@ int scd_lsq_decompose(const void* A, scd_dtype dt, int64_t m, int64_t n, int64_t
         bufs.push_back(*p);
         return true;
     };
-    double *uA = nullptr, *vA = nullptr, *e = nullptr, *ga = nullptr, *gb = nullptr, *absp = nullptr, *dotp = nullptr;
+    double *uA = nullptr, *W = nullptr, *e = nullptr, *D = nullptr, *g = nullptr, *absp = nullptr, *dotp = nullptr;
     double *scal = nullptr, *L = nullptr, *yv = nullptr, *c = nullptr, *work = nullptr, *bvec = nullptr, *cparts = nullptr;
     double* sq = nullptr;
     void* partials = nullptr;
-    uint64_t *sb = nullptr, *tb = nullptr;
+    uint64_t *kr_out = nullptr, *kr_in = nullptr;
+    uint64_t* cur[SCD_MAX_ORDER] = {nullptr};
     int* status = nullptr;
     std::vector<int32_t> it_host((size_t)wl, 0);
-    bool ok = alloc((void**)&uA, (size_t)m * 8) && alloc((void**)&vA, (size_t)n * 8) && alloc((void**)&e, (size_t)wl * 8) &&
-              alloc((void**)&ga, (size_t)wl * 8) && alloc((void**)&gb, (size_t)wl * 8) && alloc((void**)&absp, (size_t)nw * 8) &&
-              alloc((void**)&dotp, (size_t)nw * 8) && alloc((void**)&scal, 16) && alloc((void**)&L, (size_t)wl * wl * 8) &&
-              alloc((void**)&yv, (size_t)wl * 8) && alloc((void**)&c, (size_t)wl * 8) && alloc((void**)&work, (size_t)wl * 8) &&
-              alloc((void**)&bvec, (size_t)wl * 8) && alloc((void**)&cparts, (size_t)nw * 8) &&
-              alloc((void**)&sq, (size_t)nsq * 8) && alloc(&partials, (size_t)grid * (size_t)n * es) &&
-              alloc((void**)&sb, (size_t)mw * 8) && alloc((void**)&tb, (size_t)nw * 8) && alloc((void**)&status, 4);
+    bool ok = alloc((void**)&uA, (size_t)max_dim * 8) && alloc((void**)&W, (size_t)max_w * 8) &&
+              alloc((void**)&e, (size_t)wl * 8) && alloc((void**)&D, (size_t)order * wl * 8) && alloc((void**)&g, (size_t)wl * 8) &&
+              alloc((void**)&absp, (size_t)max_words * 8) && alloc((void**)&dotp, (size_t)max_words * 8) &&
+              alloc((void**)&scal, 16) && alloc((void**)&L, (size_t)wl * wl * 8) && alloc((void**)&yv, (size_t)wl * 8) &&
+              alloc((void**)&c, (size_t)wl * 8) && alloc((void**)&work, (size_t)wl * 8) && alloc((void**)&bvec, (size_t)wl * 8) &&
+              alloc((void**)&cparts, (size_t)words_for(max_w) * 8) && alloc((void**)&sq, (size_t)nsq * 8) &&
+              alloc(&partials, (size_t)max_part * 8) && alloc((void**)&kr_out, (size_t)words_for(max_kron) * 8) &&
+              alloc((void**)&kr_in, (size_t)words_for(max_kron) * 8) && alloc((void**)&status, 4);
+    for (int i = 0; ok && i < order; ++i) ok = alloc((void**)&cur[i], (size_t)nwords[i] * 8);
     if (ok && hipHostMalloc((void**)&host, 4 * sizeof(double), hipHostMallocDefault) != hipSuccess) {
         (void)hipGetLastError();
         host = nullptr;
@@ -1042,35 +1069,76 @@ int scd_lsq_decompose(const void* A, scd_dtype dt, int64_t m, int64_t n, int64_t
     } while (0)
 
     LQ(hipMemsetAsync(status, 0, 4, st));
-    // ||A||_F^2
-    LQ(launch_lsq_sumsq(A, dt, m * n, sq, nsq, st));
+    // ||a||^2
+    LQ(launch_lsq_sumsq(A, dt, total, sq, nsq, st));
     LQ(launch_lsq_sum2(sq, nullptr, nsq, scal, st));
     LQ(hipMemcpyAsync(host, scal, 16, hipMemcpyDeviceToHost, st));
     LQ(hipStreamSynchronize(st));
     const double fro0sq = host[0];
     if (!isfinite(fro0sq)) return cleanup(SCD_ENONFINITE);
-    {
-        const double f0 = sqrt(fro0sq);
-        host[2] = f0;
-        LQ(hipMemcpyAsync(fro_trace, host + 2, 8, hipMemcpyHostToDevice, st));
-        LQ(hipStreamSynchronize(st));
-    }
+    host[2] = sqrt(fro0sq);
+    LQ(hipMemcpyAsync(fro_trace, host + 2, 8, hipMemcpyHostToDevice, st));
+    LQ(hipStreamSynchronize(st));
+
+    // u = a x_i (tensor product of the other modes' current sign vectors), the part of the mode sum that
+    // comes from the tensor itself: signed column sums over the leading modes, then signed row sums over
+    // the trailing ones.
+    auto tensor_part = [&](int i) -> hipError_t {
+        hipError_t err = hipSuccess;
+        const void* src = A;
+        scd_dtype sdt = dt;
+        const bool leading = i > 0, trailing = i < order - 1;  // modes before / after mode i (even of size 1: a sign)
+        if (leading) {
+            const uint64_t* sigma = cur[0];
+            if (i > 1) {
+                err = launch_lsq_kron(cur, dims, 0, i, outer[i], kr_out, st);
+                if (err != hipSuccess) return err;
+                sigma = kr_out;
+            }
+            int rpw, grid;
+            halfstep_geometry(outer[i], &rpw, &grid);
+            const int64_t wcols = dims[i] * inner[i];
+            err = launch_halfstep(A, dt, outer[i], wcols, rpw, grid, 0, nullptr, sigma, partials, nullptr, st);
+            if (err != hipSuccess) return err;
+            err = launch_reduce_plain(partials, dt, grid, wcols, trailing ? W : uA, nullptr, cparts, st);
+            if (err != hipSuccess) return err;
+            src = W;
+            sdt = SCD_F64;
+        }
+        if (trailing) {
+            const uint64_t* tau = cur[order - 1];
+            if (i < order - 2) {
+                err = launch_lsq_kron(cur, dims, i + 1, order, inner[i], kr_in, st);
+                if (err != hipSuccess) return err;
+                tau = kr_in;
+            }
+            int rpw, grid;
+            halfstep_geometry(dims[i], &rpw, &grid);
+            err = launch_halfstep(src, sdt, dims[i], inner[i], rpw, grid, 1, tau, nullptr, nullptr, uA, st);
+        }
+        return err;
+    };
+
     for (int64_t k = 0; k < w; ++k) {
-        // Algorithm 4 on the implicit remainder, from the keyed random start of term k (Algorithm 6 line 6)
-        LQ(launch_rng(seed, (uint64_t)k, 1u, n, tb, st));
+        // Algorithm 12 on the implicit remainder a - S_k c_k, from the keyed random start of term k
+        for (int i = 1; i < order; ++i) {
+            LQ(launch_rng(seed, (uint64_t)k, (uint32_t)i, dims[i], cur[i], st));
+            LQ(launch_lsq_dots(signs[i], k, nwords[i], dims[i], cur[i], nullptr, D + (int64_t)i * wl, st));
+        }
         double c_prev = -INFINITY, bnew = 0.0;
         int32_t j = 0;
         for (;;) {
-            // s = sgn(A t - S (c o T^T t))
-            LQ(launch_halfstep(A, dt, m, n, rpw, grid, 1, tb, nullptr, nullptr, uA, st));
-            LQ(launch_lsq_dots(T, k, nw, n, tb, c, e, st));
-            LQ(launch_lsq_correct(S, k, mw, m, e, uA, sb, nullptr, nullptr, st));
-            // t = sgn(A^T s - T (c o S^T s)), cut value sum |.|, and <t, A^T s> = <s, A t>
-            LQ(launch_halfstep(A, dt, m, n, rpw, grid, 0, nullptr, sb, partials, nullptr, st));
-            LQ(launch_reduce_plain(partials, dt, grid, n, vA, nullptr, cparts, st));
-            LQ(launch_lsq_dots(S, k, mw, m, sb, c, e, st));
-            LQ(launch_lsq_correct(T, k, nw, n, e, vA, tb, absp, dotp, st));
-            LQ(launch_lsq_sum2(absp, dotp, nw, scal, st));
+            for (int i = 0; i < order; ++i) {
+                // s^(i) = sgn(a x_i (others) - sum_j c_j (prod_{m != i} <s_j^(m), s^(m)>) s_j^(i))
+                LQ(tensor_part(i));
+                LQ(launch_lsq_prod(D, wl, order, i, k, c, e, st));
+                const bool last = i == order - 1;
+                LQ(launch_lsq_correct(signs[i], k, nwords[i], dims[i], e, uA, cur[i], last ? absp : nullptr,
+                                      last ? dotp : nullptr, st));
+                LQ(launch_lsq_dots(signs[i], k, nwords[i], dims[i], cur[i], nullptr, D + (int64_t)i * wl, st));
+            }
+            // after the last mode: the cut value sum |.| and <S_new, a> (Algorithm 12 line 10)
+            LQ(launch_lsq_sum2(absp, dotp, nwords[order - 1], scal, st));
             LQ(hipMemcpyAsync(host, scal, 16, hipMemcpyDeviceToHost, st));
             LQ(hipStreamSynchronize(st));
             ++j;
@@ -1084,14 +1152,13 @@ int scd_lsq_decompose(const void* A, scd_dtype dt, int64_t m, int64_t n, int64_t
             c_prev = cut;
         }
         it_host[(size_t)k] = j;
-        // append (lines 7-8) and refit every coefficient (line 9)
-        LQ(hipMemcpyAsync(S + k * mw, sb, (size_t)mw * 8, hipMemcpyDeviceToDevice, st));
-        LQ(hipMemcpyAsync(T + k * nw, tb, (size_t)nw * 8, hipMemcpyDeviceToDevice, st));
+        // append and refit every coefficient
+        for (int i = 0; i < order; ++i)
+            LQ(hipMemcpyAsync(signs[i] + k * nwords[i], cur[i], (size_t)nwords[i] * 8, hipMemcpyDeviceToDevice, st));
         host[2] = bnew;
         LQ(hipMemcpyAsync(bvec + k, host + 2, 8, hipMemcpyHostToDevice, st));
-        LQ(launch_lsq_dots(S, k, mw, m, sb, nullptr, ga, st));
-        LQ(launch_lsq_dots(T, k, nw, n, tb, nullptr, gb, st));
-        LQ(launch_lsq_solve(L, wl, k, ga, gb, (double)m * (double)n, bvec, yv, c, work, fro0sq, fro_trace + k + 1, status, st));
+        LQ(launch_lsq_prod(D, wl, order, -1, k, nullptr, g, st));  // Gram row: product of the per-mode inner products
+        LQ(launch_lsq_solve(L, wl, k, g, (double)total, bvec, yv, c, work, fro0sq, fro_trace + k + 1, status, st));
         LQ(hipMemcpyAsync(host + 3, status, 4, hipMemcpyDeviceToHost, st));
         LQ(hipStreamSynchronize(st));  // host[2] is reused by the next term
         if (*(const int*)(host + 3) != 0) return cleanup(SCD_ESINGULAR);
@@ -1101,6 +1168,14 @@ int scd_lsq_decompose(const void* A, scd_dtype dt, int64_t m, int64_t n, int64_t
     LQ(hipStreamSynchronize(st));
 #undef LQ
     return cleanup(rc);
+}
+
+int scd_lsq_decompose(const void* A, scd_dtype dt, int64_t m, int64_t n, int64_t w, uint64_t seed, int32_t max_iters,
+                      void* stream, uint64_t* S, uint64_t* T, void* cvec, double* fro_trace, int32_t* iters)
+{
+    const int64_t dims[2] = {m, n};
+    uint64_t* const signs[2] = {S, T};
+    return scd_lsq_decompose_tensor(A, dt, 2, dims, w, seed, max_iters, stream, signs, cvec, fro_trace, iters);
 }
 
 size_t scd_apply_workspace_bytes(int64_t m, int64_t n, int64_t w)

@@ -194,9 +194,12 @@ hipError_t launch_lsq_correct(const uint64_t* bits, int64_t k, int64_t mw, int64
 hipError_t launch_lsq_sum2(const double* a, const double* b, int64_t n, double* out, hipStream_t st);
 hipError_t launch_lsq_sumsq(const void* A, scd_dtype dt, int64_t total, double* parts, int nparts, hipStream_t st);
 hipError_t launch_lsq_cast(const double* c, int64_t k, scd_dtype dt, void* out, hipStream_t st);
-hipError_t launch_lsq_solve(double* L, int64_t ld, int64_t k, const double* ga, const double* gb, double diag,
-                            const double* bvec, double* yv, double* c, double* work, double fro0sq, double* trace_out,
-                            int* status, hipStream_t st);
+hipError_t launch_lsq_prod(const double* D, int64_t ld, int order, int skip, int64_t k, const double* coef, double* out,
+                           hipStream_t st);
+hipError_t launch_lsq_kron(const uint64_t* const* signs, const int64_t* dims, int first, int last, int64_t len, uint64_t* out,
+                           hipStream_t st);
+hipError_t launch_lsq_solve(double* L, int64_t ld, int64_t k, const double* g, double diag, const double* bvec, double* yv,
+                            double* c, double* work, double fro0sq, double* trace_out, int* status, hipStream_t st);
 
 // ---- launchers implemented in scd_kernels.hip ----------------------------------------------------
 hipError_t launch_rowpass(const RowPassArgs& a, scd_dtype dt, int grid, int variant, hipStream_t st);

@@ -131,6 +131,44 @@ __global__ void __launch_bounds__(256) lsq_cast_kernel(const double* __restrict_
     if (j < k) out[j] = (TE)c[j];
 }
 
+// out[j] = (coef ? coef[j] : 1) * product over the modes m != skip of D[m * ld + j]   (skip < 0: all modes)
+__global__ void __launch_bounds__(256) lsq_prod_kernel(const double* __restrict__ D, int64_t ld, int order, int skip, int64_t k,
+                                                      const double* __restrict__ coef, double* __restrict__ out)
+{
+    const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (j >= k) return;
+    double p = coef ? coef[j] : 1.0;
+    for (int m = 0; m < order; ++m)
+        if (m != skip) p *= D[(int64_t)m * ld + j];
+    out[j] = p;
+}
+
+// Sign bits of the tensor product of the sign vectors of modes first..last-1 (last mode fastest): bit q is
+// the xor of the modes' bits at the multi-index of q (Algorithm 12 lines 5-7).  One lane per entry.
+struct LsqKronArgs {
+    const uint64_t* signs[SCD_MAX_ORDER];
+    int64_t dims[SCD_MAX_ORDER];
+    int first, last;
+    int64_t len;
+    uint64_t* out;
+};
+
+__global__ void __launch_bounds__(256) lsq_kron_kernel(LsqKronArgs a)
+{
+    const int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    unsigned bit = 0;
+    if (q < a.len) {
+        int64_t rest = q;
+        for (int m = a.last - 1; m >= a.first; --m) {
+            const int64_t i = rest % a.dims[m];
+            rest /= a.dims[m];
+            bit ^= (unsigned)((a.signs[m][i >> 6] >> (i & 63)) & 1ull);
+        }
+    }
+    const uint64_t word = __ballot(q < a.len && bit);
+    if ((threadIdx.x & (kWave - 1)) == 0 && (q >> 6) < (a.len + 63) / 64) a.out[q >> 6] = word;
+}
+
 constexpr int kLqThreads = 1024;
 
 // sum over the workgroup in a fixed order; every thread gets the same bits
@@ -148,13 +186,12 @@ __device__ double lq_block_sum(double v, double* red)
 }
 
 // The new term has index k.  Appends row k to the Cholesky factor L (lower triangular, row-major, leading
-// dimension ld) of the Gram matrix, whose new row is ga[j] * gb[j] (j < k) with `diag` on the diagonal;
+// dimension ld) of the Gram matrix, whose new row is g[j] (j < k) with `diag` on the diagonal;
 // extends the forward solution y of L y = b by one entry; solves L^T c = y for all k + 1 coefficients;
 // and records ||A - S diag(c) T^T||_F = sqrt(||A||^2 - <c, b>) (the remainder is orthogonal to the fit).
 // One workgroup.  status: 1 if the new term is (numerically) in the span of the old ones.
 __global__ void __launch_bounds__(kLqThreads)
-    lsq_solve_kernel(double* __restrict__ L, int64_t ld, int64_t k, const double* __restrict__ ga, const double* __restrict__ gb,
-                     double diag, const double* __restrict__ bvec, double* __restrict__ yv, double* __restrict__ c,
+    lsq_solve_kernel(double* __restrict__ L, int64_t ld, int64_t k, const double* __restrict__ g, double diag, const double* __restrict__ bvec, double* __restrict__ yv, double* __restrict__ c,
                      double* __restrict__ work, double fro0sq, double* __restrict__ trace_out, int* __restrict__ status)
 {
     __shared__ double red[kLqThreads / kWave];
@@ -165,7 +202,7 @@ __global__ void __launch_bounds__(kLqThreads)
         double s = 0.0;
         for (int64_t q = tid; q < r; q += kLqThreads) s += L[r * ld + q] * row[q];
         s = lq_block_sum(s, red);
-        if (tid == 0) row[r] = (ga[r] * gb[r] - s) / L[r * ld + r];
+        if (tid == 0) row[r] = (g[r] - s) / L[r * ld + r];
         __threadfence_block();
         __syncthreads();
     }
@@ -226,6 +263,31 @@ hipError_t launch_lsq_correct(const uint64_t* bits, int64_t k, int64_t mw, int64
     return hipGetLastError();
 }
 
+hipError_t launch_lsq_prod(const double* D, int64_t ld, int order, int skip, int64_t k, const double* coef, double* out,
+                           hipStream_t st)
+{
+    if (k <= 0) return hipSuccess;
+    hipLaunchKernelGGL(lsq_prod_kernel, dim3((unsigned)((k + 255) / 256)), dim3(256), 0, st, D, ld, order, skip, k, coef, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_lsq_kron(const uint64_t* const* signs, const int64_t* dims, int first, int last, int64_t len, uint64_t* out,
+                           hipStream_t st)
+{
+    LsqKronArgs a;
+    for (int m = 0; m < SCD_MAX_ORDER; ++m) {
+        a.signs[m] = (m >= first && m < last) ? signs[m] : nullptr;
+        a.dims[m] = (m >= first && m < last) ? dims[m] : 1;
+    }
+    a.first = first;
+    a.last = last;
+    a.len = len;
+    a.out = out;
+    const int64_t padded = ((len + 63) / 64) * 64;
+    hipLaunchKernelGGL(lsq_kron_kernel, dim3((unsigned)((padded + 255) / 256)), dim3(256), 0, st, a);
+    return hipGetLastError();
+}
+
 hipError_t launch_lsq_sum2(const double* a, const double* b, int64_t n, double* out, hipStream_t st)
 {
     hipLaunchKernelGGL(lsq_sum2_kernel, dim3(1), dim3(256), 0, st, a, b, n, out);
@@ -252,11 +314,10 @@ hipError_t launch_lsq_cast(const double* c, int64_t k, scd_dtype dt, void* out, 
     return hipGetLastError();
 }
 
-hipError_t launch_lsq_solve(double* L, int64_t ld, int64_t k, const double* ga, const double* gb, double diag,
-                            const double* bvec, double* yv, double* c, double* work, double fro0sq, double* trace_out,
-                            int* status, hipStream_t st)
+hipError_t launch_lsq_solve(double* L, int64_t ld, int64_t k, const double* g, double diag, const double* bvec, double* yv,
+                            double* c, double* work, double fro0sq, double* trace_out, int* status, hipStream_t st)
 {
-    hipLaunchKernelGGL(lsq_solve_kernel, dim3(1), dim3(kLqThreads), 0, st, L, ld, k, ga, gb, diag, bvec, yv, c, work, fro0sq,
+    hipLaunchKernelGGL(lsq_solve_kernel, dim3(1), dim3(kLqThreads), 0, st, L, ld, k, g, diag, bvec, yv, c, work, fro0sq,
                        trace_out, status);
     return hipGetLastError();
 }

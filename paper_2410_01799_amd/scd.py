@@ -25,7 +25,7 @@ EXPORTS = [
     "scd_width", "scd_results", "scd_remainder", "scd_set_remainder", "scd_row_signed_sum", "scd_col_signed_sum",
     "scd_expand", "scd_pack", "scd_unpack", "scd_rng_signs", "scd_strerror", "scd_last_hip_error", "scd_traffic",
     "scd_probe_stream", "scd_profile_sweeps", "scd_probe_exchange", "scd_engine", "scd_set_workgroups",
-    "scd_apply", "scd_apply_workspace_bytes", "scd_lsq_decompose", "scd_sparse_flips",
+    "scd_apply", "scd_apply_workspace_bytes", "scd_lsq_decompose", "scd_lsq_decompose_tensor", "scd_sparse_flips",
 ]
 
 
@@ -57,6 +57,7 @@ def lib() -> C.CDLL:
         L.scd_set_workgroups.argtypes = [vp, C.c_int]
         L.scd_sparse_flips.argtypes = [vp, pi64, pi64]
         L.scd_lsq_decompose.argtypes = [vp, C.c_int, i64, i64, i64, C.c_uint64, i32, vp, vp, vp, vp, vp, vp]
+        L.scd_lsq_decompose_tensor.argtypes = [vp, C.c_int, C.c_int, pi64, i64, C.c_uint64, i32, vp, pvp, vp, vp, vp]
         L.scd_apply_workspace_bytes.argtypes = [i64, i64, i64]
         L.scd_apply_workspace_bytes.restype = C.c_size_t
         L.scd_apply.argtypes = [vp, vp, vp, C.c_int, i64, i64, i64, C.c_int, vp, i64, vp, vp, C.c_size_t, vp]
@@ -169,21 +170,24 @@ def scd_expand(signs: Sequence[torch.Tensor], c: torch.Tensor, dims: Sequence[in
 
 
 def scd_lsq_decompose(A: torch.Tensor, w: int, seed: int, max_iters: int = 4096) -> dict:
-    """Algorithm 6: greedy cuts with all coefficients refitted by least squares after every term.
-    Returns dict(signs=[S, T], c (final coefficients), trace, iters, status)."""
+    """Algorithms 6 (matrices) and 14 (tensors): greedy cuts with all coefficients refitted by least squares
+    after every term.  Returns dict(signs=[per-mode bitsets], c (final coefficients), trace, iters, status)."""
     A = _dev(A, "A")
-    if A.dim() != 2:
-        raise ValueError("matrices only")
-    m, n = int(A.shape[0]), int(A.shape[1])
-    S = _bits(int(w) * words(m), A.device).reshape(int(w), words(m))
-    T = _bits(int(w) * words(n), A.device).reshape(int(w), words(n))
-    c = torch.empty(int(w), dtype=A.dtype, device=A.device)
-    trace = torch.empty(int(w) + 1, dtype=torch.float64, device=A.device)
-    iters = torch.empty(int(w), dtype=torch.int32, device=A.device)
-    st = lib().scd_lsq_decompose(_ptr(A), _dt(A), m, n, int(w), int(seed), int(max_iters), _stream(), _ptr(S), _ptr(T),
-                                 _ptr(c), _ptr(trace), _ptr(iters))
+    if A.dim() < 2:
+        raise ValueError("order >= 2")
+    w = int(w)
+    signs = [_bits(w * words(int(d)), A.device).reshape(w, words(int(d))) for d in A.shape]
+    c = torch.empty(w, dtype=A.dtype, device=A.device)
+    trace = torch.empty(w + 1, dtype=torch.float64, device=A.device)
+    iters = torch.empty(w, dtype=torch.int32, device=A.device)
+    if A.dim() == 2:
+        st = lib().scd_lsq_decompose(_ptr(A), _dt(A), int(A.shape[0]), int(A.shape[1]), w, int(seed), int(max_iters),
+                                     _stream(), _ptr(signs[0]), _ptr(signs[1]), _ptr(c), _ptr(trace), _ptr(iters))
+    else:
+        st = lib().scd_lsq_decompose_tensor(_ptr(A), _dt(A), A.dim(), _dims(A.shape), w, int(seed), int(max_iters),
+                                            _stream(), _ptr_array(signs), _ptr(c), _ptr(trace), _ptr(iters))
     st = _check(st, "scd_lsq_decompose")
-    return dict(signs=[S, T], c=c, trace=trace, iters=iters, status=st)
+    return dict(signs=signs, c=c, trace=trace, iters=iters, status=st)
 
 
 def scd_apply(S: torch.Tensor, T: torch.Tensor, c: torch.Tensor, m: int, n: int, x: torch.Tensor,

@@ -125,3 +125,60 @@ def test_lsq_edges_and_errors(scd):
     one = scd.scd_lsq_decompose(A, 3, 1)
     two = scd.scd_lsq_decompose(A, 3, 1)
     assert torch.equal(one["c"], two["c"]) and torch.equal(one["trace"], two["trace"])   # bit-identical reruns
+
+
+# ---- tensors (Algorithm 14)
+
+def run_and_check_tensor(scd, oracle, a, w, seed):
+    shape = a.shape
+    f32 = a.dtype == np.float32
+    a64 = a.astype(np.float64)
+    res = scd.scd_lsq_decompose(torch.from_numpy(a).cuda(), w, seed)
+    assert res["status"] == 0
+    sg = [to_np_bits(s) for s in res["signs"]]
+    c = res["c"].cpu().numpy().astype(np.float64)
+    trace = res["trace"].cpu().numpy()
+    iters = res["iters"].cpu().numpy()
+    rtol_norm = 2e-6 if f32 else 1e-10
+    for k in range(w):
+        sk = [s[:k] for s in sg]
+        rk = a64 - (oracle.expand(sk, oracle.tensor_lsq_coefficients(a64, sk), shape) if k else 0.0)
+        assert trace[k] == pytest.approx(np.linalg.norm(rk), rel=rtol_norm), f"trace[{k}]"
+        start = [oracle.rng_signs(seed, k, i, d) for i, d in enumerate(shape)]
+        g = oracle.axial_greedy_cut(rk, start)
+        if all(np.array_equal(g["signs"][i], sg[i][k]) for i in range(len(shape))):
+            assert iters[k] == g["iters"], f"term {k}: sweep count"
+        else:
+            assert g["margin"].min() < (10 * TIE_TOL if f32 else 1e-9), \
+                f"term {k}: signs differ although the oracle's margin is {g['margin'].min():.2e}"
+        for i, d in enumerate(shape):
+            if d % 64:
+                assert int(sg[i][k][-1]) >> (d % 64) == 0
+    cw = oracle.tensor_lsq_coefficients(a64, sg)
+    np.testing.assert_allclose(c, cw, rtol=C_RTOL if f32 else 1e-9, atol=1e-7 * np.abs(cw).max())
+    rw = a64 - oracle.expand(sg, cw, shape)
+    assert trace[w] == pytest.approx(np.linalg.norm(rw), rel=rtol_norm)
+    assert np.all(np.diff(trace) < 0)
+    # the definition, through the library's own expansion
+    E = scd.scd_expand(res["signs"], res["c"], shape).double().cpu().numpy()
+    assert np.linalg.norm(a64 - E) == pytest.approx(trace[w], rel=1e-4 if f32 else 1e-10)
+
+
+@pytest.mark.parametrize("shape,w,dtype", [((40, 30, 3), 12, np.float32), ((40, 30, 3), 10, np.float64), ((9, 70, 5, 2), 8, np.float32),
+                                           ((130, 1, 3), 6, np.float64), ((1, 66, 4), 6, np.float32), ((200, 150, 3), 10, np.float32)])
+def test_tensor_lsq_matches_oracle_in_lockstep(scd, oracle, shape, w, dtype):
+    run_and_check_tensor(scd, oracle, gauss(shape, sum(shape) + w, dtype), w, 5)
+
+
+def test_tensor_lsq_first_term_and_image_like(scd):
+    from paper_2410_01799_amd import workloads
+
+    a = torch.from_numpy(workloads.image_like_tensor(120, 90, 3, blobs=30, seed=400)).cuda()
+    one = scd.scd_lsq_decompose(a, 1, 4)
+    greedy = scd.scd_decompose(a, 1, 4)
+    for x, y in zip(one["signs"], greedy["signs"]):
+        assert torch.equal(x, y)
+    assert float(one["trace"][1]) == pytest.approx(float(greedy["trace"][1]), rel=1e-6)
+    ls = scd.scd_lsq_decompose(a, 24, 4)
+    gr = scd.scd_decompose(a, 24, 4)
+    assert float(ls["trace"][24]) <= float(gr["trace"][24]) * (1 + 1e-9)
