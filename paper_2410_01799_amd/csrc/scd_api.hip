@@ -991,16 +991,13 @@ int scd_lsq_decompose_tensor(const void* A, scd_dtype dt, int order, const int64
         if (dims[i] > (1ll << 31)) return SCD_EINVAL;
     }
     hipStream_t st = (hipStream_t)stream;
-    const size_t es = dt == SCD_F32 ? 4 : 8;
     const int64_t wl = w > 0 ? w : 1;
     const int nsq = 256;
-    // mode i sees the tensor as (outer_i) x n_i x (inner_i), last mode fastest
-    int64_t outer[SCD_MAX_ORDER], inner[SCD_MAX_ORDER], nwords[SCD_MAX_ORDER];
+    // mode i sees the tensor as (leading modes) x n_i x inner_i, last mode fastest
+    int64_t inner[SCD_MAX_ORDER], nwords[SCD_MAX_ORDER];
     int64_t max_dim = 1, max_w = 1, max_kron = 1, max_part = 1, max_words = 1;
     for (int i = 0; i < order; ++i) {
-        outer[i] = 1;
         inner[i] = 1;
-        for (int q = 0; q < i; ++q) outer[i] *= dims[q];
         for (int q = i + 1; q < order; ++q) inner[i] *= dims[q];
         nwords[i] = words_for(dims[i]);
         if (dims[i] > max_dim) max_dim = dims[i];
@@ -1009,9 +1006,8 @@ int scd_lsq_decompose_tensor(const void* A, scd_dtype dt, int order, const int64
             const int64_t wcols = dims[i] * inner[i];
             if (wcols > max_w) max_w = wcols;
             int rpw, grid;
-            halfstep_geometry(outer[i], &rpw, &grid);
+            halfstep_geometry(dims[i - 1], &rpw, &grid);
             if ((int64_t)grid * wcols > max_part) max_part = (int64_t)grid * wcols;
-            if (outer[i] > max_kron) max_kron = outer[i];
         }
         if (inner[i] > max_kron) max_kron = inner[i];
     }
@@ -1028,21 +1024,21 @@ int scd_lsq_decompose_tensor(const void* A, scd_dtype dt, int order, const int64
         bufs.push_back(*p);
         return true;
     };
-    double *uA = nullptr, *W = nullptr, *e = nullptr, *D = nullptr, *g = nullptr, *absp = nullptr, *dotp = nullptr;
+    double *uA = nullptr, *W = nullptr, *W2 = nullptr, *e = nullptr, *D = nullptr, *g = nullptr, *absp = nullptr, *dotp = nullptr;
     double *scal = nullptr, *L = nullptr, *yv = nullptr, *c = nullptr, *work = nullptr, *bvec = nullptr, *cparts = nullptr;
     double* sq = nullptr;
     void* partials = nullptr;
-    uint64_t *kr_out = nullptr, *kr_in = nullptr;
+    uint64_t* kr_in = nullptr;
     uint64_t* cur[SCD_MAX_ORDER] = {nullptr};
     int* status = nullptr;
     std::vector<int32_t> it_host((size_t)wl, 0);
-    bool ok = alloc((void**)&uA, (size_t)max_dim * 8) && alloc((void**)&W, (size_t)max_w * 8) &&
+    bool ok = alloc((void**)&uA, (size_t)max_dim * 8) && alloc((void**)&W, (size_t)max_w * 8) && alloc((void**)&W2, (size_t)max_w * 8) &&
               alloc((void**)&e, (size_t)wl * 8) && alloc((void**)&D, (size_t)order * wl * 8) && alloc((void**)&g, (size_t)wl * 8) &&
               alloc((void**)&absp, (size_t)max_words * 8) && alloc((void**)&dotp, (size_t)max_words * 8) &&
               alloc((void**)&scal, 16) && alloc((void**)&L, (size_t)wl * wl * 8) && alloc((void**)&yv, (size_t)wl * 8) &&
               alloc((void**)&c, (size_t)wl * 8) && alloc((void**)&work, (size_t)wl * 8) && alloc((void**)&bvec, (size_t)wl * 8) &&
               alloc((void**)&cparts, (size_t)words_for(max_w) * 8) && alloc((void**)&sq, (size_t)nsq * 8) &&
-              alloc(&partials, (size_t)max_part * 8) && alloc((void**)&kr_out, (size_t)words_for(max_kron) * 8) &&
+              alloc(&partials, (size_t)max_part * 8) &&
               alloc((void**)&kr_in, (size_t)words_for(max_kron) * 8) && alloc((void**)&status, 4);
     for (int i = 0; ok && i < order; ++i) ok = alloc((void**)&cur[i], (size_t)nwords[i] * 8);
     if (ok && hipHostMalloc((void**)&host, 4 * sizeof(double), hipHostMallocDefault) != hipSuccess) {
@@ -1081,28 +1077,29 @@ int scd_lsq_decompose_tensor(const void* A, scd_dtype dt, int order, const int64
     LQ(hipStreamSynchronize(st));
 
     // u = a x_i (tensor product of the other modes' current sign vectors), the part of the mode sum that
-    // comes from the tensor itself: signed column sums over the leading modes, then signed row sums over
-    // the trailing ones.
+    // comes from the tensor itself.  The leading modes are contracted first, one at a time: W_1 = signed
+    // column sums of the tensor (n_0 rows) with s^(0), and W_i = signed column sums of W_{i-1} (n_{i-1} rows,
+    // tiny) with s^(i-1), valid because a sweep visits the modes in order; then a signed row sum over the
+    // trailing modes.  Only modes 0 and 1 pass over the tensor itself.
+    double* Wbuf[2] = {W, W2};
     auto tensor_part = [&](int i) -> hipError_t {
         hipError_t err = hipSuccess;
         const void* src = A;
         scd_dtype sdt = dt;
         const bool leading = i > 0, trailing = i < order - 1;  // modes before / after mode i (even of size 1: a sign)
         if (leading) {
-            const uint64_t* sigma = cur[0];
-            if (i > 1) {
-                err = launch_lsq_kron(cur, dims, 0, i, outer[i], kr_out, st);
-                if (err != hipSuccess) return err;
-                sigma = kr_out;
-            }
-            int rpw, grid;
-            halfstep_geometry(outer[i], &rpw, &grid);
+            const int64_t rows = dims[i - 1];
             const int64_t wcols = dims[i] * inner[i];
-            err = launch_halfstep(A, dt, outer[i], wcols, rpw, grid, 0, nullptr, sigma, partials, nullptr, st);
+            const void* from = i == 1 ? A : (const void*)Wbuf[(i - 1) & 1];
+            const scd_dtype fdt = i == 1 ? dt : SCD_F64;
+            double* to = trailing ? Wbuf[i & 1] : uA;
+            int rpw, grid;
+            halfstep_geometry(rows, &rpw, &grid);
+            err = launch_halfstep(from, fdt, rows, wcols, rpw, grid, 0, nullptr, cur[i - 1], partials, nullptr, st);
             if (err != hipSuccess) return err;
-            err = launch_reduce_plain(partials, dt, grid, wcols, trailing ? W : uA, nullptr, cparts, st);
+            err = launch_reduce_plain(partials, fdt, grid, wcols, to, nullptr, cparts, st);
             if (err != hipSuccess) return err;
-            src = W;
+            src = to;
             sdt = SCD_F64;
         }
         if (trailing) {
