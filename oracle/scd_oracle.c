@@ -14,6 +14,7 @@
  *   - Section 5.2, Algorithm 13 TENSOR GREEDY DECOMPOSITION-> scdo_tensor_decompose
  *   - Section 5.3, Algorithm 14 TENSOR LEAST SQUARES       -> scdo_tensor_lsq_coefficients,
  *                                                             scdo_tensor_lsq_decompose
+ *   - Section 5, "RGB scalars": sum_j s_j (x) t_j (x) c_j with real c_j -> scdo_scalars_decompose
  *   - Section 2.2 / 5.2 definition  a - r_w = sum_j c_j s_j -> scdo_expand
  *   - Section 6.1 (Question A) product of the decomposition with a vector, without expanding it
  *                                                          -> scdo_apply
@@ -33,6 +34,10 @@
  *     (seed, term, mode, word), see scdo_rng_word.
  *   - Bitsets are uint64 words, element 64p+q is bit q (LSB first) of word p, padding bits 0.
  *   - An iteration cap (max_iters) guards the unbounded loop of Algorithm 4 / 12.
+ *   - "RGB scalars" is named in Section 5 without an algorithm.  Reading: every term is found by the
+ *     axial greedy cut of Algorithm 12 on the whole tensor (all modes signs, as for "RGB signs"); the
+ *     last mode's sign vector and the scalar are then replaced by the real vector that is optimal for
+ *     the other modes' sign vectors, one least-squares coefficient per slice of the last mode.
  *
  * OpenMP pragmas only split loops whose iterations are independent (rows of R t, column
  * ranges of R^T s, rows of the update); the order of every floating point sum is the same
@@ -672,6 +677,70 @@ int scdo_tensor_lsq_decompose(const double* a, int order, const int64_t* dims, i
             const uint64_t* sj[SCDO_MAX_ORDER];
             for (int i = 0; i < order; ++i) sj[i] = signs_out[i] + j * words_for(dims[i]);
             scdo_tensor_update(r, order, dims, c[j], sj);
+        }
+        trace[k + 1] = sqrt(scdo_fro2(r, 1, N));
+    }
+    free(r);
+    return capped;
+}
+
+/* ---------------------------------------------------------------- real last mode ("RGB scalars", Section 5) */
+
+/*
+ * a - r_w = sum_j (s_j^(1) x ... x s_j^(k-1)) x c_j with c_j in R^{n_k}.  Term j: axial greedy cut of
+ * r_j (Algorithm 12, keyed random start as in Algorithm 13); P = n_1 ... n_{k-1};
+ *   c_j[ch] = < s^(1) x ... x s^(k-1), r_j[..., ch] > / P,      r_{j+1}[..., ch] = r_j[..., ch] - c_j[ch] (s^(1) x ...).
+ * signs_out: `order` bitset arrays as in scdo_tensor_decompose (the last mode's is the cut's sign vector,
+ * equal to sgn(c_j); it is not part of the decomposition).  cvec: w * n_k coefficients, term-major.
+ */
+int scdo_scalars_decompose(const double* a, int order, const int64_t* dims, int64_t w, uint64_t seed,
+                           int32_t max_iters, uint64_t* const* signs_out, double* cvec, double* trace,
+                           int32_t* iters, double* margins)
+{
+    int64_t N = total_size(order, dims);
+    int64_t q = dims[order - 1];
+    int64_t P = N / q;
+    size_t bytes = sizeof(double) * (size_t)N;
+    double* r = (double*)malloc(bytes ? bytes : 8);
+    uint64_t* cur[SCDO_MAX_ORDER];
+    int capped = 0;
+    memcpy(r, a, bytes);
+    trace[0] = sqrt(scdo_fro2(r, 1, N));
+    for (int64_t k = 0; k < w; ++k) {
+        double cu;
+        int32_t it;
+        for (int i = 0; i < order; ++i) {
+            cur[i] = signs_out[i] + k * words_for(dims[i]);
+            scdo_rng_signs(seed, (uint64_t)k, (uint32_t)i, dims[i], cur[i]);
+        }
+        capped += scdo_axial_greedy_cut(r, order, dims, cur, &cu, max_iters, &it, NULL,
+                                        margins ? margins + order * k : NULL);
+        if (iters) iters[k] = it;
+        for (int64_t ch = 0; ch < q; ++ch) {
+            int64_t idx[SCDO_MAX_ORDER] = {0};
+            double acc = 0.0;
+            for (int64_t p = 0; p < P; ++p) { /* p runs over the leading modes, last of them fastest */
+                double sg = 1.0;
+                for (int i = 0; i + 1 < order; ++i) sg *= sign_at(cur[i], idx[i]);
+                acc += sg * r[p * q + ch];
+                for (int i = order - 2; i >= 0; --i) {
+                    if (++idx[i] < dims[i]) break;
+                    idx[i] = 0;
+                }
+            }
+            cvec[k * q + ch] = acc / (double)P;
+        }
+        {
+            int64_t idx[SCDO_MAX_ORDER] = {0};
+            for (int64_t p = 0; p < P; ++p) {
+                double sg = 1.0;
+                for (int i = 0; i + 1 < order; ++i) sg *= sign_at(cur[i], idx[i]);
+                for (int64_t ch = 0; ch < q; ++ch) r[p * q + ch] -= cvec[k * q + ch] * sg;
+                for (int i = order - 2; i >= 0; --i) {
+                    if (++idx[i] < dims[i]) break;
+                    idx[i] = 0;
+                }
+            }
         }
         trace[k + 1] = sqrt(scdo_fro2(r, 1, N));
     }

@@ -81,6 +81,9 @@ def _load():
     L.scdo_tensor_lsq_decompose.argtypes = [_f64p, C.c_int, _i64p, C.c_int64, C.c_uint64, C.c_int32, C.POINTER(vp), _f64p,
                                             _f64p, C.c_void_p, C.c_void_p]
     L.scdo_tensor_lsq_decompose.restype = C.c_int
+    L.scdo_scalars_decompose.argtypes = [_f64p, C.c_int, _i64p, C.c_int64, C.c_uint64, C.c_int32, C.POINTER(vp), _f64p, _f64p,
+                                         C.c_void_p, C.c_void_p]
+    L.scdo_scalars_decompose.restype = C.c_int
     L.scdo_apply.argtypes = [C.c_int64, C.c_int64, C.c_int64, _u64p, _u64p, _f64p, C.c_int, _f64p, _f64p]
     L.scdo_bruteforce_signed_cut_norm.argtypes = [_f64p, C.c_int64, C.c_int64, C.POINTER(C.c_uint64)]
     L.scdo_bruteforce_signed_cut_norm.restype = C.c_double
@@ -322,6 +325,21 @@ def tensor_lsq_decompose(a, w: int, seed: int, max_iters: int = DEFAULT_MAX_ITER
                                                iters.ctypes.data, margins.ctypes.data)
     if capped < 0:
         raise np.linalg.LinAlgError("normal equations singular")
+    return dict(signs=sg, c=c, trace=trace, iters=iters, margins=margins, capped=int(capped))
+
+
+def scalars_decompose(a, w: int, seed: int, max_iters: int = DEFAULT_MAX_ITERS):
+    """"RGB scalars" (Section 5): sign vectors for all modes but the last, a real vector over the last mode per
+    term.  Returns dict(signs (all modes, the last one being the cut's), c (w, n_last), trace, iters, margins)."""
+    a = _f64(a)
+    dims = np.asarray(a.shape, dtype=np.int64)
+    sg = [np.zeros((w, words(d)), dtype=np.uint64) for d in a.shape]
+    c = np.zeros((w, a.shape[-1]), dtype=np.float64)
+    trace = np.zeros(w + 1, dtype=np.float64)
+    iters = np.zeros(w, dtype=np.int32)
+    margins = np.zeros((w, a.ndim), dtype=np.float64)
+    capped = _load().scdo_scalars_decompose(a.reshape(-1), a.ndim, dims, w, seed, max_iters, _ptrs(sg), c.reshape(-1), trace,
+                                            iters.ctypes.data, margins.ctypes.data)
     return dict(signs=sg, c=c, trace=trace, iters=iters, margins=margins, capped=int(capped))
 
 

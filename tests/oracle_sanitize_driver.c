@@ -13,6 +13,8 @@ int scdo_tensor_decompose(const double*, int, const int64_t*, int64_t, uint64_t,
                           int32_t*, double*, double*);
 int scdo_tensor_lsq_decompose(const double*, int, const int64_t*, int64_t, uint64_t, int32_t, uint64_t* const*, double*,
                               double*, int32_t*, double*);
+int scdo_scalars_decompose(const double*, int, const int64_t*, int64_t, uint64_t, int32_t, uint64_t* const*, double*, double*,
+                           int32_t*, double*);
 void scdo_expand(int, const int64_t*, int64_t, const uint64_t* const*, const double*, double*);
 void scdo_apply(int64_t, int64_t, int64_t, const uint64_t*, const uint64_t*, const double*, int, const double*, double*);
 double scdo_bruteforce_signed_cut_norm(const double*, int64_t, int64_t, uint64_t*);
@@ -67,6 +69,9 @@ int main(void)
         scdo_expand(3, dims, 4, sg, c, r);
         if (!(trace[4] <= trace[0])) return 5;
         if (scdo_tensor_lsq_decompose(a, 3, dims, 4, 9, 64, so, c, trace, iters, margins) < 0) return 6;
+        double cv[4 * 3];
+        scdo_scalars_decompose(a, 3, dims, 4, 9, 64, so, cv, trace, iters, margins);
+        if (!(trace[4] <= trace[0])) return 7;
     }
     return 0;
 }

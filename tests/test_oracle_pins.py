@@ -342,6 +342,62 @@ def test_order2_tensor_lsq_is_the_matrix_lsq(oracle):
     np.testing.assert_allclose(oracle.tensor_lsq_coefficients(A, [S, T]), oracle.lsq_coefficients(A, S, T), rtol=1e-12)
 
 
+# ------------------------------------------------------------------ real last mode ("RGB scalars", Section 5)
+
+
+def lead_product(signs, j, shape):
+    """Dense tensor product of term j's sign vectors over all modes but the last."""
+    t = np.ones(())
+    for i, d in enumerate(shape[:-1]):
+        t = np.multiply.outer(t, dense(signs[i][j], d))
+    return t
+
+
+@pytest.mark.parametrize("shape,w,seed", [((12, 20, 3), 8, 1), ((5, 70, 4, 3), 6, 2), ((66, 9, 1), 7, 3)])
+def test_scalars_decomposition_invariants(oracle, shape, w, seed):
+    a = np.random.default_rng(80 + seed).standard_normal(shape)
+    res = oracle.scalars_decompose(a, w, seed)
+    P = int(np.prod(shape[:-1]))
+    r = a.copy()
+    for k in range(w):
+        # the sign vectors are the axial greedy cut (Algorithm 12) of the current remainder from the keyed start
+        start = [oracle.rng_signs(seed, k, i, d) for i, d in enumerate(shape)]
+        cut = oracle.axial_greedy_cut(r, start)
+        for i in range(len(shape)):
+            assert np.array_equal(cut["signs"][i], res["signs"][i][k])
+        lead = lead_product(res["signs"], k, shape)
+        ck = np.tensordot(lead, r, axes=len(shape) - 1) / P          # per-slice least squares coefficient
+        np.testing.assert_allclose(res["c"][k], ck, rtol=1e-10, atol=1e-14)
+        assert np.array_equal(np.sign(ck) < 0, dense(res["signs"][-1][k], shape[-1]) < 0)   # the cut's last vector is sgn(c)
+        before = np.linalg.norm(r)
+        r = r - np.multiply.outer(lead, ck)
+        assert np.abs(np.tensordot(lead, r, axes=len(shape) - 1)).max() <= 1e-9 * np.abs(a).sum()   # every slice orthogonal
+        assert res["trace"][k + 1] == pytest.approx(np.linalg.norm(r), rel=1e-12)
+        assert res["trace"][k + 1] ** 2 == pytest.approx(before ** 2 - P * float(ck @ ck), rel=1e-9)
+        # never worse than the all-signs step (Algorithm 13) from the same remainder: c k is one admissible real vector
+        signs_step = before ** 2 - cut["c"] ** 2 / a.size
+        assert res["trace"][k + 1] ** 2 <= signs_step * (1 + 1e-12)
+    # the definition: a - r_w = sum_j (s_j x t_j x ...) x c_j
+    total = sum(np.multiply.outer(lead_product(res["signs"], j, shape), res["c"][j]) for j in range(w))
+    np.testing.assert_allclose(a - total, r, rtol=0, atol=1e-12 * np.abs(a).sum())
+
+
+def test_scalars_with_one_slice_is_the_matrix_decomposition(oracle):
+    # last mode of size 1: the real "vector" is the scalar c, and Algorithm 12 on m x n x 1 is Algorithm 4 on m x n
+    A = rng_matrix(30, 41, 90)
+    res = oracle.scalars_decompose(A[:, :, None], 6, 4)
+    # (the matrix draws t_0 as mode 1 of the random stream, and so does the tensor; the tensor also draws a random
+    # sign for its one-entry third vector, which flips s and the coefficient together: compare the products)
+    mat = oracle.decompose(A, 6, 4)
+    k3 = 1.0 - 2.0 * (res["signs"][2][:, 0] & np.uint64(1)).astype(np.float64)
+    for j in range(6):
+        assert np.array_equal(dense(res["signs"][0][j], 30) * k3[j], dense(mat["S"][j], 30))
+        assert np.array_equal(res["signs"][1][j], mat["T"][j])
+    np.testing.assert_allclose(res["c"][:, 0] * k3, mat["c"], rtol=1e-12)
+    np.testing.assert_allclose(res["trace"], mat["trace"], rtol=1e-12)
+    assert np.array_equal(res["iters"], mat["iters"])
+
+
 # ------------------------------------------------------------------ product with a vector (Section 6.1)
 
 
