@@ -155,6 +155,22 @@ int scd_lsq_decompose_tensor(const void* A, scd_dtype dt, int order, const int64
                              int32_t max_iters, void* stream, uint64_t* const* signs, void* c, double* fro_trace,
                              int32_t* iters);
 
+/* ---- real last mode ("RGB scalars", Section 5) ----------------------------------------------------
+ * a - r_w = sum_j (s_j^(1) x ... x s_j^(k-1)) x c_j with sign vectors for every mode but the last and a real
+ * vector c_j over the last mode (the three colour channels of the paper's image).  The paper names the variant
+ * without an algorithm; this entry point takes each term from the axial greedy cut of Algorithm 12 on the
+ * whole remainder (keyed random start as in Algorithm 13) and then replaces the last mode's sign vector and
+ * the scalar by the real vector that is optimal for the other modes' sign vectors:
+ *     c_j[ch] = < s^(1) x ... x s^(k-1), r_j[..., ch] > / (n_1 ... n_{k-1}),   r_{j+1} = r_j - (s^(1) x ...) x c_j.
+ * A: device, order >= 2, row-major, last mode fastest, not modified.  signs: host array of order - 1 device
+ * pointers (modes 1..k-1), term-major bitsets as in scd_decompose.  c: device out, w * dims[order-1] values of
+ * dt, term-major.  fro_trace: device out, w + 1 doubles.  iters: device out, optional (sweeps per term).
+ * The remainder is kept in dt; allocates its work space and frees it before returning; synchronous on stream.
+ * Returns SCD_OK, SCD_WMAXITER, or SCD_EINVAL / SCD_ENOMEM / SCD_EHIP / SCD_ENONFINITE. */
+int scd_decompose_scalars(const void* A, scd_dtype dt, int order, const int64_t* dims, int64_t w, uint64_t seed,
+                          int32_t max_iters, void* stream, uint64_t* const* signs, void* c, double* fro_trace,
+                          int32_t* iters);
+
 /* Product of a matrix decomposition with a vector, straight from the packed factors, without expanding
  * the matrix (Section 6.1, Question A):
  *   transpose == 0:  y = (sum_{j<w} c_j s_j t_j^T) x      x: n entries, y: m entries

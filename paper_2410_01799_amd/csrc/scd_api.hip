@@ -976,46 +976,29 @@ int scd_expand(const uint64_t* const* signs, const void* cvec, scd_dtype dt, int
     return SCD_OK;
 }
 
-// ---------------------------------------------------------------------------------------------- Algorithms 6 and 14
+// ---------------------------------------------------------------------------------------------- mode sums on caller data
 
-int scd_lsq_decompose_tensor(const void* A, scd_dtype dt, int order, const int64_t* dims, int64_t w, uint64_t seed,
-                             int32_t max_iters, void* stream, uint64_t* const* signs, void* cvec, double* fro_trace,
-                             int32_t* iters)
-{
-    int64_t total = 0;
-    if (!A || !dtype_ok(dt) || w < 0 || w > SCD_LSQ_MAX_WIDTH || max_iters < 1 || !fro_trace) return SCD_EINVAL;
-    SCD_TRY(check_dims(order, dims, &total));
-    if (w > 0 && (!signs || !cvec)) return SCD_EINVAL;
-    for (int i = 0; i < order; ++i) {
-        if (w > 0 && !signs[i]) return SCD_EINVAL;
-        if (dims[i] > (1ll << 31)) return SCD_EINVAL;
-    }
-    hipStream_t st = (hipStream_t)stream;
-    const int64_t wl = w > 0 ? w : 1;
-    const int nsq = 256;
-    // mode i sees the tensor as (leading modes) x n_i x inner_i, last mode fastest
-    int64_t inner[SCD_MAX_ORDER], nwords[SCD_MAX_ORDER];
-    int64_t max_dim = 1, max_w = 1, max_kron = 1, max_part = 1, max_words = 1;
-    for (int i = 0; i < order; ++i) {
-        inner[i] = 1;
-        for (int q = i + 1; q < order; ++q) inner[i] *= dims[q];
-        nwords[i] = words_for(dims[i]);
-        if (dims[i] > max_dim) max_dim = dims[i];
-        if (nwords[i] > max_words) max_words = nwords[i];
-        if (i > 0) {
-            const int64_t wcols = dims[i] * inner[i];
-            if (wcols > max_w) max_w = wcols;
-            int rpw, grid;
-            halfstep_geometry(dims[i - 1], &rpw, &grid);
-            if ((int64_t)grid * wcols > max_part) max_part = (int64_t)grid * wcols;
-        }
-        if (inner[i] > max_kron) max_kron = inner[i];
-    }
+namespace {
 
+// One mode step of Algorithm 12 on a tensor given as plain data (the half-step kernels, no context):
+// u = x x_i (tensor product of the other modes' current sign vectors).  Mode i sees the tensor as
+// (leading modes) x n_i x inner_i, last mode fastest.  The leading modes are contracted one at a time:
+// W_1 = signed column sums of the tensor (n_0 rows) with s^(0), W_i = signed column sums of W_{i-1}
+// (n_{i-1} rows, small) with s^(i-1) -- valid because a sweep visits the modes in order -- then a signed
+// row sum over the trailing modes (sign vector = Kronecker product of their bitsets).  Only modes 0 and 1
+// pass over the tensor itself.
+struct ModeSums {
+    int order = 0;
+    int64_t dims[SCD_MAX_ORDER] = {0}, inner[SCD_MAX_ORDER] = {0}, nwords[SCD_MAX_ORDER] = {0};
+    int64_t max_dim = 1, max_words = 1;
+    double *uA = nullptr, *W[2] = {nullptr, nullptr}, *cparts = nullptr;
+    void* partials = nullptr;
+    uint64_t* kr_in = nullptr;
+    uint64_t* cur[SCD_MAX_ORDER] = {nullptr};  // current sign vector of every mode
     std::vector<void*> bufs;
-    double* host = nullptr;  // pinned: [0] cut value, [1] b of the current term, [2] upload slot, [3] status
-    int rc = SCD_OK;
-    auto alloc = [&](void** p, size_t bytes) {
+
+    bool alloc(void** p, size_t bytes)
+    {
         if (hipMalloc(p, bytes ? bytes : 8) != hipSuccess) {
             (void)hipGetLastError();
             *p = nullptr;
@@ -1023,24 +1006,115 @@ int scd_lsq_decompose_tensor(const void* A, scd_dtype dt, int order, const int64
         }
         bufs.push_back(*p);
         return true;
-    };
-    double *uA = nullptr, *W = nullptr, *W2 = nullptr, *e = nullptr, *D = nullptr, *g = nullptr, *absp = nullptr, *dotp = nullptr;
-    double *scal = nullptr, *L = nullptr, *yv = nullptr, *c = nullptr, *work = nullptr, *bvec = nullptr, *cparts = nullptr;
-    double* sq = nullptr;
-    void* partials = nullptr;
-    uint64_t* kr_in = nullptr;
-    uint64_t* cur[SCD_MAX_ORDER] = {nullptr};
+    }
+    bool init(int ord, const int64_t* d)
+    {
+        order = ord;
+        int64_t max_w = 1, max_kron = 1, max_part = 1;
+        for (int i = 0; i < order; ++i) {
+            dims[i] = d[i];
+            inner[i] = 1;
+            for (int q = i + 1; q < order; ++q) inner[i] *= d[q];
+            nwords[i] = words_for(d[i]);
+            if (d[i] > max_dim) max_dim = d[i];
+            if (nwords[i] > max_words) max_words = nwords[i];
+            if (i > 0) {
+                const int64_t wcols = d[i] * inner[i];
+                if (wcols > max_w) max_w = wcols;
+                int rpw, grid;
+                halfstep_geometry(d[i - 1], &rpw, &grid);
+                if ((int64_t)grid * wcols > max_part) max_part = (int64_t)grid * wcols;
+            }
+            if (inner[i] > max_kron) max_kron = inner[i];
+        }
+        bool ok = alloc((void**)&uA, (size_t)max_dim * 8) && alloc((void**)&W[0], (size_t)max_w * 8) &&
+                  alloc((void**)&W[1], (size_t)max_w * 8) && alloc((void**)&cparts, (size_t)words_for(max_w) * 8) &&
+                  alloc(&partials, (size_t)max_part * 8) && alloc((void**)&kr_in, (size_t)words_for(max_kron) * 8);
+        for (int i = 0; ok && i < order; ++i) ok = alloc((void**)&cur[i], (size_t)nwords[i] * 8);
+        return ok;
+    }
+    void release()
+    {
+        for (void* p : bufs) (void)hipFree(p);
+        bufs.clear();
+    }
+    // uA <- x x_i (others), x of dtype dt
+    hipError_t part(const void* x, scd_dtype dt, int i, hipStream_t st)
+    {
+        hipError_t err = hipSuccess;
+        const void* src = x;
+        scd_dtype sdt = dt;
+        const bool leading = i > 0, trailing = i < order - 1;  // modes before / after mode i (even of size 1: a sign)
+        if (leading) {
+            const int64_t rows = dims[i - 1];
+            const int64_t wcols = dims[i] * inner[i];
+            const void* from = i == 1 ? x : (const void*)W[(i - 1) & 1];
+            const scd_dtype fdt = i == 1 ? dt : SCD_F64;
+            double* to = trailing ? W[i & 1] : uA;
+            int rpw, grid;
+            halfstep_geometry(rows, &rpw, &grid);
+            err = launch_halfstep(from, fdt, rows, wcols, rpw, grid, 0, nullptr, cur[i - 1], partials, nullptr, st);
+            if (err != hipSuccess) return err;
+            err = launch_reduce_plain(partials, fdt, grid, wcols, to, nullptr, cparts, st);
+            if (err != hipSuccess) return err;
+            src = to;
+            sdt = SCD_F64;
+        }
+        if (trailing) {
+            const uint64_t* tau = cur[order - 1];
+            if (i < order - 2) {
+                err = launch_lsq_kron(cur, dims, i + 1, order, inner[i], kr_in, st);
+                if (err != hipSuccess) return err;
+                tau = kr_in;
+            }
+            int rpw, grid;
+            halfstep_geometry(dims[i], &rpw, &grid);
+            err = launch_halfstep(src, sdt, dims[i], inner[i], rpw, grid, 1, tau, nullptr, nullptr, uA, st);
+        }
+        return err;
+    }
+};
+
+int check_tensor_args(const void* A, scd_dtype dt, int order, const int64_t* dims, int64_t w, int32_t max_iters,
+                      const double* fro_trace, int64_t* total)
+{
+    if (!A || !dtype_ok(dt) || w < 0 || max_iters < 1 || !fro_trace) return SCD_EINVAL;
+    SCD_TRY(check_dims(order, dims, total));
+    for (int i = 0; i < order; ++i)
+        if (dims[i] > (1ll << 31)) return SCD_EINVAL;
+    return SCD_OK;
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------------------------- Algorithms 6 and 14
+
+int scd_lsq_decompose_tensor(const void* A, scd_dtype dt, int order, const int64_t* dims, int64_t w, uint64_t seed,
+                             int32_t max_iters, void* stream, uint64_t* const* signs, void* cvec, double* fro_trace,
+                             int32_t* iters)
+{
+    int64_t total = 0;
+    SCD_TRY(check_tensor_args(A, dt, order, dims, w, max_iters, fro_trace, &total));
+    if (w > SCD_LSQ_MAX_WIDTH || (w > 0 && (!signs || !cvec))) return SCD_EINVAL;
+    for (int i = 0; i < order; ++i)
+        if (w > 0 && !signs[i]) return SCD_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    const int64_t wl = w > 0 ? w : 1;
+    const int nsq = 256;
+    ModeSums ms;
+    double* host = nullptr;  // pinned: [0] cut value, [1] b of the current term, [2] upload slot, [3] status
+    int rc = SCD_OK;
+    double *e = nullptr, *D = nullptr, *g = nullptr, *absp = nullptr, *dotp = nullptr;
+    double *scal = nullptr, *L = nullptr, *yv = nullptr, *c = nullptr, *work = nullptr, *bvec = nullptr, *sq = nullptr;
     int* status = nullptr;
     std::vector<int32_t> it_host((size_t)wl, 0);
-    bool ok = alloc((void**)&uA, (size_t)max_dim * 8) && alloc((void**)&W, (size_t)max_w * 8) && alloc((void**)&W2, (size_t)max_w * 8) &&
-              alloc((void**)&e, (size_t)wl * 8) && alloc((void**)&D, (size_t)order * wl * 8) && alloc((void**)&g, (size_t)wl * 8) &&
-              alloc((void**)&absp, (size_t)max_words * 8) && alloc((void**)&dotp, (size_t)max_words * 8) &&
-              alloc((void**)&scal, 16) && alloc((void**)&L, (size_t)wl * wl * 8) && alloc((void**)&yv, (size_t)wl * 8) &&
-              alloc((void**)&c, (size_t)wl * 8) && alloc((void**)&work, (size_t)wl * 8) && alloc((void**)&bvec, (size_t)wl * 8) &&
-              alloc((void**)&cparts, (size_t)words_for(max_w) * 8) && alloc((void**)&sq, (size_t)nsq * 8) &&
-              alloc(&partials, (size_t)max_part * 8) &&
-              alloc((void**)&kr_in, (size_t)words_for(max_kron) * 8) && alloc((void**)&status, 4);
-    for (int i = 0; ok && i < order; ++i) ok = alloc((void**)&cur[i], (size_t)nwords[i] * 8);
+    bool ok = ms.init(order, dims);
+    ok = ok && ms.alloc((void**)&e, (size_t)wl * 8) && ms.alloc((void**)&D, (size_t)order * wl * 8) &&
+         ms.alloc((void**)&g, (size_t)wl * 8) && ms.alloc((void**)&absp, (size_t)ms.max_words * 8) &&
+         ms.alloc((void**)&dotp, (size_t)ms.max_words * 8) && ms.alloc((void**)&scal, 16) &&
+         ms.alloc((void**)&L, (size_t)wl * wl * 8) && ms.alloc((void**)&yv, (size_t)wl * 8) && ms.alloc((void**)&c, (size_t)wl * 8) &&
+         ms.alloc((void**)&work, (size_t)wl * 8) && ms.alloc((void**)&bvec, (size_t)wl * 8) &&
+         ms.alloc((void**)&sq, (size_t)nsq * 8) && ms.alloc((void**)&status, 4);
     if (ok && hipHostMalloc((void**)&host, 4 * sizeof(double), hipHostMallocDefault) != hipSuccess) {
         (void)hipGetLastError();
         host = nullptr;
@@ -1048,7 +1122,7 @@ int scd_lsq_decompose_tensor(const void* A, scd_dtype dt, int order, const int64
     }
     auto cleanup = [&](int code) {
         (void)hipStreamSynchronize(st);
-        for (void* p : bufs) (void)hipFree(p);
+        ms.release();
         if (host) (void)hipHostFree(host);
         (void)hipGetLastError();
         return code;
@@ -1076,66 +1150,26 @@ int scd_lsq_decompose_tensor(const void* A, scd_dtype dt, int order, const int64
     LQ(hipMemcpyAsync(fro_trace, host + 2, 8, hipMemcpyHostToDevice, st));
     LQ(hipStreamSynchronize(st));
 
-    // u = a x_i (tensor product of the other modes' current sign vectors), the part of the mode sum that
-    // comes from the tensor itself.  The leading modes are contracted first, one at a time: W_1 = signed
-    // column sums of the tensor (n_0 rows) with s^(0), and W_i = signed column sums of W_{i-1} (n_{i-1} rows,
-    // tiny) with s^(i-1), valid because a sweep visits the modes in order; then a signed row sum over the
-    // trailing modes.  Only modes 0 and 1 pass over the tensor itself.
-    double* Wbuf[2] = {W, W2};
-    auto tensor_part = [&](int i) -> hipError_t {
-        hipError_t err = hipSuccess;
-        const void* src = A;
-        scd_dtype sdt = dt;
-        const bool leading = i > 0, trailing = i < order - 1;  // modes before / after mode i (even of size 1: a sign)
-        if (leading) {
-            const int64_t rows = dims[i - 1];
-            const int64_t wcols = dims[i] * inner[i];
-            const void* from = i == 1 ? A : (const void*)Wbuf[(i - 1) & 1];
-            const scd_dtype fdt = i == 1 ? dt : SCD_F64;
-            double* to = trailing ? Wbuf[i & 1] : uA;
-            int rpw, grid;
-            halfstep_geometry(rows, &rpw, &grid);
-            err = launch_halfstep(from, fdt, rows, wcols, rpw, grid, 0, nullptr, cur[i - 1], partials, nullptr, st);
-            if (err != hipSuccess) return err;
-            err = launch_reduce_plain(partials, fdt, grid, wcols, to, nullptr, cparts, st);
-            if (err != hipSuccess) return err;
-            src = to;
-            sdt = SCD_F64;
-        }
-        if (trailing) {
-            const uint64_t* tau = cur[order - 1];
-            if (i < order - 2) {
-                err = launch_lsq_kron(cur, dims, i + 1, order, inner[i], kr_in, st);
-                if (err != hipSuccess) return err;
-                tau = kr_in;
-            }
-            int rpw, grid;
-            halfstep_geometry(dims[i], &rpw, &grid);
-            err = launch_halfstep(src, sdt, dims[i], inner[i], rpw, grid, 1, tau, nullptr, nullptr, uA, st);
-        }
-        return err;
-    };
-
     for (int64_t k = 0; k < w; ++k) {
         // Algorithm 12 on the implicit remainder a - S_k c_k, from the keyed random start of term k
         for (int i = 1; i < order; ++i) {
-            LQ(launch_rng(seed, (uint64_t)k, (uint32_t)i, dims[i], cur[i], st));
-            LQ(launch_lsq_dots(signs[i], k, nwords[i], dims[i], cur[i], nullptr, D + (int64_t)i * wl, st));
+            LQ(launch_rng(seed, (uint64_t)k, (uint32_t)i, dims[i], ms.cur[i], st));
+            LQ(launch_lsq_dots(signs[i], k, ms.nwords[i], dims[i], ms.cur[i], nullptr, D + (int64_t)i * wl, st));
         }
         double c_prev = -INFINITY, bnew = 0.0;
         int32_t j = 0;
         for (;;) {
             for (int i = 0; i < order; ++i) {
                 // s^(i) = sgn(a x_i (others) - sum_j c_j (prod_{m != i} <s_j^(m), s^(m)>) s_j^(i))
-                LQ(tensor_part(i));
+                LQ(ms.part(A, dt, i, st));
                 LQ(launch_lsq_prod(D, wl, order, i, k, c, e, st));
                 const bool last = i == order - 1;
-                LQ(launch_lsq_correct(signs[i], k, nwords[i], dims[i], e, uA, cur[i], last ? absp : nullptr,
+                LQ(launch_lsq_correct(signs[i], k, ms.nwords[i], dims[i], e, ms.uA, ms.cur[i], last ? absp : nullptr,
                                       last ? dotp : nullptr, st));
-                LQ(launch_lsq_dots(signs[i], k, nwords[i], dims[i], cur[i], nullptr, D + (int64_t)i * wl, st));
+                LQ(launch_lsq_dots(signs[i], k, ms.nwords[i], dims[i], ms.cur[i], nullptr, D + (int64_t)i * wl, st));
             }
             // after the last mode: the cut value sum |.| and <S_new, a> (Algorithm 12 line 10)
-            LQ(launch_lsq_sum2(absp, dotp, nwords[order - 1], scal, st));
+            LQ(launch_lsq_sum2(absp, dotp, ms.nwords[order - 1], scal, st));
             LQ(hipMemcpyAsync(host, scal, 16, hipMemcpyDeviceToHost, st));
             LQ(hipStreamSynchronize(st));
             ++j;
@@ -1151,7 +1185,7 @@ int scd_lsq_decompose_tensor(const void* A, scd_dtype dt, int order, const int64
         it_host[(size_t)k] = j;
         // append and refit every coefficient
         for (int i = 0; i < order; ++i)
-            LQ(hipMemcpyAsync(signs[i] + k * nwords[i], cur[i], (size_t)nwords[i] * 8, hipMemcpyDeviceToDevice, st));
+            LQ(hipMemcpyAsync(signs[i] + k * ms.nwords[i], ms.cur[i], (size_t)ms.nwords[i] * 8, hipMemcpyDeviceToDevice, st));
         host[2] = bnew;
         LQ(hipMemcpyAsync(bvec + k, host + 2, 8, hipMemcpyHostToDevice, st));
         LQ(launch_lsq_prod(D, wl, order, -1, k, nullptr, g, st));  // Gram row: product of the per-mode inner products
@@ -1161,6 +1195,104 @@ int scd_lsq_decompose_tensor(const void* A, scd_dtype dt, int order, const int64
         if (*(const int*)(host + 3) != 0) return cleanup(SCD_ESINGULAR);
     }
     LQ(launch_lsq_cast(c, w, dt, cvec, st));
+    if (iters && w > 0) LQ(hipMemcpyAsync(iters, it_host.data(), (size_t)w * 4, hipMemcpyHostToDevice, st));
+    LQ(hipStreamSynchronize(st));
+    return cleanup(rc);
+}
+
+// ---------------------------------------------------------------------------------------------- real last mode
+
+int scd_decompose_scalars(const void* A, scd_dtype dt, int order, const int64_t* dims, int64_t w, uint64_t seed,
+                          int32_t max_iters, void* stream, uint64_t* const* signs, void* cvec, double* fro_trace,
+                          int32_t* iters)
+{
+    int64_t total = 0;
+    SCD_TRY(check_tensor_args(A, dt, order, dims, w, max_iters, fro_trace, &total));
+    if (w > 0 && (!signs || !cvec)) return SCD_EINVAL;
+    for (int i = 0; i + 1 < order; ++i)
+        if (w > 0 && !signs[i]) return SCD_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    const size_t es = dt == SCD_F32 ? 4 : 8;
+    const int64_t q = dims[order - 1], P = total / q;
+    const int nsq = 256;
+    ModeSums ms;
+    double* host = nullptr;  // pinned: [0], [1] sums read back, [2] upload slot
+    int rc = SCD_OK;
+    void* R = nullptr;
+    double *absp = nullptr, *dotp = nullptr, *scal = nullptr, *sq = nullptr;
+    uint64_t* lead = nullptr;
+    std::vector<int32_t> it_host((size_t)(w > 0 ? w : 1), 0);
+    bool ok = ms.init(order, dims);
+    ok = ok && ms.alloc(&R, (size_t)total * es) && ms.alloc((void**)&absp, (size_t)ms.max_words * 8) &&
+         ms.alloc((void**)&dotp, (size_t)ms.max_words * 8) && ms.alloc((void**)&scal, 16) &&
+         ms.alloc((void**)&sq, (size_t)nsq * 8) && ms.alloc((void**)&lead, (size_t)words_for(P) * 8);
+    if (ok && hipHostMalloc((void**)&host, 4 * sizeof(double), hipHostMallocDefault) != hipSuccess) {
+        (void)hipGetLastError();
+        host = nullptr;
+        ok = false;
+    }
+    auto cleanup = [&](int code) {
+        (void)hipStreamSynchronize(st);
+        ms.release();
+        if (host) (void)hipHostFree(host);
+        (void)hipGetLastError();
+        return code;
+    };
+    if (!ok) return cleanup(SCD_ENOMEM);
+    LQ(hipMemcpyAsync(R, A, (size_t)total * es, hipMemcpyDeviceToDevice, st));
+    LQ(launch_lsq_sumsq(R, dt, total, sq, nsq, st));
+    LQ(launch_lsq_sum2(sq, nullptr, nsq, scal, st));
+    LQ(hipMemcpyAsync(host, scal, 16, hipMemcpyDeviceToHost, st));
+    LQ(hipStreamSynchronize(st));
+    if (!isfinite(host[0])) return cleanup(SCD_ENONFINITE);
+    host[2] = sqrt(host[0]);
+    LQ(hipMemcpyAsync(fro_trace, host + 2, 8, hipMemcpyHostToDevice, st));
+    LQ(hipStreamSynchronize(st));
+
+    for (int64_t k = 0; k < w; ++k) {
+        // Algorithm 12 on the remainder, all modes signs, from the keyed random start of term k
+        for (int i = 1; i < order; ++i) LQ(launch_rng(seed, (uint64_t)k, (uint32_t)i, dims[i], ms.cur[i], st));
+        double c_prev = -INFINITY;
+        int32_t j = 0;
+        for (;;) {
+            for (int i = 0; i < order; ++i) {
+                LQ(ms.part(R, dt, i, st));
+                const bool last = i == order - 1;
+                LQ(launch_lsq_correct(nullptr, 0, ms.nwords[i], dims[i], nullptr, ms.uA, ms.cur[i], last ? absp : nullptr,
+                                      last ? dotp : nullptr, st));
+            }
+            LQ(launch_lsq_sum2(absp, dotp, ms.nwords[order - 1], scal, st));
+            LQ(hipMemcpyAsync(host, scal, 16, hipMemcpyDeviceToHost, st));
+            LQ(hipStreamSynchronize(st));
+            ++j;
+            const double cut = host[0];
+            if (!isfinite(cut)) return cleanup(SCD_ENONFINITE);
+            if (cut <= c_prev || j >= max_iters) {
+                if (!(cut <= c_prev)) rc = SCD_WMAXITER;
+                break;
+            }
+            c_prev = cut;
+        }
+        it_host[(size_t)k] = j;
+        // ms.uA holds r x (leading modes' sign vectors), one value per slice of the last mode: the real
+        // coefficients are that over P; they are stored in dt and the stored values are what is subtracted
+        void* ck = (char*)cvec + (size_t)k * (size_t)q * es;
+        LQ(launch_scalars_coef(ms.uA, q, (double)P, dt, ck, st));
+        for (int i = 0; i + 1 < order; ++i)
+            LQ(hipMemcpyAsync(signs[i] + k * ms.nwords[i], ms.cur[i], (size_t)ms.nwords[i] * 8, hipMemcpyDeviceToDevice, st));
+        const uint64_t* lead_bits = ms.cur[0];
+        if (order > 2) {
+            LQ(launch_lsq_kron(ms.cur, dims, 0, order - 1, P, lead, st));
+            lead_bits = lead;
+        }
+        LQ(launch_scalars_update(R, dt, total, q, lead_bits, ck, sq, nsq, st));
+        LQ(launch_lsq_sum2(sq, nullptr, nsq, scal, st));
+        LQ(hipMemcpyAsync(host, scal, 16, hipMemcpyDeviceToHost, st));
+        LQ(hipStreamSynchronize(st));
+        host[2] = sqrt(host[0]);
+        LQ(hipMemcpyAsync(fro_trace + k + 1, host + 2, 8, hipMemcpyHostToDevice, st));
+        LQ(hipStreamSynchronize(st));
+    }
     if (iters && w > 0) LQ(hipMemcpyAsync(iters, it_host.data(), (size_t)w * 4, hipMemcpyHostToDevice, st));
     LQ(hipStreamSynchronize(st));
 #undef LQ

@@ -198,6 +198,9 @@ hipError_t launch_lsq_prod(const double* D, int64_t ld, int order, int skip, int
                            hipStream_t st);
 hipError_t launch_lsq_kron(const uint64_t* const* signs, const int64_t* dims, int first, int last, int64_t len, uint64_t* out,
                            hipStream_t st);
+hipError_t launch_scalars_coef(const double* u, int64_t q, double P, scd_dtype dt, void* c, hipStream_t st);
+hipError_t launch_scalars_update(void* r, scd_dtype dt, int64_t total, int64_t q, const uint64_t* lead, const void* c,
+                                 double* parts, int nparts, hipStream_t st);
 hipError_t launch_lsq_solve(double* L, int64_t ld, int64_t k, const double* g, double diag, const double* bvec, double* yv,
                             double* c, double* work, double fro0sq, double* trace_out, int* status, hipStream_t st);
 

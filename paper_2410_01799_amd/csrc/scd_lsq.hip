@@ -169,6 +169,39 @@ __global__ void __launch_bounds__(256) lsq_kron_kernel(LsqKronArgs a)
     if ((threadIdx.x & (kWave - 1)) == 0 && (q >> 6) < (a.len + 63) / 64) a.out[q >> 6] = word;
 }
 
+// Real last mode: c[ch] = u[ch] / P, rounded to the element type (the stored value is what gets subtracted).
+template <typename TE>
+__global__ void __launch_bounds__(256) scalars_coef_kernel(const double* __restrict__ u, int64_t q, double P, TE* __restrict__ c)
+{
+    const int64_t ch = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (ch < q) c[ch] = (TE)(u[ch] / P);
+}
+
+// r[p][ch] -= sign_p * c[ch] over the whole tensor (p = index over the leading modes, sign_p = bit p of
+// `lead`, a 1 bit standing for -1), and the sum of the squares of what is left, per workgroup.
+template <typename TE>
+__global__ void __launch_bounds__(256) scalars_update_kernel(TE* __restrict__ r, int64_t total, int64_t q,
+                                                            const uint64_t* __restrict__ lead, const TE* __restrict__ c,
+                                                            double* __restrict__ parts)
+{
+    __shared__ double red[256];
+    double s = 0.0;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+        const int64_t p = i / q, ch = i - p * q;
+        const TE d = ((lead[p >> 6] >> (p & 63)) & 1ull) ? -c[ch] : c[ch];
+        const TE v = r[i] - d;
+        r[i] = v;
+        s += (double)v * (double)v;
+    }
+    red[threadIdx.x] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double t = 0.0;
+        for (int z = 0; z < 256; ++z) t += red[z];
+        parts[blockIdx.x] = t;
+    }
+}
+
 constexpr int kLqThreads = 1024;
 
 // sum over the workgroup in a fixed order; every thread gets the same bits
@@ -285,6 +318,28 @@ hipError_t launch_lsq_kron(const uint64_t* const* signs, const int64_t* dims, in
     a.out = out;
     const int64_t padded = ((len + 63) / 64) * 64;
     hipLaunchKernelGGL(lsq_kron_kernel, dim3((unsigned)((padded + 255) / 256)), dim3(256), 0, st, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_scalars_coef(const double* u, int64_t q, double P, scd_dtype dt, void* c, hipStream_t st)
+{
+    const unsigned g = (unsigned)((q + 255) / 256);
+    if (dt == SCD_F32)
+        hipLaunchKernelGGL((scalars_coef_kernel<float>), dim3(g), dim3(256), 0, st, u, q, P, (float*)c);
+    else
+        hipLaunchKernelGGL((scalars_coef_kernel<double>), dim3(g), dim3(256), 0, st, u, q, P, (double*)c);
+    return hipGetLastError();
+}
+
+hipError_t launch_scalars_update(void* r, scd_dtype dt, int64_t total, int64_t q, const uint64_t* lead, const void* c,
+                                 double* parts, int nparts, hipStream_t st)
+{
+    if (dt == SCD_F32)
+        hipLaunchKernelGGL((scalars_update_kernel<float>), dim3(nparts), dim3(256), 0, st, (float*)r, total, q, lead,
+                           (const float*)c, parts);
+    else
+        hipLaunchKernelGGL((scalars_update_kernel<double>), dim3(nparts), dim3(256), 0, st, (double*)r, total, q, lead,
+                           (const double*)c, parts);
     return hipGetLastError();
 }
 

@@ -25,7 +25,7 @@ EXPORTS = [
     "scd_width", "scd_results", "scd_remainder", "scd_set_remainder", "scd_row_signed_sum", "scd_col_signed_sum",
     "scd_expand", "scd_pack", "scd_unpack", "scd_rng_signs", "scd_strerror", "scd_last_hip_error", "scd_traffic",
     "scd_probe_stream", "scd_profile_sweeps", "scd_probe_exchange", "scd_engine", "scd_set_workgroups",
-    "scd_apply", "scd_apply_workspace_bytes", "scd_lsq_decompose", "scd_lsq_decompose_tensor", "scd_sparse_flips",
+    "scd_apply", "scd_apply_workspace_bytes", "scd_lsq_decompose", "scd_lsq_decompose_tensor", "scd_decompose_scalars", "scd_sparse_flips",
 ]
 
 
@@ -58,6 +58,7 @@ def lib() -> C.CDLL:
         L.scd_sparse_flips.argtypes = [vp, pi64, pi64]
         L.scd_lsq_decompose.argtypes = [vp, C.c_int, i64, i64, i64, C.c_uint64, i32, vp, vp, vp, vp, vp, vp]
         L.scd_lsq_decompose_tensor.argtypes = [vp, C.c_int, C.c_int, pi64, i64, C.c_uint64, i32, vp, pvp, vp, vp, vp]
+        L.scd_decompose_scalars.argtypes = [vp, C.c_int, C.c_int, pi64, i64, C.c_uint64, i32, vp, pvp, vp, vp, vp]
         L.scd_apply_workspace_bytes.argtypes = [i64, i64, i64]
         L.scd_apply_workspace_bytes.restype = C.c_size_t
         L.scd_apply.argtypes = [vp, vp, vp, C.c_int, i64, i64, i64, C.c_int, vp, i64, vp, vp, C.c_size_t, vp]
@@ -187,6 +188,23 @@ def scd_lsq_decompose(A: torch.Tensor, w: int, seed: int, max_iters: int = 4096)
         st = lib().scd_lsq_decompose_tensor(_ptr(A), _dt(A), A.dim(), _dims(A.shape), w, int(seed), int(max_iters),
                                             _stream(), _ptr_array(signs), _ptr(c), _ptr(trace), _ptr(iters))
     st = _check(st, "scd_lsq_decompose")
+    return dict(signs=signs, c=c, trace=trace, iters=iters, status=st)
+
+
+def scd_decompose_scalars(A: torch.Tensor, w: int, seed: int, max_iters: int = 4096) -> dict:
+    """"RGB scalars" (Section 5): sign vectors for every mode but the last, a real vector over the last mode per
+    term.  Returns dict(signs=[bitsets of modes 1..k-1], c (w, n_last), trace, iters, status)."""
+    A = _dev(A, "A")
+    if A.dim() < 2:
+        raise ValueError("order >= 2")
+    w = int(w)
+    signs = [_bits(w * words(int(d)), A.device).reshape(w, words(int(d))) for d in A.shape[:-1]]
+    c = torch.empty((w, int(A.shape[-1])), dtype=A.dtype, device=A.device)
+    trace = torch.empty(w + 1, dtype=torch.float64, device=A.device)
+    iters = torch.empty(w, dtype=torch.int32, device=A.device)
+    st = lib().scd_decompose_scalars(_ptr(A), _dt(A), A.dim(), _dims(A.shape), w, int(seed), int(max_iters), _stream(),
+                                     _ptr_array(signs), _ptr(c), _ptr(trace), _ptr(iters))
+    st = _check(st, "scd_decompose_scalars")
     return dict(signs=signs, c=c, trace=trace, iters=iters, status=st)
 
 
