@@ -182,6 +182,51 @@ def lsq_mode(args, scd, workloads, torch, np) -> int:
     return 0
 
 
+def image_mode(args, scd, workloads, torch, np) -> int:
+    """Workload 4: the 4000x3000x3 image-like tensor.  "RGB signs" (Algorithms 12/13, w = 129), "RGB scalars"
+    (real last mode, w = 128) and, on a 1000x750x3 reduction, the least squares variant (Algorithm 14): seconds
+    and the error at the logged widths in both normalisations of Section 5."""
+    a_np, w_signs, seed = workloads.config4()
+    a = torch.from_numpy(a_np).cuda()
+    m, n, q = a_np.shape
+    norm_a = float(np.linalg.norm(a_np.astype(np.float64)))
+    norm_255 = 255.0 * (3.0 * m * n) ** 0.5
+
+    def timed(fn):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        r = fn()
+        torch.cuda.synchronize()
+        return r, time.perf_counter() - t0
+
+    def curve(res, widths):
+        tr = res["trace"].cpu().numpy()
+        return {str(k): {"rel": round(float(tr[k] / norm_a), 5), "per_255": round(float(tr[k] / norm_255), 5)} for k in widths}
+
+    rows = []
+    scd.scd_decompose(a, 2, seed)
+    res, dt = timed(lambda: scd.scd_decompose(a, w_signs, seed))
+    rows.append({"variant": "RGB signs (Alg 12/13)", "width": w_signs, "packed_bytes": w_signs * (m + n + q + 32) // 8,
+                 "seconds": round(dt, 3), "terms_per_s": round(w_signs / dt, 1),
+                 "sweeps_per_term": round(float(res["iters"].float().mean()), 1), "error": curve(res, (8, 16, 32, 64, 129))})
+    scd.scd_decompose_scalars(a, 2, seed)
+    res, dt = timed(lambda: scd.scd_decompose_scalars(a, 128, seed))
+    rows.append({"variant": "RGB scalars (real last mode)", "width": 128, "packed_bytes": 128 * (m + n + 96) // 8,
+                 "seconds": round(dt, 3), "terms_per_s": round(128 / dt, 1),
+                 "sweeps_per_term": round(float(res["iters"].float().mean()), 1), "error": curve(res, (8, 16, 32, 64, 128))})
+    small = torch.from_numpy(workloads.image_like_tensor(1000, 750, 3, blobs=100, seed=400)).cuda()
+    norm_s = float(small.double().norm())
+    scd.scd_lsq_decompose(small, 2, seed)
+    ls, dt = timed(lambda: scd.scd_lsq_decompose(small, 64, seed))
+    gr = scd.scd_decompose(small, 64, seed)
+    rows.append({"variant": "RGB signs + least squares (Alg 14) on 1000x750x3", "width": 64, "seconds": round(dt, 3),
+                 "terms_per_s": round(64 / dt, 1), "rel_error_least_squares": round(float(ls["trace"][64]) / norm_s, 5),
+                 "rel_error_greedy": round(float(gr["trace"][64]) / norm_s, 5)})
+    print(json.dumps({"metric": "image-like tensor 4000x3000x3 f32 (workload 4)", "n_gpus": 1, "dtype": "f32", "data": "synthetic",
+                      "runs": rows}))
+    return 0
+
+
 def oracle_mode(args, workloads, np) -> int:
     """The CPU oracle (plain f64, as it stands) timed on fixed prefixes of the workloads, with one thread and
     with all host cores: terms/s to quote beside the GPU figures.  No GPU work."""
@@ -231,6 +276,9 @@ def main() -> int:
     ap.add_argument("--apply", action="store_true",
                     help="instead of the headline: time the product of a decomposition with a vector from the "
                          "packed factors (scd_apply) on the layer shapes")
+    ap.add_argument("--image", action="store_true",
+                    help="instead of the headline: workload 4 (4000x3000x3 image-like tensor): RGB signs, RGB scalars, "
+                         "least squares")
     ap.add_argument("--lsq", action="store_true",
                     help="instead of the headline: time the least squares decomposition (Algorithm 6)")
     ap.add_argument("--oracle-timing", action="store_true",
@@ -272,6 +320,8 @@ def main() -> int:
         return apply_mode(args, scd, torch)
     if args.lsq:
         return lsq_mode(args, scd, workloads, torch, np)
+    if args.image:
+        return image_mode(args, scd, workloads, torch, np)
     m = n = args.size
     w, seed = args.width, 2
     A64 = workloads.gaussian_matrix(m, n, seed, np.float64)
