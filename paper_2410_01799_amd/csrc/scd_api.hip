@@ -411,6 +411,15 @@ int run_sparse(scd_ctx* c, int64_t n)
     a.rs = c->rs;
     a.cs = c->cs;
     a.grid = c->sp_grid;
+    // Delayed updates (Section 3.2) trade the writes of the dense start of a term for a correction on every
+    // half step.  Measured: that pays from about 400 MiB on when the context has the device to itself (32000x4096:
+    // +13 %; 224 MiB: even; 64 MiB: -15 %), and from 128 MiB on when it shares the device and with it the
+    // bandwidth (224 MiB on 64 compute units beside three others: +15 %).  SCD_SPARSE_DELAY = 0 / 1 overrides.
+    {
+        const double mib = (double)c->total * (double)c->esize / (1024.0 * 1024.0);
+        const int dflt = mib >= (c->share > 0 ? 128.0 : 384.0) ? 1 : 0;
+        a.delay_width = env_int("SCD_SPARSE_DELAY", dflt) != 0 ? sparse_delay_width(c->dims[0], c->dims[1]) : 0;
+    }
     a.profile = env_int("SCD_RESIDENT_VERBOSE", 0);
     a.res = c->res_dev;
     SlotLease lease;

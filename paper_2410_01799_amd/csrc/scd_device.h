@@ -165,9 +165,11 @@ struct SparseArgs {
     int32_t rs, cs;          // rows / columns owned per workgroup (multiples of 8)
     int32_t grid;            // workgroups of this launch (power of two, at most kSpGrid)
     int32_t profile;         // 1: workgroup 0 times its phases
+    int32_t delay_width;     // > 0: finished terms wait in a list of this length before they are subtracted
     ResidentResult* res;
 };
 
+int sparse_delay_width(int64_t m, int64_t n);
 bool sparse_supported(scd_dtype dt, int order, const int64_t* dims, int grid, int* rs, int* cs);
 size_t sparse_xbuf_bytes();
 hipError_t launch_sparse(const SparseArgs& a, scd_dtype dt, hipStream_t st);

@@ -572,6 +572,377 @@ __global__ void __launch_bounds__(kSpThreads) sparse_kernel(SparseArgs a)
     }
 }
 
+// =================================================================================================
+// Delayed updates (Section 3.2): the finished terms are not subtracted at once.  The two copies hold
+// R' = R_k + sum over the pending terms of c_j s_j t_j^T; every product with the true remainder is the
+// product with R' minus a correction from the pending terms' bitsets,
+//     (R_k t)_i   = (R' t)_i   - sum_j c_j s_j[i] <t_j, t>,      <t_j, t> = n - 2 popcount(t_j xor t),
+//     (R_k^T s)_l = (R'^T s)_l - sum_j c_j t_j[l] <s_j, s>,
+// and when the list is full (or the launch ends) all pending terms are subtracted in one pass over each
+// copy, term after term per entry, so the copies end up bit-identical to those of immediate updates.
+// The dense start of a term then only reads.  ||R_k||_F between flushes follows from the cut value:
+// ||R - c s t^T||^2 = ||R||^2 - 2 c <s, R t> + c^2 mn; at a flush it is measured again.
+
+struct SpPending {
+    uint32_t* PS;        // [width][ps_stride] row sign bits of the pending terms
+    uint32_t* PT;        // [width][pt_stride] column sign bits
+    double* coef;        // [32] coefficients as stored (rounded to the element type)
+    double* ej;          // [32] coefficient times inner product, per half step
+    double* effu;        // [kSpThreads] u of the true remainder on this workgroup's rows
+    double* effv;        // [kSpThreads] v on its columns
+    uint32_t* rowmask;   // [4]
+    int ps_stride, pt_stride;
+};
+
+// ej[j] = coef[j] * <p_j, cur> for the np pending vectors of one side, 0 for j >= np
+__device__ void sp_pending_dots(const uint32_t* P, int stride, int nwords32, int64_t nbits, const uint32_t* cur, int np,
+                                const double* coef, double* ej)
+{
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
+    for (int j = wv; j < 32; j += kSpWaves) {
+        if (j >= np) {
+            if (lane == 0) ej[j] = 0.0;
+            continue;
+        }
+        int cnt = 0;
+        for (int p = lane; p < nwords32; p += kWave) cnt += __popc(P[j * stride + p] ^ cur[p]);
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) cnt += __shfl_xor(cnt, off, kWave);
+        if (lane == 0) ej[j] = coef[j] * (double)(nbits - 2 * (int64_t)cnt);
+    }
+    __syncthreads();
+}
+
+// eff[tid] = acc[tid] - sum_j ej[j] * (sign of pending vector j at this thread's entry), in the order
+// j = 0..31 (ej is zero past the last pending term); `own` holds those signs, bit j for term j.
+// Every thread reads back only its own entry, so no barrier follows.
+__device__ __forceinline__ void sp_effective(const double* acc, int len, uint32_t own, const double* ej, double* eff)
+{
+    const int tid = threadIdx.x;
+    if (tid < len) {
+        double v = acc[tid];
+#pragma unroll
+        for (int j = 0; j < 32; ++j) {
+            const double e = ej[j];
+            v -= ((own >> j) & 1u) ? -e : e;
+        }
+        eff[tid] = v;
+    }
+}
+
+// Flush: rows row0 .. row0+nrows-1 of Y (row length ld) lose the np pending terms, one after the other
+// per entry (sign of term j at (row, col) = Prow_j[row] xor Pcol_j[col]); the squares of what is left
+// are summed, and the signed row sums with `sumbits` are formed for the next term's start.  Columns are
+// taken in tiles of one 16-byte chunk per thread, so that a thread keeps its columns' pending signs in
+// registers while it streams down the rows.
+template <typename TE>
+__device__ void sp_flush_rows(TE* __restrict__ Y, int64_t ld, int64_t row0, int nrows, const uint32_t* Prow, int prs,
+                              const uint32_t* Pcol, int pcs, int np, const double* coef, const uint32_t* colbits_sum,
+                              double* acc, double& fsq_out, double* red, uint32_t* rowmask)
+{
+    constexpr int VE = SpVec<TE>::N;
+    constexpr int RB = 4;
+    typedef typename SpVec<TE>::type V;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
+    const int64_t nch = ld / VE;
+    double fsq = 0.0;
+    if (tid < nrows) acc[tid] = 0.0;
+    for (int64_t c0 = 0; c0 < nch; c0 += kSpThreads) {
+        const int64_t c = c0 + tid;
+        const bool active = c < nch;
+        const int64_t col = (active ? c : 0) * VE;
+        uint32_t cm[VE];
+#pragma unroll
+        for (int e = 0; e < VE; ++e) cm[e] = 0u;
+        for (int j = 0; j < np; ++j) {
+            const uint32_t bits = Pcol[j * pcs + (int)(col >> 5)] >> (col & 31);
+#pragma unroll
+            for (int e = 0; e < VE; ++e) cm[e] |= ((bits >> e) & 1u) << j;
+        }
+        const uint32_t bsum = sp_bits4(colbits_sum, col & ~3ll) >> (col & 3);
+        for (int rb = 0; rb < nrows; rb += RB) {
+            __syncthreads();  // rowmask and red are free again
+            if (tid < RB) {
+                const int rr = rb + tid < nrows ? rb + tid : nrows - 1;
+                const int64_t row = row0 + rr;
+                uint32_t mk = 0u;
+                for (int j = 0; j < np; ++j) mk |= ((Prow[j * prs + (int)(row >> 5)] >> (row & 31)) & 1u) << j;
+                rowmask[tid] = mk;
+            }
+            __syncthreads();
+            double ps[RB];
+            V v[RB];
+            V* rowp[RB];
+#pragma unroll
+            for (int r = 0; r < RB; ++r) {
+                const int rr = rb + r < nrows ? rb + r : nrows - 1;
+                rowp[r] = (V*)(Y + (row0 + rr) * ld);
+                ps[r] = 0.0;
+                v[r] = rowp[r][active ? c : 0];
+            }
+#pragma unroll
+            for (int r = 0; r < RB; ++r) {
+                if (rb + r >= nrows || !active) continue;
+                TE x[VE];
+                if constexpr (VE == 4) {
+                    x[0] = v[r].x; x[1] = v[r].y; x[2] = v[r].z; x[3] = v[r].w;
+                } else {
+                    x[0] = v[r].x; x[1] = v[r].y;
+                }
+                uint32_t z[VE];
+#pragma unroll
+                for (int e = 0; e < VE; ++e) z[e] = rowmask[r] ^ cm[e];
+                for (int j = 0; j < np; ++j) {
+                    const TE ck = (TE)coef[j];
+#pragma unroll
+                    for (int e = 0; e < VE; ++e) x[e] = x[e] - sp_flip(ck, (z[e] >> j) & 1u);
+                }
+                V o;
+                if constexpr (VE == 4) o = V{x[0], x[1], x[2], x[3]};
+                else o = V{x[0], x[1]};
+                rowp[r][c] = o;
+#pragma unroll
+                for (int e = 0; e < VE; ++e) {
+                    fsq += (double)x[e] * (double)x[e];
+                    ps[r] += (double)sp_flip(x[e], (bsum >> e) & 1u);
+                }
+            }
+#pragma unroll
+            for (int r = 0; r < RB; ++r) ps[r] = sp_wave_sum(ps[r]);
+            if (lane == 0) {
+#pragma unroll
+                for (int r = 0; r < RB; ++r) red[wv * RB + r] = ps[r];
+            }
+            __syncthreads();
+            if (tid < RB && rb + tid < nrows) {
+                double t = 0.0;
+                for (int q = 0; q < kSpWaves; ++q) t += red[q * RB + tid];
+                acc[rb + tid] += t;
+            }
+        }
+    }
+    fsq = sp_wave_sum(fsq);
+    __syncthreads();
+    if (lane == 0) red[wv] = fsq;
+    __syncthreads();
+    double f = 0.0;
+    for (int q = 0; q < kSpWaves; ++q) f += red[q];
+    fsq_out = f;
+    __syncthreads();
+}
+
+template <typename TE>
+__global__ void __launch_bounds__(kSpThreads) sparse_delay_kernel(SparseArgs a)
+{
+    extern __shared__ __align__(16) unsigned char sp_lds[];
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
+    const int g = blockIdx.x;
+    const int64_t m = a.m, n = a.n;
+    const int64_t mwords32 = (m + 31) >> 5, nwords32 = (n + 31) >> 5;
+    const int width = a.delay_width;
+
+    SpShared sh;
+    SpPending pd;
+    {
+        size_t o = 0;
+        auto take = [&](size_t bytes) {
+            unsigned char* p = sp_lds + o;
+            o += (bytes + 15) & ~(size_t)15;
+            return p;
+        };
+        sh.sA = (uint32_t*)take((size_t)mwords32 * 4 + 8);
+        sh.sB = (uint32_t*)take((size_t)mwords32 * 4 + 8);
+        sh.tA = (uint32_t*)take((size_t)nwords32 * 4 + 8);
+        sh.tB = (uint32_t*)take((size_t)nwords32 * 4 + 8);
+        sh.list = (uint16_t*)take((size_t)kSpListCap * 2);
+        sh.accu = (double*)take((size_t)kSpThreads * 8);
+        sh.accv = (double*)take((size_t)kSpThreads * 8);
+        sh.red = (double*)take((size_t)kSpThreads * 8);
+        sh.scal = (uint32_t*)take((size_t)2 * kSpGrid * 2 * 4);
+        sh.scan = (int*)take((size_t)(kSpWaves + 1) * 4);
+        pd.ps_stride = (int)mwords32 + 1;
+        pd.pt_stride = (int)nwords32 + 1;
+        pd.coef = (double*)take(32 * 8);
+        pd.ej = (double*)take(32 * 8);
+        pd.effu = (double*)take((size_t)kSpThreads * 8);
+        pd.effv = (double*)take((size_t)kSpThreads * 8);
+        pd.rowmask = (uint32_t*)take(16);
+        pd.PS = (uint32_t*)take((size_t)width * pd.ps_stride * 4);
+        pd.PT = (uint32_t*)take((size_t)width * pd.pt_stride * 4);
+    }
+    for (int64_t i = tid; i < mwords32 + 2; i += kSpThreads) {
+        sh.sA[i] = 0;
+        sh.sB[i] = 0;
+    }
+    for (int64_t i = tid; i < nwords32 + 2; i += kSpThreads) {
+        sh.tA[i] = 0;
+        sh.tB[i] = 0;
+    }
+    __syncthreads();
+    uint32_t *s_cur = sh.sA, *s_oth = sh.sB, *t_cur = sh.tA, *t_oth = sh.tB;
+
+    const int rs = a.rs, cs = a.cs;
+    const int64_t i0 = (int64_t)g * rs < m ? (int64_t)g * rs : m;
+    const int rlen = (int)((i0 + rs < m ? i0 + rs : m) - i0);
+    const int64_t j0 = (int64_t)g * cs < n ? (int64_t)g * cs : n;
+    const int clen = (int)((j0 + cs < n ? j0 + cs : n) - j0);
+    TE* R = (TE*)a.R;
+    TE* RT = (TE*)a.RT;
+    const double total = (double)m * (double)n;
+
+    int64_t k = a.k_start;
+    uint32_t seq = a.seq;
+    int alternations = 0, updates = 0, warn = 0, spins = 0;
+    int64_t flips = 0, flips_rows = 0;
+    int np = 0;  // pending terms
+    uint32_t own_u = 0u, own_v = 0u;  // their signs at this thread's row of I_g / column of J_g, bit j for term j
+    double F;    // ||R_k||_F^2 of the true remainder
+    {
+        const double f0 = a.trace[k];
+        F = f0 * f0;
+    }
+
+    for (;;) {
+        if (k >= a.w_target && np == 0) break;
+        const bool last = k >= a.w_target;
+        const bool flush = np > 0 && (np == width || last);
+        // t_0 of term k (Algorithm 4 line 2), into the other column buffer
+        for (int64_t i = tid; i < nwords32; i += kSpThreads) {
+            uint32_t v = (uint32_t)(sp_rng_word(a.seed, (uint64_t)k, 1u, (uint64_t)(i >> 1)) >> (32 * (i & 1)));
+            const int64_t rem = n - i * 32;
+            if (rem < 32) v &= (1u << rem) - 1u;
+            t_oth[i] = v;
+        }
+        __syncthreads();
+        double fsq = 0.0, dummy = 0.0;
+        // rows I_g: u = R t_0 (Algorithm 4 line 5), from the flushed copy or from R' with the correction
+        if (flush) {
+            if (rlen > 0)
+                sp_flush_rows<TE>(R, n, i0, rlen, pd.PS, pd.ps_stride, pd.PT, pd.pt_stride, np, pd.coef, t_oth, sh.accu, fsq,
+                                  sh.red, pd.rowmask);
+            if (tid < rlen) pd.effu[tid] = sh.accu[tid];
+        } else {
+            if (rlen > 0)
+                sp_dense_rows<TE>(R, n, i0, rlen, false, s_cur, t_cur, (TE)0, t_oth, sh.accu, dummy, sh.red);
+            sp_pending_dots(pd.PT, pd.pt_stride, (int)nwords32, n, t_oth, np, pd.coef, pd.ej);
+            sp_effective(sh.accu, rlen, own_u, pd.ej, pd.effu);
+        }
+        if (!sp_exchange(a, ++seq, pd.effu, rlen, rs, m, fsq, 0.0, s_oth, sh, spins, flush)) {
+            if (tid == 0) atomicExch((unsigned*)&a.res->err, 1u);
+            return;
+        }
+        ++alternations;
+        if (flush) {
+            F = sp_sum_scalar(sh, 0, sh.red, a.grid);  // measured again
+            if (g == 0 && tid == 0) a.trace[k] = sqrt(F);
+        }
+        // rows J_g of the transposed copy: v = R^T s_1 (Algorithm 4 line 6)
+        if (flush) {
+            if (clen > 0)
+                sp_flush_rows<TE>(RT, m, j0, clen, pd.PT, pd.pt_stride, pd.PS, pd.ps_stride, np, pd.coef, s_oth, sh.accv, dummy,
+                                  sh.red, pd.rowmask);
+            updates += np;
+            np = 0;
+            own_u = 0u;
+            own_v = 0u;
+            if (last) break;
+            if (tid < clen) pd.effv[tid] = sh.accv[tid];
+        } else {
+            if (clen > 0)
+                sp_dense_rows<TE>(RT, m, j0, clen, false, t_cur, s_cur, (TE)0, s_oth, sh.accv, dummy, sh.red);
+            sp_pending_dots(pd.PS, pd.ps_stride, (int)mwords32, m, s_oth, np, pd.coef, pd.ej);
+            sp_effective(sh.accv, clen, own_v, pd.ej, pd.effv);
+        }
+        {
+            uint32_t* z = s_cur; s_cur = s_oth; s_oth = z;
+            z = t_cur; t_cur = t_oth; t_oth = z;
+        }
+        int j = 0;
+        double c_prev = -INFINITY;
+        bool handover = flush;  // the transposed copy was rewritten: the next exchange carries the fences
+        for (;;) {
+            // ---- finish the column half: t = sgn(v), c = sum |v| (Algorithm 4 lines 6-7), all-gather
+            double cabs = (tid < clen) ? fabs(pd.effv[tid]) : 0.0;
+            cabs = sp_wave_sum(cabs);
+            __syncthreads();
+            if (lane == 0) sh.red[wv] = cabs;
+            __syncthreads();
+            double cpart = 0.0;
+            for (int q = 0; q < kSpWaves; ++q) cpart += sh.red[q];
+            __syncthreads();
+            if (!sp_exchange(a, ++seq, pd.effv, clen, cs, n, cpart, 0.0, t_oth, sh, spins, handover)) {
+                if (tid == 0) atomicExch((unsigned*)&a.res->err, 1u);
+                return;
+            }
+            handover = false;
+            {
+                uint32_t* z = t_cur; t_cur = t_oth; t_oth = z;
+            }
+            ++j;
+            const double c = sp_sum_scalar(sh, 0, sh.red, a.grid);
+            // ---- Algorithm 4 line 8
+            if (c <= c_prev || j >= a.max_iters) {
+                if (!(c <= c_prev)) warn = 1;
+                const double ck = c / total;
+                const double ckt = (double)(TE)ck;  // the stored coefficient is what the flush subtracts
+                if (g == 0) {
+                    for (int p = tid; p < a.mw; p += kSpThreads)
+                        a.S[k * a.mw + p] = (uint64_t)s_cur[2 * p] | ((uint64_t)(2 * p + 1 < mwords32 ? s_cur[2 * p + 1] : 0u) << 32);
+                    if (tid == 0) {
+                        ((TE*)a.c)[k] = (TE)ck;
+                        a.iters[k] = j;
+                    }
+                }
+                if (g == (a.grid > 1 ? 1 : 0)) {
+                    for (int p = tid; p < a.nw; p += kSpThreads)
+                        a.T[k * a.nw + p] = (uint64_t)t_cur[2 * p] | ((uint64_t)(2 * p + 1 < nwords32 ? t_cur[2 * p + 1] : 0u) << 32);
+                }
+                // the term joins the pending list (Section 3.2)
+                for (int p = tid; p < (int)mwords32; p += kSpThreads) pd.PS[np * pd.ps_stride + p] = s_cur[p];
+                for (int p = tid; p < (int)nwords32; p += kSpThreads) pd.PT[np * pd.pt_stride + p] = t_cur[p];
+                if (tid == 0) pd.coef[np] = ckt;
+                if (tid < rlen) own_u |= ((s_cur[(i0 + tid) >> 5] >> ((i0 + tid) & 31)) & 1u) << np;
+                if (tid < clen) own_v |= ((t_cur[(j0 + tid) >> 5] >> ((j0 + tid) & 31)) & 1u) << np;
+                __syncthreads();
+                ++np;
+                F = F - 2.0 * ckt * c + ckt * ckt * total;
+                if (F < 0.0) F = 0.0;
+                ++k;
+                if (g == 0 && tid == 0) a.trace[k] = sqrt(F);
+                break;
+            }
+            c_prev = c;
+            // ---- row half, sparse: u' += 2 sum over flipped columns (rows of the transposed copy), correction, s
+            sp_accumulate_flips<TE>(RT, m, i0, rlen, t_cur, t_oth, n, sh.accu, sh, flips);
+            sp_pending_dots(pd.PT, pd.pt_stride, (int)nwords32, n, t_cur, np, pd.coef, pd.ej);
+            sp_effective(sh.accu, rlen, own_u, pd.ej, pd.effu);
+            if (!sp_exchange(a, ++seq, pd.effu, rlen, rs, m, 0.0, 0.0, s_oth, sh, spins, false)) {
+                if (tid == 0) atomicExch((unsigned*)&a.res->err, 1u);
+                return;
+            }
+            {
+                uint32_t* z = s_cur; s_cur = s_oth; s_oth = z;
+            }
+            ++alternations;
+            // ---- column half, sparse: v' += 2 sum over flipped rows, correction
+            sp_accumulate_flips<TE>(R, n, j0, clen, s_cur, s_oth, m, sh.accv, sh, flips_rows);
+            sp_pending_dots(pd.PS, pd.ps_stride, (int)mwords32, m, s_cur, np, pd.coef, pd.ej);
+            sp_effective(sh.accv, clen, own_v, pd.ej, pd.effv);
+        }
+    }
+    if (g == 0 && tid == 0) {
+        a.res->k = k;
+        a.res->alternations = alternations;
+        a.res->updates = updates;
+        a.res->seq_u = seq;
+        a.res->seq_v = seq;
+        a.res->warn = warn;
+        a.res->spins = spins;
+        a.res->flips = flips;
+        a.res->flips_rows = flips_rows;
+    }
+}
+
 // out (cols x rows) = in^T (rows x cols), 32 x 32 tiles through LDS
 template <typename TE>
 __global__ void __launch_bounds__(256) transpose_kernel(const TE* __restrict__ in, TE* __restrict__ out, int64_t rows,
@@ -587,12 +958,16 @@ __global__ void __launch_bounds__(256) transpose_kernel(const TE* __restrict__ i
         if (c0 + i < cols && r0 + tx < rows) out[(c0 + i) * rows + r0 + tx] = tile[tx][i];
 }
 
-size_t sparse_lds_bytes(int64_t m, int64_t n)
+size_t sparse_lds_bytes(int64_t m, int64_t n, int delay_width)
 {
     auto al = [](size_t b) { return (b + 15) & ~(size_t)15; };
     const size_t mw = (size_t)((m + 31) >> 5), nw = (size_t)((n + 31) >> 5);
-    return 2 * al(mw * 4 + 8) + 2 * al(nw * 4 + 8) + al((size_t)kSpListCap * 2) + 3 * al((size_t)kSpThreads * 8) +
-           al((size_t)2 * kSpGrid * 2 * 4) + al((size_t)(kSpWaves + 1) * 4);
+    size_t b = 2 * al(mw * 4 + 8) + 2 * al(nw * 4 + 8) + al((size_t)kSpListCap * 2) + 3 * al((size_t)kSpThreads * 8) +
+               al((size_t)2 * kSpGrid * 2 * 4) + al((size_t)(kSpWaves + 1) * 4);
+    if (delay_width > 0)
+        b += 2 * al(32 * 8) + 2 * al((size_t)kSpThreads * 8) + al(16) + al((size_t)delay_width * (mw + 1) * 4) +
+             al((size_t)delay_width * (nw + 1) * 4);
+    return b;
 }
 
 }  // namespace
@@ -609,7 +984,7 @@ bool sparse_supported(scd_dtype dt, int order, const int64_t* dims, int grid, in
     const int64_t c = 8 * ((n + 8 * grid - 1) / (8 * grid));
     if (r > kSpThreads || c > kSpThreads) return false;
     if (r > 32 * kSpPayload || c > 32 * kSpPayload) return false;
-    if (sparse_lds_bytes(m, n) > kSpMaxLds) return false;
+    if (sparse_lds_bytes(m, n, 0) > kSpMaxLds) return false;
     if (rs) *rs = (int)r;
     if (cs) *cs = (int)c;
     return true;
@@ -627,25 +1002,37 @@ hipError_t launch_transpose(const void* in, void* out, scd_dtype dt, int64_t row
     return hipGetLastError();
 }
 
+// Most pending terms (at most 32) whose sign vectors fit into LDS beside the rest; 0 if fewer than 4 would.
+int sparse_delay_width(int64_t m, int64_t n)
+{
+    int w = 32;
+    while (w >= 4 && sparse_lds_bytes(m, n, w) > kSpMaxLds) --w;
+    return w >= 4 ? w : 0;
+}
+
 template <typename TE>
 static hipError_t launch_sparse_t(const SparseArgs& a, hipStream_t st)
 {
-    const size_t lds = sparse_lds_bytes(a.m, a.n);
-    if (lds > kSpMaxLds) return hipErrorInvalidValue;
+    const size_t lds = sparse_lds_bytes(a.m, a.n, a.delay_width);
+    if (lds > kSpMaxLds || a.delay_width < 0 || a.delay_width > 32) return hipErrorInvalidValue;
+    const void* fn = a.delay_width > 0 ? (const void*)sparse_delay_kernel<TE> : (const void*)sparse_kernel<TE>;
     // always the same ceiling, whatever this launch needs: launches from several host threads set it too
-    hipError_t e = hipFuncSetAttribute((const void*)sparse_kernel<TE>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)kSpMaxLds);
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSpMaxLds);
     if (e != hipSuccess) return e;
     int dev = 0, per_cu = 0;
     hipDeviceProp_t prop;
     e = hipGetDevice(&dev);
     if (e == hipSuccess) e = hipGetDeviceProperties(&prop, dev);
-    if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, sparse_kernel<TE>, kSpThreads, lds);
+    if (e == hipSuccess) {
+        if (a.delay_width > 0) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, sparse_delay_kernel<TE>, kSpThreads, lds);
+        else e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, sparse_kernel<TE>, kSpThreads, lds);
+    }
     if (e != hipSuccess) return e;
     // all workgroups must be resident at once (every wait in the kernel is bounded in case they are not)
     if (a.grid < 1 || a.grid > kSpGrid) return hipErrorInvalidValue;
     if ((int64_t)per_cu * prop.multiProcessorCount < a.grid) return hipErrorCooperativeLaunchTooLarge;
-    hipLaunchKernelGGL((sparse_kernel<TE>), dim3(a.grid), dim3(kSpThreads), lds, st, a);
+    if (a.delay_width > 0) hipLaunchKernelGGL((sparse_delay_kernel<TE>), dim3(a.grid), dim3(kSpThreads), lds, st, a);
+    else hipLaunchKernelGGL((sparse_kernel<TE>), dim3(a.grid), dim3(kSpThreads), lds, st, a);
     return hipGetLastError();
 }
 
