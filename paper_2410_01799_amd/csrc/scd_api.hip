@@ -412,13 +412,15 @@ int run_sparse(scd_ctx* c, int64_t n)
     a.cs = c->cs;
     a.grid = c->sp_grid;
     // Delayed updates (Section 3.2) trade the writes of the dense start of a term for a correction on every
-    // half step.  Measured: that pays from about 400 MiB on when the context has the device to itself (32000x4096:
-    // +13 %; 224 MiB: even; 64 MiB: -15 %), and from 128 MiB on when it shares the device and with it the
-    // bandwidth (224 MiB on 64 compute units beside three others: +15 %).  SCD_SPARSE_DELAY = 0 / 1 overrides.
+    // half step, whose cost grows with the length of the pending list.  Measured on this chip the best length
+    // is 8, not the paper's 32 (14336x4096: 1084 terms/s immediate, 1175 with 8, 1144 with 16, 1017 with 32;
+    // 32000x4096: 781 / 900 / 873; 4096x4096: 1137 / 1165 / 1076 / 942).  SCD_SPARSE_DELAY = 0 switches them
+    // off, SCD_SPARSE_DELAY_WIDTH sets the length (4..32).
     {
-        const double mib = (double)c->total * (double)c->esize / (1024.0 * 1024.0);
-        const int dflt = mib >= (c->share > 0 ? 128.0 : 384.0) ? 1 : 0;
-        a.delay_width = env_int("SCD_SPARSE_DELAY", dflt) != 0 ? sparse_delay_width(c->dims[0], c->dims[1]) : 0;
+        int width = env_int("SCD_SPARSE_DELAY", 1) != 0 ? sparse_delay_width(c->dims[0], c->dims[1]) : 0;
+        const int cap = env_int("SCD_SPARSE_DELAY_WIDTH", 8);
+        if (width > cap && cap >= 4) width = cap;
+        a.delay_width = width;
     }
     a.profile = env_int("SCD_RESIDENT_VERBOSE", 0);
     a.res = c->res_dev;

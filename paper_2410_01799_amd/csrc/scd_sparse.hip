@@ -596,10 +596,10 @@ struct SpPending {
 
 // ej[j] = coef[j] * <p_j, cur> for the np pending vectors of one side, 0 for j >= np
 __device__ void sp_pending_dots(const uint32_t* P, int stride, int nwords32, int64_t nbits, const uint32_t* cur, int np,
-                                const double* coef, double* ej)
+                                int width, const double* coef, double* ej)
 {
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
-    for (int j = wv; j < 32; j += kSpWaves) {
+    for (int j = wv; j < ((width + 7) & ~7); j += kSpWaves) {
         if (j >= np) {
             if (lane == 0) ej[j] = 0.0;
             continue;
@@ -616,15 +616,18 @@ __device__ void sp_pending_dots(const uint32_t* P, int stride, int nwords32, int
 // eff[tid] = acc[tid] - sum_j ej[j] * (sign of pending vector j at this thread's entry), in the order
 // j = 0..31 (ej is zero past the last pending term); `own` holds those signs, bit j for term j.
 // Every thread reads back only its own entry, so no barrier follows.
-__device__ __forceinline__ void sp_effective(const double* acc, int len, uint32_t own, const double* ej, double* eff)
+__device__ __forceinline__ void sp_effective(const double* acc, int len, uint32_t own, const double* ej, int width,
+                                             double* eff)
 {
     const int tid = threadIdx.x;
     if (tid < len) {
         double v = acc[tid];
+        for (int j0 = 0; j0 < width; j0 += 8) {
 #pragma unroll
-        for (int j = 0; j < 32; ++j) {
-            const double e = ej[j];
-            v -= ((own >> j) & 1u) ? -e : e;
+            for (int j = 0; j < 8; ++j) {
+                const double e = ej[j0 + j];
+                v -= ((own >> (j0 + j)) & 1u) ? -e : e;
+            }
         }
         eff[tid] = v;
     }
@@ -824,8 +827,8 @@ __global__ void __launch_bounds__(kSpThreads) sparse_delay_kernel(SparseArgs a)
         } else {
             if (rlen > 0)
                 sp_dense_rows<TE>(R, n, i0, rlen, false, s_cur, t_cur, (TE)0, t_oth, sh.accu, dummy, sh.red);
-            sp_pending_dots(pd.PT, pd.pt_stride, (int)nwords32, n, t_oth, np, pd.coef, pd.ej);
-            sp_effective(sh.accu, rlen, own_u, pd.ej, pd.effu);
+            sp_pending_dots(pd.PT, pd.pt_stride, (int)nwords32, n, t_oth, np, width, pd.coef, pd.ej);
+            sp_effective(sh.accu, rlen, own_u, pd.ej, width, pd.effu);
         }
         if (!sp_exchange(a, ++seq, pd.effu, rlen, rs, m, fsq, 0.0, s_oth, sh, spins, flush)) {
             if (tid == 0) atomicExch((unsigned*)&a.res->err, 1u);
@@ -850,8 +853,8 @@ __global__ void __launch_bounds__(kSpThreads) sparse_delay_kernel(SparseArgs a)
         } else {
             if (clen > 0)
                 sp_dense_rows<TE>(RT, m, j0, clen, false, t_cur, s_cur, (TE)0, s_oth, sh.accv, dummy, sh.red);
-            sp_pending_dots(pd.PS, pd.ps_stride, (int)mwords32, m, s_oth, np, pd.coef, pd.ej);
-            sp_effective(sh.accv, clen, own_v, pd.ej, pd.effv);
+            sp_pending_dots(pd.PS, pd.ps_stride, (int)mwords32, m, s_oth, np, width, pd.coef, pd.ej);
+            sp_effective(sh.accv, clen, own_v, pd.ej, width, pd.effv);
         }
         {
             uint32_t* z = s_cur; s_cur = s_oth; s_oth = z;
@@ -914,8 +917,8 @@ __global__ void __launch_bounds__(kSpThreads) sparse_delay_kernel(SparseArgs a)
             c_prev = c;
             // ---- row half, sparse: u' += 2 sum over flipped columns (rows of the transposed copy), correction, s
             sp_accumulate_flips<TE>(RT, m, i0, rlen, t_cur, t_oth, n, sh.accu, sh, flips);
-            sp_pending_dots(pd.PT, pd.pt_stride, (int)nwords32, n, t_cur, np, pd.coef, pd.ej);
-            sp_effective(sh.accu, rlen, own_u, pd.ej, pd.effu);
+            sp_pending_dots(pd.PT, pd.pt_stride, (int)nwords32, n, t_cur, np, width, pd.coef, pd.ej);
+            sp_effective(sh.accu, rlen, own_u, pd.ej, width, pd.effu);
             if (!sp_exchange(a, ++seq, pd.effu, rlen, rs, m, 0.0, 0.0, s_oth, sh, spins, false)) {
                 if (tid == 0) atomicExch((unsigned*)&a.res->err, 1u);
                 return;
@@ -926,8 +929,8 @@ __global__ void __launch_bounds__(kSpThreads) sparse_delay_kernel(SparseArgs a)
             ++alternations;
             // ---- column half, sparse: v' += 2 sum over flipped rows, correction
             sp_accumulate_flips<TE>(R, n, j0, clen, s_cur, s_oth, m, sh.accv, sh, flips_rows);
-            sp_pending_dots(pd.PS, pd.ps_stride, (int)mwords32, m, s_cur, np, pd.coef, pd.ej);
-            sp_effective(sh.accv, clen, own_v, pd.ej, pd.effv);
+            sp_pending_dots(pd.PS, pd.ps_stride, (int)mwords32, m, s_cur, np, width, pd.coef, pd.ej);
+            sp_effective(sh.accv, clen, own_v, pd.ej, width, pd.effv);
         }
     }
     if (g == 0 && tid == 0) {

@@ -25,7 +25,7 @@ def engines(request):
     os.environ["SCD_RESIDENT"] = "0"        # so that the sparse engine also serves the resident engine's shapes
     os.environ["SCD_SPARSE_MIN_MIB"] = "0"  # ... and matrices below the size from which it pays off
     os.environ.pop("SCD_SPARSE", None)
-    # updates subtracted at once, or kept in a list of up to 32 pending terms (Section 3.2)
+    # updates subtracted at once, or kept in a list of pending terms (Section 3.2)
     os.environ["SCD_SPARSE_DELAY"] = "1" if request.param == "delayed" else "0"
     yield request.param
     for k in ("SCD_RESIDENT", "SCD_SPARSE", "SCD_SPARSE_MIN_MIB", "SCD_SPARSE_DELAY"):
@@ -77,6 +77,16 @@ def test_sparse_matches_oracle_f64(scd, oracle, m, n, w):
 @pytest.mark.parametrize("m,n,w,dtype", [(256, 256, 70, np.float32), (100, 76, 45, np.float64), (1000, 520, 36, np.float32)])
 def test_sparse_more_terms_than_the_pending_list_holds(scd, oracle, m, n, w, dtype):
     run_and_check(scd, oracle, gauss((m, n), m + n + w, dtype), w, 19)
+
+
+def test_sparse_pending_list_of_the_papers_length(scd, oracle, engines):
+    # the default list holds 8 terms; Section 3.2's 32 (and the shortest, 4) go through the same code
+    for width in ("32", "4"):
+        os.environ["SCD_SPARSE_DELAY_WIDTH"] = width
+        try:
+            run_and_check(scd, oracle, gauss((300, 260), 31 + int(width)), 70, 23)
+        finally:
+            os.environ.pop("SCD_SPARSE_DELAY_WIDTH", None)
 
 
 def test_sparse_large_layer_shape(scd, oracle):
