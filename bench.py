@@ -50,17 +50,29 @@ def layer_mode(args, scd, workloads, torch, np) -> int:
     """Seconds per decoder layer at 50 % of the bf16 size (workload 3): every matrix decomposed to its
     Table 2 width, all inputs resident in HBM before the timer starts.  With --concurrency K the seven
     matrices are taken from a queue (largest first) by K host threads, each decomposition on its own
-    stream and on 256/K compute units; the figure is the wall time of the whole layer."""
+    stream; the compute units are split evenly among the matrices in flight (64 each with four, all 256 for the
+    last one); the figure is the wall time of the whole layer."""
     import threading
 
     K = args.concurrency
-    share = 0 if K == 1 else 256 // K
     jobs = []
     for name, M, wfull, seed in workloads.config3():
         jobs.append(dict(name=name, A=torch.from_numpy(M).cuda(), shape=list(M.shape), wfull=wfull, seed=seed,
                          w=max(1, int(round(wfull * args.layer_fraction)))))
     order = sorted(range(len(jobs)), key=lambda i: -jobs[i]["wfull"] * jobs[i]["shape"][0] * jobs[i]["shape"][1])
     rows, lock, errors = [None] * len(jobs), threading.Lock(), []
+    busy = [0]   # workers that hold a matrix right now
+    t_begin = [0.0]
+
+    def fair_share():
+        # the device is split among the matrices in flight: 64 compute units each with four, 128 with two, all of
+        # them for the last one (a context can change its share between launches)
+        with lock:
+            n = max(1, busy[0])
+        sh = 256
+        while sh > 256 // n:
+            sh //= 2
+        return 0 if sh >= 256 else sh
 
     def worker():
         torch.cuda.set_device(0)
@@ -71,14 +83,19 @@ def layer_mode(args, scd, workloads, torch, np) -> int:
                     if not order or errors:
                         return
                     i = order.pop(0)
+                    busy[0] += 1
                 j = jobs[i]
                 try:
                     t0 = time.perf_counter()
                     with scd.ScdContext(j["A"], j["w"], j["seed"]) as ctx:
-                        if share:
-                            ctx.set_workgroups(share)
                         step = j["w"] if K == 1 else 1024
+                        share_now = None
                         for k in range(0, j["w"], step):
+                            if K > 1:
+                                want = fair_share()
+                                if want != share_now:
+                                    ctx.set_workgroups(want)
+                                    share_now = want
                             ctx.run(min(step, j["w"] - k))
                         res = ctx.results()
                         eng = ctx.engine()["engine"]
@@ -87,17 +104,21 @@ def layer_mode(args, scd, workloads, torch, np) -> int:
                 except Exception as err:  # noqa: BLE001 - reported by the main thread
                     with lock:
                         errors.append((j["name"], repr(err)))
+                        busy[0] -= 1
                     return
+                with lock:
+                    busy[0] -= 1
                 tr = res["trace"].cpu().numpy()
                 it = res["iters"].cpu().numpy()
                 rows[i] = {"matrix": j["name"], "shape": j["shape"], "width": j["wfull"], "terms_run": j["w"],
-                           "seconds": round(dt, 3), "terms_per_s": round(j["w"] / dt, 1),
+                           "started_at": round(t0 - t_begin[0], 3), "seconds": round(dt, 3),
+                           "terms_per_s": round(j["w"] / dt, 1),
                            "alternations_per_term": round(float(it.mean()), 2),
                            "relative_error": round(float(tr[-1] / tr[0]), 5),
-                           "engine": ["launch-stream", "register-resident", "sparse"][eng]}
+                           "engine_at_the_end": ["launch-stream", "register-resident", "sparse"][eng]}
 
     torch.cuda.synchronize()
-    t_begin = time.perf_counter()
+    t_begin[0] = time.perf_counter()
     if K == 1:
         worker()
     else:
@@ -107,7 +128,7 @@ def layer_mode(args, scd, workloads, torch, np) -> int:
         for t in threads:
             t.join()
     torch.cuda.synchronize()
-    wall = time.perf_counter() - t_begin
+    wall = time.perf_counter() - t_begin[0]
     if errors:
         print(f"layer run failed: {errors}", file=sys.stderr)
         return 1
@@ -116,7 +137,7 @@ def layer_mode(args, scd, workloads, torch, np) -> int:
     print(json.dumps({"metric": "seconds per Mistral-7B-shaped decoder layer at 50% of bf16 size", "value": round(total_s, 2),
                       "unit": "s/layer", "n_gpus": 1, "higher_is_better": False, "dtype": "f32", "data": "synthetic",
                       "extrapolated": args.layer_fraction < 1.0, "terms": total_terms, "concurrency": K,
-                      "compute_units_per_matrix": share or 256,
+                      "compute_units_per_matrix": "256 / matrices in flight",
                       "terms_per_s": round(total_terms / total_s, 1), "matrices": rows}))
     return 0
 

@@ -11,8 +11,10 @@
 #include <string.h>
 
 #include <condition_variable>
+#include <map>
 #include <mutex>
 #include <new>
+#include <utility>
 #include <vector>
 
 #include "scd_device.h"
@@ -108,21 +110,87 @@ struct scd_ctx {
     hipEvent_t ev0 = nullptr, ev1 = nullptr;  // around the engine's launch
     double last_launch_seconds = 0.0;
     double last_launch_bytes = 0.0;
-    std::vector<void*> allocs;
+    std::vector<std::pair<void*, size_t>> allocs;  // device blocks of the context and their sizes
 };
 
 namespace {
 
+// Persistent launches of different contexts (host threads, streams) share the device: each needs all of
+// its workgroups resident at once, one per compute unit, so a launch waits until that many compute units
+// are free of other persistent launches of this process (SlotLease below).
+std::mutex g_slots_mutex;
+std::condition_variable g_slots_cv;
+int g_slots_in_use = 0;
+
+// hipFree and hipHostFree wait for every stream of the device.  While other contexts keep the device busy
+// from other threads that wait lasts until their launches end, so a context destroyed then parks its
+// blocks here, and contexts created later take blocks of the same size back out (the matrices of a model
+// come in a handful of shapes).  With the device idle the blocks are freed.
+std::mutex g_pool_mutex;
+std::multimap<size_t, void*> g_pool_dev, g_pool_host;
+size_t g_pool_dev_bytes = 0;
+constexpr size_t kPoolMaxBytes = (size_t)48 << 30;
+
+bool others_running()
+{
+    std::lock_guard<std::mutex> lk(g_slots_mutex);
+    return g_slots_in_use > 0;
+}
+
+hipError_t pool_malloc(void** p, size_t bytes, bool host)
+{
+    {
+        std::lock_guard<std::mutex> lk(g_pool_mutex);
+        auto& pool = host ? g_pool_host : g_pool_dev;
+        auto it = pool.find(bytes);
+        if (it != pool.end()) {
+            *p = it->second;
+            pool.erase(it);
+            if (!host) g_pool_dev_bytes -= bytes;
+            return hipSuccess;
+        }
+    }
+    return host ? hipHostMalloc(p, bytes, hipHostMallocDefault) : hipMalloc(p, bytes);
+}
+
+void pool_free(void* p, size_t bytes, bool host)
+{
+    if (!p) return;
+    if (others_running()) {
+        std::lock_guard<std::mutex> lk(g_pool_mutex);
+        if (host || g_pool_dev_bytes + bytes <= kPoolMaxBytes) {
+            (host ? g_pool_host : g_pool_dev).emplace(bytes, p);
+            if (!host) g_pool_dev_bytes += bytes;
+            return;
+        }
+    }
+    if (host) (void)hipHostFree(p);
+    else (void)hipFree(p);
+}
+
+void pool_drain()
+{
+    std::multimap<size_t, void*> dev, host;
+    {
+        std::lock_guard<std::mutex> lk(g_pool_mutex);
+        dev.swap(g_pool_dev);
+        host.swap(g_pool_host);
+        g_pool_dev_bytes = 0;
+    }
+    for (auto& kv : dev) (void)hipFree(kv.second);
+    for (auto& kv : host) (void)hipHostFree(kv.second);
+}
+
 int dev_alloc(scd_ctx* c, void** p, size_t bytes)
 {
     if (bytes == 0) bytes = 8;
-    hipError_t e = hipMalloc(p, bytes);
+    hipError_t e = pool_malloc(p, bytes, false);
     if (e != hipSuccess) {
         g_last_hip = (int)e;
         (void)hipGetLastError();
         return SCD_ENOMEM;
     }
-    c->allocs.push_back(*p);
+    c->allocs.emplace_back(*p, bytes);
     return SCD_OK;
 }
 
@@ -298,13 +366,6 @@ int resync_stream_state(scd_ctx* c)
     return SCD_OK;
 }
 
-// Persistent launches of different contexts (host threads, streams) share the device: each needs all of
-// its workgroups resident at once, one per compute unit, so a launch waits here until that many compute
-// units are free of other persistent launches of this process.
-std::mutex g_slots_mutex;
-std::condition_variable g_slots_cv;
-int g_slots_in_use = 0;
-
 struct SlotLease {
     int n = 0;
     void acquire(int want, int capacity)
@@ -355,12 +416,12 @@ int setup_engines(scd_ctx* c)
     };
     if (c->sparse && !c->RT) {
         // the transpose doubles the footprint: without room for it the launch-stream engine serves
-        if (hipMalloc(&c->RT, (size_t)c->total * c->esize) != hipSuccess) {
+        if (pool_malloc(&c->RT, (size_t)c->total * c->esize, false) != hipSuccess) {
             (void)hipGetLastError();
             c->RT = nullptr;
             c->sparse = false;
         } else {
-            c->allocs.push_back(c->RT);
+            c->allocs.emplace_back(c->RT, (size_t)c->total * c->esize);
             c->rt_stale = true;
             SCD_TRY(dev_alloc(c, (void**)&c->xbuf_sp, sparse_xbuf_bytes()));
             if (!hip_ok(hipMemsetAsync(c->xbuf_sp, 0, sparse_xbuf_bytes(), c->stream))) return SCD_EHIP;
@@ -373,7 +434,7 @@ int setup_engines(scd_ctx* c)
     }
     if ((c->resident || c->sparse) && !c->res_dev) {
         SCD_TRY(dev_alloc(c, (void**)&c->res_dev, sizeof(ResidentResult)));
-        if (!hip_ok(hipHostMalloc((void**)&c->res_pin, sizeof(ResidentResult), hipHostMallocDefault))) return SCD_EHIP;
+        if (!hip_ok(pool_malloc((void**)&c->res_pin, sizeof(ResidentResult), true))) return SCD_EHIP;
         c->max_spin = env_int("SCD_RESIDENT_MAX_SPIN", 1 << 22);
         if (!hip_ok(hipEventCreate(&c->ev0)) || !hip_ok(hipEventCreate(&c->ev1))) return SCD_EHIP;
     }
@@ -591,7 +652,7 @@ int scd_create(scd_ctx** out, const void* A, scd_dtype dt, int order, const int6
     CTRY(dev_alloc(c, (void**)&c->iters, (size_t)w_capacity * 4));
     CTRY(dev_alloc(c, (void**)&c->cur, sizeof(State)));
     CTRY(dev_alloc(c, (void**)&c->next, sizeof(State)));
-    CHIP(hipHostMalloc((void**)&c->pinned, sizeof(State), hipHostMallocDefault));
+    CHIP(pool_malloc((void**)&c->pinned, sizeof(State), true));
 
     int64_t cols = total;
     for (int l = 0; l < c->nlevels; ++l) {
@@ -647,9 +708,10 @@ void scd_destroy(scd_ctx* c)
 {
     if (!c) return;
     (void)hipStreamSynchronize(c->stream);
-    for (void* p : c->allocs) (void)hipFree(p);
-    if (c->pinned) (void)hipHostFree(c->pinned);
-    if (c->res_pin) (void)hipHostFree(c->res_pin);
+    for (auto& b : c->allocs) pool_free(b.first, b.second, false);
+    pool_free(c->pinned, sizeof(State), true);
+    pool_free(c->res_pin, sizeof(ResidentResult), true);
+    if (!others_running()) pool_drain();
     if (c->ev0) (void)hipEventDestroy(c->ev0);
     if (c->ev1) (void)hipEventDestroy(c->ev1);
     (void)hipGetLastError();

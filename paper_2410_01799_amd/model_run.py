@@ -37,19 +37,22 @@ def device_weight_like(m: int, n: int, seed: int, kind: str) -> torch.Tensor:
     return G.bfloat16().float().contiguous()   # bf16-representable values, stored as f32
 
 
-def decompose_one(e: dict, share: int, chunk: int) -> dict:
-    """One matrix of the manifest on the current stream; returns its result row."""
+def decompose_one(e: dict, share_fn, chunk: int) -> dict:
+    """One matrix of the manifest on the current stream; returns its result row.  share_fn() says, before every
+    launch, how many compute units this matrix may take (0 = all)."""
     m, n = e["m"], e["n"]
     A = device_weight_like(m, n, e["seed"], e["kind"])
     w = e["widths"]["1/2"]
     torch.cuda.current_stream().synchronize()
     t0 = time.perf_counter()
     with scd.ScdContext(A, w, e["seed"]) as ctx:
-        if share:
-            ctx.set_workgroups(share)
-        # launches of bounded length: a thread that frees device memory waits for the launches in flight
-        # on every stream, so nobody should hold the device for tens of seconds
+        share_now = 0
+        # launches of bounded length, so that the split of the device can follow the matrices in flight
         for k in range(0, w, chunk):
+            want = share_fn()
+            if want != share_now:
+                ctx.set_workgroups(want)
+                share_now = want
             ctx.run(min(chunk, w - k))
         res = ctx.results()
         eng = ctx.engine()["engine"]
@@ -61,7 +64,7 @@ def decompose_one(e: dict, share: int, chunk: int) -> dict:
     rel = {p: float(tr[e["widths"][p]] / tr[0]) for p in ("1/4", "3/8", "1/2")}
     return dict(index=e["index"], name=e["name"], m=m, n=n, seed=e["seed"], width=w, seconds=round(dt, 3),
                 terms_per_s=round(w / dt, 1), alternations_per_term=round(float(res["iters"].float().mean()), 2),
-                rel_err=rel, identity_max_violation=ident, engine=eng, share=share or 256)
+                rel_err=rel, identity_max_violation=ident, engine_at_the_end=eng)
 
 
 def main() -> int:
@@ -71,8 +74,8 @@ def main() -> int:
     ap.add_argument("--out", type=str, required=True)
     ap.add_argument("--budget-seconds", type=float, default=1e9, help="take no new matrix that would overrun")
     ap.add_argument("--concurrency", type=int, default=1, choices=[1, 2, 4, 8],
-                    help="matrices decomposed side by side, each on 256/K compute units (the matrices of a model "
-                         "are independent, and one decomposition is latency-bound)")
+                    help="matrices decomposed side by side, the compute units split evenly among those in flight "
+                         "(the matrices of a model are independent, and one decomposition is latency-bound)")
     ap.add_argument("--chunk", type=int, default=1024, help="terms per launch when matrices run side by side")
     args = ap.parse_args()
     man = workloads.config5_manifest()
@@ -82,9 +85,21 @@ def main() -> int:
     out = Path(args.out)
     out.parent.mkdir(parents=True, exist_ok=True)
     K = args.concurrency
-    share = 0 if K == 1 else 256 // K
     chunk = 1 << 30 if K == 1 else args.chunk
     lock = threading.Lock()
+    busy = [0]           # workers that hold a matrix right now
+
+    def fair_share() -> int:
+        # the compute units are split evenly among the matrices in flight (64 each with four, all for the last one)
+        if K == 1:
+            return 0
+        with lock:
+            n = max(1, busy[0])
+        sh = 256
+        while sh > 256 // n:
+            sh //= 2
+        return 0 if sh >= 256 else sh
+
     t_begin = time.perf_counter()
     cost: dict = {}      # (m, n) -> seconds the last matrix of that shape took
     failures = []
@@ -104,13 +119,16 @@ def main() -> int:
                         if time.perf_counter() - t_begin + 1.2 * guess > args.budget_seconds:
                             return
                         todo.pop(0)
+                        busy[0] += 1
                     try:
-                        row = decompose_one(e, share, chunk)
+                        row = decompose_one(e, fair_share, chunk)
                     except Exception as err:  # noqa: BLE001 - reported by the main thread
                         with lock:
                             failures.append((e["index"], repr(err)))
+                            busy[0] -= 1
                         return
                     with lock:
+                        busy[0] -= 1
                         cost[(e["m"], e["n"])] = row["seconds"]
                         fh.write(json.dumps(row) + "\n")
                         fh.flush()
