@@ -211,11 +211,13 @@ int scd_traffic(const scd_ctx* ctx, double* bytes, int64_t* passes, int64_t* swe
 
 /* Which engine scd_run uses for this context: 0 = a stream of launches that re-read the remainder from
  * memory every alternation (any shape, dtype, order); 1 = one persistent launch that keeps the whole
- * remainder in the register files of a 16 x 16 grid of workgroups (f32 matrices of 1024x4096, 2048x2048,
- * 4096x4096; switched off by the environment variable SCD_RESIDENT=0); 2 = one persistent launch that
- * caches R t and R^T s and updates them from the flipped signs only (Section 3.1; f32/f64 matrices with
- * 8 <= m, n <= 65536 whose rows and columns are multiples of 16 bytes and whose remainder takes at
- * least 48 MiB (SCD_SPARSE_MIN_MIB); keeps a transposed copy of the remainder; switched off by
+ * remainder in the register files of a grid of workgroups (f32 matrices of 256x256, 512x512, 1024x1024,
+ * 1024x4096, 2048x2048, 4096x4096; switched off by the environment variable SCD_RESIDENT=0); 2 = one persistent
+ * launch that caches R t and R^T s and updates them from the flipped signs only (Section 3.1; f32/f64 matrices
+ * with 8 <= m, n <= 65536 whose rows and columns are multiples of 16 bytes and whose remainder takes at
+ * least 48 MiB (SCD_SPARSE_MIN_MIB), or any size once the context has a share of the device; keeps a transposed
+ * copy of the remainder; finished terms wait in a list of 8 (SCD_SPARSE_DELAY_WIDTH, 4..32) before they are
+ * subtracted, Section 3.2, unless SCD_SPARSE_DELAY=0; the engine is switched off by
  * SCD_SPARSE=0).  For engines 1 and 2 also the duration of the most recent
  * launch by HIP events on the context's stream and its dense-equivalent bytes: (alternations + updates)
  * * bytes of the remainder, what a streaming pass per alternation would move.  host pointers, each may

@@ -19,6 +19,8 @@
 // bypass the non-coherent caches; slots alternate by sequence parity; every wait is bounded).
 // Flipped indices are compacted in ascending order and added in a fixed order: results are
 // bit-identical from run to run.
+// A second kernel (further down) delays the subtraction of finished terms as Section 3.2 does: pending
+// terms live in LDS, the products are corrected from their bitsets, one pass flushes the list.
 #include "scd_device.h"
 
 namespace scd {
