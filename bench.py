@@ -46,7 +46,7 @@ def cpu_baseline(A64, seed: int, budget_s: float):
                        f"{float(res['iters'].mean()):.1f} alternations/term)")
 
 
-def layer_mode(args, scd, workloads, torch, np) -> int:
+def layer_mode(args, scd, workloads, torch, np) -> dict:
     """Seconds per decoder layer at 50 % of the bf16 size (workload 3): every matrix decomposed to its
     Table 2 width, all inputs resident in HBM before the timer starts.  With --concurrency K the seven
     matrices are taken from a queue (largest first) by K host threads, each decomposition on its own
@@ -130,16 +130,14 @@ def layer_mode(args, scd, workloads, torch, np) -> int:
     torch.cuda.synchronize()
     wall = time.perf_counter() - t_begin[0]
     if errors:
-        print(f"layer run failed: {errors}", file=sys.stderr)
-        return 1
+        raise RuntimeError(f"layer run failed: {errors}")
     total_terms = sum(j["wfull"] for j in jobs)
     total_s = wall / args.layer_fraction
-    print(json.dumps({"metric": "seconds per Mistral-7B-shaped decoder layer at 50% of bf16 size", "value": round(total_s, 2),
-                      "unit": "s/layer", "n_gpus": 1, "higher_is_better": False, "dtype": "f32", "data": "synthetic",
-                      "extrapolated": args.layer_fraction < 1.0, "terms": total_terms, "concurrency": K,
-                      "compute_units_per_matrix": "256 / matrices in flight",
-                      "terms_per_s": round(total_terms / total_s, 1), "matrices": rows}))
-    return 0
+    return {"metric": "seconds per Mistral-7B-shaped decoder layer at 50% of bf16 size", "value": round(total_s, 2),
+            "unit": "s/layer", "n_gpus": 1, "higher_is_better": False, "dtype": "f32", "data": "synthetic",
+            "extrapolated": args.layer_fraction < 1.0, "terms": total_terms, "concurrency": K,
+            "compute_units_per_matrix": "256 / matrices in flight",
+            "terms_per_s": round(total_terms / total_s, 1), "matrices": rows}
 
 
 def apply_mode(args, scd, torch) -> int:
@@ -289,6 +287,8 @@ def main() -> int:
     ap.add_argument("--layer", action="store_true",
                     help="instead of the headline: decompose one synthetic Mistral-7B-shaped decoder layer (7 "
                          "matrices, each to 50 %% of its bf16 footprint) and print seconds per layer")
+    ap.add_argument("--no-layer", action="store_true",
+                    help="headline only: skip the decoder-layer figure that the default run appends")
     ap.add_argument("--layer-fraction", type=float, default=1.0,
                     help="with --layer: run only this fraction of every matrix's width (the rest is extrapolated "
                          "and the line says so)")
@@ -336,7 +336,8 @@ def main() -> int:
                           "us_per_launch": round(sec * 1e6, 2)}))
         return 0
     if args.layer:
-        return layer_mode(args, scd, workloads, torch, np)
+        print(json.dumps(layer_mode(args, scd, workloads, torch, np)))
+        return 0
     if args.apply:
         return apply_mode(args, scd, torch)
     if args.lsq:
@@ -466,6 +467,12 @@ def main() -> int:
     }
     if args.cpu_seconds > 0:
         out["cpu_baseline"] = cpu_baseline(A64, seed, args.cpu_seconds)
+    if not args.no_layer and (m, n, w) == (4096, 4096, 8192):
+        # the metric's second figure: one decoder layer at the 50 % widths (its own timed region)
+        del A
+        lay = layer_mode(args, scd, workloads, torch, np)
+        out["layer"] = {k: lay[k] for k in ("metric", "value", "unit", "terms", "terms_per_s", "concurrency", "extrapolated")}
+        out["layer"]["matrix_seconds"] = {r["matrix"]: r["seconds"] for r in lay["matrices"]}
     print(json.dumps(out))
     return 0
 
