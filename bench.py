@@ -69,9 +69,7 @@ def layer_mode(args, scd, workloads, torch, np) -> dict:
         # them for the last one (a context can change its share between launches)
         with lock:
             n = max(1, busy[0])
-        sh = 256
-        while sh > 256 // n:
-            sh //= 2
+        sh = 256 // n
         return 0 if sh >= 256 else sh
 
     def worker():

@@ -87,7 +87,7 @@ void scd_destroy(scd_ctx* ctx);
 int scd_set_max_iters(scd_ctx* ctx, int32_t max_iters);
 
 /* Share of the device for this context: its persistent launches take at most `workgroups` workgroups
- * (one per compute unit; 16 or more, rounded down to a power of two; 0 = the whole device, the default).
+ * (one per compute unit; 16 or more; 0 = the whole device, the default).
  * The matrices of a model are decomposed independently of one another (Section 4.2), and one greedy
  * decomposition is bound by the latency of its alternations, not by bandwidth: contexts with a share,
  * driven from different host threads on different streams, run side by side and fill each other's

@@ -400,8 +400,7 @@ int setup_engines(scd_ctx* c)
         // line).  A context that was given a share of the device runs side by side with others, which
         // hides exactly that latency: it takes the sparse engine at any size.
         const double mib = (double)c->total * (double)c->esize / (1024.0 * 1024.0);
-        int grid = kSpGrid;
-        while (grid > limit) grid >>= 1;
+        const int grid = limit < kSpGrid ? limit : kSpGrid;
         const bool big = c->share > 0 || mib >= (double)env_int("SCD_SPARSE_MIN_MIB", 48);
         if (big && grid >= 1 && sparse_supported(c->dt, c->order, c->dims, grid, &c->rs, &c->cs)) {
             c->sparse = true;

@@ -163,7 +163,7 @@ struct SparseArgs {
     double* trace;
     int32_t mw, nw;
     int32_t rs, cs;          // rows / columns owned per workgroup (multiples of 8)
-    int32_t grid;            // workgroups of this launch (power of two, at most kSpGrid)
+    int32_t grid;            // workgroups of this launch (at most kSpGrid)
     int32_t profile;         // 1: workgroup 0 times its phases
     int32_t delay_width;     // > 0: finished terms wait in a list of this length before they are subtracted
     ResidentResult* res;

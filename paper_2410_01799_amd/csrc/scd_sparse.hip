@@ -7,7 +7,7 @@
 // matrix and its transpose so that both kinds of slices are contiguous; so does this engine (R and RT
 // in HBM, both updated when a term is subtracted).
 //
-// G workgroups (a power of two up to 256, one per compute unit: the whole device by default, a share
+// G workgroups (up to 256, one per compute unit: the whole device by default, a share
 // of it when several decompositions run side by side).  Workgroup g owns the slice I_g of the rows
 // (its entries of u = R t) and the slice J_g of the columns (its entries of v = R^T s), in f64.
 //   term start   dense: rows I_g of R   -> subtract the finished term (Algorithm 5 line 10), ||R||^2,
@@ -980,7 +980,7 @@ size_t sparse_lds_bytes(int64_t m, int64_t n, int delay_width)
 bool sparse_supported(scd_dtype dt, int order, const int64_t* dims, int grid, int* rs, int* cs)
 {
     if (order != 2) return false;
-    if (grid < 1 || grid > kSpGrid || (grid & (grid - 1))) return false;
+    if (grid < 1 || grid > kSpGrid) return false;
     const int64_t m = dims[0], n = dims[1];
     const int ve = dt == SCD_F32 ? 4 : 2;
     if (m % ve || n % ve) return false;               // rows of R and of RT start on 16-byte boundaries

@@ -95,9 +95,7 @@ def main() -> int:
             return 0
         with lock:
             n = max(1, busy[0])
-        sh = 256
-        while sh > 256 // n:
-            sh //= 2
+        sh = 256 // n
         return 0 if sh >= 256 else sh
 
     t_begin = time.perf_counter()

@@ -169,7 +169,7 @@ def test_sparse_iteration_cap_and_set_remainder(scd):
 # ---- a share of the device per context (several decompositions side by side)
 
 @pytest.mark.parametrize("m,n,w,share", [(1000, 4096, 10, 64), (2052, 516, 10, 128), (256, 256, 16, 16),
-                                         (4096, 4096, 6, 32), (100, 76, 12, 100)])
+                                         (4096, 4096, 6, 32), (100, 76, 12, 100), (2052, 516, 10, 85), (1000, 4096, 10, 51)])
 def test_share_matches_oracle(scd, oracle, m, n, w, share):
     run_and_check(scd, oracle, gauss((m, n), m + n + share), w, 13, share)
 
