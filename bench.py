@@ -172,7 +172,7 @@ def apply_mode(args, scd, torch) -> int:
         rows.append({"shape": [m, n], "width": w, "us_per_product": round(dt * 1e6, 1), "sign_bit_bytes": bits,
                      "sign_bits_gbs": round(bits / dt / 1e9, 1), "dense_f32_matvec_us": round(dg * 1e6, 1)})
     print(json.dumps({"metric": "microseconds per packed product y = (sum_j c_j s_j t_j^T) x", "unit": "us", "n_gpus": 1,
-                      "dtype": "f32 in/out, f64 sums", "data": "synthetic", "products": rows}))
+                      "dtype": "f32 in/out, int8 fixed-point sums joined in f64", "data": "synthetic", "products": rows}))
     return 0
 
 
@@ -290,7 +290,7 @@ def main() -> int:
     ap.add_argument("--layer-fraction", type=float, default=1.0,
                     help="with --layer: run only this fraction of every matrix's width (the rest is extrapolated "
                          "and the line says so)")
-    ap.add_argument("--concurrency", type=int, default=4, choices=[1, 2, 4, 8],
+    ap.add_argument("--concurrency", type=int, default=4, choices=list(range(1, 9)),
                     help="with --layer: matrices decomposed side by side, each on 256/K compute units")
     ap.add_argument("--apply", action="store_true",
                     help="instead of the headline: time the product of a decomposition with a vector from the "

@@ -176,9 +176,10 @@ int scd_decompose_scalars(const void* A, scd_dtype dt, int order, const int64_t*
  *   transpose == 0:  y = (sum_{j<w} c_j s_j t_j^T) x      x: n entries, y: m entries
  *   transpose != 0:  y = (sum_{j<w} c_j s_j t_j^T)^T x    x: m entries, y: n entries
  * computed as z_j = c_j <t_j, x> and y = sum_j z_j s_j, every sum in a fixed order, y rounded once to dt.
- * dt = SCD_F64: all sums in f64.  dt = SCD_F32: <t_j, x> is formed in block fixed point (each chunk of 4096
- * entries of x scaled by a power of two and rounded to integers below 2^30: at most max|x| 2^-30 per entry,
- * exact integer sums afterwards), the rest in f64.  Non-finite entries of x give NaN.  S, T: device, term-major bitsets as scd_decompose writes them (w * ceil(m/64) and
+ * dt = SCD_F64: all sums in f64.  dt = SCD_F32: both sums are formed in block fixed point (each chunk of 4096
+ * entries of x, and the z_j of each split of at most 2048 terms, scaled by a power of two and rounded to
+ * integers below 2^30: at most max|x| 2^-30 per entry and max|z| 2^-30 per term, exact integer sums
+ * afterwards), the rest in f64.  Non-finite entries of x give NaN.  S, T: device, term-major bitsets as scd_decompose writes them (w * ceil(m/64) and
  * w * ceil(n/64) words, padding bits 0); c, x, y: device, dtype dt; x and y must not overlap.
  * nvec >= 1 vectors are taken one after the other: x is nvec rows of the input length, y nvec rows of the
  * output length.  workspace: device, at least scd_apply_workspace_bytes(m, n, w) bytes, 8-byte aligned,

@@ -4,14 +4,15 @@
 // The matrix is never expanded: the kernels read the w (m + n) / 8 bytes of sign bits once and do one
 // select and one add per bit.
 //
-// On the vector units (inner pass for f64, outer pass) the step is: a wave owns 64 consecutive entries (one
-// per lane), takes a 64-bit word of sign bits that is the same for all its lanes (fetched by one lane,
+// f32: both passes are contractions of a +-1 matrix with a vector and run on the matrix cores in block
+// fixed point (see the two MFMA kernels).  f64: vector units; a wave owns 64 consecutive entries (one per
+// lane), takes a 64-bit word of sign bits that is the same for all its lanes (fetched by one lane,
 // broadcast through a scalar register), turns bit `lane` into a multiplier +-1.0 and adds with one fused
 // multiply-add in f64 (the product with +-1 is exact, so each step rounds like the sign-flip-and-add of
-// Section 3.4).  The inner pass for f32 runs on the matrix cores in fixed point (see there).
+// Section 3.4).
 //   inner pass  <t_j, x> per chunk of 4096 entries
-//   outer pass  lanes = 64 entries of y; z_j = c_j * (sum of the chunk parts, in order) is formed on the
-//               way in, and for every term of its split the wave adds +-z_j
+//   outer pass  z_j = c_j * (sum of the chunk parts, in order) is formed on the way in; per split of the
+//               terms, y_i = sum_j +-z_j
 //   reduce      y = sum of the splits, in order, rounded once to the output type
 // Every sum has a fixed order: results are bit-identical from run to run.
 #include "scd_device.h"
@@ -307,6 +308,182 @@ __global__ void __launch_bounds__(kApOuterWaves* kWave)
     ypart[split * (mw * 64) + p * 64 + lane] = (a4[0] + a4[1]) + (a4[2] + a4[3]);
 }
 
+// ------------------------------------------------------------------------------------------------
+// Outer pass on the matrix cores (f32).  y_i = sum_j z_j s_j[i] is the same kind of contraction as the
+// inner pass with the roles swapped: the terms are the contraction index and z plays the part of x (block
+// fixed point per split of the terms: |z| 2^s < 2^30, four balanced base-256 digits, at most
+// max|z| 2^-30 per term, exact sums afterwards).  The bitset is term-major, so the four signs an
+// instruction wants per lane (one output entry, four consecutive terms) sit in four different words:
+// a wave loads word p of 64 consecutive terms (one per lane) and transposes the 64 x 64 bits across
+// its lanes (six butterfly stages); lane i then holds the signs of output entry 64 p + i for the 64 terms,
+// packed along the contraction exactly as the inner pass has them.
+constexpr int kApFxMaxTerms = 2048;  // terms per split: one group of four per thread of the workgroup
+// digits of one kind are kApFxPitch words apart: the four that a wave reads together fall into different banks
+constexpr int kApFxPitch = kApFxMaxTerms / 4 + 4;
+
+// 64 x 64 bit transpose across a wave: lane q brings row q (bit i = column i), lane i leaves with column i.
+// Six butterfly stages (distance 32, 16, .., 1): in every 2s x 2s block the two off-diagonal s x s blocks
+// change places, the partner row is s lanes away.  The rows are kept as two 32-bit halves; below distance
+// 32 a stage is, per half, one lane exchange, one rotate (the partner's bits move s columns up in the
+// upper row, s down in the lower) and one bitfield insert.  Distances 1..8 stay within a row of 16 lanes
+// and use the data-parallel lane modes (no LDS traffic).
+template <int S>
+__device__ __forceinline__ uint32_t ap_lane_xor(uint32_t v)
+{
+    if constexpr (S == 1) return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0xB1, 0xF, 0xF, true);  // quad_perm 1,0,3,2
+    else if constexpr (S == 2) return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0x4E, 0xF, 0xF, true);  // quad_perm 2,3,0,1
+    else if constexpr (S == 4) {
+        // lane ^ 7 (mirror of half a row), then lane ^ 3 (quad_perm 3,2,1,0)
+        const int h = __builtin_amdgcn_mov_dpp((int)v, 0x141, 0xF, 0xF, true);
+        return (uint32_t)__builtin_amdgcn_mov_dpp(h, 0x1B, 0xF, 0xF, true);
+    } else if constexpr (S == 8) {
+        // lane ^ 15 (mirror of a row), then lane ^ 7
+        const int h = __builtin_amdgcn_mov_dpp((int)v, 0x140, 0xF, 0xF, true);
+        return (uint32_t)__builtin_amdgcn_mov_dpp(h, 0x141, 0xF, 0xF, true);
+    } else
+        return (uint32_t)__shfl_xor((int)v, S, kWave);
+}
+
+template <int S>
+__device__ __forceinline__ uint32_t ap_butterfly(uint32_t h, int lane)
+{
+    constexpr uint32_t m = S == 16 ? 0x0000FFFFu : S == 8 ? 0x00FF00FFu : S == 4 ? 0x0F0F0F0Fu : S == 2 ? 0x33333333u : 0x55555555u;
+    const bool lower = (lane & S) != 0;
+    const uint32_t p = ap_lane_xor<S>(h);
+    const uint32_t rot = __builtin_amdgcn_alignbit(p, p, lower ? S : 32 - S);  // partner >> S (lower row), << S (upper)
+    const uint32_t keep = lower ? ~m : m;
+    return (h & keep) | (rot & ~keep);
+}
+
+__device__ __forceinline__ uint64_t ap_transpose64(uint64_t x, int lane)
+{
+    uint32_t lo = (uint32_t)x, hi = (uint32_t)(x >> 32);
+    {
+        // distance 32: the upper rows take the partner's low half as their high half, the lower rows the
+        // partner's high half as their low half
+        const bool lower = (lane & 32) != 0;
+        const uint32_t got = (uint32_t)__shfl_xor((int)(lower ? lo : hi), 32, kWave);
+        lo = lower ? got : lo;
+        hi = lower ? hi : got;
+    }
+    lo = ap_butterfly<16>(lo, lane), hi = ap_butterfly<16>(hi, lane);
+    lo = ap_butterfly<8>(lo, lane), hi = ap_butterfly<8>(hi, lane);
+    lo = ap_butterfly<4>(lo, lane), hi = ap_butterfly<4>(hi, lane);
+    lo = ap_butterfly<2>(lo, lane), hi = ap_butterfly<2>(hi, lane);
+    lo = ap_butterfly<1>(lo, lane), hi = ap_butterfly<1>(hi, lane);
+    return ((uint64_t)hi << 32) | lo;
+}
+
+__global__ void __launch_bounds__(kApMfmaWaves* kWave)
+    apply_outer_mfma_kernel(const uint64_t* __restrict__ bits, int64_t mw, int64_t w, const double* __restrict__ part,
+                            int chunks, const float* __restrict__ c, int64_t terms_per_split, double* __restrict__ ypart)
+{
+    __shared__ __align__(16) int zd[4 * kApFxPitch];  // [digit][group of 4 terms]: 4 packed int8
+    __shared__ int lut[16];            // nibble -> 4 packed int8 signs
+    __shared__ double redmax[kApMfmaWaves];
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int wv = __builtin_amdgcn_readfirstlane(tid / kWave);
+    const int64_t p = (int64_t)blockIdx.x * kApMfmaWaves + wv;  // word of the output this wave owns
+    const int64_t pc = p < mw ? p : mw - 1;
+    const int64_t split = blockIdx.y;
+    const int64_t j0 = split * terms_per_split;
+    const int64_t j1 = j0 + terms_per_split < w ? j0 + terms_per_split : w;  // (the plan leaves no split empty)
+    // lane q fetches word p of term (tile + q); terms past the end re-read the last one (their z is zero)
+    auto fetch = [&](int64_t tile) {
+        const int64_t j = j0 + tile * kWave + lane;
+        return bits[(j < j1 ? j : j1 - 1) * mw + pc];
+    };
+    uint64_t next = fetch(0);
+
+    // ---- z of this split in fixed point: thread t owns the group of four terms t
+    double zv[4];
+    double amax = 0.0;
+    bool finite = true;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int64_t j = j0 + 4 * tid + k;
+        const int64_t jc = j < j1 ? j : j1 - 1;
+        double s = part[jc];
+        for (int q = 1; q < chunks; ++q) s += part[(int64_t)q * w + jc];
+        zv[k] = j < j1 ? (double)c[jc] * s : 0.0;
+        finite = finite && (fabs(zv[k]) <= 1.7e308);
+        amax = fmax(amax, fabs(zv[k]));
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) amax = fmax(amax, __shfl_xor(amax, off, kWave));
+    if (tid < 16) {
+        uint32_t v = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) v |= (((tid >> k) & 1) ? 0xFFu : 0x01u) << (8 * k);
+        lut[tid] = (int)v;
+    }
+    if (lane == 0) redmax[wv] = amax;
+    const bool all_finite = !__syncthreads_or(finite ? 0 : 1);
+    amax = 0.0;
+#pragma unroll
+    for (int q = 0; q < kApMfmaWaves; ++q) amax = fmax(amax, redmax[q]);
+    int ex = 0;
+    if (amax > 0.0) (void)frexp(amax, &ex);  // amax < 2^ex
+    int sh = 30 - ex;
+    sh = sh > 1000 ? 1000 : sh;              // (2^sh stays a normal number; smaller z round to zero)
+    const double scale = ldexp(1.0, sh), inv_scale = ldexp(1.0, -sh);
+    {
+        uint32_t dig[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            int q = all_finite ? (int)rint(zv[k] * scale) : 0;
+#pragma unroll
+            for (int jd = 0; jd < 3; ++jd) {
+                const int d = (int)(int8_t)(q & 0xFF);
+                dig[jd] |= (uint32_t)(d & 0xFF) << (8 * k);
+                q = (q - d) >> 8;
+            }
+            dig[3] |= (uint32_t)(q & 0xFF) << (8 * k);
+        }
+#pragma unroll
+        for (int jd = 0; jd < 4; ++jd) zd[jd * kApFxPitch + tid] = (int)dig[jd];
+    }
+    __syncthreads();
+    if (p >= mw) return;  // (no workgroup-wide barrier below)
+
+    const int jd = lane & 3;
+    const int ntiles = (int)((j1 - j0 + kWave - 1) / kWave);
+    ap_int4 acc0 = {0, 0, 0, 0}, acc1 = {0, 0, 0, 0};
+    for (int t = 0; t < ntiles; ++t) {
+        const uint64_t mine = next;
+        if (t + 1 < ntiles) next = fetch(t + 1);
+        const uint64_t col = ap_transpose64(mine, lane);  // bit q: sign of term (tile + q) at this lane's entry
+        const uint32_t half[2] = {(uint32_t)col, (uint32_t)(col >> 32)};
+        // this lane's digit of the tile's 16 groups of four terms (four 16-byte reads)
+        const ap_int4* zq = (const ap_int4*)(zd + jd * kApFxPitch + t * 16);
+        int zg[16];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const ap_int4 v = zq[q];
+            zg[4 * q] = v[0], zg[4 * q + 1] = v[1], zg[4 * q + 2] = v[2], zg[4 * q + 3] = v[3];
+        }
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+            const uint32_t hw = half[q >> 3];
+            const int s4 = 4 * (q & 7);
+            const uint32_t off = s4 >= 2 ? ((hw >> (s4 - 2)) & 0x3Cu) : ((hw << 2) & 0x3Cu);
+            const int a = *(const int*)((const char*)lut + off);
+            if (q & 1) acc1 = __builtin_amdgcn_mfma_i32_4x4x4i8(a, zg[q], acc1, 0, 0, 0);
+            else acc0 = __builtin_amdgcn_mfma_i32_4x4x4i8(a, zg[q], acc0, 0, 0, 0);
+        }
+    }
+    // D register i = output entry 64 p + 4 (lane / 4) + i, digit (lane % 4): recombine the digits (exact in f64)
+    const double digit_weight = (double)(1u << (8 * jd));
+    double* out = ypart + split * (mw * 64) + p * 64 + 4 * (lane >> 2);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        double v = (double)(acc0[i] + acc1[i]) * digit_weight;
+        v += __shfl_xor(v, 1, kWave);
+        v += __shfl_xor(v, 2, kWave);
+        if (jd == 0) out[i] = all_finite ? v * inv_scale : __longlong_as_double(0x7FF8000000000000ll);
+    }
+}
+
 // y = sum of the splits in order, rounded once.  64 entries per workgroup; the splits are cut into four
 // runs that are added side by side (their loads in flight together) and joined in order.
 template <typename TE>
@@ -354,10 +531,27 @@ void apply_plan(int64_t nin, int64_t nout, int64_t w, ApplyPlan* pl)
     if (pl->terms_per_split < 1) pl->terms_per_split = 1;
     pl->splits = (int)((w + pl->terms_per_split - 1) / pl->terms_per_split);
     if (pl->splits < 1) pl->splits = 1;
+    // outer pass in fixed point (f32): a workgroup takes 8 words of the output and one split of the terms
+    // (whole tiles of 64, at most kApFxMaxTerms); two to four workgroups per compute unit
+    {
+        const int64_t gx = (wout + kApMfmaWaves - 1) / kApMfmaWaves;
+        const int64_t target = gx >= 16 ? 1024 : 512;
+        int64_t want = gx > 0 ? (target + gx - 1) / gx : 1;
+        const int64_t least = (w + kApFxMaxTerms - 1) / kApFxMaxTerms, most = (w + kWave - 1) / kWave;
+        if (want > most) want = most;
+        if (want < least) want = least;
+        if (want < 1) want = 1;
+        int64_t tps = ((w + want - 1) / want + kWave - 1) / kWave * kWave;
+        if (tps < kWave) tps = kWave;
+        pl->terms_per_split_fx = tps;
+        pl->splits_fx = (int)((w + tps - 1) / tps);
+        if (pl->splits_fx < 1) pl->splits_fx = 1;
+    }
     pl->off_part = 0;
     pl->parts = pl->chunks;  // slices of <t_j, x> the inner pass writes per term
     pl->off_ypart = pl->off_part + (size_t)pl->parts * (size_t)w * 8;
-    pl->bytes = pl->off_ypart + (size_t)pl->splits * (size_t)wout * 64 * 8;
+    const int most_splits = pl->splits > pl->splits_fx ? pl->splits : pl->splits_fx;
+    pl->bytes = pl->off_ypart + (size_t)most_splits * (size_t)wout * 64 * 8;
     if (pl->bytes < 8) pl->bytes = 8;
 }
 
@@ -394,15 +588,16 @@ hipError_t launch_apply(const uint64_t* in_bits, const uint64_t* out_bits, const
         hipLaunchKernelGGL((apply_inner_kernel<double>), gi, dim3(kApInnerWaves * kWave), 0, st, in_bits, win, w,
                            (const double*)x, nin, part, pl.terms_per_wave);
     dim3 go((unsigned)((wout + kApOuterWaves - 1) / kApOuterWaves), (unsigned)pl.splits);
-    if (dt == SCD_F32)
-        hipLaunchKernelGGL((apply_outer_kernel<float>), go, dim3(kApOuterWaves * kWave), 0, st, out_bits, wout, w, part,
-                           pl.parts, (const float*)c, pl.terms_per_split, ypart);
-    else
+    if (dt == SCD_F32) {
+        dim3 gf((unsigned)((wout + kApMfmaWaves - 1) / kApMfmaWaves), (unsigned)pl.splits_fx);
+        hipLaunchKernelGGL(apply_outer_mfma_kernel, gf, dim3(kApMfmaWaves * kWave), 0, st, out_bits, wout, w, part, pl.parts,
+                           (const float*)c, pl.terms_per_split_fx, ypart);
+    } else
         hipLaunchKernelGGL((apply_outer_kernel<double>), go, dim3(kApOuterWaves * kWave), 0, st, out_bits, wout, w, part,
                            pl.parts, (const double*)c, pl.terms_per_split, ypart);
     const unsigned gr = (unsigned)((nout + 63) / 64);
     if (dt == SCD_F32)
-        hipLaunchKernelGGL((apply_reduce_kernel<float>), dim3(gr), dim3(256), 0, st, ypart, pl.splits, wout * 64, nout, (float*)y);
+        hipLaunchKernelGGL((apply_reduce_kernel<float>), dim3(gr), dim3(256), 0, st, ypart, pl.splits_fx, wout * 64, nout, (float*)y);
     else
         hipLaunchKernelGGL((apply_reduce_kernel<double>), dim3(gr), dim3(256), 0, st, ypart, pl.splits, wout * 64, nout, (double*)y);
     return hipGetLastError();

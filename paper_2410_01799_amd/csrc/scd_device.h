@@ -182,6 +182,8 @@ struct ApplyPlan {
     int terms_per_wave;       // inner pass
     int splits;               // outer pass: parts the terms are split into
     int64_t terms_per_split;
+    int splits_fx;            // outer pass in fixed point (f32): splits of whole tiles of 64 terms
+    int64_t terms_per_split_fx;
     size_t off_part, off_ypart, bytes;  // workspace layout
 };
 void apply_plan(int64_t nin, int64_t nout, int64_t w, ApplyPlan* pl);

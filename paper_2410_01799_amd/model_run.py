@@ -73,7 +73,7 @@ def main() -> int:
     ap.add_argument("--stop", type=int, default=226)
     ap.add_argument("--out", type=str, required=True)
     ap.add_argument("--budget-seconds", type=float, default=1e9, help="take no new matrix that would overrun")
-    ap.add_argument("--concurrency", type=int, default=1, choices=[1, 2, 4, 8],
+    ap.add_argument("--concurrency", type=int, default=1, choices=list(range(1, 9)),
                     help="matrices decomposed side by side, the compute units split evenly among those in flight "
                          "(the matrices of a model are independent, and one decomposition is latency-bound)")
     ap.add_argument("--chunk", type=int, default=1024, help="terms per launch when matrices run side by side")

@@ -31,6 +31,14 @@ def random_factors(m, n, w, seed, dtype):
     return S, T, c
 
 
+def fixed_point_tol(c64, x64, nin, w):
+    """Bound on what the two block fixed points of the f32 path may cost (independent roundings: of the order
+    of the square root of their number; 4 times that is far above it and far below a lost digit)."""
+    zmax = float(np.abs(c64).max(initial=0.0) * np.abs(x64).sum())
+    return (4.0 * np.sqrt(nin) * float(np.abs(x64).max(initial=0.0)) * 2.0 ** -30 * float(np.abs(c64).sum())
+            + 4.0 * np.sqrt(max(w, 1)) * zmax * 2.0 ** -30)
+
+
 def dev_bits(a):
     return torch.from_numpy(a.view(np.int64).copy()).cuda()
 
@@ -51,11 +59,13 @@ def check(scd, oracle, m, n, w, seed, dtype, transpose, nvec=1):
         # largest entry of its chunk of 4096 (at most max|x| 2^-30 per entry, exact sums afterwards), the rest
         # is f64; the result is rounded once to f32.  The roundings are independent, so their sum over a row is
         # of the order sqrt(n) of them; 4 sqrt(n) is far above that and far below what a lost digit would cost.
+        # The sum over the terms is formed the same way: z_j = c_j <t_j, x> is rounded to 30 bits below the
+        # largest |z| of its split of the terms (|z_j| <= |c_j| sum|x|), exact sums afterwards.
         c64, x64 = c.astype(np.float64), x[v].astype(np.float64)
         zabs = float(np.abs(c64).sum() * np.abs(x64).sum())
         tol = 1e-13 * zabs
         if dtype == np.float32:
-            tol = tol + 4.0 * np.sqrt(nin) * float(np.abs(x64).max()) * 2.0 ** -30 * float(np.abs(c64).sum()) + 2.0 ** -23 * np.abs(ref)
+            tol = tol + fixed_point_tol(c64, x64, nin, w) + 2.0 ** -23 * np.abs(ref)
         assert np.all(np.abs(y[v] - ref) <= tol + 1e-300), (m, n, w, transpose, float(np.abs(y[v] - ref).max()))
 
 
@@ -76,12 +86,12 @@ def test_apply_scales_of_x(scd, oracle):
         x = (rs.standard_normal(n) * scale).astype(np.float32)
         y = scd.scd_apply(dev_bits(S), dev_bits(T), torch.from_numpy(c).cuda(), m, n, torch.from_numpy(x).cuda())
         ref = oracle.apply(S, T, c.astype(np.float64), m, n, x.astype(np.float64))
-        tol = 4.0 * np.sqrt(n) * float(np.abs(x).max()) * 2.0 ** -30 * float(np.abs(c).sum()) + 2.0 ** -23 * np.abs(ref)
+        tol = fixed_point_tol(c.astype(np.float64), x.astype(np.float64), n, w) + 2.0 ** -23 * np.abs(ref)
         assert np.all(np.abs(y.cpu().numpy().astype(np.float64) - ref) <= tol)
     x = (rs.standard_normal(n) * 10.0 ** rs.uniform(-6, 0, n)).astype(np.float32)
     y = scd.scd_apply(dev_bits(S), dev_bits(T), torch.from_numpy(c).cuda(), m, n, torch.from_numpy(x).cuda())
     ref = oracle.apply(S, T, c.astype(np.float64), m, n, x.astype(np.float64))
-    tol = 4.0 * np.sqrt(n) * float(np.abs(x).max()) * 2.0 ** -30 * float(np.abs(c).sum()) + 2.0 ** -23 * np.abs(ref)
+    tol = fixed_point_tol(c.astype(np.float64), x.astype(np.float64), n, w) + 2.0 ** -23 * np.abs(ref)
     assert np.all(np.abs(y.cpu().numpy().astype(np.float64) - ref) <= tol)
 
 
