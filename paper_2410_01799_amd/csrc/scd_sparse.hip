@@ -30,7 +30,7 @@ namespace {
 constexpr int kSpThreads = 512;
 constexpr int kSpWaves = kSpThreads / kWave;
 constexpr int kSpPayload = 16;                    // payload words per slot (32 sign bits each)
-constexpr int kSpSlotUsed = kSpPayload + 4;       // + two doubles as four tagged halves
+constexpr int kSpSlotUsed = kSpPayload + 2;       // + one double as two tagged halves
 // Every workgroup reads every slot: slots 4 KB apart land on different memory channels, so that the
 // 256 x 256 reads of one exchange do not queue up at a handful of them.
 constexpr int kSpSlot = 512;
@@ -111,7 +111,7 @@ __device__ void sp_dense_rows(TE* __restrict__ Y, int64_t ld, int64_t row0, int 
                               const uint32_t* colbits_sum, double* acc, double& fsq_out, double* red)
 {
     constexpr int VE = SpVec<TE>::N;
-    constexpr int RB = 4;
+    constexpr int RB = 8;
     typedef typename SpVec<TE>::type V;
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
     const int64_t nch = ld / VE;
@@ -183,6 +183,23 @@ __device__ void sp_dense_rows(TE* __restrict__ Y, int64_t ld, int64_t row0, int 
     __syncthreads();
 }
 
+// part + the signed entries of flips f, f + Q, .., f + (Z - 1) Q of the list (those below total), added in
+// that order; every load is issued before the first add
+template <typename TE, int Z>
+__device__ __forceinline__ double sp_gather_batch(const TE* __restrict__ ycol, int64_t ld, int64_t ibase, const uint16_t* list,
+                                                  int f, int Q, int total, double part)
+{
+    uint16_t en[Z];
+    TE val[Z];
+#pragma unroll
+    for (int z = 0; z < Z; ++z) en[z] = f + z * Q < total ? list[f + z * Q] : (uint16_t)0;
+#pragma unroll
+    for (int z = 0; z < Z; ++z) val[z] = ycol[(ibase + (en[z] & 0x3FFF)) * ld];
+#pragma unroll
+    for (int z = 0; z < Z; ++z) part += f + z * Q < total ? (double)sp_flip(val[z], (uint32_t)(en[z] >> 15)) : 0.0;
+    return part;
+}
+
 // acc[e] += 2 * sum over the indices i whose sign changed (cur xor prev) of sign_cur(i) * Y[i][off + e],
 // e < len.  Flipped indices are compacted in ascending order, one 32-bit word of sign bits per thread
 // and round, and every thread adds its share of the list in order.
@@ -227,46 +244,27 @@ __device__ void sp_accumulate_flips(const TE* __restrict__ Y, int64_t ld, int64_
         }
         __syncthreads();
         nflips += total;
-        // ---- gather: thread (e, q) takes flips q, q+Q, ... ; four loads in flight
+        // ---- gather: thread (e, q) takes flips q, q+Q, ... in order.  All loads of a batch are issued before
+        // the first is used, and the batch is sized to what is left (16, 8, 4 or 2 per thread), so a round
+        // of up to 16 Q flips costs one trip to memory; slots past the end re-read a valid row and add zero.
         if (active) {
             const int64_t ibase = w0 * 32;
-            int f = q;
-            for (; f + 7 * Q < total; f += 8 * Q) {
-                uint16_t en[8];
-                TE val[8];
-#pragma unroll
-                for (int z = 0; z < 8; ++z) en[z] = sh.list[f + z * Q];
-#pragma unroll
-                for (int z = 0; z < 8; ++z) val[z] = ycol[(ibase + (en[z] & 0x3FFF)) * ld];
-#pragma unroll
-                for (int z = 0; z < 8; ++z) part += (double)sp_flip(val[z], (uint32_t)(en[z] >> 15));
-            }
-            if (f + 3 * Q < total) {
-                uint16_t en[4];
-                TE val[4];
-#pragma unroll
-                for (int z = 0; z < 4; ++z) en[z] = sh.list[f + z * Q];
-#pragma unroll
-                for (int z = 0; z < 4; ++z) val[z] = ycol[(ibase + (en[z] & 0x3FFF)) * ld];
-#pragma unroll
-                for (int z = 0; z < 4; ++z) part += (double)sp_flip(val[z], (uint32_t)(en[z] >> 15));
-                f += 4 * Q;
-            }
-            {
-                // the last (at most three) flips of this thread, loaded together
-                uint16_t en[3];
-                TE val[3];
-#pragma unroll
-                for (int z = 0; z < 3; ++z) en[z] = f + z * Q < total ? sh.list[f + z * Q] : (uint16_t)0;
-#pragma unroll
-                for (int z = 0; z < 3; ++z) val[z] = f + z * Q < total ? ycol[(ibase + (en[z] & 0x3FFF)) * ld] : (TE)0;
-#pragma unroll
-                for (int z = 0; z < 3; ++z) part += (double)sp_flip(val[z], (uint32_t)(en[z] >> 15));
-                f += 3 * Q;
-            }
-            for (; f < total; f += Q) {
-                const uint16_t en = sh.list[f];
-                part += (double)sp_flip(ycol[(ibase + (en & 0x3FFF)) * ld], (uint32_t)(en >> 15));
+            int f0 = 0;
+            while (f0 < total) {
+                const int left = (total - f0 + Q - 1) / Q;  // loads the busiest thread still has to make
+                if (left > 8) {
+                    part = sp_gather_batch<TE, 16>(ycol, ld, ibase, sh.list, f0 + q, Q, total, part);
+                    f0 += 16 * Q;
+                } else if (left > 4) {
+                    part = sp_gather_batch<TE, 8>(ycol, ld, ibase, sh.list, f0 + q, Q, total, part);
+                    f0 += 8 * Q;
+                } else if (left > 2) {
+                    part = sp_gather_batch<TE, 4>(ycol, ld, ibase, sh.list, f0 + q, Q, total, part);
+                    f0 += 4 * Q;
+                } else {
+                    part = sp_gather_batch<TE, 2>(ycol, ld, ibase, sh.list, f0 + q, Q, total, part);
+                    f0 += 2 * Q;
+                }
             }
         }
     }
@@ -286,13 +284,13 @@ __device__ __forceinline__ void sp_store_tagged(uint64_t* p, uint32_t v, uint32_
     __hip_atomic_store(p, ((uint64_t)seq << 32) | (uint64_t)v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Publish this workgroup's slice of sign bits (taken from acc < 0) and two scalars, then read every
+// Publish this workgroup's slice of sign bits (taken from acc < 0) and, if asked, one scalar, then read every
 // workgroup's: the full bit vector lands in `dest`, the scalars in sh.scal.  Returns false on time-out.
 // `fence`: this exchange also hands over ordinary data (the rows of R or RT this workgroup has just
 // rewritten): the writes are released to the whole device before anything is published, and the
 // caches are invalidated after the gather, because the L2 of one XCD does not see another's writes.
 __device__ bool sp_exchange(const SparseArgs& a, uint32_t seq, const double* acc, int len, int slice, int64_t total_bits,
-                            double sc0, double sc1, uint32_t* dest, SpShared& sh, int& spins, bool fence)
+                            double sc0, bool has_scalar, uint32_t* dest, SpShared& sh, int& spins, bool fence)
 {
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
     const int g = blockIdx.x;
@@ -311,27 +309,31 @@ __device__ bool sp_exchange(const SparseArgs& a, uint32_t seq, const double* acc
             if (b + 32 < slice) sp_store_tagged(mine + (b >> 5) + 1, (uint32_t)(bal >> 32), seq);
         }
     }
-    if (tid == kSpThreads - 1) {
-        const uint64_t b0 = (uint64_t)__double_as_longlong(sc0), b1 = (uint64_t)__double_as_longlong(sc1);
+    if (has_scalar && tid == kSpThreads - 1) {
+        const uint64_t b0 = (uint64_t)__double_as_longlong(sc0);
         sp_store_tagged(mine + kSpPayload + 0, (uint32_t)b0, seq);
         sp_store_tagged(mine + kSpPayload + 1, (uint32_t)(b0 >> 32), seq);
-        sp_store_tagged(mine + kSpPayload + 2, (uint32_t)b1, seq);
-        sp_store_tagged(mine + kSpPayload + 3, (uint32_t)(b1 >> 32), seq);
     }
     for (int d = 0; d < a.poll_delay; ++d) __builtin_amdgcn_s_sleep(1);
-    // ---- gather: (words + 4) items from each of the a.grid members, spread over the threads
-    const int per = words + 4;
+    // ---- gather: the payload words (+ the two halves of the scalar) of each of the a.grid members, spread
+    // over the threads.  Every workgroup polls every slot and every word read or written is a trip through
+    // the fabric, so a word that is not needed is not sent: an exchange without a scalar took 5.9 us with the
+    // two unused scalars of an earlier layout in it and takes 2.9 us without (14336 x 4096, 256 workgroups).
+    const int per = words + (has_scalar ? 2 : 0);
     const int items = a.grid * per;
     uint64_t w[kSpMaxItems];
     const uint64_t* xb = a.xbuf + (size_t)(seq & 1u) * kSpGrid * kSpSlot;
     bool ok = true;
     int spin = 0;
+#pragma unroll
+    for (int it = 0; it < kSpMaxItems; ++it) w[it] = (uint64_t)(~seq) << 32;  // a tag that is not the current one
     for (;;) {
         bool fresh = true;
+        // only the words that have not arrived yet are read again
 #pragma unroll
         for (int it = 0; it < kSpMaxItems; ++it) {
             const int idx = tid + it * kSpThreads;
-            if (idx < items) {
+            if (idx < items && (uint32_t)(w[it] >> 32) != seq) {
                 const int mem = idx / per, k = idx - mem * per;
                 const int word = k < words ? k : kSpPayload + (k - words);
                 w[it] = __hip_atomic_load(xb + (size_t)mem * kSpSlot + word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -367,8 +369,7 @@ __device__ bool sp_exchange(const SparseArgs& a, uint32_t seq, const double* acc
                     for (int b = 0; b < 4; ++b)
                         if (4 * k + b < sbytes && b0 + b < tbytes) dbytes[b0 + b] = (uint8_t)(v >> (8 * b));
                 } else {
-                    const int z = k - words;  // 0,1: first scalar lo/hi; 2,3: second
-                    sh.scal[((z >> 1) * kSpGrid + mem) * 2 + (z & 1)] = v;
+                    sh.scal[mem * 2 + (k - words)] = v;  // low, high half of the scalar
                 }
             }
         }
@@ -377,13 +378,13 @@ __device__ bool sp_exchange(const SparseArgs& a, uint32_t seq, const double* acc
 }
 
 // Sum of one gathered scalar over the members, in a fixed order; every thread gets the same bits.
-__device__ double sp_sum_scalar(const SpShared& sh, int which, double* scratch, int grid)
+__device__ double sp_sum_scalar(const SpShared& sh, double* scratch, int grid)
 {
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     if (tid < kWave) {
         double s = 0.0;
         for (int g = lane; g < grid; g += kWave) {
-            const uint32_t lo = sh.scal[(which * kSpGrid + g) * 2], hi = sh.scal[(which * kSpGrid + g) * 2 + 1];
+            const uint32_t lo = sh.scal[g * 2], hi = sh.scal[g * 2 + 1];
             s += __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
         }
         s = sp_wave_sum(s);
@@ -475,13 +476,13 @@ __global__ void __launch_bounds__(kSpThreads) sparse_kernel(SparseArgs a)
         // rows I_g of R: R <- R - ck s t^T (Algorithm 5 line 10), squares, u = R t_0 (Algorithm 4 line 5)
         if (rlen > 0) sp_dense_rows<TE>(R, n, i0, rlen, pending, s_cur, t_cur, ckt, t_oth, sh.accu, fsq, sh.red);
         const bool was_pending = pending;
-        if (!sp_exchange(a, ++seq, sh.accu, rlen, rs, m, fsq, 0.0, s_oth, sh, spins, was_pending)) {
+        if (!sp_exchange(a, ++seq, sh.accu, rlen, rs, m, fsq, true, s_oth, sh, spins, was_pending)) {
             if (tid == 0) atomicExch((unsigned*)&a.res->err, 1u);
             return;
         }
         ++alternations;
         if (pending) {
-            const double F = sp_sum_scalar(sh, 0, sh.red, a.grid);
+            const double F = sp_sum_scalar(sh, sh.red, a.grid);
             if (g == 0 && tid == 0) a.trace[k] = sqrt(F);
         }
         // rows J_g of RT (columns of R): same update, v = R^T s_1 (Algorithm 4 line 6)
@@ -510,7 +511,7 @@ __global__ void __launch_bounds__(kSpThreads) sparse_kernel(SparseArgs a)
             double cpart = 0.0;
             for (int q = 0; q < kSpWaves; ++q) cpart += sh.red[q];
             __syncthreads();
-            if (!sp_exchange(a, ++seq, sh.accv, clen, cs, n, cpart, 0.0, t_oth, sh, spins, handover)) {
+            if (!sp_exchange(a, ++seq, sh.accv, clen, cs, n, cpart, true, t_oth, sh, spins, handover)) {
                 if (tid == 0) atomicExch((unsigned*)&a.res->err, 1u);
                 return;
             }
@@ -520,7 +521,7 @@ __global__ void __launch_bounds__(kSpThreads) sparse_kernel(SparseArgs a)
             }
             ++j;
             SP_TICK(1)
-            const double c = sp_sum_scalar(sh, 0, sh.red, a.grid);
+            const double c = sp_sum_scalar(sh, sh.red, a.grid);
             // ---- Algorithm 4 line 8
             if (c <= c_prev || j >= a.max_iters) {
                 if (!(c <= c_prev)) warn = 1;
@@ -546,7 +547,7 @@ __global__ void __launch_bounds__(kSpThreads) sparse_kernel(SparseArgs a)
             SP_TICK(2)
             sp_accumulate_flips<TE>(RT, m, i0, rlen, t_cur, t_oth, n, sh.accu, sh, flips);
             SP_TICK(3)
-            if (!sp_exchange(a, ++seq, sh.accu, rlen, rs, m, 0.0, 0.0, s_oth, sh, spins, false)) {
+            if (!sp_exchange(a, ++seq, sh.accu, rlen, rs, m, 0.0, false, s_oth, sh, spins, false)) {
                 if (tid == 0) atomicExch((unsigned*)&a.res->err, 1u);
                 return;
             }
@@ -832,13 +833,13 @@ __global__ void __launch_bounds__(kSpThreads) sparse_delay_kernel(SparseArgs a)
             sp_pending_dots(pd.PT, pd.pt_stride, (int)nwords32, n, t_oth, np, width, pd.coef, pd.ej);
             sp_effective(sh.accu, rlen, own_u, pd.ej, width, pd.effu);
         }
-        if (!sp_exchange(a, ++seq, pd.effu, rlen, rs, m, fsq, 0.0, s_oth, sh, spins, flush)) {
+        if (!sp_exchange(a, ++seq, pd.effu, rlen, rs, m, fsq, flush, s_oth, sh, spins, flush)) {
             if (tid == 0) atomicExch((unsigned*)&a.res->err, 1u);
             return;
         }
         ++alternations;
         if (flush) {
-            F = sp_sum_scalar(sh, 0, sh.red, a.grid);  // measured again
+            F = sp_sum_scalar(sh, sh.red, a.grid);  // measured again
             if (g == 0 && tid == 0) a.trace[k] = sqrt(F);
         }
         // rows J_g of the transposed copy: v = R^T s_1 (Algorithm 4 line 6)
@@ -875,7 +876,7 @@ __global__ void __launch_bounds__(kSpThreads) sparse_delay_kernel(SparseArgs a)
             double cpart = 0.0;
             for (int q = 0; q < kSpWaves; ++q) cpart += sh.red[q];
             __syncthreads();
-            if (!sp_exchange(a, ++seq, pd.effv, clen, cs, n, cpart, 0.0, t_oth, sh, spins, handover)) {
+            if (!sp_exchange(a, ++seq, pd.effv, clen, cs, n, cpart, true, t_oth, sh, spins, handover)) {
                 if (tid == 0) atomicExch((unsigned*)&a.res->err, 1u);
                 return;
             }
@@ -884,7 +885,7 @@ __global__ void __launch_bounds__(kSpThreads) sparse_delay_kernel(SparseArgs a)
                 uint32_t* z = t_cur; t_cur = t_oth; t_oth = z;
             }
             ++j;
-            const double c = sp_sum_scalar(sh, 0, sh.red, a.grid);
+            const double c = sp_sum_scalar(sh, sh.red, a.grid);
             // ---- Algorithm 4 line 8
             if (c <= c_prev || j >= a.max_iters) {
                 if (!(c <= c_prev)) warn = 1;
@@ -921,7 +922,7 @@ __global__ void __launch_bounds__(kSpThreads) sparse_delay_kernel(SparseArgs a)
             sp_accumulate_flips<TE>(RT, m, i0, rlen, t_cur, t_oth, n, sh.accu, sh, flips);
             sp_pending_dots(pd.PT, pd.pt_stride, (int)nwords32, n, t_cur, np, width, pd.coef, pd.ej);
             sp_effective(sh.accu, rlen, own_u, pd.ej, width, pd.effu);
-            if (!sp_exchange(a, ++seq, pd.effu, rlen, rs, m, 0.0, 0.0, s_oth, sh, spins, false)) {
+            if (!sp_exchange(a, ++seq, pd.effu, rlen, rs, m, 0.0, false, s_oth, sh, spins, false)) {
                 if (tid == 0) atomicExch((unsigned*)&a.res->err, 1u);
                 return;
             }
