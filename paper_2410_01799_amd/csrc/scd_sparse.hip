@@ -36,7 +36,10 @@ constexpr int kSpSlotUsed = kSpPayload + 2;       // + one double as two tagged 
 constexpr int kSpSlot = 512;
 constexpr int kSpListCap = 32 * kSpThreads;       // flips handled per compaction round: one 32-bit word per thread
 constexpr size_t kSpMaxLds = 150 * 1024;          // most dynamic LDS a launch may ask for
-constexpr int kSpMaxItems = (kSpGrid * kSpSlotUsed + kSpThreads - 1) / kSpThreads;
+// Words a thread may have to gather: grid * (ceil(slice / 32) + 2) over the supported pairs, where
+// grid * slice <= 65536 + 8 * grid: at most 67584 / 32 + 256 + 512 = 2880 words for the 512 threads
+// (sparse_supported checks it).
+constexpr int kSpMaxItems = 6;
 
 __device__ __forceinline__ uint64_t sp_mix64(uint64_t z)
 {
@@ -268,12 +271,17 @@ __device__ void sp_accumulate_flips(const TE* __restrict__ Y, int64_t ld, int64_
             }
         }
     }
+    // the lanes of a wave that hold the same entry are joined first (their groups in ascending order of the
+    // distance), then the waves in order
+    for (int d = slp; d < kWave; d <<= 1) part += __shfl_xor(part, d, kWave);
     __syncthreads();
-    sh.red[tid] = part;
+    if (slp >= kWave) sh.red[tid] = part;
+    else if (lane < slp) sh.red[wv * slp + e] = part;
     __syncthreads();
     if (tid < len) {
+        const int groups = slp >= kWave ? Q : kSpWaves;
         double s = 0.0;
-        for (int z = 0; z < Q; ++z) s += sh.red[z * slp + tid];
+        for (int z = 0; z < groups; ++z) s += sh.red[z * slp + tid];
         acc[tid] += 2.0 * s;
     }
     __syncthreads();
@@ -322,28 +330,34 @@ __device__ bool sp_exchange(const SparseArgs& a, uint32_t seq, const double* acc
     const int per = words + (has_scalar ? 2 : 0);
     const int items = a.grid * per;
     uint64_t w[kSpMaxItems];
+    // where this thread's words lie (member * kSpSlot + word; -1: none), worked out once.  item / per by a
+    // float product: (item + 0.5) / per is at least 0.5 / 18 away from an integer, items stay below 4608.
+    int where[kSpMaxItems];
+    {
+        const float rper = 1.0f / (float)per;
+#pragma unroll
+        for (int it = 0; it < kSpMaxItems; ++it) {
+            const int idx = tid + it * kSpThreads;
+            const int mem = (int)(((float)idx + 0.5f) * rper), k = idx - mem * per;
+            const int word = k < words ? k : kSpPayload + (k - words);
+            where[it] = idx < items ? mem * kSpSlot + word : -1;
+        }
+    }
     const uint64_t* xb = a.xbuf + (size_t)(seq & 1u) * kSpGrid * kSpSlot;
     bool ok = true;
     int spin = 0;
 #pragma unroll
-    for (int it = 0; it < kSpMaxItems; ++it) w[it] = (uint64_t)(~seq) << 32;  // a tag that is not the current one
+    for (int it = 0; it < kSpMaxItems; ++it) w[it] = (uint64_t)(where[it] >= 0 ? ~seq : seq) << 32;  // missing: not the current tag
     for (;;) {
         bool fresh = true;
         // only the words that have not arrived yet are read again
 #pragma unroll
         for (int it = 0; it < kSpMaxItems; ++it) {
-            const int idx = tid + it * kSpThreads;
-            if (idx < items && (uint32_t)(w[it] >> 32) != seq) {
-                const int mem = idx / per, k = idx - mem * per;
-                const int word = k < words ? k : kSpPayload + (k - words);
-                w[it] = __hip_atomic_load(xb + (size_t)mem * kSpSlot + word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
+            if ((uint32_t)(w[it] >> 32) != seq)
+                w[it] = __hip_atomic_load(xb + where[it], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
 #pragma unroll
-        for (int it = 0; it < kSpMaxItems; ++it) {
-            const int idx = tid + it * kSpThreads;
-            if (idx < items) fresh = fresh && ((uint32_t)(w[it] >> 32) == seq);
-        }
+        for (int it = 0; it < kSpMaxItems; ++it) fresh = fresh && ((uint32_t)(w[it] >> 32) == seq);
         if (fresh) break;
         if (++spin > a.max_spin) {
             ok = false;
@@ -359,17 +373,16 @@ __device__ bool sp_exchange(const SparseArgs& a, uint32_t seq, const double* acc
         const int64_t tbytes = (total_bits + 7) >> 3;
 #pragma unroll
         for (int it = 0; it < kSpMaxItems; ++it) {
-            const int idx = tid + it * kSpThreads;
-            if (idx < items) {
-                const int mem = idx / per, k = idx - mem * per;
+            if (where[it] >= 0) {
+                const int mem = where[it] / kSpSlot, word = where[it] % kSpSlot;  // (kSpSlot is a power of two)
                 const uint32_t v = (uint32_t)w[it];
-                if (k < words) {
-                    const int64_t b0 = (int64_t)mem * sbytes + 4 * k;
+                if (word < kSpPayload) {
+                    const int64_t b0 = (int64_t)mem * sbytes + 4 * word;
 #pragma unroll
                     for (int b = 0; b < 4; ++b)
-                        if (4 * k + b < sbytes && b0 + b < tbytes) dbytes[b0 + b] = (uint8_t)(v >> (8 * b));
+                        if (4 * word + b < sbytes && b0 + b < tbytes) dbytes[b0 + b] = (uint8_t)(v >> (8 * b));
                 } else {
-                    sh.scal[mem * 2 + (k - words)] = v;  // low, high half of the scalar
+                    sh.scal[mem * 2 + (word - kSpPayload)] = v;  // low, high half of the scalar
                 }
             }
         }
@@ -990,6 +1003,7 @@ bool sparse_supported(scd_dtype dt, int order, const int64_t* dims, int grid, in
     const int64_t c = 8 * ((n + 8 * grid - 1) / (8 * grid));
     if (r > kSpThreads || c > kSpThreads) return false;
     if (r > 32 * kSpPayload || c > 32 * kSpPayload) return false;
+    if ((int64_t)grid * (((r > c ? r : c) + 31) / 32 + 2) > (int64_t)kSpMaxItems * kSpThreads) return false;
     if (sparse_lds_bytes(m, n, 0) > kSpMaxLds) return false;
     if (rs) *rs = (int)r;
     if (cs) *cs = (int)c;
