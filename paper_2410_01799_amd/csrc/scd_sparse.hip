@@ -607,8 +607,15 @@ struct SpPending {
     double* effu;        // [kSpThreads] u of the true remainder on this workgroup's rows
     double* effv;        // [kSpThreads] v on its columns
     uint32_t* rowmask;   // [4]
+    uint32_t* T0;        // [kSpAhead][pt_stride] random starts t_0 of the next terms
+    double* U0;          // [kSpAhead][kSpThreads] their first products R' t_0 on this workgroup's rows
     int ps_stride, pt_stride;
 };
+
+// Between two flushes the stored copy R' does not change, so the first product R' t_0 of each of the next
+// terms (t_0 is a keyed random vector, known in advance) can be formed in the pass that flushes: that pass
+// reads R anyway, and the dense start of those terms then reads only the transposed copy.
+constexpr int kSpAhead = 8;
 
 // ej[j] = coef[j] * <p_j, cur> for the np pending vectors of one side, 0 for j >= np
 __device__ void sp_pending_dots(const uint32_t* P, int stride, int nwords32, int64_t nbits, const uint32_t* cur, int np,
@@ -649,15 +656,15 @@ __device__ __forceinline__ void sp_effective(const double* acc, int len, uint32_
     }
 }
 
-// Flush: rows row0 .. row0+nrows-1 of Y (row length ld) lose the np pending terms, one after the other
-// per entry (sign of term j at (row, col) = Prow_j[row] xor Pcol_j[col]); the squares of what is left
-// are summed, and the signed row sums with `sumbits` are formed for the next term's start.  Columns are
-// taken in tiles of one 16-byte chunk per thread, so that a thread keeps its columns' pending signs in
-// registers while it streams down the rows.
-template <typename TE>
+// Flush: rows row0 .. row0+nrows-1 of Y (row length ld) lose the np pending terms (possibly none), one after
+// the other per entry (sign of term j at (row, col) = Prow_j[row] xor Pcol_j[col]); the squares of what is
+// left are summed, and the signed row sums with each of the nvec <= NV bit vectors sums + j * sstride are
+// formed: out[j * kSpThreads + row].  Columns are taken in tiles of one 16-byte chunk per thread, so that a
+// thread keeps its columns' pending signs in registers while it streams down the rows.
+template <typename TE, int NV>
 __device__ void sp_flush_rows(TE* __restrict__ Y, int64_t ld, int64_t row0, int nrows, const uint32_t* Prow, int prs,
-                              const uint32_t* Pcol, int pcs, int np, const double* coef, const uint32_t* colbits_sum,
-                              double* acc, double& fsq_out, double* red, uint32_t* rowmask)
+                              const uint32_t* Pcol, int pcs, int np, const double* coef, const uint32_t* sums, int sstride,
+                              int nvec, double* out, double& fsq_out, double* red, uint32_t* rowmask)
 {
     constexpr int VE = SpVec<TE>::N;
     constexpr int RB = 4;
@@ -665,7 +672,8 @@ __device__ void sp_flush_rows(TE* __restrict__ Y, int64_t ld, int64_t row0, int 
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
     const int64_t nch = ld / VE;
     double fsq = 0.0;
-    if (tid < nrows) acc[tid] = 0.0;
+    if (tid < nrows)
+        for (int j = 0; j < nvec; ++j) out[j * kSpThreads + tid] = 0.0;
     for (int64_t c0 = 0; c0 < nch; c0 += kSpThreads) {
         const int64_t c = c0 + tid;
         const bool active = c < nch;
@@ -678,7 +686,10 @@ __device__ void sp_flush_rows(TE* __restrict__ Y, int64_t ld, int64_t row0, int 
 #pragma unroll
             for (int e = 0; e < VE; ++e) cm[e] |= ((bits >> e) & 1u) << j;
         }
-        const uint32_t bsum = sp_bits4(colbits_sum, col & ~3ll) >> (col & 3);
+        uint32_t bsum = 0u;  // four bits per sum vector: its signs at this thread's columns
+#pragma unroll
+        for (int j = 0; j < NV; ++j)
+            if (j < nvec) bsum |= ((sp_bits4(sums + j * sstride, col & ~3ll) >> (col & 3)) & 0xFu) << (4 * j);
         for (int rb = 0; rb < nrows; rb += RB) {
             __syncthreads();  // rowmask and red are free again
             if (tid < RB) {
@@ -689,14 +700,15 @@ __device__ void sp_flush_rows(TE* __restrict__ Y, int64_t ld, int64_t row0, int 
                 rowmask[tid] = mk;
             }
             __syncthreads();
-            double ps[RB];
+            double ps[RB][NV];
             V v[RB];
             V* rowp[RB];
 #pragma unroll
             for (int r = 0; r < RB; ++r) {
                 const int rr = rb + r < nrows ? rb + r : nrows - 1;
                 rowp[r] = (V*)(Y + (row0 + rr) * ld);
-                ps[r] = 0.0;
+#pragma unroll
+                for (int j = 0; j < NV; ++j) ps[r][j] = 0.0;
                 v[r] = rowp[r][active ? c : 0];
             }
 #pragma unroll
@@ -708,35 +720,72 @@ __device__ void sp_flush_rows(TE* __restrict__ Y, int64_t ld, int64_t row0, int 
                 } else {
                     x[0] = v[r].x; x[1] = v[r].y;
                 }
-                uint32_t z[VE];
+                if (np > 0) {
+                    uint32_t z[VE];
 #pragma unroll
-                for (int e = 0; e < VE; ++e) z[e] = rowmask[r] ^ cm[e];
-                for (int j = 0; j < np; ++j) {
-                    const TE ck = (TE)coef[j];
+                    for (int e = 0; e < VE; ++e) z[e] = rowmask[r] ^ cm[e];
+                    for (int j = 0; j < np; ++j) {
+                        const TE ck = (TE)coef[j];
 #pragma unroll
-                    for (int e = 0; e < VE; ++e) x[e] = x[e] - sp_flip(ck, (z[e] >> j) & 1u);
+                        for (int e = 0; e < VE; ++e) x[e] = x[e] - sp_flip(ck, (z[e] >> j) & 1u);
+                    }
+                    V o;
+                    if constexpr (VE == 4) o = V{x[0], x[1], x[2], x[3]};
+                    else o = V{x[0], x[1]};
+                    rowp[r][c] = o;
                 }
-                V o;
-                if constexpr (VE == 4) o = V{x[0], x[1], x[2], x[3]};
-                else o = V{x[0], x[1]};
-                rowp[r][c] = o;
+                double xd[VE];
 #pragma unroll
                 for (int e = 0; e < VE; ++e) {
-                    fsq += (double)x[e] * (double)x[e];
-                    ps[r] += (double)sp_flip(x[e], (bsum >> e) & 1u);
+                    xd[e] = (double)x[e];
+                    fsq += xd[e] * xd[e];
+                }
+#pragma unroll
+                for (int j = 0; j < NV; ++j) {
+                    if (j >= nvec) continue;
+#pragma unroll
+                    for (int e = 0; e < VE; ++e) ps[r][j] += sp_flip(xd[e], (bsum >> (4 * j + e)) & 1u);
                 }
             }
+            if constexpr (RB * NV == 32) {
+                // 32 sums over the wave at once: at distance 32, 16, .., 2 a lane hands half of what it holds to
+                // its partner and keeps the other half (31 exchanges instead of 32 x 6); after the last
+                // distance the pair of lanes 2 i, 2 i + 1 holds the sum number i
+                double vv[32];
 #pragma unroll
-            for (int r = 0; r < RB; ++r) ps[r] = sp_wave_sum(ps[r]);
-            if (lane == 0) {
+                for (int r = 0; r < RB; ++r)
 #pragma unroll
-                for (int r = 0; r < RB; ++r) red[wv * RB + r] = ps[r];
+                    for (int j = 0; j < NV; ++j) vv[r * NV + j] = ps[r][j];
+#pragma unroll
+                for (int h = 16; h >= 1; h >>= 1) {
+                    const bool upper = (lane & (2 * h)) != 0;  // distance 2 h: 32, 16, 8, 4, 2
+#pragma unroll
+                    for (int i = 0; i < h; ++i) {
+                        const double send = upper ? vv[i] : vv[i + h];
+                        const double keep = upper ? vv[i + h] : vv[i];
+                        vv[i] = keep + __shfl_xor(send, 2 * h, kWave);
+                    }
+                }
+                vv[0] += __shfl_xor(vv[0], 1, kWave);
+                if ((lane & 1) == 0) red[wv * 32 + (lane >> 1)] = vv[0];
+            } else {
+#pragma unroll
+                for (int r = 0; r < RB; ++r)
+#pragma unroll
+                    for (int j = 0; j < NV; ++j) {
+                        if (j >= nvec) continue;
+                        const double t = sp_wave_sum(ps[r][j]);
+                        if (lane == 0) red[(wv * RB + r) * NV + j] = t;
+                    }
             }
             __syncthreads();
-            if (tid < RB && rb + tid < nrows) {
-                double t = 0.0;
-                for (int q = 0; q < kSpWaves; ++q) t += red[q * RB + tid];
-                acc[rb + tid] += t;
+            if (tid < RB * NV) {
+                const int r = tid / NV, j = tid % NV;
+                if (rb + r < nrows && j < nvec) {
+                    double t = 0.0;
+                    for (int q = 0; q < kSpWaves; ++q) t += red[(q * RB + r) * NV + j];
+                    out[j * kSpThreads + rb + r] += t;
+                }
             }
         }
     }
@@ -788,6 +837,8 @@ __global__ void __launch_bounds__(kSpThreads) sparse_delay_kernel(SparseArgs a)
         pd.rowmask = (uint32_t*)take(16);
         pd.PS = (uint32_t*)take((size_t)width * pd.ps_stride * 4);
         pd.PT = (uint32_t*)take((size_t)width * pd.pt_stride * 4);
+        pd.T0 = (uint32_t*)take((size_t)kSpAhead * pd.pt_stride * 4);
+        pd.U0 = (double*)take((size_t)kSpAhead * kSpThreads * 8);
     }
     for (int64_t i = tid; i < mwords32 + 2; i += kSpThreads) {
         sh.sA[i] = 0;
@@ -814,6 +865,7 @@ __global__ void __launch_bounds__(kSpThreads) sparse_delay_kernel(SparseArgs a)
     int alternations = 0, updates = 0, warn = 0, spins = 0;
     int64_t flips = 0, flips_rows = 0;
     int np = 0;  // pending terms
+    int ahead = 0, ahead_made = 0;  // first products R' t_0 formed in advance: still unused / formed by the last pass
     uint32_t own_u = 0u, own_v = 0u;  // their signs at this thread's row of I_g / column of J_g, bit j for term j
     double F;    // ||R_k||_F^2 of the true remainder
     {
@@ -825,6 +877,9 @@ __global__ void __launch_bounds__(kSpThreads) sparse_delay_kernel(SparseArgs a)
         if (k >= a.w_target && np == 0) break;
         const bool last = k >= a.w_target;
         const bool flush = np > 0 && (np == width || last);
+        // a pass over the rows of R that forms first products in advance: every flush, and the start of a launch
+        // (nothing pending: the pass only reads)
+        const bool pass = flush || (np == 0 && ahead == 0);
         // t_0 of term k (Algorithm 4 line 2), into the other column buffer
         for (int64_t i = tid; i < nwords32; i += kSpThreads) {
             uint32_t v = (uint32_t)(sp_rng_word(a.seed, (uint64_t)k, 1u, (uint64_t)(i >> 1)) >> (32 * (i & 1)));
@@ -835,14 +890,34 @@ __global__ void __launch_bounds__(kSpThreads) sparse_delay_kernel(SparseArgs a)
         __syncthreads();
         double fsq = 0.0, dummy = 0.0;
         // rows I_g: u = R t_0 (Algorithm 4 line 5), from the flushed copy or from R' with the correction
-        if (flush) {
+        if (pass) {
+            // the random starts of this term and the next ones of the launch, as many as there is room for
+            const int64_t left = a.w_target - k;
+            const int nvec = (int)(left < kSpAhead ? (left > 0 ? left : 0) : kSpAhead);
+            for (int64_t i = tid; i < (int64_t)nvec * nwords32; i += kSpThreads) {
+                const int64_t jv = i / nwords32, iw = i - jv * nwords32;
+                uint32_t v = (uint32_t)(sp_rng_word(a.seed, (uint64_t)(k + jv), 1u, (uint64_t)(iw >> 1)) >> (32 * (iw & 1)));
+                const int64_t rem = n - iw * 32;
+                if (rem < 32) v &= (1u << rem) - 1u;
+                pd.T0[jv * pd.pt_stride + iw] = v;
+            }
+            __syncthreads();
             if (rlen > 0)
-                sp_flush_rows<TE>(R, n, i0, rlen, pd.PS, pd.ps_stride, pd.PT, pd.pt_stride, np, pd.coef, t_oth, sh.accu, fsq,
-                                  sh.red, pd.rowmask);
+                sp_flush_rows<TE, kSpAhead>(R, n, i0, rlen, pd.PS, pd.ps_stride, pd.PT, pd.pt_stride, np, pd.coef, pd.T0,
+                                            pd.pt_stride, nvec, pd.U0, fsq, sh.red, pd.rowmask);
+            ahead = nvec;
+            ahead_made = nvec;
+        }
+        if (pass || ahead > 0) {
+            // (past the end of the launch nothing was formed and the signs published below are not used)
+            const int slot = ahead > 0 ? ahead_made - ahead : 0;
+            if (tid < rlen) sh.accu[tid] = pd.U0[slot * kSpThreads + tid];
+            if (ahead > 0) --ahead;
+        } else if (rlen > 0)
+            sp_dense_rows<TE>(R, n, i0, rlen, false, s_cur, t_cur, (TE)0, t_oth, sh.accu, dummy, sh.red);
+        if (flush) {
             if (tid < rlen) pd.effu[tid] = sh.accu[tid];
         } else {
-            if (rlen > 0)
-                sp_dense_rows<TE>(R, n, i0, rlen, false, s_cur, t_cur, (TE)0, t_oth, sh.accu, dummy, sh.red);
             sp_pending_dots(pd.PT, pd.pt_stride, (int)nwords32, n, t_oth, np, width, pd.coef, pd.ej);
             sp_effective(sh.accu, rlen, own_u, pd.ej, width, pd.effu);
         }
@@ -858,8 +933,8 @@ __global__ void __launch_bounds__(kSpThreads) sparse_delay_kernel(SparseArgs a)
         // rows J_g of the transposed copy: v = R^T s_1 (Algorithm 4 line 6)
         if (flush) {
             if (clen > 0)
-                sp_flush_rows<TE>(RT, m, j0, clen, pd.PT, pd.pt_stride, pd.PS, pd.ps_stride, np, pd.coef, s_oth, sh.accv, dummy,
-                                  sh.red, pd.rowmask);
+                sp_flush_rows<TE, 1>(RT, m, j0, clen, pd.PT, pd.pt_stride, pd.PS, pd.ps_stride, np, pd.coef, s_oth, 0, 1, sh.accv,
+                                     dummy, sh.red, pd.rowmask);
             updates += np;
             np = 0;
             own_u = 0u;
@@ -985,7 +1060,8 @@ size_t sparse_lds_bytes(int64_t m, int64_t n, int delay_width)
                al((size_t)2 * kSpGrid * 2 * 4) + al((size_t)(kSpWaves + 1) * 4);
     if (delay_width > 0)
         b += 2 * al(32 * 8) + 2 * al((size_t)kSpThreads * 8) + al(16) + al((size_t)delay_width * (mw + 1) * 4) +
-             al((size_t)delay_width * (nw + 1) * 4);
+             al((size_t)delay_width * (nw + 1) * 4) + al((size_t)kSpAhead * (nw + 1) * 4) +
+             al((size_t)kSpAhead * kSpThreads * 8);
     return b;
 }
 
