@@ -20,7 +20,8 @@
 // Flipped indices are compacted in ascending order and added in a fixed order: results are
 // bit-identical from run to run.
 // A second kernel (further down) delays the subtraction of finished terms as Section 3.2 does: pending
-// terms live in LDS, the products are corrected from their bitsets, one pass flushes the list.
+// terms live in LDS, the products are corrected from their bitsets, one pass flushes the list and, while
+// it is at it, forms the first products R' t_0 of the next terms (their random starts are known in advance).
 #include "scd_device.h"
 
 namespace scd {
