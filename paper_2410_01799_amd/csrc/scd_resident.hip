@@ -174,25 +174,29 @@ __device__ __forceinline__ void res_publish_f64(uint64_t* p, double v, uint32_t 
     __hip_atomic_store(p + 1, ((uint64_t)seq << 32) | (b >> 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// H members' values of one element (one half of a group of 2H) plus the two piggybacked doubles of one
-// member (four more words), all loads in flight together.  If any word is still from an earlier exchange, all
-// are read again (re-reads are rare once the first read is delayed a little).
-template <int H>
+// H members' values of one element (one half of a group of 2H) plus NX / 2 piggybacked doubles of one
+// member (NX = 2 or 4 more words; only what the phase at hand uses is published and read: every word is a
+// trip through the fabric), all loads in flight together.  If any word is still from an earlier exchange,
+// all are read again (re-reads are rare once the first read is delayed a little).
+template <int H, int NX>
 __device__ __forceinline__ bool res_gather_x2(const uint64_t* xbuf, uint32_t off, uint32_t stride, uint32_t xoff,
                                               uint32_t seq, int max_spin, double& sum, double& x0, double& x1,
                                               int& spin)
 {
+    static_assert(NX == 2 || NX == 4, "one or two piggybacked doubles");
     uint64_t w[H + 4];
+    w[H + 2] = 0;
+    w[H + 3] = 0;
     for (;;) {
 #pragma unroll
         for (int q = 0; q < H; ++q)
             w[q] = __hip_atomic_load(xbuf + (off + q * stride), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
-        for (int q = 0; q < 4; ++q)
+        for (int q = 0; q < NX; ++q)
             w[H + q] = __hip_atomic_load(xbuf + (xoff + q), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         bool fresh = true;
 #pragma unroll
-        for (int q = 0; q < H + 4; ++q) fresh = fresh && ((uint32_t)(w[q] >> 32) == seq);
+        for (int q = 0; q < H + NX; ++q) fresh = fresh && ((uint32_t)(w[q] >> 32) == seq);
         if (fresh) break;
         if (++spin > max_spin) return false;
         __builtin_amdgcn_s_sleep(1);
@@ -354,7 +358,7 @@ __global__ void __launch_bounds__(kResThreads) resident_kernel(ResidentArgs a)
             }
             if (tid == 0) {
                 res_publish_f64(mine + BM, cpart, seq_u);
-                res_publish_f64(mine + BM + 2, fsq_block, seq_u);
+                if (norm_stage == 1) res_publish_f64(mine + BM + 2, fsq_block, seq_u);  // (only the exchange after an update)
             }
         }
         for (int d = 0; d < a.poll_delay; ++d) __builtin_amdgcn_s_sleep(1);
@@ -369,8 +373,9 @@ __global__ void __launch_bounds__(kResThreads) resident_kernel(ResidentArgs a)
             double half = 0.0;
             if (wv == kResThreads / 64 - 1) {
                 double x0 = 0.0, x1 = 0.0;
-                ok = res_gather_x2<H>(a.xbuf, off, kResSlotWords, res_slot_off(0, seq_u, pr * P + (lane & (P - 1))) + BM,
-                                      seq_u, a.max_spin, half, x0, x1, spin);
+                const uint32_t xoff = res_slot_off(0, seq_u, pr * P + (lane & (P - 1))) + BM;
+                if (norm_stage == 1) ok = res_gather_x2<H, 4>(a.xbuf, off, kResSlotWords, xoff, seq_u, a.max_spin, half, x0, x1, spin);
+                else ok = res_gather_x2<H, 2>(a.xbuf, off, kResSlotWords, xoff, seq_u, a.max_spin, half, x0, x1, spin);
                 if (lane < P) {
                     lds_x[0][lane] = x0;
                     lds_x[1][lane] = x1;
@@ -482,10 +487,7 @@ __global__ void __launch_bounds__(kResThreads) resident_kernel(ResidentArgs a)
                 for (int q = 0; q < kResThreads / 64; ++q) s += lds_q[q][tid];
                 res_publish(mine + tid, s, seq_v);
             }
-            if (tid == kResThreads - 1) {
-                res_publish_f64(mine + BN, frow, seq_v);
-                res_publish_f64(mine + BN + 2, 0.0, seq_v);
-            }
+            if (norm_stage == 2 && tid == kResThreads - 1) res_publish_f64(mine + BN, frow, seq_v);
         }
         for (int d = 0; d < a.poll_delay; ++d) __builtin_amdgcn_s_sleep(1);
         ok = true;
@@ -495,10 +497,11 @@ __global__ void __launch_bounds__(kResThreads) resident_kernel(ResidentArgs a)
             const int colc = col < BN ? col : BN - 1;
             const uint32_t off = res_slot_off(1, seq_v, (h * H) * P + pc) + (uint32_t)colc;
             double half = 0.0;
-            if (wv == kResThreads / 64 - 1) {
+            if (norm_stage == 2 && wv == kResThreads / 64 - 1) {
+                // the block-row sums of squares travel on this exchange once per term
                 double x0 = 0.0, x1 = 0.0;
-                ok = res_gather_x2<H>(a.xbuf, off, P * kResSlotWords, res_slot_off(1, seq_v, (lane & (P - 1)) * P + pc) + BN,
-                                      seq_v, a.max_spin, half, x0, x1, spin);
+                ok = res_gather_x2<H, 2>(a.xbuf, off, P * kResSlotWords, res_slot_off(1, seq_v, (lane & (P - 1)) * P + pc) + BN,
+                                         seq_v, a.max_spin, half, x0, x1, spin);
                 if (lane < P) lds_x[1][lane] = x0;
             } else {
                 ok = res_gather<H>(a.xbuf, off, P * kResSlotWords, seq_v, a.max_spin, half, spin);
