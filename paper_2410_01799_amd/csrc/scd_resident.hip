@@ -393,16 +393,24 @@ __global__ void __launch_bounds__(kResThreads) resident_kernel(ResidentArgs a)
         }
         spins += spin;
         spin = 0;
-        double c_tot = 0.0, f_tot = 0.0;
-#pragma unroll 2
-        for (int q = 0; q < P; ++q) {
-            c_tot += lds_x[0][q];
-            f_tot += lds_x[1][q];
+        // (all loads first, then the adds in order: a dependent chain of LDS reads would cost a latency each)
+        double c_tot = 0.0;
+        {
+            double cq[P];
+#pragma unroll
+            for (int q = 0; q < P; ++q) cq[q] = lds_x[0][q];
+#pragma unroll
+            for (int q = 0; q < P; ++q) c_tot += cq[q];
         }
         c_tot = uniform_f64(c_tot);
-        f_tot = uniform_f64(f_tot);
         if (norm_stage == 1) {
-            frow = f_tot;
+            double f_tot = 0.0;
+            double fq[P];
+#pragma unroll
+            for (int q = 0; q < P; ++q) fq[q] = lds_x[1][q];
+#pragma unroll
+            for (int q = 0; q < P; ++q) f_tot += fq[q];
+            frow = uniform_f64(f_tot);
             norm_stage = 2;
         }
         if (j > 0) {
@@ -520,14 +528,23 @@ __global__ void __launch_bounds__(kResThreads) resident_kernel(ResidentArgs a)
             return;
         }
         {
-            double cs = 0.0, ft = 0.0;
-#pragma unroll 2
-            for (int q = 0; q < kResThreads / 64; ++q) cs += lds_red[q];
-#pragma unroll 2
-            for (int q = 0; q < P; ++q) ft += lds_x[1][q];
+            double cs = 0.0;
+            {
+                double cq[kResThreads / 64];
+#pragma unroll
+                for (int q = 0; q < kResThreads / 64; ++q) cq[q] = lds_red[q];
+#pragma unroll
+                for (int q = 0; q < kResThreads / 64; ++q) cs += cq[q];
+            }
             cpart = uniform_f64(cs);
-            ft = uniform_f64(ft);
             if (norm_stage == 2) {
+                double ft = 0.0;
+                double fq[P];
+#pragma unroll
+                for (int q = 0; q < P; ++q) fq[q] = lds_x[1][q];
+#pragma unroll
+                for (int q = 0; q < P; ++q) ft += fq[q];
+                ft = uniform_f64(ft);
                 if (wg == 0 && tid == 0) a.trace[norm_k] = sqrt(ft);
                 norm_stage = 0;
             }
