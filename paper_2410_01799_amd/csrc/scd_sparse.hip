@@ -61,10 +61,55 @@ __device__ __forceinline__ uint64_t sp_rng_word(uint64_t seed, uint64_t term, ui
     return h;
 }
 
+// The value of lane (l ^ D) for D = 1, 2, 4, 8 by the data-parallel lane modes (vector-unit latency; a
+// ds_bpermute would cost an LDS round trip per step of a dependent chain).
+template <int D>
+__device__ __forceinline__ double sp_lane_xor_f64(double v)
+{
+    const long long b = __double_as_longlong(v);
+    int lo = (int)(b & 0xFFFFFFFFll), hi = (int)(b >> 32);
+    if constexpr (D == 1) {  // quad_perm 1,0,3,2
+        lo = __builtin_amdgcn_update_dpp(0, lo, 0xB1, 0xF, 0xF, true);
+        hi = __builtin_amdgcn_update_dpp(0, hi, 0xB1, 0xF, 0xF, true);
+    } else if constexpr (D == 2) {  // quad_perm 2,3,0,1
+        lo = __builtin_amdgcn_update_dpp(0, lo, 0x4E, 0xF, 0xF, true);
+        hi = __builtin_amdgcn_update_dpp(0, hi, 0x4E, 0xF, 0xF, true);
+    } else if constexpr (D == 4) {  // mirror of half a row (l ^ 7), then quad_perm 3,2,1,0 (l ^ 3)
+        lo = __builtin_amdgcn_update_dpp(0, __builtin_amdgcn_update_dpp(0, lo, 0x141, 0xF, 0xF, true), 0x1B, 0xF, 0xF, true);
+        hi = __builtin_amdgcn_update_dpp(0, __builtin_amdgcn_update_dpp(0, hi, 0x141, 0xF, 0xF, true), 0x1B, 0xF, 0xF, true);
+    } else {  // D == 8: mirror of a row (l ^ 15), then of half a row (l ^ 7)
+        static_assert(D == 8, "distance within a row of 16 lanes");
+        lo = __builtin_amdgcn_update_dpp(0, __builtin_amdgcn_update_dpp(0, lo, 0x140, 0xF, 0xF, true), 0x141, 0xF, 0xF, true);
+        hi = __builtin_amdgcn_update_dpp(0, __builtin_amdgcn_update_dpp(0, hi, 0x140, 0xF, 0xF, true), 0x141, 0xF, 0xF, true);
+    }
+    return __longlong_as_double(((long long)hi << 32) | (long long)(unsigned)lo);
+}
+
+// Sum over the 64 lanes, the same bits in every lane: distances 1, 2, 4, 8 by the lane modes above, 16 and 32
+// by the row-swap instructions of gfx950 (swapping the odd rows of one copy with the even rows of another
+// leaves the two partners of every lane in the two results, in the same order for both partners).
 __device__ __forceinline__ double sp_wave_sum(double a)
 {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) a += __shfl_xor(a, off, kWave);
+    a += sp_lane_xor_f64<1>(a);
+    a += sp_lane_xor_f64<2>(a);
+    a += sp_lane_xor_f64<4>(a);
+    a += sp_lane_xor_f64<8>(a);
+    {
+        const unsigned long long b = (unsigned long long)__double_as_longlong(a);
+        const unsigned lo = (unsigned)b, hi = (unsigned)(b >> 32);
+        const auto rl = __builtin_amdgcn_permlane16_swap(lo, lo, false, false);
+        const auto rh = __builtin_amdgcn_permlane16_swap(hi, hi, false, false);
+        a = __longlong_as_double((long long)(((unsigned long long)rh[0] << 32) | rl[0])) +
+            __longlong_as_double((long long)(((unsigned long long)rh[1] << 32) | rl[1]));
+    }
+    {
+        const unsigned long long b = (unsigned long long)__double_as_longlong(a);
+        const unsigned lo = (unsigned)b, hi = (unsigned)(b >> 32);
+        const auto rl = __builtin_amdgcn_permlane32_swap(lo, lo, false, false);
+        const auto rh = __builtin_amdgcn_permlane32_swap(hi, hi, false, false);
+        a = __longlong_as_double((long long)(((unsigned long long)rh[0] << 32) | rl[0])) +
+            __longlong_as_double((long long)(((unsigned long long)rh[1] << 32) | rl[1]));
+    }
     return a;
 }
 
@@ -235,10 +280,17 @@ __device__ void sp_accumulate_flips(const TE* __restrict__ Y, int64_t ld, int64_
         __syncthreads();  // the list and the scan cells of the previous round are free
         if (lane == kWave - 1) sh.scan[wv + 1] = incl;
         __syncthreads();
-        int base = 0;
-        for (int i = 0; i < wv; ++i) base += sh.scan[i + 1];
-        int total = 0;
-        for (int i = 0; i < kSpWaves; ++i) total += sh.scan[i + 1];
+        // (all eight cells are loaded before any is added: a loop with a run-time bound would pay an LDS
+        // latency per turn)
+        int sc[kSpWaves];
+#pragma unroll
+        for (int i = 0; i < kSpWaves; ++i) sc[i] = sh.scan[i + 1];
+        int base = 0, total = 0;
+#pragma unroll
+        for (int i = 0; i < kSpWaves; ++i) {
+            total += sc[i];
+            base += i < wv ? sc[i] : 0;
+        }
         int pos = base + incl - cnt;
         uint32_t bits = x;
         while (bits) {
@@ -280,9 +332,13 @@ __device__ void sp_accumulate_flips(const TE* __restrict__ Y, int64_t ld, int64_
     else if (lane < slp) sh.red[wv * slp + e] = part;
     __syncthreads();
     if (tid < len) {
-        const int groups = slp >= kWave ? Q : kSpWaves;
+        const int groups = slp >= kWave ? Q : kSpWaves;  // 8 or fewer
+        double gsum[kSpWaves];
+#pragma unroll
+        for (int z = 0; z < kSpWaves; ++z) gsum[z] = z < groups ? sh.red[z * slp + tid] : 0.0;  // loaded together
         double s = 0.0;
-        for (int z = 0; z < groups; ++z) s += sh.red[z * slp + tid];
+#pragma unroll
+        for (int z = 0; z < kSpWaves; ++z) s += gsum[z];
         acc[tid] += 2.0 * s;
     }
     __syncthreads();
