@@ -113,6 +113,57 @@ __device__ __forceinline__ double sp_wave_sum(double a)
     return a;
 }
 
+// a[l] + a[l ^ 16] and a[l] + a[l ^ 32], the same bits in both partners (see sp_wave_sum)
+__device__ __forceinline__ double sp_sum_xor16(double a)
+{
+    const unsigned long long b = (unsigned long long)__double_as_longlong(a);
+    const unsigned lo = (unsigned)b, hi = (unsigned)(b >> 32);
+    const auto rl = __builtin_amdgcn_permlane16_swap(lo, lo, false, false);
+    const auto rh = __builtin_amdgcn_permlane16_swap(hi, hi, false, false);
+    return __longlong_as_double((long long)(((unsigned long long)rh[0] << 32) | rl[0])) +
+           __longlong_as_double((long long)(((unsigned long long)rh[1] << 32) | rl[1]));
+}
+__device__ __forceinline__ double sp_sum_xor32(double a)
+{
+    const unsigned long long b = (unsigned long long)__double_as_longlong(a);
+    const unsigned lo = (unsigned)b, hi = (unsigned)(b >> 32);
+    const auto rl = __builtin_amdgcn_permlane32_swap(lo, lo, false, false);
+    const auto rh = __builtin_amdgcn_permlane32_swap(hi, hi, false, false);
+    return __longlong_as_double((long long)(((unsigned long long)rh[0] << 32) | rl[0])) +
+           __longlong_as_double((long long)(((unsigned long long)rh[1] << 32) | rl[1]));
+}
+
+// Sum of an int over the 64 lanes (every lane gets it) and inclusive prefix sum across the lanes, both
+// without LDS traffic.  The scan is the classic one of this architecture: shifts by 1, 2, 4, 8 within each
+// row of 16 lanes (lanes without a source add zero), then lane 15 of rows 0 and 2 is added to rows 1 and 3,
+// then lane 31 to rows 2 and 3.
+__device__ __forceinline__ int sp_wave_sum_int(int v)
+{
+    v += __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xF, 0xF, true);                                                    // l ^ 1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xF, 0xF, true);                                                    // l ^ 2
+    v += __builtin_amdgcn_update_dpp(0, __builtin_amdgcn_update_dpp(0, v, 0x141, 0xF, 0xF, true), 0x1B, 0xF, 0xF, true);   // l ^ 4
+    v += __builtin_amdgcn_update_dpp(0, __builtin_amdgcn_update_dpp(0, v, 0x140, 0xF, 0xF, true), 0x141, 0xF, 0xF, true);  // l ^ 8
+    {
+        const auto r = __builtin_amdgcn_permlane16_swap((unsigned)v, (unsigned)v, false, false);
+        v = (int)(r[0] + r[1]);
+    }
+    {
+        const auto r = __builtin_amdgcn_permlane32_swap((unsigned)v, (unsigned)v, false, false);
+        v = (int)(r[0] + r[1]);
+    }
+    return v;
+}
+__device__ __forceinline__ int sp_wave_scan_int(int v)
+{
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xF, 0xF, true);   // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xF, 0xF, true);   // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xF, 0xF, true);   // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xF, 0xF, true);   // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xA, 0xF, false);  // row_bcast:15 into rows 1 and 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xC, 0xF, false);  // row_bcast:31 into rows 2 and 3
+    return v;
+}
+
 __device__ __forceinline__ uint32_t sp_bits4(const uint32_t* bits, int64_t col)
 {
     // the bits of `col .. col+3` (col is a multiple of 4, so they sit in one word)
@@ -271,12 +322,7 @@ __device__ void sp_accumulate_flips(const TE* __restrict__ Y, int64_t ld, int64_
         const uint32_t cw = wi < nwords ? cur[wi] : 0u;
         const uint32_t x = wi < nwords ? (cw ^ prev[wi]) : 0u;
         const int cnt = __popc(x);
-        int incl = cnt;
-#pragma unroll
-        for (int d = 1; d < kWave; d <<= 1) {
-            const int o = __shfl_up(incl, d, kWave);
-            if (lane >= d) incl += o;
-        }
+        const int incl = sp_wave_scan_int(cnt);
         __syncthreads();  // the list and the scan cells of the previous round are free
         if (lane == kWave - 1) sh.scan[wv + 1] = incl;
         __syncthreads();
@@ -326,7 +372,8 @@ __device__ void sp_accumulate_flips(const TE* __restrict__ Y, int64_t ld, int64_
     }
     // the lanes of a wave that hold the same entry are joined first (their groups in ascending order of the
     // distance), then the waves in order
-    for (int d = slp; d < kWave; d <<= 1) part += __shfl_xor(part, d, kWave);
+    if (slp <= 16) part = sp_sum_xor16(part);
+    if (slp <= 32) part = sp_sum_xor32(part);
     __syncthreads();
     if (slp >= kWave) sh.red[tid] = part;
     else if (lane < slp) sh.red[wv * slp + e] = part;
@@ -686,8 +733,7 @@ __device__ void sp_pending_dots(const uint32_t* P, int stride, int nwords32, int
         }
         int cnt = 0;
         for (int p = lane; p < nwords32; p += kWave) cnt += __popc(P[j * stride + p] ^ cur[p]);
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) cnt += __shfl_xor(cnt, off, kWave);
+        cnt = sp_wave_sum_int(cnt);
         if (lane == 0) ej[j] = coef[j] * (double)(nbits - 2 * (int64_t)cnt);
     }
     __syncthreads();
