@@ -112,10 +112,49 @@ __device__ __forceinline__ uint64_t rng_word_res(uint64_t seed, uint64_t term, u
     return h;
 }
 
+// Sum over the 64 lanes, the same bits in every lane, without LDS traffic (a chain of ds_bpermute would cost
+// an LDS round trip per step): distances 1, 2, 4, 8 by the data-parallel lane modes (4 = mirror of half a row
+// then reversed quads, 8 = mirror of a row then of half a row), 16 and 32 by the row-swap instructions of
+// gfx950 (swapping the odd rows of one copy with the even rows of another leaves the two partners of every
+// lane in the two results, in the same order for both partners).
+template <int C0, int C1>
+__device__ __forceinline__ double dpp_f64_res(double v)
+{
+    const long long b = __double_as_longlong(v);
+    int lo = __builtin_amdgcn_update_dpp(0, (int)(b & 0xFFFFFFFFll), C0, 0xF, 0xF, true);
+    int hi = __builtin_amdgcn_update_dpp(0, (int)(b >> 32), C0, 0xF, 0xF, true);
+    if constexpr (C1 != 0) {
+        lo = __builtin_amdgcn_update_dpp(0, lo, C1, 0xF, 0xF, true);
+        hi = __builtin_amdgcn_update_dpp(0, hi, C1, 0xF, 0xF, true);
+    }
+    return __longlong_as_double(((long long)hi << 32) | (long long)(unsigned)lo);
+}
+template <int D>
+__device__ __forceinline__ double swap_sum_f64_res(double a)
+{
+    const unsigned long long b = (unsigned long long)__double_as_longlong(a);
+    const unsigned lo = (unsigned)b, hi = (unsigned)(b >> 32);
+    unsigned l0, l1, h0, h1;
+    if constexpr (D == 16) {
+        const auto rl = __builtin_amdgcn_permlane16_swap(lo, lo, false, false);
+        const auto rh = __builtin_amdgcn_permlane16_swap(hi, hi, false, false);
+        l0 = rl[0], l1 = rl[1], h0 = rh[0], h1 = rh[1];
+    } else {
+        const auto rl = __builtin_amdgcn_permlane32_swap(lo, lo, false, false);
+        const auto rh = __builtin_amdgcn_permlane32_swap(hi, hi, false, false);
+        l0 = rl[0], l1 = rl[1], h0 = rh[0], h1 = rh[1];
+    }
+    return __longlong_as_double((long long)(((unsigned long long)h0 << 32) | l0)) +
+           __longlong_as_double((long long)(((unsigned long long)h1 << 32) | l1));
+}
 __device__ __forceinline__ double wave_sum_res(double a)
 {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) a += __shfl_xor(a, off, kWave);
+    a += dpp_f64_res<0xB1, 0>(a);       // lane ^ 1
+    a += dpp_f64_res<0x4E, 0>(a);       // lane ^ 2
+    a += dpp_f64_res<0x141, 0x1B>(a);   // lane ^ 4
+    a += dpp_f64_res<0x140, 0x141>(a);  // lane ^ 8
+    a = swap_sum_f64_res<16>(a);
+    a = swap_sum_f64_res<32>(a);
     return a;
 }
 
