@@ -258,6 +258,21 @@ __global__ void __launch_bounds__(kApMfmaWaves* kWave)
     }
 }
 
+// sum over the chunks of <t_j, x>, in order; four loads in flight at a time (a loop that adds each part before
+// it loads the next would pay a trip to memory per chunk)
+__device__ __forceinline__ double ap_sum_parts(const double* __restrict__ part, int64_t w, int64_t jc, int chunks)
+{
+    double s = 0.0;
+    for (int q0 = 0; q0 < chunks; q0 += 4) {
+        double v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = q0 + u < chunks ? part[(int64_t)(q0 + u) * w + jc] : 0.0;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) s += v[u];
+    }
+    return s;
+}
+
 // Outer pass.  Wave (p, split) owns the 64 output entries of word p and the terms of its split; lane q
 // fetches word p of term (tile + q) and forms z of that term (the scale step: c times the chunk parts in
 // order); z goes through a wave-private strip of LDS so that every lane can read every term's value.
@@ -279,8 +294,7 @@ __global__ void __launch_bounds__(kApOuterWaves* kWave)
         const int64_t j = tile + lane;
         const int64_t jc = j < j1 ? j : j1 - 1;
         word = bits[jc * mw + p];
-        double s = part[jc];
-        for (int q = 1; q < chunks; ++q) s += part[(int64_t)q * w + jc];
+        const double s = ap_sum_parts(part, w, jc, chunks);
         z = j < j1 ? (double)c[jc] * s : 0.0;
     };
     double a4[4] = {0.0, 0.0, 0.0, 0.0};
@@ -403,8 +417,7 @@ __global__ void __launch_bounds__(kApMfmaWaves* kWave)
     for (int k = 0; k < 4; ++k) {
         const int64_t j = j0 + 4 * tid + k;
         const int64_t jc = j < j1 ? j : j1 - 1;
-        double s = part[jc];
-        for (int q = 1; q < chunks; ++q) s += part[(int64_t)q * w + jc];
+        const double s = ap_sum_parts(part, w, jc, chunks);
         zv[k] = j < j1 ? (double)c[jc] * s : 0.0;
         finite = finite && (fabs(zv[k]) <= 1.7e308);
         amax = fmax(amax, fabs(zv[k]));
