@@ -25,11 +25,86 @@ constexpr int kApChunkWords = 64;   // words of sign bits per lane-resident chun
 constexpr int kApInnerWaves = 4;    // waves per workgroup of the inner pass
 constexpr int kApOuterWaves = 8;    // waves per workgroup of the outer pass: 8 adjacent words = one 64-byte line
 
+// Cross-lane steps without LDS traffic (a chain of ds_bpermute costs an LDS round trip per step): the value
+// of lane (l ^ D) for D = 1, 2, 4, 8 by the data-parallel lane modes (4 = mirror of half a row then reversed
+// quads, 8 = mirror of a row then of half a row); the two partners at distance 16 or 32 by the row-swap
+// instructions of gfx950 (swapping the odd rows of one copy with the even rows of another leaves them in the
+// two results, in the same order for both partners).
+template <int D>
+__device__ __forceinline__ uint32_t ap_dpp_xor(uint32_t v)
+{
+    static_assert(D == 1 || D == 2 || D == 4 || D == 8, "distance within a row of 16 lanes");
+    constexpr int c0 = D == 1 ? 0xB1 : D == 2 ? 0x4E : D == 4 ? 0x141 : 0x140;
+    constexpr int c1 = D == 4 ? 0x1B : D == 8 ? 0x141 : 0;
+    int r = __builtin_amdgcn_update_dpp(0, (int)v, c0, 0xF, 0xF, true);
+    if constexpr (c1 != 0) r = __builtin_amdgcn_update_dpp(0, r, c1, 0xF, 0xF, true);
+    return (uint32_t)r;
+}
+template <int D>
+__device__ __forceinline__ double ap_dpp_xor_f64(double v)
+{
+    const unsigned long long b = (unsigned long long)__double_as_longlong(v);
+    const uint32_t lo = ap_dpp_xor<D>((uint32_t)b), hi = ap_dpp_xor<D>((uint32_t)(b >> 32));
+    return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
+}
+// (a, b) = the values of the two partners at distance D = 16 or 32, the same pair in both of them
+template <int D>
+__device__ __forceinline__ void ap_swap_pair(uint32_t v, uint32_t& a, uint32_t& b)
+{
+    if constexpr (D == 16) {
+        const auto r = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+        a = r[0], b = r[1];
+    } else {
+        const auto r = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+        a = r[0], b = r[1];
+    }
+}
+template <int D>
+__device__ __forceinline__ void ap_swap_pair_f64(double v, double& a, double& b)
+{
+    const unsigned long long w = (unsigned long long)__double_as_longlong(v);
+    uint32_t la, lb, ha, hb;
+    ap_swap_pair<D>((uint32_t)w, la, lb);
+    ap_swap_pair<D>((uint32_t)(w >> 32), ha, hb);
+    a = __longlong_as_double((long long)(((unsigned long long)ha << 32) | la));
+    b = __longlong_as_double((long long)(((unsigned long long)hb << 32) | lb));
+}
+
 __device__ __forceinline__ double ap_wave_sum(double a)
 {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) a += __shfl_xor(a, off, kWave);
-    return a;
+    a += ap_dpp_xor_f64<1>(a);
+    a += ap_dpp_xor_f64<2>(a);
+    a += ap_dpp_xor_f64<4>(a);
+    a += ap_dpp_xor_f64<8>(a);
+    double p, q;
+    ap_swap_pair_f64<16>(a, p, q);
+    a = p + q;
+    ap_swap_pair_f64<32>(a, p, q);
+    return p + q;
+}
+__device__ __forceinline__ double ap_wave_max(double a)
+{
+    a = fmax(a, ap_dpp_xor_f64<1>(a));
+    a = fmax(a, ap_dpp_xor_f64<2>(a));
+    a = fmax(a, ap_dpp_xor_f64<4>(a));
+    a = fmax(a, ap_dpp_xor_f64<8>(a));
+    double p, q;
+    ap_swap_pair_f64<16>(a, p, q);
+    a = fmax(p, q);
+    ap_swap_pair_f64<32>(a, p, q);
+    return fmax(p, q);
+}
+__device__ __forceinline__ float ap_wave_max(float a)
+{
+    a = fmaxf(a, __uint_as_float(ap_dpp_xor<1>(__float_as_uint(a))));
+    a = fmaxf(a, __uint_as_float(ap_dpp_xor<2>(__float_as_uint(a))));
+    a = fmaxf(a, __uint_as_float(ap_dpp_xor<4>(__float_as_uint(a))));
+    a = fmaxf(a, __uint_as_float(ap_dpp_xor<8>(__float_as_uint(a))));
+    uint32_t p, q;
+    ap_swap_pair<16>(__float_as_uint(a), p, q);
+    a = fmaxf(__uint_as_float(p), __uint_as_float(q));
+    ap_swap_pair<32>(__float_as_uint(a), p, q);
+    return fmaxf(__uint_as_float(p), __uint_as_float(q));
 }
 
 // +-1.0 for lane `lane` from bit `lane` of a wave-uniform word (a 1 bit stands for -1)
@@ -167,8 +242,7 @@ __global__ void __launch_bounds__(kApMfmaWaves* kWave)
             finite = finite && (fabsf(xv[r][k]) <= 3.0e38f);
             amax = fmaxf(amax, fabsf(xv[r][k]));
         }
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off, kWave));
+    amax = ap_wave_max(amax);
     if (tid < 16) {
         uint32_t v = 0;
 #pragma unroll
@@ -242,8 +316,8 @@ __global__ void __launch_bounds__(kApMfmaWaves* kWave)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             double v = (double)(acc0[i] + acc1[i]) * digit_weight;
-            v += __shfl_xor(v, 1, kWave);
-            v += __shfl_xor(v, 2, kWave);
+            v += ap_dpp_xor_f64<1>(v);
+            v += ap_dpp_xor_f64<2>(v);
             if (jd == 0) wsum[wv][4 * (lane >> 2) + i] = v;
         }
         __syncthreads();  // (every wave of the workgroup runs the same tiles)
@@ -340,9 +414,9 @@ constexpr int kApFxPitch = kApFxMaxTerms / 4 + 4;
 // change places, the partner row is s lanes away.  The rows are kept as two 32-bit halves; below distance
 // 32 a stage is, per half, one lane exchange, one rotate (the partner's bits move s columns up in the
 // upper row, s down in the lower) and one bitfield insert.  Distances 1..8 stay within a row of 16 lanes
-// and use the data-parallel lane modes (no LDS traffic).
+// and use the data-parallel lane modes, distances 16 and 32 the row-swap instructions (no LDS traffic).
 template <int S>
-__device__ __forceinline__ uint32_t ap_lane_xor(uint32_t v)
+__device__ __forceinline__ uint32_t ap_lane_xor(uint32_t v, int lane)
 {
     if constexpr (S == 1) return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0xB1, 0xF, 0xF, true);  // quad_perm 1,0,3,2
     else if constexpr (S == 2) return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0x4E, 0xF, 0xF, true);  // quad_perm 2,3,0,1
@@ -354,8 +428,13 @@ __device__ __forceinline__ uint32_t ap_lane_xor(uint32_t v)
         // lane ^ 15 (mirror of a row), then lane ^ 7
         const int h = __builtin_amdgcn_mov_dpp((int)v, 0x140, 0xF, 0xF, true);
         return (uint32_t)__builtin_amdgcn_mov_dpp(h, 0x141, 0xF, 0xF, true);
-    } else
-        return (uint32_t)__shfl_xor((int)v, S, kWave);
+    } else {
+        // distance 16 or 32: the row swap leaves (value of the lower partner, value of the upper partner) in
+        // both lanes; each takes the other's
+        uint32_t a, b;
+        ap_swap_pair<S>(v, a, b);
+        return (lane & S) ? a : b;
+    }
 }
 
 template <int S>
@@ -363,7 +442,7 @@ __device__ __forceinline__ uint32_t ap_butterfly(uint32_t h, int lane)
 {
     constexpr uint32_t m = S == 16 ? 0x0000FFFFu : S == 8 ? 0x00FF00FFu : S == 4 ? 0x0F0F0F0Fu : S == 2 ? 0x33333333u : 0x55555555u;
     const bool lower = (lane & S) != 0;
-    const uint32_t p = ap_lane_xor<S>(h);
+    const uint32_t p = ap_lane_xor<S>(h, lane);
     const uint32_t rot = __builtin_amdgcn_alignbit(p, p, lower ? S : 32 - S);  // partner >> S (lower row), << S (upper)
     const uint32_t keep = lower ? ~m : m;
     return (h & keep) | (rot & ~keep);
@@ -376,7 +455,7 @@ __device__ __forceinline__ uint64_t ap_transpose64(uint64_t x, int lane)
         // distance 32: the upper rows take the partner's low half as their high half, the lower rows the
         // partner's high half as their low half
         const bool lower = (lane & 32) != 0;
-        const uint32_t got = (uint32_t)__shfl_xor((int)(lower ? lo : hi), 32, kWave);
+        const uint32_t got = ap_lane_xor<32>(lower ? lo : hi, lane);
         lo = lower ? got : lo;
         hi = lower ? hi : got;
     }
@@ -422,8 +501,7 @@ __global__ void __launch_bounds__(kApMfmaWaves* kWave)
         finite = finite && (fabs(zv[k]) <= 1.7e308);
         amax = fmax(amax, fabs(zv[k]));
     }
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) amax = fmax(amax, __shfl_xor(amax, off, kWave));
+    amax = ap_wave_max(amax);
     if (tid < 16) {
         uint32_t v = 0;
 #pragma unroll
@@ -491,8 +569,8 @@ __global__ void __launch_bounds__(kApMfmaWaves* kWave)
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         double v = (double)(acc0[i] + acc1[i]) * digit_weight;
-        v += __shfl_xor(v, 1, kWave);
-        v += __shfl_xor(v, 2, kWave);
+        v += ap_dpp_xor_f64<1>(v);
+        v += ap_dpp_xor_f64<2>(v);
         if (jd == 0) out[i] = all_finite ? v * inv_scale : __longlong_as_double(0x7FF8000000000000ll);
     }
 }
