@@ -591,7 +591,10 @@ __global__ void __launch_bounds__(kResThreads) resident_kernel(ResidentArgs a)
         ++j;
         spins += spin;
         spin = 0;
-        __syncthreads();  // lds_red / lds_x are rewritten in the next phase
+        // No barrier here: what was read above (lds_red, lds_x[1]) is next written after the two barriers of the
+        // coming row and column phases (lds_x[1] in a row phase only right after an update, never right after
+        // the column phase that read it), and what the coming row phase writes first (lds_s of the other
+        // parity, lds_x[0]) was last read before this phase's barriers.
     }
 
     // ---- write the block back
