@@ -323,7 +323,9 @@ __device__ void sp_accumulate_flips(const TE* __restrict__ Y, int64_t ld, int64_
         const uint32_t x = wi < nwords ? (cw ^ prev[wi]) : 0u;
         const int cnt = __popc(x);
         const int incl = sp_wave_scan_int(cnt);
-        __syncthreads();  // the list and the scan cells of the previous round are free
+        // the list and the scan cells of the previous round are free (before the first round they have been
+        // since the barriers that closed the previous call)
+        if (w0 > 0) __syncthreads();
         if (lane == kWave - 1) sh.scan[wv + 1] = incl;
         __syncthreads();
         // (all eight cells are loaded before any is added: a loop with a run-time bound would pay an LDS
@@ -388,7 +390,9 @@ __device__ void sp_accumulate_flips(const TE* __restrict__ Y, int64_t ld, int64_
         for (int z = 0; z < kSpWaves; ++z) s += gsum[z];
         acc[tid] += 2.0 * s;
     }
-    __syncthreads();
+    // No barrier here: a thread reads back only its own entry of acc, and every path from here passes a barrier
+    // before sh.red is written again (the pending-term products, the exchange, the sum of |v| all start or end
+    // with one).
 }
 
 __device__ __forceinline__ void sp_store_tagged(uint64_t* p, uint32_t v, uint32_t seq)
