@@ -24,7 +24,7 @@ if str(ROOT) not in sys.path:
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # HBM/fabric bytes measured with rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE (two runs, each scaled by the
 # plain copy kernel of known size); figures and commands in profiles/memory_traffic_f32_pmc.txt
-RESIDENT_TRAFFIC_PER_ROW_PHASE = 6.06e6   # bytes per alternation of resident_kernel<8,16> (4096x4096 f32)
+RESIDENT_TRAFFIC_PER_ROW_PHASE = 6.16e6   # bytes per alternation of resident_kernel<8,16,16> (4096x4096 f32)
 STREAM_TRAFFIC_PER_LAUNCH = 68.7e6        # bytes per launch of rowpass_tiled_kernel<float,4,4> (4096x4096 f32)
 
 
