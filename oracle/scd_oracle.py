@@ -196,6 +196,102 @@ def greedy_signed_cut(R, t0bits, max_iters: int = DEFAULT_MAX_ITERS):
                 capped=bool(capped))
 
 
+def greedy_signed_cut_near_ties(R, t0bits, tol: float, tol_c: float = 0.0, accept=None,
+                                max_iters: int = DEFAULT_MAX_ITERS, max_runs: int = 64):
+    """Every outcome of Algorithm 4 that differs from the literal one only at decisions that are near ties.
+
+    Algorithm 4 takes two kinds of decisions: a sign, s_i = sgn((R t)_i) or t_l = sgn((R^T s)_l) (lines 5-6),
+    and the stop test c_j <= c_{j-1} (line 8).  An implementation that sums in another order or precision may
+    take a sign decision the other way where |value| < tol * max|value| of its vector, and the stop decision
+    the other way where 0 < |c_j - c_{j-1}| <= tol_c * |c_j|; everything after such a decision follows
+    Algorithm 4 again from the changed state.  This walks the tree of those alternatives, smallest margin
+    first: the literal run is outcome 0; with tol = tol_c = 0 it is the only one.
+
+    Steps are the oracle's own (row_signed_sum, col_signed_sum, pack), in the order of Algorithm 4.
+    accept: optional predicate on an outcome; the search stops at the first outcome it accepts.
+    Returns dict(outcomes=[dict(c, s, t, iters, flips)], accepted=index or None, truncated=bool) where
+    `flips` counts the decisions taken against the literal rule on the way to that outcome.
+    """
+    import heapq
+
+    R = _f64(R)
+    m, n = R.shape
+    outcomes = []
+    accepted = [None]
+    counter = [0]
+    heap = []
+
+    def push(prio, state):
+        counter[0] += 1
+        heapq.heappush(heap, (prio, counter[0], state))
+
+    def emit(c, s, t, j, nflips):
+        outcomes.append(dict(c=float(c), s=s.copy(), t=t.copy(), iters=int(j), flips=int(nflips)))
+        if accept is not None and accepted[0] is None and accept(outcomes[-1]):
+            accepted[0] = len(outcomes) - 1
+
+    def decide(x, flip_idx):
+        """sgn of a vector with the entries `flip_idx` taken the other way; also the near-tie entries."""
+        bits = pack(x)
+        ax = np.abs(x)
+        mx = ax.max() if ax.size else 0.0
+        near = np.nonzero(ax < tol * mx)[0] if tol > 0.0 and mx > 0.0 else np.zeros(0, dtype=np.int64)
+        for i in flip_idx:
+            bits[i >> 6] ^= np.uint64(1) << np.uint64(i & 63)
+        return bits, near, (ax / mx if mx > 0.0 else ax)
+
+    def run(state):
+        """Follow Algorithm 4 from a saved decision point to its end, queueing the alternatives met on the way."""
+        j, phase, x, s, c_prev, flips_here, nflips = (state[k] for k in ("j", "phase", "x", "s", "c_prev", "flips", "nflips"))
+        first = True
+        while True:
+            if phase == 0:
+                # line 5: s_j = sgn(R t_{j-1}), x = R t_{j-1}
+                fl = flips_here if first else ()
+                s, near, rel = decide(x, fl)
+                lo = max(fl) if fl else -1
+                for i in near[near > lo]:
+                    push(rel[i] / tol, dict(j=j, phase=0, x=x, s=s, c_prev=c_prev, flips=tuple(fl) + (int(i),),
+                                            nflips=nflips + 1))
+                first = False
+                x = col_signed_sum(R, s)
+                phase = 1
+            # line 6: t_j = sgn(R^T s_j), x = R^T s_j
+            fl = flips_here if first else ()
+            t, near, rel = decide(x, fl)
+            lo = max(fl) if fl else -1
+            for i in near[near > lo]:
+                push(rel[i] / tol, dict(j=j, phase=1, x=x, s=s, c_prev=c_prev, flips=tuple(fl) + (int(i),),
+                                        nflips=nflips + 1))
+            first = False
+            u = row_signed_sum(R, t)
+            c = float(np.cumsum(unpack(s, m) * u)[-1])  # line 7, added in the order i = 0..m-1
+            stop = c <= c_prev
+            close = tol_c > 0.0 and c != c_prev and abs(c - c_prev) <= tol_c * abs(c)
+            if stop or j >= max_iters:
+                emit(c, s, t, j, nflips)
+                if close and j < max_iters:
+                    # the other implementation saw an increase: it goes on from here
+                    push(abs(c - c_prev) / (tol_c * abs(c)), dict(j=j + 1, phase=0, x=u, s=s, c_prev=c, flips=(),
+                                                                   nflips=nflips + 1))
+                return
+            if close:
+                # the other implementation saw no increase: it stops here with the current triple (line 9)
+                emit(c, s, t, j, nflips + 1)
+            c_prev = c
+            j += 1
+            phase = 0
+            x = u
+
+    push(0.0, dict(j=1, phase=0, x=row_signed_sum(R, _u64(t0bits)), s=None, c_prev=-np.inf, flips=(), nflips=0))
+    runs = 0
+    while heap and accepted[0] is None and runs < max_runs:
+        _, _, state = heapq.heappop(heap)
+        run(state)
+        runs += 1
+    return dict(outcomes=outcomes, accepted=accepted[0], truncated=bool(heap) and accepted[0] is None)
+
+
 def decompose(A, w: int, seed: int, max_iters: int = DEFAULT_MAX_ITERS, want_remainder: bool = False):
     """Algorithm 5.  Returns dict(S, T, c, trace, iters, margins, capped[, R])."""
     A = _f64(A)
@@ -280,6 +376,71 @@ def axial_greedy_cut(a, signs0, max_iters: int = DEFAULT_MAX_ITERS):
                                            C.byref(it), hist.ctypes.data, margin.ctypes.data)
     return dict(c=c.value, signs=sg, iters=it.value, c_hist=hist[: it.value].copy(), margin=margin,
                 capped=bool(capped))
+
+
+def axial_greedy_cut_near_ties(a, signs0, tol: float, tol_c: float = 0.0, accept=None,
+                               max_iters: int = DEFAULT_MAX_ITERS, max_runs: int = 64):
+    """Algorithm 12 with its near-tie decisions left open, as greedy_signed_cut_near_ties does for Algorithm 4:
+    a sign of mode i may go the other way where |value| < tol * max|value| of that mode's sums, the stop test
+    (line 11) where 0 < |c_j - c_{j-1}| <= tol_c |c_j|.  Steps: mode_signed_sum, pack, tensor_inner, in the
+    order of Algorithm 12.  Returns dict(outcomes=[dict(c, signs, iters, flips)], accepted, truncated)."""
+    import heapq
+
+    a = _f64(a)
+    order = a.ndim
+    outcomes, accepted, counter, heap = [], [None], [0], []
+
+    def push(prio, state):
+        counter[0] += 1
+        heapq.heappush(heap, (prio, counter[0], state))
+
+    def emit(c, sg, j, nflips):
+        outcomes.append(dict(c=float(c), signs=[s.copy() for s in sg], iters=int(j), flips=int(nflips)))
+        if accept is not None and accepted[0] is None and accept(outcomes[-1]):
+            accepted[0] = len(outcomes) - 1
+
+    def run(state):
+        j, i0, sg, c_prev, flips_here, nflips = (state[k] for k in ("j", "mode", "signs", "c_prev", "flips", "nflips"))
+        sg = [s.copy() for s in sg]
+        first = True
+        while True:
+            for i in range(i0, order):
+                x = mode_signed_sum(a, sg, i)          # lines 5-8: modes before i new, after i old
+                fl = flips_here if first else ()
+                first = False
+                bits = pack(x)
+                ax = np.abs(x)
+                mx = ax.max()
+                if tol > 0.0 and mx > 0.0:
+                    lo = max(fl) if fl else -1
+                    for q in np.nonzero(ax < tol * mx)[0]:
+                        if q > lo:
+                            push(ax[q] / mx / tol, dict(j=j, mode=i, signs=[s.copy() for s in sg], c_prev=c_prev,
+                                                        flips=tuple(fl) + (int(q),), nflips=nflips + 1))
+                for q in fl:
+                    bits[q >> 6] ^= np.uint64(1) << np.uint64(q & 63)
+                sg[i] = bits
+            i0 = 0
+            c = tensor_inner(a, sg)                    # line 10
+            stop = c <= c_prev
+            close = tol_c > 0.0 and c != c_prev and abs(c - c_prev) <= tol_c * abs(c)
+            if stop or j >= max_iters:
+                emit(c, sg, j, nflips)
+                if close and j < max_iters:
+                    push(abs(c - c_prev) / (tol_c * abs(c)), dict(j=j + 1, mode=0, signs=[s.copy() for s in sg], c_prev=c,
+                                                                   flips=(), nflips=nflips + 1))
+                return
+            if close:
+                emit(c, sg, j, nflips + 1)
+            c_prev = c
+            j += 1
+
+    push(0.0, dict(j=1, mode=0, signs=[_u64(s).copy() for s in signs0], c_prev=-np.inf, flips=(), nflips=0))
+    runs = 0
+    while heap and accepted[0] is None and runs < max_runs:
+        run(heapq.heappop(heap)[2])
+        runs += 1
+    return dict(outcomes=outcomes, accepted=accepted[0], truncated=bool(heap) and accepted[0] is None)
 
 
 def tensor_decompose(a, w: int, seed: int, max_iters: int = DEFAULT_MAX_ITERS, want_remainder: bool = False):

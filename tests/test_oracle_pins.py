@@ -125,6 +125,94 @@ def test_greedy_cut_is_monotone_and_a_fixed_point(oracle, m, n, seed):
     assert 0 <= g["margin"][0] <= 1 and 0 <= g["margin"][1] <= 1
 
 
+def test_margin_reports_a_planted_near_tie(oracle):
+    # The margin output is what lets a parity test call a term tie-sensitive, so it is pinned by hand:
+    # R t_0 = (8, -4, 8e-7) with t_0 = (+,+): the smallest relative |entry| of the row decision is 1e-7;
+    # s = (+,-,+) gives R^T s = (4 + 4e-7, 8 + 4e-7): column margin (4 + 4e-7)/(8 + 4e-7); t = t_0 again,
+    # so the second alternation repeats the first and the minima stay.
+    R = np.array([[3.0, 5.0], [-1.0, -3.0], [4e-7, 4e-7]])
+    g = oracle.greedy_signed_cut(R, bits_of([1.0, 1.0]))
+    assert g["iters"] == 2 and np.array_equal(dense(g["s"], 3), [1.0, -1.0, 1.0])
+    assert g["margin"][0] == pytest.approx(1e-7, rel=1e-12)
+    assert g["margin"][1] == pytest.approx((4.0 + 4e-7) / (8.0 + 4e-7), rel=1e-12)
+    # a tie-free case: every |entry| of both products is known, the margin is their smallest ratio
+    R = np.array([[2.0, 1.0], [1.0, 3.0]])
+    g = oracle.greedy_signed_cut(R, bits_of([1.0, 1.0]))    # u = (3, 4), s = (+,+), v = (3, 4), fixed point
+    assert g["iters"] == 2 and g["margin"][0] == pytest.approx(0.75, rel=1e-15)
+    assert g["margin"][1] == pytest.approx(0.75, rel=1e-15)
+    # an exact tie (u_i = 0) is a margin of zero
+    g = oracle.greedy_signed_cut(np.array([[1.0, -1.0], [2.0, 1.0]]), bits_of([1.0, 1.0]))
+    assert g["margin"][0] == 0.0
+    # on a random matrix the margin is the minimum over every decision vector of a replay by hand
+    R = rng_matrix(40, 30, 9)
+    t0 = oracle.rng_signs(9, 0, 1, 30)
+    g = oracle.greedy_signed_cut(R, t0)
+    t = dense(t0, 30)
+    mu, mv = np.inf, np.inf
+    for _ in range(g["iters"]):
+        u = R @ t
+        mu = min(mu, np.abs(u).min() / np.abs(u).max())
+        s = np.where(u < 0, -1.0, 1.0)
+        v = R.T @ s
+        mv = min(mv, np.abs(v).min() / np.abs(v).max())
+        t = np.where(v < 0, -1.0, 1.0)
+    assert g["margin"][0] == pytest.approx(mu, rel=1e-9) and g["margin"][1] == pytest.approx(mv, rel=1e-9)
+
+
+def test_near_tie_search_is_algorithm4_plus_the_planted_alternatives(oracle):
+    # (i) with no tolerance the search is Algorithm 4 itself: one outcome, the C routine's, bit for bit
+    for seed, (m, n) in enumerate([(8, 8), (40, 70), (129, 65), (200, 333)]):
+        R = rng_matrix(m, n, 50 + seed)
+        t0 = oracle.rng_signs(seed, 3, 1, n)
+        g = oracle.greedy_signed_cut(R, t0)
+        r = oracle.greedy_signed_cut_near_ties(R, t0, 0.0)
+        assert len(r["outcomes"]) == 1 and not r["truncated"]
+        o = r["outcomes"][0]
+        assert o["iters"] == g["iters"] and o["c"] == g["c"] and o["flips"] == 0
+        assert np.array_equal(o["s"], g["s"]) and np.array_equal(o["t"], g["t"])
+    # (ii) a planted near tie: row i of R is moved so that (R t_0)_i = +-delta with delta = 1e-8 max|R t_0|.
+    # The two matrices differ by 2e-8 relative in one row, so Algorithm 4 (the C routine) run on each gives
+    # the two legitimate outcomes; the search on either matrix with tol = 1e-6 must list both, and the one
+    # that needs a decision taken against the literal rule carries flips >= 1.
+    m, n, i = 60, 45, 17
+    R = rng_matrix(m, n, 77)
+    t0 = oracle.rng_signs(77, 0, 1, n)
+    t0d = dense(t0, n)
+    u = R @ t0d
+    delta = 1e-8 * np.abs(u).max()
+    Rp, Rm = R.copy(), R.copy()
+    Rp[i] += (delta - u[i]) / n * t0d      # (Rp t_0)_i = +delta
+    Rm[i] += (-delta - u[i]) / n * t0d     # (Rm t_0)_i = -delta
+    gp, gm = oracle.greedy_signed_cut(Rp, t0), oracle.greedy_signed_cut(Rm, t0)
+    assert gp["margin"][0] == pytest.approx(1e-8, rel=1e-3) and gm["margin"][0] == pytest.approx(1e-8, rel=1e-3)
+    for Rx, lit, other in ((Rp, gp, gm), (Rm, gm, gp)):
+        r = oracle.greedy_signed_cut_near_ties(Rx, t0, 1e-6)
+        outs = r["outcomes"]
+        assert not r["truncated"] and len(outs) >= 2
+        assert np.array_equal(outs[0]["s"], lit["s"]) and np.array_equal(outs[0]["t"], lit["t"]) and outs[0]["flips"] == 0
+        hit = [o for o in outs if np.array_equal(o["s"], other["s"]) and np.array_equal(o["t"], other["t"])
+               and o["iters"] == other["iters"]]
+        assert hit and hit[0]["flips"] >= 1
+        assert hit[0]["c"] == pytest.approx(other["c"], rel=1e-6)
+        # every listed outcome is a valid cut of Rx: c = <s, Rx t>
+        for o in outs:
+            assert o["c"] == pytest.approx(dense(o["s"], m) @ Rx @ dense(o["t"], n), rel=1e-12)
+    # (iii) accept stops the search at the first match and reports its index
+    r = oracle.greedy_signed_cut_near_ties(Rp, t0, 1e-6, accept=lambda o: np.array_equal(o["s"], gm["s"])
+                                           and np.array_equal(o["t"], gm["t"]))
+    assert r["accepted"] is not None and np.array_equal(r["outcomes"][r["accepted"]]["t"], gm["t"])
+    # (iv) the stop decision: when the last increase of c is below tol_c the earlier triple is an outcome too
+    R = rng_matrix(30, 30, 5)
+    t0 = oracle.rng_signs(5, 0, 1, 30)
+    g = oracle.greedy_signed_cut(R, t0)
+    h = g["c_hist"]
+    rel = (h[-2] - h[-3]) / h[-2]          # the last strict increase
+    r = oracle.greedy_signed_cut_near_ties(R, t0, 0.0, tol_c=rel * 1.01)
+    assert any(o["iters"] == g["iters"] - 1 and o["flips"] == 1 for o in r["outcomes"])
+    r = oracle.greedy_signed_cut_near_ties(R, t0, 0.0, tol_c=rel * 0.5)
+    assert all(o["iters"] != g["iters"] - 1 for o in r["outcomes"])
+
+
 def test_greedy_cut_against_brute_force(oracle):
     # Section 2.2: ||A|| = max_{s,t} <s, A t>.  Greedy never exceeds it, ends 1-flip optimal,
     # and the best start among all 2^n reaches it.
@@ -530,6 +618,35 @@ def test_axial_cut_sweeps_in_order_and_is_monotone(oracle):
             w = np.einsum("ijk,i,j->k", a, np.array(s1), np.array(s2))
             best = max(best, np.abs(w).sum())
     assert g["c"] <= best * (1 + 1e-12)
+
+
+def test_tensor_near_tie_search_is_algorithm12_plus_the_planted_alternatives(oracle):
+    rs = np.random.default_rng(21)
+    for shape in [(6, 5, 4), (20, 13, 3), (7, 6, 5, 2)]:
+        a = rs.standard_normal(shape)
+        s0 = [oracle.rng_signs(3, 1, i, d) for i, d in enumerate(shape)]
+        g = oracle.axial_greedy_cut(a, s0)
+        r = oracle.axial_greedy_cut_near_ties(a, s0, 0.0)
+        assert len(r["outcomes"]) == 1 and not r["truncated"]
+        o = r["outcomes"][0]
+        assert o["iters"] == g["iters"] and o["c"] == g["c"]
+        assert all(np.array_equal(x, y) for x, y in zip(o["signs"], g["signs"]))
+    # planted near tie in the first decision (mode 0, entry i): two tensors that differ by 2e-8 relative in
+    # one slice give Algorithm 12's two legitimate outcomes; the search with tol = 1e-6 lists both
+    shape, i = (15, 12, 3), 4
+    a = rs.standard_normal(shape)
+    s0 = [oracle.rng_signs(8, 0, q, d) for q, d in enumerate(shape)]
+    others = np.multiply.outer(dense(s0[1], 12), dense(s0[2], 3))
+    u = (a * others).sum(axis=(1, 2))
+    delta = 1e-8 * np.abs(u).max()
+    ap, am = a.copy(), a.copy()
+    ap[i] += (delta - u[i]) / others.size * others
+    am[i] += (-delta - u[i]) / others.size * others
+    gp, gm = oracle.axial_greedy_cut(ap, s0), oracle.axial_greedy_cut(am, s0)
+    r = oracle.axial_greedy_cut_near_ties(ap, s0, 1e-6)
+    assert all(np.array_equal(x, y) for x, y in zip(r["outcomes"][0]["signs"], gp["signs"]))
+    hit = [o for o in r["outcomes"] if all(np.array_equal(x, y) for x, y in zip(o["signs"], gm["signs"]))]
+    assert hit and hit[0]["flips"] >= 1 and hit[0]["iters"] == gm["iters"]
 
 
 @pytest.mark.parametrize("shape,w,seed", [((6, 5, 4), 12, 1), ((3, 4, 2, 5), 10, 2), ((70, 9, 3), 8, 3)])
