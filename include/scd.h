@@ -55,13 +55,15 @@ typedef enum {
     SCD_ENODEVICE = -6,  /* no usable HIP device */
     SCD_ETIMEOUT = -7,   /* a bounded device-side wait ran out (workgroups of a persistent launch were not all
                             resident); the context refuses further steps until scd_set_remainder */
-    SCD_ESINGULAR = -8   /* scd_lsq_decompose: a new term lies in the span of the earlier ones (normal equations
+    SCD_ESINGULAR = -8,  /* scd_lsq_decompose: a new term lies in the span of the earlier ones (normal equations
                             singular to working precision) */
+    SCD_ETOOBIG = -9     /* scd_col_signed_sum_noalloc: the input needs more than SCD_NOALLOC_SCRATCH_BYTES */
 } scd_status;
 
 #define SCD_MAX_ORDER 8
 #define SCD_DEFAULT_MAX_ITERS 4096
 #define SCD_LSQ_MAX_WIDTH 4096
+#define SCD_NOALLOC_SCRATCH_BYTES (24u << 20) /* fixed work space of scd_col_signed_sum_noalloc, per device */
 
 typedef struct scd_ctx scd_ctx; /* opaque: remainder, scratch, outputs so far, position in the random stream */
 
@@ -124,6 +126,23 @@ int scd_row_signed_sum(const void* R, scd_dtype dt, int64_t m, int64_t n, const 
                        void* stream, double* u, uint64_t* sbits);
 int scd_col_signed_sum(const void* R, scd_dtype dt, int64_t m, int64_t n, const uint64_t* sbits,
                        void* stream, double* v, uint64_t* tbits, double* c);
+
+/* The column half step for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels, same geometry and therefore the
+ * same bits in v, tbits and c as scd_col_signed_sum, but
+ *  - the per-workgroup partial column sums and the partial sums of |v| live in a fixed work space of
+ *    SCD_NOALLOC_SCRATCH_BYTES that is part of the library's code object (one copy per device, held until the
+ *    process ends); the call allocates and frees nothing;
+ *  - the call only enqueues its three launches on `stream` and returns: v, tbits and c are complete once the
+ *    stream has reached that point (the caller synchronises, or orders later work on the same stream);
+ *  - inputs with 256 + 256*ceil(ceil(n/64)/32) + ceil(m / ceil(m/1024)) * n * sizeof(dt) bytes of work space above
+ *    the limit are refused with SCD_ETOOBIG before anything is enqueued (4096 x 4096 f32 fits; f64 does not);
+ *  - every call on a device shares that device's work space, which keeps the previous call's contents (each call
+ *    overwrites all it reads, nothing needs clearing): calls that overlap in time on one device race, also from
+ *    different streams or threads.  Order them on one stream or with events.
+ * The device is the current one at the time of the call; R, sbits and the outputs must live on it. */
+int scd_col_signed_sum_noalloc(const void* R, scd_dtype dt, int64_t m, int64_t n, const uint64_t* sbits,
+                               void* stream, double* v, uint64_t* tbits, double* c);
 
 /* ---- expansion (the definition, Section 2.2 / 5.2) ---------------------------------------------
  * out (dtype dt, dims) = sum_{j<w} c_j * tensor product of term j's sign vectors.  Per entry the

@@ -970,6 +970,19 @@ int scd_row_signed_sum(const void* R, scd_dtype dt, int64_t m, int64_t n, const 
     return rc;
 }
 
+// The three launches of a column half step on caller data: per-workgroup partial column sums, their
+// fixed-order join (v, t, partial sums of |v|), the sum of those.  `partials` holds grid * n elements of dt,
+// `cparts` ceil(n/64) doubles.
+static hipError_t enqueue_col_signed_sum(const void* R, scd_dtype dt, int64_t m, int64_t n, int rpw, int grid,
+                                         const uint64_t* sbits, void* partials, double* cparts, double* v, uint64_t* tbits,
+                                         double* cout, hipStream_t st)
+{
+    hipError_t e = launch_halfstep(R, dt, m, n, rpw, grid, 0, nullptr, sbits, partials, nullptr, st);
+    if (e == hipSuccess) e = launch_reduce_plain(partials, dt, grid, n, v, tbits, cparts, st);
+    if (e == hipSuccess) e = launch_sum_parts(cparts, (int)words_for(n), cout, st);
+    return e;
+}
+
 int scd_col_signed_sum(const void* R, scd_dtype dt, int64_t m, int64_t n, const uint64_t* sbits, void* stream, double* v,
                        uint64_t* tbits, double* cout)
 {
@@ -991,9 +1004,7 @@ int scd_col_signed_sum(const void* R, scd_dtype dt, int64_t m, int64_t n, const 
         (void)hipGetLastError();
         rc = SCD_ENOMEM;
     } else {
-        e = launch_halfstep(R, dt, m, n, rpw, grid, 0, nullptr, sbits, partials, nullptr, st);
-        if (e == hipSuccess) e = launch_reduce_plain(partials, dt, grid, n, v, tbits, cparts, st);
-        if (e == hipSuccess) e = launch_sum_parts(cparts, ncp, cout ? cout : ctmp, st);
+        e = enqueue_col_signed_sum(R, dt, m, n, rpw, grid, sbits, partials, cparts, v, tbits, cout ? cout : ctmp, st);
         if (e == hipSuccess) e = hipStreamSynchronize(st);
         if (e != hipSuccess) {
             g_last_hip = (int)e;
@@ -1005,6 +1016,60 @@ int scd_col_signed_sum(const void* R, scd_dtype dt, int64_t m, int64_t n, const 
     if (cparts) (void)hipFree(cparts);
     if (ctmp) (void)hipFree(ctmp);
     return rc;
+}
+
+// ---------------------------------------------------------------------------------------------- no allocation
+
+// Work space of scd_col_signed_sum_noalloc: one array per device, part of the code object, held until the
+// process ends.  Host code never uses the array's name as an address (it is a host-side stand-in): the
+// device address is asked for once per device with hipGetSymbolAddress and kept in g_scratch_ptr.
+static __device__ __align__(256) unsigned char scratch[SCD_NOALLOC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {nullptr};
+
+// Device address of `scratch` on the current device (looked up on the first call on that device).
+int scratch_address(unsigned char** out)
+{
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return SCD_ENODEVICE;
+    std::lock_guard<std::mutex> lk(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return SCD_EHIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = (unsigned char*)g_scratch_ptr[dev];
+    return SCD_OK;
+}
+}  // namespace
+
+int scd_col_signed_sum_noalloc(const void* R, scd_dtype dt, int64_t m, int64_t n, const uint64_t* sbits, void* stream,
+                               double* v, uint64_t* tbits, double* cout)
+{
+    if (!R || !sbits || !dtype_ok(dt) || m < 1 || n < 1) return SCD_EINVAL;
+    int rpw, grid;
+    halfstep_geometry(m, &rpw, &grid);
+    const size_t es = dt == SCD_F32 ? 4 : 8;
+    // layout: [0, 256) the cut value when the caller does not want it; then ceil(n/64) doubles of partial
+    // sums of |v|, padded to 256 bytes; then grid * n partial column sums
+    const size_t cparts_bytes = (((size_t)words_for(n) * 8 + 255) / 256) * 256;
+    const size_t need = 256 + cparts_bytes + (size_t)grid * (size_t)n * es;
+    if ((double)grid * (double)n * (double)es > (double)SCD_NOALLOC_SCRATCH_BYTES || need > (size_t)SCD_NOALLOC_SCRATCH_BYTES)
+        return SCD_ETOOBIG;
+    unsigned char* base = nullptr;
+    SCD_TRY(scratch_address(&base));
+    double* ctmp = (double*)base;
+    double* cparts = (double*)(base + 256);
+    void* partials = base + 256 + cparts_bytes;
+    // every word of the work space that is read was written by this call: nothing to clear
+    HIP_TRY(enqueue_col_signed_sum(R, dt, m, n, rpw, grid, sbits, partials, cparts, v, tbits, cout ? cout : ctmp,
+                                   (hipStream_t)stream));
+    return SCD_OK;
 }
 
 // ---------------------------------------------------------------------------------------------- expand, bitsets
@@ -1531,6 +1596,7 @@ const char* scd_strerror(int code)
         case SCD_ENODEVICE: return "no HIP device";
         case SCD_ETIMEOUT: return "a bounded device-side wait ran out; give the context a remainder again or destroy it";
         case SCD_ESINGULAR: return "a new term lies in the span of the earlier ones: normal equations singular";
+        case SCD_ETOOBIG: return "the input needs more work space than the call's fixed work space holds";
         default: return "unknown status";
     }
 }

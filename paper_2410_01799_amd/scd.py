@@ -18,7 +18,8 @@ _lib = None
 
 F32, F64 = 0, 1
 OK, WMAXITER = 0, 1
-EINVAL, ENOMEM, EHIP, EFULL, ENONFINITE, ENODEVICE, ETIMEOUT = -1, -2, -3, -4, -5, -6, -7
+EINVAL, ENOMEM, EHIP, EFULL, ENONFINITE, ENODEVICE, ETIMEOUT, ESINGULAR, ETOOBIG = -1, -2, -3, -4, -5, -6, -7, -8, -9
+NOALLOC_SCRATCH_BYTES = 24 << 20
 
 EXPORTS = [
     "scd_decompose", "scd_create", "scd_destroy", "scd_set_max_iters", "scd_step", "scd_run", "scd_step_from",
@@ -26,6 +27,7 @@ EXPORTS = [
     "scd_expand", "scd_pack", "scd_unpack", "scd_rng_signs", "scd_strerror", "scd_last_hip_error", "scd_traffic",
     "scd_probe_stream", "scd_profile_sweeps", "scd_probe_exchange", "scd_engine", "scd_set_workgroups",
     "scd_apply", "scd_apply_workspace_bytes", "scd_lsq_decompose", "scd_lsq_decompose_tensor", "scd_decompose_scalars", "scd_sparse_flips",
+    "scd_col_signed_sum_noalloc",
 ]
 
 
@@ -71,6 +73,7 @@ def lib() -> C.CDLL:
         L.scd_set_remainder.argtypes = [vp, vp]
         L.scd_row_signed_sum.argtypes = [vp, C.c_int, i64, i64, vp, vp, vp, vp]
         L.scd_col_signed_sum.argtypes = [vp, C.c_int, i64, i64, vp, vp, vp, vp, vp]
+        L.scd_col_signed_sum_noalloc.argtypes = [vp, C.c_int, i64, i64, vp, vp, vp, vp, vp]
         L.scd_expand.argtypes = [pvp, vp, C.c_int, C.c_int, pi64, i64, vp, vp]
         L.scd_pack.argtypes = [vp, C.c_int, i64, vp, vp]
         L.scd_unpack.argtypes = [vp, i64, C.c_int, vp, vp]
@@ -275,6 +278,16 @@ def scd_col_signed_sum(R: torch.Tensor, sbits: torch.Tensor):
     st = lib().scd_col_signed_sum(_ptr(R), _dt(R), m, n, _ptr(_dev(sbits, "sbits")), _stream(), _ptr(v), _ptr(t), _ptr(c))
     _check(st, "scd_col_signed_sum")
     return v, t, c
+
+
+def scd_col_signed_sum_noalloc(R: torch.Tensor, sbits: torch.Tensor, v: torch.Tensor, t: torch.Tensor, c: torch.Tensor):
+    """The column half step into caller-provided outputs, without any device allocation inside the library;
+    enqueued on the current stream, not waited for."""
+    R = _dev(R, "R")
+    m, n = R.shape
+    st = lib().scd_col_signed_sum_noalloc(_ptr(R), _dt(R), m, n, _ptr(_dev(sbits, "sbits")), _stream(), _ptr(v), _ptr(t),
+                                          _ptr(c))
+    _check(st, "scd_col_signed_sum_noalloc")
 
 
 def scd_probe_stream(src: torch.Tensor, dst: Optional[torch.Tensor] = None, grid: int = 2048, reps: int = 20) -> float:
