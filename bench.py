@@ -12,7 +12,6 @@ from __future__ import annotations
 
 import argparse
 import json
-import os
 import sys
 import time
 from pathlib import Path
@@ -21,11 +20,25 @@ ROOT = Path(__file__).resolve().parent
 if str(ROOT) not in sys.path:
     sys.path.insert(0, str(ROOT))
 
-HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
-# HBM/fabric bytes measured with rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE (two runs, each scaled by the
-# plain copy kernel of known size); figures and commands in profiles/memory_traffic_f32_pmc.txt
-RESIDENT_TRAFFIC_PER_ROW_PHASE = 6.16e6   # bytes per alternation of resident_kernel<8,16,16> (4096x4096 f32)
-STREAM_TRAFFIC_PER_LAUNCH = 68.7e6        # bytes per launch of rowpass_tiled_kernel<float,4,4> (4096x4096 f32)
+HBM_PEAK_GBS = 8000.0        # MI355X published HBM3E bandwidth
+FP32_VECTOR_PEAK_TFLOPS = 157.3  # MI355X published fp32 vector rate: 256 CUs x 128 lanes x 2 flop (FMA) x 2.4 GHz
+# What add-only work without packed FP32 can issue: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz lane-operations/s
+# (one 64-lane instruction per SIMD every 4 cycles); packed FP32 is switched off on the test machines, and an add is
+# one flop where the published rate counts two per FMA.
+UNPACKED_LANE_OPS_PER_S = 256 * 64 * 2.4e9
+TRAFFIC_FILE = ROOT / "profiles" / "memory_traffic_pmc.txt"
+
+
+def measured_traffic() -> dict:
+    """HBM/fabric bytes from the committed rocprofv3 --pmc summary (FETCH_SIZE and WRITE_SIZE, each scaled by the
+    plain copy kernel of known size): lines `TRAFFIC <key> <bytes> <per what>`.  Not measured by this run."""
+    out = {}
+    if TRAFFIC_FILE.exists():
+        for line in TRAFFIC_FILE.read_text().splitlines():
+            f = line.split()
+            if len(f) >= 3 and f[0] == "TRAFFIC":
+                out[f[1]] = float(f[2])
+    return out
 
 
 def cpu_baseline(A64, seed: int, budget_s: float):
@@ -287,6 +300,8 @@ def main() -> int:
                          "matrices, each to 50 %% of its bf16 footprint) and print seconds per layer")
     ap.add_argument("--no-layer", action="store_true",
                     help="headline only: skip the decoder-layer figure that the default run appends")
+    ap.add_argument("--no-extra", action="store_true",
+                    help="headline only: skip the f64 run, the error curves and the secondary rooflines")
     ap.add_argument("--layer-fraction", type=float, default=1.0,
                     help="with --layer: run only this fraction of every matrix's width (the rest is extrapolated "
                          "and the line says so)")
@@ -306,8 +321,6 @@ def main() -> int:
                     help="only run the plain copy kernel (64 MiB, 20+1 launches): the known-size reference "
                          "for scaling the profiler's FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
-    if args.engine == "stream":
-        os.environ["SCD_RESIDENT"] = "0"
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
         return 2
@@ -347,13 +360,15 @@ def main() -> int:
     A64 = workloads.gaussian_matrix(m, n, seed, np.float64)
     A = torch.from_numpy(A64.astype(np.float32)).cuda()
     torch.cuda.synchronize()
-
     esize = A.element_size()
+    headline = (m, n, w) == (4096, 4096, 8192)
+    traffic = measured_traffic()
+    engine_opts = {"resident": 0, "sparse": 0} if args.engine == "stream" else {}
 
     def one_step():
         # one whole decomposition through the stateful calls (what scd_decompose does internally),
         # so that the engine's own launch timing can be read before the context goes away
-        with scd.ScdContext(A, w, seed) as ctx:
+        with scd.ScdContext(A, w, seed, options=engine_opts) as ctx:
             ctx.run(w)
             res = ctx.results()
             eng = ctx.engine()
@@ -375,30 +390,16 @@ def main() -> int:
     iters_total = int(iters.sum())
     final_rel = float(trace[-1] / trace[0])
     terms_per_s = args.steps * w / elapsed
-    # algorithmic bytes of one decomposition: every alternation reads R once; every term's update
-    # writes it once (fused into the first alternation of the next term): (I_k + 1) * mn * E per term
+    # algorithmic bytes of one decomposition by a streaming implementation: every alternation reads R once,
+    # every term's update writes it once (fused into the first alternation of the next term)
     algo_bytes = (iters_total + w) * m * n * esize
     stream_s = scd.scd_probe_stream(A, None, 256, 50)
+    stream_gbs = m * n * esize / stream_s / 1e9
 
-    if eng["engine"] == 1:
-        # register-resident engine: the dominant kernel is the one persistent launch per decomposition;
-        # its duration comes from HIP events recorded around it on the library's stream, inside the
-        # timed region
-        sec = sum(launch_s) / len(launch_s)
-        bpl = sum(launch_bytes) / len(launch_bytes)
-        achieved = bpl / sec / 1e9
-        roof = {"bound": "hbm", "kernel": "resident_kernel (one persistent launch per decomposition)",
-                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": round(RESIDENT_TRAFFIC_PER_ROW_PHASE * bpl / (m * n * esize)) if (m, n) == (4096, 4096) else None,
-                "bytes_per_launch": round(bpl), "launch_us": round(sec * 1e6, 1),
-                "us_per_alternation": round(sec * 1e6 / (bpl / (m * n * esize)), 3),
-                "note": "remainder held in registers: algorithmic bytes are what a streaming pass per "
-                        "alternation would move, not HBM traffic",
-                "measured_stream_read_gbs": round(m * n * esize / stream_s / 1e9, 1)}
-    else:
-        # launch-stream engine: HIP events around each row-pass launch of a sample of sweeps
-        with scd.ScdContext(A, args.profile_sweeps // 8 + 64, seed) as ctx:
+    def stream_roofline(ctx_terms):
+        """The row pass of the launch-stream engine (one launch = one read of R = one alternation, or the fused
+        update + first alternation): HIP events around each launch of a sample of sweeps."""
+        with scd.ScdContext(A, ctx_terms, seed, options={"resident": 0, "sparse": 0}) as ctx:
             ctx.run(8)
             before = ctx.traffic()
             rowpass_s, reduce_s = ctx.profile_sweeps(args.profile_sweeps)
@@ -406,42 +407,77 @@ def main() -> int:
         passes = after["passes"] - before["passes"]
         bytes_per_launch = (after["bytes"] - before["bytes"]) / max(passes, 1)
         achieved = bytes_per_launch / rowpass_s / 1e9
-        roof = {"bound": "hbm", "kernel": "rowpass_tiled_kernel<float,4,4>",
-                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": round(STREAM_TRAFFIC_PER_LAUNCH) if (m, n) == (4096, 4096) else None,
+        return {"bound": "hbm", "kernel": "rowpass_tiled_kernel<float,4,4>", "achieved": round(achieved, 1),
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": traffic.get("rowpass_tiled_4096x4096_f32_per_launch") if (m, n) == (4096, 4096) else None,
+                "traffic_source": str(TRAFFIC_FILE.relative_to(ROOT)),
                 "bytes_per_launch": round(bytes_per_launch), "launch_us": round(rowpass_s * 1e6, 3),
                 "reduce_launch_us": round(reduce_s * 1e6, 3),
-                "measured_stream_read_gbs": round(m * n * esize / stream_s / 1e9, 1)}
+                "frac_with_reduce": round(bytes_per_launch / (rowpass_s + reduce_s) / 1e9 / HBM_PEAK_GBS, 4),
+                "measured_stream_read_gbs": round(stream_gbs, 1),
+                "note": "launch_us by HIP events around every launch (2-4 us of dispatch overhead included); "
+                        "rocprofv3's kernel-only duration is in profiles/"}
+
+    extra = {}
+    if eng["engine"] == 1:
+        # Register-resident engine: the dominant kernel is the one persistent launch per decomposition; its
+        # duration comes from HIP events recorded around it on the library's stream, inside the timed region.
+        # The remainder never leaves the registers, so neither HBM nor the matrix cores bound it: its work is
+        # one add per element and half step (Section 3.4), priced against the chip's fp32 vector rate; what
+        # actually limits it is the latency of the two exchanges per alternation (latency_floor).
+        sec = sum(launch_s) / len(launch_s)
+        phases = sum(launch_bytes) / len(launch_bytes) / (m * n * esize)     # row phases + updates of one launch
+        alternations = phases - w                                           # launch_bytes counts one write per update
+        real_alternations = iters_total                                     # the dropped row phase per term is not work
+        flops = 2.0 * m * n * real_alternations + 3.0 * m * n * w           # adds of both half steps; update: sub, square, add
+        achieved = flops / sec / 1e12
+        us_alt = sec * 1e6 / alternations
+        lane_ops = 2.0 * m * n * alternations + 3.0 * m * n * w             # executed, dropped phases included
+        xchg_s = scd.scd_probe_exchange(0, 256, 16, 2000)
+        roof = {"bound": "alu", "kernel": "resident_kernel (one persistent launch per decomposition)",
+                "achieved": round(achieved, 3), "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(achieved / FP32_VECTOR_PEAK_TFLOPS, 4),
+                "traffic": round(traffic["resident_kernel_4096x4096_f32_per_alternation"] * alternations)
+                if (m, n) == (4096, 4096) and "resident_kernel_4096x4096_f32_per_alternation" in traffic else None,
+                "traffic_source": str(TRAFFIC_FILE.relative_to(ROOT)) + " (committed counter run, not measured by this run)",
+                "flops_per_launch": round(flops), "launch_us": round(sec * 1e6, 1),
+                "us_per_alternation": round(us_alt, 3),
+                "issue": {"lane_ops_per_launch": round(lane_ops), "peak_lane_ops_per_s": UNPACKED_LANE_OPS_PER_S,
+                          "frac": round(lane_ops / sec / UNPACKED_LANE_OPS_PER_S, 4),
+                          "note": "vector instructions issued against what add-only work can issue without packed FP32"},
+                "latency_floor": {"exchange_us": round(xchg_s * 1e6, 3), "exchanges_per_alternation": 2,
+                                  "frac_of_alternation": round(min(1.0, 2 * xchg_s * 1e6 / us_alt), 4),
+                                  "note": "two dependent all-to-all exchanges of partial sums per alternation "
+                                          "(16 workgroups each), timed alone by the exchange probe"},
+                "hbm_equivalent_gbs": round(algo_bytes / (elapsed / args.steps) / 1e9, 1),
+                "note": "the remainder is held in registers: hbm_equivalent_gbs is what a streaming pass per "
+                        "alternation would have to move, not traffic, and is no roofline fraction"}
+        if headline and not args.no_extra:
+            extra["roofline_stream"] = stream_roofline(args.profile_sweeps // 8 + 64)
+    else:
+        roof = stream_roofline(args.profile_sweeps // 8 + 64)
 
     # Bytes the paper's own scheme would move for this run (Section 3.1's cached products, Section 3.2's
     # delayed update): dense first alternation of a term (R once for u, once for v), then one row of R per
     # changed row sign and one column per changed column sign, plus the update amortised over 32 terms.
     # The sign changes are counted by the sparse engine on the first terms of the same decomposition.
     sample_terms = min(w, 128)
-    saved = {k: os.environ.get(k) for k in ("SCD_RESIDENT", "SCD_SPARSE_MIN_MIB")}
-    os.environ["SCD_RESIDENT"] = "0"
-    os.environ["SCD_SPARSE_MIN_MIB"] = "0"
-    try:
-        with scd.ScdContext(A, sample_terms, seed) as ctx:
-            useful = None
-            if ctx.engine()["engine"] == 2:
-                ctx.run(sample_terms)
-                fl = ctx.sparse_flips()
-                per_term = (2.0 * m * n * esize + esize * (n * fl["rows"] + m * fl["cols"]) / sample_terms
-                            + 2.0 * m * n * esize / 32.0)
-                useful = {"bytes_per_term": round(per_term), "row_sign_changes_per_term": round(fl["rows"] / sample_terms, 1),
-                          "col_sign_changes_per_term": round(fl["cols"] / sample_terms, 1),
-                          "gbs": round(per_term * terms_per_s / 1e9, 1),
-                          "frac": round(per_term * terms_per_s / 1e9 / HBM_PEAK_GBS, 4),
-                          "sample": f"sign changes counted on the first {sample_terms} terms"}
-    finally:
-        for k, v in saved.items():
-            if v is None:
-                os.environ.pop(k, None)
-            else:
-                os.environ[k] = v
+    with scd.ScdContext(A, sample_terms, seed, options={"resident": 0, "sparse_min_mib": 0}) as ctx:
+        useful = None
+        if ctx.engine()["engine"] == 2:
+            ctx.run(sample_terms)
+            fl = ctx.sparse_flips()
+            per_term = (2.0 * m * n * esize + esize * (n * fl["rows"] + m * fl["cols"]) / sample_terms
+                        + 2.0 * m * n * esize / 32.0)
+            useful = {"bytes_per_term": round(per_term), "row_sign_changes_per_term": round(fl["rows"] / sample_terms, 1),
+                      "col_sign_changes_per_term": round(fl["cols"] / sample_terms, 1),
+                      "gbs": round(per_term * terms_per_s / 1e9, 1),
+                      "frac": round(per_term * terms_per_s / 1e9 / HBM_PEAK_GBS, 4),
+                      "sample": f"sign changes counted on the first {sample_terms} terms"}
     roof["useful_bytes"] = useful
+
+    def curve_of(tr, every=256):
+        return {str(k): round(float(tr[k] / tr[0]), 6) for k in range(0, len(tr), every)}
 
     out = {
         "metric": f"signed-cut terms/s on {m}x{n} f32 (w={w})",
@@ -459,13 +495,50 @@ def main() -> int:
         "config": {"workload": f"config 2: {m}x{n} f32 i.i.d. N(0,1) (PCG64 seed {seed}), greedy decomposition to w={w}",
                    "terms": w, "alternations_per_term": round(iters_total / w, 2),
                    "final_relative_error": round(final_rel, 6),
-                   "engine": "register-resident" if eng["engine"] == 1 else "launch-stream"},
-        "effective_gbs": round(algo_bytes / (elapsed / args.steps) / 1e9, 1),
+                   "engine": ["launch-stream", "register-resident", "sparse"][eng["engine"]]},
         "roofline": roof,
     }
+    out.update(extra)
+    if headline and not args.no_extra:
+        # the rest of workload 2: the f64 copy of the same matrix to w = 2048 (sparse engine), and the relative
+        # error every 256 terms for both runs, beside the values Figure 7's slope gives
+        A64d = torch.from_numpy(A64).cuda()
+        with scd.ScdContext(A64d, 2048, seed) as ctx:   # warm-up of the code path on a few terms
+            ctx.run(8)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        with scd.ScdContext(A64d, 2048, seed) as ctx:
+            ctx.run(2048)
+            r64 = ctx.results()
+            e64 = ctx.engine()
+        torch.cuda.synchronize()
+        dt64 = time.perf_counter() - t0
+        tr64 = r64["trace"].cpu().numpy()
+        it64 = int(r64["iters"].sum())
+        sparse_roof = None
+        key = "sparse_delay_kernel_4096x4096_f64_per_term"
+        if e64["engine"] == 2 and key in traffic:
+            gbs = traffic[key] * 2048 / e64["last_launch_seconds"] / 1e9
+            sparse_roof = {"bound": "hbm", "kernel": "sparse_delay_kernel<double> (one persistent launch)",
+                           "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4),
+                           "traffic": round(traffic[key] * 2048), "traffic_source": str(TRAFFIC_FILE.relative_to(ROOT)),
+                           "launch_us": round(e64["last_launch_seconds"] * 1e6, 1),
+                           "note": "achieved = counter bytes (committed counter run) over this run's launch time: the "
+                                   "sparse engine moves what the flipped signs need, and is bound by the latency of its "
+                                   "exchanges, not by bandwidth"}
+        out["f64"] = {"workload": "the f64 copy of the same matrix to w=2048", "w": 2048, "terms_per_s": round(2048 / dt64, 2),
+                      "seconds": round(dt64, 3), "alternations_per_term": round(it64 / 2048, 2),
+                      "engine": ["launch-stream", "register-resident", "sparse"][e64["engine"]],
+                      "final_relative_error": round(float(tr64[-1] / tr64[0]), 6)}
+        if sparse_roof:
+            out["roofline_sparse"] = sparse_roof
+        out["curve"] = {"every": 256, "f32": curve_of(trace), "f64": curve_of(tr64),
+                        "figure7_slope": {"r(2048)": 0.614, "r(8192)": 0.142,
+                                          "note": "exp(-2.3845e-4 k), the decay that both printed points of Figure 7 give"}}
+        del A64d
     if args.cpu_seconds > 0:
         out["cpu_baseline"] = cpu_baseline(A64, seed, args.cpu_seconds)
-    if not args.no_layer and (m, n, w) == (4096, 4096, 8192):
+    if not args.no_layer and headline:
         # the metric's second figure: one decoder layer at the 50 % widths (its own timed region)
         del A
         lay = layer_mode(args, scd, workloads, torch, np)

@@ -99,6 +99,31 @@ int scd_set_max_iters(scd_ctx* ctx, int32_t max_iters);
  * Call it between runs, never while another thread uses the context.  May allocate (SCD_ENOMEM). */
 int scd_set_workgroups(scd_ctx* ctx, int workgroups);
 
+/* Per-context options.  Everything that selects an engine or tunes one is set here, per context, between
+ * runs; the library reads no environment variable.  scd_set_option returns SCD_EINVAL for an unknown option or
+ * a value outside its range, and may allocate when it switches an engine on (SCD_ENOMEM). */
+typedef enum {
+    SCD_OPT_RESIDENT = 0,           /* 0/1 (default 1): the register-resident engine may serve this context */
+    SCD_OPT_SPARSE = 1,             /* 0/1 (default 1): the sparse engine (Section 3.1) may serve this context */
+    SCD_OPT_SPARSE_MIN_MIB = 2,     /* smallest remainder, in MiB, that the sparse engine takes on a whole device
+                                       (default 48; 0 = any size) */
+    SCD_OPT_SPARSE_DELAY_WIDTH = 3, /* length of the list of pending terms (Section 3.2): 4..32 (default 8, the
+                                       measured optimum; the paper's CPU value is 32), 0 = subtract at once */
+    SCD_OPT_ROWPASS_KERNEL = 4,     /* launch-stream engine: 1 = register-tiled row pass where the shape allows
+                                       (default), 0 = the generic kernel */
+    SCD_OPT_POLL_DELAY = 5,         /* persistent engines: sleep units between publishing and the first read of
+                                       the partners' data (default 16) */
+    SCD_OPT_MAX_SPIN = 6,           /* persistent engines: re-reads of stale exchange data after which a wait gives
+                                       up (default 2^22; 0 = give up at the first stale read: for tests of the
+                                       SCD_ETIMEOUT path, every workgroup still exits normally) */
+    SCD_OPT_SWEEP_BATCH = 7,        /* launch-stream engine: sweeps enqueued between two looks at the device
+                                       state (default 64) */
+    SCD_OPT_VERBOSE = 8,            /* 0/1: persistent engines print counters of each launch to stderr */
+    SCD_OPT_COUNT = 9
+} scd_option;
+int scd_set_option(scd_ctx* ctx, int option, int64_t value);
+int scd_get_option(const scd_ctx* ctx, int option, int64_t* value /* host */);
+
 /* Advance exactly one term (Algorithm 5 lines 6-10): greedy cut from the keyed random start of the
  * current term, append (s, t, c), update the remainder, record ||R||_F. */
 int scd_step(scd_ctx* ctx);
@@ -219,53 +244,6 @@ int scd_rng_signs(uint64_t seed, uint64_t term, uint32_t mode, int64_t n, void* 
 /* ---- diagnostics ------------------------------------------------------------------------------ */
 const char* scd_strerror(int code);
 int scd_last_hip_error(void);        /* hipError_t of the most recent SCD_EHIP on this thread */
-/* Sparse engine only (zeros otherwise): how many row signs and column signs changed after the first
- * alternation of their term, summed over the terms run so far.  Section 3.1's cached products re-read one
- * row of R per changed row sign and one column per changed column sign: these counts give the bytes the
- * paper's own method moves (host pointers, may be NULL). */
-int scd_sparse_flips(const scd_ctx* ctx, int64_t* row_flips, int64_t* col_flips);
-
-/* Algorithmic bytes the row-pass kernels of this context have read+written so far and the number
- * of passes (launches) they took: the counters behind the bandwidth figures.  host pointers. */
-int scd_traffic(const scd_ctx* ctx, double* bytes, int64_t* passes, int64_t* sweeps);
-
-/* Which engine scd_run uses for this context: 0 = a stream of launches that re-read the remainder from
- * memory every alternation (any shape, dtype, order); 1 = one persistent launch that keeps the whole
- * remainder in the register files of a grid of workgroups (f32 matrices of 256x256, 512x512, 1024x1024,
- * 1024x4096, 2048x2048, 4096x4096; switched off by the environment variable SCD_RESIDENT=0); 2 = one persistent
- * launch that caches R t and R^T s and updates them from the flipped signs only (Section 3.1; f32/f64 matrices
- * with 8 <= m, n <= 65536 whose rows and columns are multiples of 16 bytes and whose remainder takes at
- * least 48 MiB (SCD_SPARSE_MIN_MIB), or any size once the context has a share of the device; keeps a transposed
- * copy of the remainder; finished terms wait in a list of 8 (SCD_SPARSE_DELAY_WIDTH, 4..32) before they are
- * subtracted, Section 3.2, unless SCD_SPARSE_DELAY=0; the engine is switched off by
- * SCD_SPARSE=0).  For engines 1 and 2 also the duration of the most recent
- * launch by HIP events on the context's stream and its dense-equivalent bytes: (alternations + updates)
- * * bytes of the remainder, what a streaming pass per alternation would move.  host pointers, each may
- * be NULL. */
-int scd_engine(const scd_ctx* ctx, int* engine, double* last_launch_seconds, double* last_launch_bytes);
-
-/* Measurement: run n (<= 4096) further sweeps of the greedy loop with a HIP event before and after
- * each kernel of the pass over the remainder; returns the average duration of the row-pass launch
- * and of the reduce launch that follows it (host pointers, seconds).  The terms found meanwhile are
- * ordinary terms of the decomposition; SCD_EFULL if the context is at capacity. */
-int scd_profile_sweeps(scd_ctx* ctx, int n, double* rowpass_seconds, double* reduce_seconds);
-
-/* Plain streaming kernels, for measurement only.  dst == NULL: read `bytes` (a multiple of 16) from
- * src and discard them; else copy src to dst.  `grid` workgroups of 256 threads, one untimed launch
- * and then `reps` timed ones; *seconds (host) = average time of one launch by HIP events on `stream`.
- * The read rate of a buffer that is re-read gives the ceiling of the cache-resident row pass; the
- * copy of known size calibrates the memory counters of the profiler. */
-int scd_probe_stream(const void* src, void* dst, int64_t bytes, int grid, int reps, void* stream,
-                     double* seconds);
-
-/* Latency of exchanging data between the workgroups of one persistent launch, for measurement only.
- * which = 0: every workgroup publishes 256 tagged values per round and reads those of its `group`
- * neighbours (the exchange the register-resident engine uses); which = 1: a counter barrier over the
- * whole grid.  grid workgroups (a multiple of group, at most 1024; keep it at most the number of
- * compute units) must all be resident at once; every wait is bounded and SCD_EINVAL is returned when
- * one runs out.  *seconds_per_round: host. */
-int scd_probe_exchange(int which, int grid, int group, int rounds, void* stream, double* seconds_per_round);
-
 #ifdef __cplusplus
 }
 #endif

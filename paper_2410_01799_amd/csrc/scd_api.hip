@@ -37,13 +37,6 @@ thread_local int g_last_hip = 0;
 
 int64_t words_for(int64_t n) { return (n + 63) / 64; }
 
-int env_int(const char* name, int dflt)
-{
-    const char* v = getenv(name);
-    if (!v || !*v) return dflt;
-    return atoi(v);
-}
-
 struct Level {
     int64_t rows = 0, cols = 0;
     void* X = nullptr;          // level 0: the remainder; else the previous level's W
@@ -85,8 +78,18 @@ struct scd_ctx {
     double* trace = nullptr;
     int32_t* iters = nullptr;
     KronArgs kron;
-    int variant = 1;
-    int batch = 64;
+    // per-context options (scd_set_option); the defaults are the measured optima
+    int64_t opt[SCD_OPT_COUNT] = {
+        1,         // SCD_OPT_RESIDENT: the register-resident engine may be used
+        1,         // SCD_OPT_SPARSE: the sparse engine may be used
+        48,        // SCD_OPT_SPARSE_MIN_MIB
+        8,         // SCD_OPT_SPARSE_DELAY_WIDTH
+        1,         // SCD_OPT_ROWPASS_KERNEL: register-tiled
+        16,        // SCD_OPT_POLL_DELAY
+        1 << 22,   // SCD_OPT_MAX_SPIN
+        64,        // SCD_OPT_SWEEP_BATCH
+        0,         // SCD_OPT_VERBOSE
+    };
     // register-resident engine
     bool resident = false;          // shape and dtype fit, and not switched off
     bool stream_stale = false;      // the launch-stream state lags behind the engine's progress
@@ -95,7 +98,6 @@ struct scd_ctx {
     ResidentResult* res_dev = nullptr;
     ResidentResult* res_pin = nullptr;
     uint32_t seq_u = 0, seq_v = 0;
-    int max_spin = 1 << 22;
     // sparse engine
     bool sparse = false;
     bool rt_stale = true;           // RT does not mirror R (R was changed by the launch-stream kernels)
@@ -222,7 +224,7 @@ int launch_sweep(scd_ctx* c)
 {
     for (int l = 0; l < c->nlevels; ++l) {
         Level& L = c->lv[l];
-        HIP_TRY(launch_rowpass(L.pass, c->dt, L.grid, c->variant, c->stream));
+        HIP_TRY(launch_rowpass(L.pass, c->dt, L.grid, (int)c->opt[SCD_OPT_ROWPASS_KERNEL], c->stream));
         const bool f32p = (l == 0 && c->dt == SCD_F32);
         HIP_TRY(launch_reduce(L.red, f32p, c->stream));
     }
@@ -391,17 +393,17 @@ struct SlotLease {
 int setup_engines(scd_ctx* c)
 {
     const int limit = c->share > 0 ? c->share : c->cus;
-    c->resident = env_int("SCD_RESIDENT", 1) != 0 && resident_supported(c->dt, c->order, c->dims) &&
+    c->resident = c->opt[SCD_OPT_RESIDENT] != 0 && resident_supported(c->dt, c->order, c->dims) &&
                   resident_workgroups(c->dims) <= limit;
     c->sparse = false;
-    if (!c->resident && env_int("SCD_SPARSE", 1) != 0) {
+    if (!c->resident && c->opt[SCD_OPT_SPARSE] != 0) {
         // The sparse engine pays about 15 us per alternation whatever the size, the launch-stream engine
-        // one pass over the remainder: the former wins from about 48 MiB on (SCD_SPARSE_MIN_MIB moves the
-        // line).  A context that was given a share of the device runs side by side with others, which
+        // one pass over the remainder: the former wins from about 48 MiB on (SCD_OPT_SPARSE_MIN_MIB moves
+        // the line).  A context that was given a share of the device runs side by side with others, which
         // hides exactly that latency: it takes the sparse engine at any size.
         const double mib = (double)c->total * (double)c->esize / (1024.0 * 1024.0);
         const int grid = limit < kSpGrid ? limit : kSpGrid;
-        const bool big = c->share > 0 || mib >= (double)env_int("SCD_SPARSE_MIN_MIB", 48);
+        const bool big = c->share > 0 || mib >= (double)c->opt[SCD_OPT_SPARSE_MIN_MIB];
         if (big && grid >= 1 && sparse_supported(c->dt, c->order, c->dims, grid, &c->rs, &c->cs)) {
             c->sparse = true;
             c->sp_grid = grid;
@@ -434,7 +436,6 @@ int setup_engines(scd_ctx* c)
     if ((c->resident || c->sparse) && !c->res_dev) {
         SCD_TRY(dev_alloc(c, (void**)&c->res_dev, sizeof(ResidentResult)));
         if (!hip_ok(pool_malloc((void**)&c->res_pin, sizeof(ResidentResult), true))) return SCD_EHIP;
-        c->max_spin = env_int("SCD_RESIDENT_MAX_SPIN", 1 << 22);
         if (!hip_ok(hipEventCreate(&c->ev0)) || !hip_ok(hipEventCreate(&c->ev1))) return SCD_EHIP;
     }
     return SCD_OK;
@@ -457,8 +458,8 @@ int run_sparse(scd_ctx* c, int64_t n)
     a.k_start = c->hs.k;
     a.w_target = c->hs.k + n;
     a.max_iters = c->hs.max_iters;
-    a.max_spin = c->max_spin;
-    a.poll_delay = env_int("SCD_SPARSE_POLL_DELAY", 16);
+    a.max_spin = (int32_t)c->opt[SCD_OPT_MAX_SPIN];
+    a.poll_delay = (int32_t)c->opt[SCD_OPT_POLL_DELAY];
     a.seq = c->seq_sp;
     a.xbuf = c->xbuf_sp;
     a.S = c->out_signs[0];
@@ -474,15 +475,15 @@ int run_sparse(scd_ctx* c, int64_t n)
     // Delayed updates (Section 3.2) trade the writes of the dense start of a term for a correction on every
     // half step, whose cost grows with the length of the pending list.  Measured on this chip the best length
     // is 8, not the paper's 32 (14336x4096: 1084 terms/s immediate, 1175 with 8, 1144 with 16, 1017 with 32;
-    // 32000x4096: 781 / 900 / 873; 4096x4096: 1137 / 1165 / 1076 / 942).  SCD_SPARSE_DELAY = 0 switches them
-    // off, SCD_SPARSE_DELAY_WIDTH sets the length (4..32).
+    // 32000x4096: 781 / 900 / 873; 4096x4096: 1137 / 1165 / 1076 / 942).  SCD_OPT_SPARSE_DELAY_WIDTH sets the
+    // length (4..32), 0 switches the list off.
     {
-        int width = env_int("SCD_SPARSE_DELAY", 1) != 0 ? sparse_delay_width(c->dims[0], c->dims[1]) : 0;
-        const int cap = env_int("SCD_SPARSE_DELAY_WIDTH", 8);
-        if (width > cap && cap >= 4) width = cap;
+        const int cap = (int)c->opt[SCD_OPT_SPARSE_DELAY_WIDTH];
+        int width = cap > 0 ? sparse_delay_width(c->dims[0], c->dims[1]) : 0;
+        if (width > cap) width = cap;
         a.delay_width = width;
     }
-    a.profile = env_int("SCD_RESIDENT_VERBOSE", 0);
+    a.profile = (int32_t)c->opt[SCD_OPT_VERBOSE];
     a.res = c->res_dev;
     SlotLease lease;
     lease.acquire(a.grid, c->cus);
@@ -503,7 +504,7 @@ int run_sparse(scd_ctx* c, int64_t n)
         c->broken = true;
         return SCD_ETIMEOUT;
     }
-    if (env_int("SCD_RESIDENT_VERBOSE", 0))
+    if (c->opt[SCD_OPT_VERBOSE])
         fprintf(stderr, "[scd sparse] terms %lld alternations %lld flips %lld re-reads %lld; us: dense %.0f, t-exchange %.0f, "
                         "decide %.0f, u-update %.0f, s-exchange %.0f, v-update %.0f\n", (long long)n,
                 (long long)r.alternations, (long long)(r.flips + r.flips_rows), (long long)r.spins, r.ticks[0] * 0.01, r.ticks[1] * 0.01,
@@ -531,8 +532,8 @@ int run_resident(scd_ctx* c, int64_t n)
     a.k_start = c->hs.k;
     a.w_target = c->hs.k + n;
     a.max_iters = c->hs.max_iters;
-    a.max_spin = c->max_spin;
-    a.poll_delay = env_int("SCD_RESIDENT_POLL_DELAY", 16);
+    a.max_spin = (int32_t)c->opt[SCD_OPT_MAX_SPIN];
+    a.poll_delay = (int32_t)c->opt[SCD_OPT_POLL_DELAY];
     a.seq_u = c->seq_u;
     a.seq_v = c->seq_v;
     a.xbuf = c->xbuf;
@@ -564,7 +565,7 @@ int run_resident(scd_ctx* c, int64_t n)
         c->broken = true;
         return SCD_ETIMEOUT;
     }
-    if (env_int("SCD_RESIDENT_VERBOSE", 0))
+    if (c->opt[SCD_OPT_VERBOSE])
         fprintf(stderr, "[scd resident] terms %lld alternations %lld re-reads %lld\n", (long long)n,
                 (long long)r.alternations, (long long)r.spins);
     c->seq_u = r.seq_u;
@@ -604,8 +605,6 @@ int scd_create(scd_ctx** out, const void* A, scd_dtype dt, int order, const int6
     c->seed = seed;
     c->esize = dt == SCD_F32 ? 4 : 8;
     c->stream = (hipStream_t)stream;
-    c->variant = env_int("SCD_ROWPASS_VARIANT", 1);
-    c->batch = env_int("SCD_SWEEP_BATCH", 64);
     for (int i = 0; i < order; ++i) c->dims[i] = dims[i];
     // one workgroup per compute unit: every partial row costs a write and a read per alternation
     int cus = 256;
@@ -617,7 +616,7 @@ int scd_create(scd_ctx** out, const void* A, scd_dtype dt, int order, const int6
             cus = prop.multiProcessorCount;
         (void)hipGetLastError();
     }
-    const int wg_target = env_int("SCD_WORKGROUPS", cus);
+    const int wg_target = cus;
 
     int st = SCD_OK;
     auto fail = [&](int code) {
@@ -733,6 +732,48 @@ int scd_set_workgroups(scd_ctx* c, int workgroups)
     return setup_engines(c);
 }
 
+int scd_set_option(scd_ctx* c, int option, int64_t value)
+{
+    if (!c || option < 0 || option >= SCD_OPT_COUNT) return SCD_EINVAL;
+    switch (option) {
+        case SCD_OPT_RESIDENT:
+        case SCD_OPT_SPARSE:
+        case SCD_OPT_ROWPASS_KERNEL:
+        case SCD_OPT_VERBOSE:
+            if (value != 0 && value != 1) return SCD_EINVAL;
+            break;
+        case SCD_OPT_SPARSE_MIN_MIB:
+            if (value < 0 || value > (1 << 30)) return SCD_EINVAL;
+            break;
+        case SCD_OPT_SPARSE_DELAY_WIDTH:
+            if (value != 0 && (value < 4 || value > 32)) return SCD_EINVAL;
+            break;
+        case SCD_OPT_POLL_DELAY:
+            if (value < 0 || value > 4096) return SCD_EINVAL;
+            break;
+        case SCD_OPT_MAX_SPIN:
+            if (value < 0 || value > (1ll << 30)) return SCD_EINVAL;
+            break;
+        case SCD_OPT_SWEEP_BATCH:
+            if (value < 1 || value > 4096) return SCD_EINVAL;
+            break;
+        default: return SCD_EINVAL;
+    }
+    c->opt[option] = value;
+    if (option == SCD_OPT_RESIDENT || option == SCD_OPT_SPARSE || option == SCD_OPT_SPARSE_MIN_MIB) {
+        if (c->broken) return SCD_ETIMEOUT;
+        return setup_engines(c);
+    }
+    return SCD_OK;
+}
+
+int scd_get_option(const scd_ctx* c, int option, int64_t* value)
+{
+    if (!c || !value || option < 0 || option >= SCD_OPT_COUNT) return SCD_EINVAL;
+    *value = c->opt[option];
+    return SCD_OK;
+}
+
 int scd_run(scd_ctx* c, int64_t n)
 {
     if (!c || n < 0) return SCD_EINVAL;
@@ -747,7 +788,7 @@ int scd_run(scd_ctx* c, int64_t n)
     c->hs.w_target = c->hs.k + n;
     c->hs.done = 0;
     SCD_TRY(write_state(c));
-    int batch = c->batch;
+    int batch = (int)c->opt[SCD_OPT_SWEEP_BATCH];
     if (n == 1 && batch > 16) batch = 16;
     SCD_TRY(run_until_done(c, batch));
     return c->hs.warn ? SCD_WMAXITER : SCD_OK;
@@ -773,7 +814,7 @@ int scd_step_from(scd_ctx* c, const uint64_t* const* init_signs)
     c->hs.c_prev = -INFINITY;
     SCD_TRY(write_state(c));
     if (c->order >= 3) SCD_TRY(seed_current_term(c, 1, false));
-    SCD_TRY(run_until_done(c, c->batch > 16 ? 16 : c->batch));
+    SCD_TRY(run_until_done(c, c->opt[SCD_OPT_SWEEP_BATCH] > 16 ? 16 : (int)c->opt[SCD_OPT_SWEEP_BATCH]));
     return c->hs.warn ? SCD_WMAXITER : SCD_OK;
 }
 
@@ -817,6 +858,14 @@ int scd_set_remainder(scd_ctx* c, const void* R_in)
     if (!c || !R_in) return SCD_EINVAL;
     c->stream_stale = false;  // the start pass below rebuilds the launch-stream state
     c->rt_stale = true;
+    if (c->broken) {
+        // A launch that gave up left tagged words of exchanges it never finished in the slots, and its
+        // sequence numbers were not handed back: start the numbering again on cleared buffers, so that no
+        // stale word can pass for a fresh one.
+        if (c->xbuf) HIP_TRY(hipMemsetAsync(c->xbuf, 0, (size_t)4 * kResGrid * kResGrid * kResSlotWords * 8, c->stream));
+        if (c->xbuf_sp) HIP_TRY(hipMemsetAsync(c->xbuf_sp, 0, sparse_xbuf_bytes(), c->stream));
+        c->seq_u = c->seq_v = c->seq_sp = 0;
+    }
     c->broken = false;
     HIP_TRY(hipMemcpyAsync(c->R, R_in, (size_t)c->total * c->esize, hipMemcpyDeviceToDevice, c->stream));
     c->hs.w_target = c->hs.k;
@@ -879,12 +928,12 @@ int scd_profile_sweeps(scd_ctx* c, int n, double* rowpass_seconds, double* reduc
     Level& L = c->lv[0];
     for (int i = 0; i < n && e == hipSuccess; ++i) {
         e = hipEventRecord(ev[3 * i], c->stream);
-        if (e == hipSuccess) e = launch_rowpass(L.pass, c->dt, L.grid, c->variant, c->stream);
+        if (e == hipSuccess) e = launch_rowpass(L.pass, c->dt, L.grid, (int)c->opt[SCD_OPT_ROWPASS_KERNEL], c->stream);
         if (e == hipSuccess) e = hipEventRecord(ev[3 * i + 1], c->stream);
         if (e == hipSuccess) e = launch_reduce(L.red, c->dt == SCD_F32, c->stream);
         if (e == hipSuccess) e = hipEventRecord(ev[3 * i + 2], c->stream);
         for (int l = 1; l < c->nlevels && e == hipSuccess; ++l) {
-            e = launch_rowpass(c->lv[l].pass, c->dt, c->lv[l].grid, c->variant, c->stream);
+            e = launch_rowpass(c->lv[l].pass, c->dt, c->lv[l].grid, (int)c->opt[SCD_OPT_ROWPASS_KERNEL], c->stream);
             if (e == hipSuccess) e = launch_reduce(c->lv[l].red, false, c->stream);
         }
         if (e == hipSuccess && c->order >= 3) e = launch_kron(c->kron, c->stream);

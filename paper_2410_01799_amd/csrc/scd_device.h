@@ -4,6 +4,7 @@
 #include <stdint.h>
 
 #include "scd.h"
+#include "scd_probe.h"
 
 namespace scd {
 

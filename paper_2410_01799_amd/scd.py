@@ -27,8 +27,12 @@ EXPORTS = [
     "scd_expand", "scd_pack", "scd_unpack", "scd_rng_signs", "scd_strerror", "scd_last_hip_error", "scd_traffic",
     "scd_probe_stream", "scd_profile_sweeps", "scd_probe_exchange", "scd_engine", "scd_set_workgroups",
     "scd_apply", "scd_apply_workspace_bytes", "scd_lsq_decompose", "scd_lsq_decompose_tensor", "scd_decompose_scalars", "scd_sparse_flips",
-    "scd_col_signed_sum_noalloc",
+    "scd_col_signed_sum_noalloc", "scd_set_option", "scd_get_option",
 ]
+
+# scd_option of include/scd.h
+OPTIONS = {"resident": 0, "sparse": 1, "sparse_min_mib": 2, "sparse_delay_width": 3, "rowpass_kernel": 4,
+           "poll_delay": 5, "max_spin": 6, "sweep_batch": 7, "verbose": 8}
 
 
 class ScdError(RuntimeError):
@@ -57,6 +61,8 @@ def lib() -> C.CDLL:
         L.scd_destroy.restype = None
         L.scd_set_max_iters.argtypes = [vp, i32]
         L.scd_set_workgroups.argtypes = [vp, C.c_int]
+        L.scd_set_option.argtypes = [vp, C.c_int, i64]
+        L.scd_get_option.argtypes = [vp, C.c_int, pi64]
         L.scd_sparse_flips.argtypes = [vp, pi64, pi64]
         L.scd_lsq_decompose.argtypes = [vp, C.c_int, i64, i64, i64, C.c_uint64, i32, vp, vp, vp, vp, vp, vp]
         L.scd_lsq_decompose_tensor.argtypes = [vp, C.c_int, C.c_int, pi64, i64, C.c_uint64, i32, vp, pvp, vp, vp, vp]
@@ -146,10 +152,17 @@ def _check(code: int, where: str) -> int:
 # --------------------------------------------------------------------------- one-shot calls
 
 
-def scd_decompose(A: torch.Tensor, w: int, seed: int, want_iters: bool = True):
+def scd_decompose(A: torch.Tensor, w: int, seed: int, want_iters: bool = True, options: Optional[dict] = None):
     """Greedy signed cut decomposition of A to width w.  Returns dict(signs=[per-mode (w, words)
-    int64 tensors holding uint64 bitsets], c, trace (float64, w+1), iters, status)."""
+    int64 tensors holding uint64 bitsets], c, trace (float64, w+1), iters, status).  With `options` (names of
+    OPTIONS) the same steps go through the stateful calls, which is where options can be set."""
     A = _dev(A, "A")
+    if options:
+        with ScdContext(A, w, seed, options=options) as ctx:
+            st = ctx.run(w)
+            res = ctx.results()
+        res["status"] = st
+        return res
     dev = A.device
     signs = [_bits(words(d), dev, rows=w) for d in A.shape]
     c = torch.zeros(w, dtype=A.dtype, device=dev)
@@ -314,7 +327,7 @@ def scd_probe_exchange(which: int, grid: int = 256, group: int = 16, rounds: int
 class ScdContext:
     """Owns an ``scd_ctx``: the remainder, the position in the random stream, the terms so far."""
 
-    def __init__(self, A: torch.Tensor, w_capacity: int, seed: int):
+    def __init__(self, A: torch.Tensor, w_capacity: int, seed: int, options: Optional[dict] = None):
         A = _dev(A, "A")
         self.shape = tuple(int(d) for d in A.shape)
         self.dtype = A.dtype
@@ -324,6 +337,16 @@ class ScdContext:
         st = lib().scd_create(C.byref(self._h), _ptr(A), _dt(A), A.dim(), _dims(A.shape), int(w_capacity), int(seed),
                               _stream())
         _check(st, "scd_create")
+        for name, value in (options or {}).items():
+            self.set_option(name, value)
+
+    def set_option(self, name: str, value: int):
+        _check(lib().scd_set_option(self._h, OPTIONS[name], int(value)), f"scd_set_option({name})")
+
+    def get_option(self, name: str) -> int:
+        v = C.c_int64()
+        _check(lib().scd_get_option(self._h, OPTIONS[name], C.byref(v)), f"scd_get_option({name})")
+        return int(v.value)
 
     def close(self):
         if getattr(self, "_h", None) and self._h.value:

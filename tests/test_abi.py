@@ -9,7 +9,7 @@ ROOT = Path(__file__).resolve().parent.parent
 
 
 def declared_symbols():
-    text = (ROOT / "include" / "scd.h").read_text()
+    text = "".join(p.read_text() for p in sorted((ROOT / "include").glob("*.h")))
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(scd_[a-z0-9_]+)\s*\(", text)))
 
@@ -27,7 +27,7 @@ def test_library_exports_every_declared_symbol():
         pytest.fail("libscd.so is not built: run __graft_entry__.build()")
     lib = ctypes.CDLL(str(scd.LIB_PATH))
     for name in declared_symbols():
-        assert hasattr(lib, name), f"{name} declared in scd.h but not exported"
+        assert hasattr(lib, name), f"{name} declared in include/*.h but not exported"
     assert sorted(scd.EXPORTS) == declared_symbols()
 
 

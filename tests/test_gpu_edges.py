@@ -4,7 +4,7 @@ import numpy as np
 import pytest
 import torch
 
-from helpers import C_RTOL, ID_RTOL, TIE_TOL, dense, to_dev_bits, to_np_bits
+from helpers import C_RTOL, ID_RTOL, dense, match_matrix_term, match_tensor_term, to_dev_bits, to_np_bits
 
 pytestmark = pytest.mark.gpu
 
@@ -22,24 +22,42 @@ def gauss(shape, seed, dtype=np.float32):
 
 
 def check_against_oracle(scd, oracle, A, w, seed):
-    """Free run on both sides; identical signs are required whenever the oracle's margins rule out ties."""
+    """Lockstep: every term must be an outcome of Algorithm 4 / 12 on the oracle's own remainder (the literal
+    one unless a decision was a near tie); then the free-running oracle's curve is compared as well."""
     A64 = A.astype(np.float64)
+    f32 = A.dtype == np.float32
     res = scd.scd_decompose(torch.from_numpy(np.ascontiguousarray(A)).cuda(), w, seed)
     c = res["c"].cpu().numpy().astype(np.float64)
     trace = res["trace"].cpu().numpy()
+    iters = res["iters"].cpu().numpy()
+    signs = [to_np_bits(s) for s in res["signs"]]
     N = A.size
     np.testing.assert_allclose(trace[1:] ** 2, trace[:-1] ** 2 - N * c ** 2, rtol=ID_RTOL, atol=1e-12 * trace[0] ** 2)
-    if A.ndim == 2:
-        ref = oracle.decompose(A64, w, seed)
-        signs_ref = [ref["S"], ref["T"]]
-    else:
-        ref = oracle.tensor_decompose(A64, w, seed)
-        signs_ref = ref["signs"]
-    if ref["margins"].min() >= 10 * TIE_TOL:
-        for got, want in zip(res["signs"], signs_ref):
-            assert np.array_equal(to_np_bits(got), want)
-        np.testing.assert_allclose(c, ref["c"], rtol=C_RTOL)
-        assert np.array_equal(res["iters"].cpu().numpy(), ref["iters"])
+    r = A64.copy()
+    literal = True
+    for k in range(w):
+        start = [oracle.rng_signs(seed, k, i, d) for i, d in enumerate(A.shape)]
+        mine = [sg[k] for sg in signs]
+        if A.ndim == 2:
+            flips, g = match_matrix_term(oracle, r, start[1], mine[0], mine[1], iters[k], f32, f"term {k}")
+        else:
+            flips, g = match_tensor_term(oracle, r, start, mine, iters[k], f32, f"term {k}")
+        literal = literal and flips == 0
+        if flips == 0 and g["c"] != 0.0:
+            assert c[k] == pytest.approx(g["c"] / N, rel=C_RTOL), f"term {k}"
+        prod = np.ones(())
+        for b, d in zip(mine, A.shape):
+            prod = np.multiply.outer(prod, dense(b, d))
+        ck = float((r * prod).sum()) / N
+        assert c[k] == pytest.approx(ck, rel=C_RTOL, abs=1e-7 * np.abs(A64).max()), f"term {k}: c vs <s, r>/N"
+        r = r - ck * prod
+        assert trace[k + 1] == pytest.approx(np.linalg.norm(r), rel=2e-5, abs=1e-6 * trace[0])
+    ref = oracle.decompose(A64, w, seed) if A.ndim == 2 else oracle.tensor_decompose(A64, w, seed)
+    if literal:
+        signs_ref = [ref["S"], ref["T"]] if A.ndim == 2 else ref["signs"]
+        for got, want in zip(signs, signs_ref):
+            assert np.array_equal(got, want)
+        assert np.array_equal(iters, ref["iters"])
     np.testing.assert_allclose(trace, ref["trace"], rtol=1e-3, atol=1e-6 * trace[0])
     return res
 

@@ -7,14 +7,13 @@ where the reference value is within 1e-6 of a tie; c within 1e-5; Frobenius iden
 error curve within 1e-3.
 """
 import math
-import os
 
 import numpy as np
 import pytest
 import torch
 
-from helpers import (C_RTOL, CURVE_RTOL, ID_RTOL, TIE_TOL, assert_signs_match, dense, sign_mismatch, to_dev_bits,
-                     to_np_bits)
+from helpers import (C_RTOL, CURVE_RTOL, ID_RTOL, TIE_TOL, adoption_bound, assert_signs_match, dense, match_matrix_term,
+                     match_tensor_term, sign_mismatch, to_dev_bits, to_np_bits)
 
 pytestmark = pytest.mark.gpu
 
@@ -30,16 +29,8 @@ def scd():
 
 @pytest.fixture(params=[1, 0], ids=["tiled", "generic"])
 def variant(request):
-    """The launch-stream engine with either row-pass kernel (the persistent engines switched off)."""
-    keys = {"SCD_ROWPASS_VARIANT": str(request.param), "SCD_RESIDENT": "0", "SCD_SPARSE": "0"}
-    old = {k: os.environ.get(k) for k in keys}
-    os.environ.update(keys)
-    yield request.param
-    for k, v in old.items():
-        if v is None:
-            os.environ.pop(k, None)
-        else:
-            os.environ[k] = v
+    """Options that select the launch-stream engine with either row-pass kernel (persistent engines off)."""
+    return {"rowpass_kernel": request.param, "resident": 0, "sparse": 0}
 
 
 def gauss(shape, seed, dtype=np.float32):
@@ -120,13 +111,13 @@ def test_half_steps(scd, oracle, m, n, dtype):
 # ------------------------------------------------------------------ one term from the same remainder and start
 
 
-def check_term(scd, oracle, A, seed, variant_name):
+def check_term(scd, oracle, A, seed, options):
     """scd_step_from vs Algorithm 4 + update of the oracle, same R and t_0."""
     m, n = A.shape
     A64 = A.astype(np.float64)
     t0 = oracle.rng_signs(seed, 0, 1, n)
     g = oracle.greedy_signed_cut(A64, t0)
-    with scd.ScdContext(dev(A), 4, seed) as ctx:
+    with scd.ScdContext(dev(A), 4, seed, options=options) as ctx:
         ctx.step_from([None, to_dev_bits(t0)])
         assert ctx.width == 1
         res = ctx.results()
@@ -143,15 +134,14 @@ def check_term(scd, oracle, A, seed, variant_name):
     # the stored remainder is R - c s t^T
     np.testing.assert_allclose(Rg, A64 - c_g * np.outer(sd, td), rtol=0,
                                atol=(1e-6 if A.dtype == np.float32 else 1e-14) * np.abs(A64).max())
+    flips, _ = match_matrix_term(oracle, A64, t0, s_g, t_g, int(res["iters"][0]), A.dtype == np.float32, str(options))
     tie_free = g["margin"].min() >= TIE_TOL
-    if tie_free or A.dtype == np.float64:
-        assert np.array_equal(s_g, g["s"]) and np.array_equal(t_g, g["t"]), variant_name
-        assert int(res["iters"][0]) == g["iters"]
+    if flips == 0:
         assert c_g == pytest.approx(g["c"] / (m * n), rel=C_RTOL)
-    else:
-        # tie-sensitive start: the result must still be a fixed point of its own alternation
+        # the literal run ends on a repeat: (s, t) is a fixed point of the alternation
         assert_signs_match(s_g, oracle.pack(A64 @ td), A64 @ td, m, "fixed point s")
-        assert_signs_match(t_g, oracle.pack(A64.T @ sd), A64.T @ sd, n, "fixed point t")
+    # t is always the sign of R^T s for the s that is returned (Algorithm 4 line 6)
+    assert_signs_match(t_g, oracle.pack(A64.T @ sd), A64.T @ sd, n, "t = sgn(R^T s)")
     return tie_free
 
 
@@ -159,35 +149,34 @@ def check_term(scd, oracle, A, seed, variant_name):
 @pytest.mark.parametrize("m,n", [(256, 256), (100, 77), (64, 1024), (1000, 4096), (130, 8200), (7, 5)])
 def test_term_parity(scd, oracle, variant, m, n, dtype):
     A = gauss((m, n), 31 * m + n, dtype)
-    check_term(scd, oracle, A, seed=m + n, variant_name=variant)
+    check_term(scd, oracle, A, seed=m + n, options=variant)
 
 
 # ------------------------------------------------------------------ whole decompositions
 
 
 def lockstep_check(oracle, A64, seed, S, T, c, trace, iters, f32):
-    """The oracle follows the GPU: term k is recomputed by Algorithm 4 on the oracle's own f64
-    remainder from the keyed start; where its signs differ from the GPU's the term must have been
-    tie-sensitive, and the oracle then adopts the GPU's signs.  Returns the oracle's curve."""
+    """The oracle follows the GPU: term k is recomputed by Algorithm 4 on the oracle's own f64 remainder from
+    the keyed start.  The GPU's term must be the literal outcome or one that differs from it only through
+    near-tie decisions (match_matrix_term); the oracle then continues from the GPU's signs.  The number of
+    such terms is bounded by what f32 rounding explains.  Returns the oracle's curve and that number."""
     m, n = A64.shape
     R = A64.copy()
     curve = [np.linalg.norm(R)]
     adopted = 0
     for k in range(len(c)):
-        g = oracle.greedy_signed_cut(R, oracle.rng_signs(seed, k, 1, n))
-        same = np.array_equal(g["s"], S[k]) and np.array_equal(g["t"], T[k])
-        if same:
-            assert iters[k] == g["iters"], f"term {k}: iteration count"
+        flips, g = match_matrix_term(oracle, R, oracle.rng_signs(seed, k, 1, n), S[k], T[k], iters[k], f32, f"term {k}")
+        if flips == 0:
             assert c[k] == pytest.approx(g["c"] / (m * n), rel=C_RTOL), f"term {k}"
         else:
-            assert f32 and g["margin"].min() < 10 * TIE_TOL, \
-                f"term {k}: signs differ although the oracle's margin is {g['margin'].min():.2e}"
             adopted += 1
         sd, td = dense(S[k], m), dense(T[k], n)
         ck = sd @ R @ td / (m * n)
         assert c[k] == pytest.approx(ck, rel=C_RTOL), f"term {k}: c does not match <s,Rt>/(mn)"
         oracle.rank1_update(R, ck, S[k], T[k])
         curve.append(math.sqrt(oracle.fro2(R)))
+    decisions = float(np.sum(iters[: len(c)])) * (m + n)
+    assert adopted <= adoption_bound(decisions, f32), f"{adopted} of {len(c)} terms differ from the literal run"
     return np.array(curve), adopted
 
 
@@ -198,7 +187,7 @@ def test_decompose_lockstep_and_free_run(scd, oracle, variant, m, n, w, dtype):
     seed = 1
     A = gauss((m, n), 1 if (m, n) == (256, 256) else m * n, dtype)
     A64 = A.astype(np.float64)
-    res = scd.scd_decompose(dev(A), w, seed)
+    res = scd.scd_decompose(dev(A), w, seed, options=variant)
     assert res["status"] == 0
     S, T = to_np_bits(res["signs"][0]), to_np_bits(res["signs"][1])
     c = res["c"].cpu().numpy().astype(np.float64)
@@ -221,8 +210,8 @@ def test_decompose_lockstep_and_free_run(scd, oracle, variant, m, n, w, dtype):
 
 def test_step_run_results_agree_with_one_shot(scd, variant):
     A = dev(gauss((300, 260), 9))
-    one = scd.scd_decompose(A, 12, 4)
-    with scd.ScdContext(A, 12, 4) as ctx:
+    one = scd.scd_decompose(A, 12, 4, options=variant)
+    with scd.ScdContext(A, 12, 4, options=variant) as ctx:
         ctx.step()
         ctx.run(5)
         assert ctx.width == 6
@@ -251,20 +240,14 @@ def test_two_runs_are_bit_identical(scd):
 
 def test_tiled_and_generic_kernels_agree(scd):
     A = dev(gauss((384, 1024), 12))
-    out = []
-    os.environ["SCD_SPARSE"] = "0"
-    for v in ("1", "0"):
-        os.environ["SCD_ROWPASS_VARIANT"] = v
-        out.append(scd.scd_decompose(A, 10, 3))
-    os.environ.pop("SCD_ROWPASS_VARIANT")
-    os.environ.pop("SCD_SPARSE")
+    out = [scd.scd_decompose(A, 10, 3, options={"rowpass_kernel": v, "resident": 0, "sparse": 0}) for v in (1, 0)]
     np.testing.assert_allclose(out[0]["trace"].cpu().numpy(), out[1]["trace"].cpu().numpy(), rtol=1e-5)
 
 
 def test_set_remainder_resumes_exactly(scd, variant):
     A = dev(gauss((256, 512), 13))
-    full = scd.scd_decompose(A, 8, 21)
-    with scd.ScdContext(A, 8, 21) as ctx:
+    full = scd.scd_decompose(A, 8, 21, options=variant)
+    with scd.ScdContext(A, 8, 21, options=variant) as ctx:
         ctx.run(5)
         R5 = ctx.remainder()
         ctx.set_remainder(R5)          # same remainder: the rest of the run must not change
@@ -332,7 +315,7 @@ def test_tensor_decompose(scd, oracle, variant, shape, w, dtype):
     a = gauss(shape, int(np.prod(shape)), dtype)
     a64 = a.astype(np.float64)
     N = a.size
-    res = scd.scd_decompose(dev(a), w, seed)
+    res = scd.scd_decompose(dev(a), w, seed, options=variant)
     signs = [to_np_bits(s) for s in res["signs"]]
     c = res["c"].cpu().numpy().astype(np.float64)
     trace = res["trace"].cpu().numpy()
@@ -342,14 +325,10 @@ def test_tensor_decompose(scd, oracle, variant, shape, w, dtype):
     r = a64.copy()
     for k in range(w):
         s0 = [oracle.rng_signs(seed, k, i, d) for i, d in enumerate(shape)]
-        g = oracle.axial_greedy_cut(r, s0)
         mine = [sg[k] for sg in signs]
-        same = all(np.array_equal(x, y) for x, y in zip(g["signs"], mine))
-        if same:
-            assert iters[k] == g["iters"]
+        flips, g = match_tensor_term(oracle, r, s0, mine, iters[k], dtype == np.float32, f"term {k}")
+        if flips == 0:
             assert c[k] == pytest.approx(g["c"] / N, rel=C_RTOL)
-        else:
-            assert dtype == np.float32 and g["margin"].min() < 10 * TIE_TOL, f"term {k} differs, margin {g['margin']}"
         ck = (r * kron_dense(mine, shape)).sum() / N
         assert c[k] == pytest.approx(ck, rel=C_RTOL)
         oracle.tensor_update(r, ck, mine)
@@ -366,7 +345,7 @@ def test_tensor_step_from(scd, oracle):
     with scd.ScdContext(dev(a), 2, 123) as ctx:
         ctx.step_from([None] + [to_dev_bits(b) for b in s0[1:]])
         res = ctx.results()
-    if g["margin"].min() >= TIE_TOL:
-        for i in range(3):
-            assert np.array_equal(to_np_bits(res["signs"][i])[0], g["signs"][i])
+    flips, _ = match_tensor_term(oracle, a.astype(np.float64), s0, [to_np_bits(res["signs"][i])[0] for i in range(3)],
+                                 int(res["iters"][0]), True, "step_from")
+    if flips == 0:
         assert float(res["c"][0]) == pytest.approx(g["c"] / a.size, rel=C_RTOL)

@@ -1,7 +1,5 @@
 """The register-resident engine (whole remainder in the register files, one persistent launch) against
 the oracle and against the launch-stream path, on every shape it is built for."""
-import os
-
 import numpy as np
 import pytest
 import torch
@@ -22,14 +20,8 @@ def scd():
     return mod
 
 
-def with_resident(flag):
-    os.environ["SCD_RESIDENT"] = "1" if flag else "0"
-
-
-@pytest.fixture(autouse=True)
-def restore_env():
-    yield
-    os.environ.pop("SCD_RESIDENT", None)
+RESIDENT = {"resident": 1}
+STREAM = {"resident": 0, "sparse": 0}
 
 
 def gauss(shape, seed):
@@ -40,8 +32,10 @@ def gauss(shape, seed):
 def test_resident_matches_oracle_in_lockstep(scd, oracle, m, n):
     w, seed = 10, 17
     A = gauss((m, n), m + n)
-    with_resident(True)
-    res = scd.scd_decompose(torch.from_numpy(A).cuda(), w, seed)
+    with scd.ScdContext(torch.from_numpy(A).cuda(), w, seed, options=RESIDENT) as ctx:
+        assert ctx.engine()["engine"] == 1
+        ctx.run(w)
+        res = ctx.results()
     S, T = to_np_bits(res["signs"][0]), to_np_bits(res["signs"][1])
     c = res["c"].cpu().numpy().astype(np.float64)
     trace = res["trace"].cpu().numpy()
@@ -58,10 +52,8 @@ def test_resident_matches_oracle_in_lockstep(scd, oracle, m, n):
 @pytest.mark.parametrize("m,n", SHAPES[:2] + SHAPES[3:])
 def test_resident_and_stream_paths_agree(scd, m, n):
     A = torch.from_numpy(gauss((m, n), 5)).cuda()
-    with_resident(True)
-    a = scd.scd_decompose(A, 8, 3)
-    with_resident(False)
-    b = scd.scd_decompose(A, 8, 3)
+    a = scd.scd_decompose(A, 8, 3, options=RESIDENT)
+    b = scd.scd_decompose(A, 8, 3, options=STREAM)
     ta, tb = a["trace"].cpu().numpy(), b["trace"].cpu().numpy()
     np.testing.assert_allclose(ta / ta[0], tb / tb[0], rtol=CURVE_RTOL)
     # same signs unless a near tie split the two summation orders: then the curves still agree (above)
@@ -74,7 +66,6 @@ def test_resident_and_stream_paths_agree(scd, m, n):
 def test_resident_chunking_determinism_and_handover(scd):
     m, n = 1024, 4096
     A = torch.from_numpy(gauss((m, n), 9)).cuda()
-    with_resident(True)
     one = scd.scd_decompose(A, 9, 4)
     two = scd.scd_decompose(A, 9, 4)
     for k in ("c", "trace", "iters"):
@@ -103,8 +94,8 @@ def test_resident_chunking_determinism_and_handover(scd):
 
 def test_resident_iteration_cap(scd):
     A = torch.from_numpy(gauss((2048, 2048), 2)).cuda()
-    with_resident(True)
     with scd.ScdContext(A, 3, 1) as ctx:
+        assert ctx.engine()["engine"] == 1
         ctx.set_max_iters(2)
         assert ctx.run(3) == scd.WMAXITER
         r = ctx.results()
@@ -122,20 +113,15 @@ def test_exchange_probe_runs(scd):
 def test_a_context_that_loses_its_share_continues_on_the_launch_stream(scd):
     m = n = 1024
     A = torch.from_numpy(gauss((m, n), 21)).cuda()
-    os.environ["SCD_SPARSE"] = "0"
-    try:
-        with_resident(True)
-        with scd.ScdContext(A, 8, 6) as ctx:
-            assert ctx.engine()["engine"] == 1
-            ctx.run(4)
-            ctx.set_workgroups(16)            # the 8 x 8 grid no longer fits, the sparse engine is switched off
-            assert ctx.engine()["engine"] == 0
-            ctx.run(4)
-            mixed = ctx.results()
-            R = ctx.remainder()
-        whole = scd.scd_decompose(A, 8, 6)
-    finally:
-        os.environ.pop("SCD_SPARSE", None)
+    with scd.ScdContext(A, 8, 6, options={"sparse": 0}) as ctx:
+        assert ctx.engine()["engine"] == 1
+        ctx.run(4)
+        ctx.set_workgroups(16)            # the 8 x 8 grid no longer fits, the sparse engine is switched off
+        assert ctx.engine()["engine"] == 0
+        ctx.run(4)
+        mixed = ctx.results()
+        R = ctx.remainder()
+    whole = scd.scd_decompose(A, 8, 6)
     tr = mixed["trace"].cpu().numpy()
     c = mixed["c"].cpu().numpy().astype(np.float64)
     np.testing.assert_allclose(tr[1:] ** 2, tr[:-1] ** 2 - m * n * c ** 2, rtol=ID_RTOL)

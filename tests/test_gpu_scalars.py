@@ -4,7 +4,7 @@ import numpy as np
 import pytest
 import torch
 
-from helpers import C_RTOL, CURVE_RTOL, TIE_TOL, dense, to_np_bits
+from helpers import C_RTOL, CURVE_RTOL, dense, match_tensor_term, to_np_bits
 
 pytestmark = pytest.mark.gpu
 
@@ -43,12 +43,7 @@ def run_and_check(scd, oracle, a, w, seed):
     curve = [np.linalg.norm(r)]
     for k in range(w):
         start = [oracle.rng_signs(seed, k, i, d) for i, d in enumerate(shape)]
-        g = oracle.axial_greedy_cut(r, start)
-        if all(np.array_equal(g["signs"][i], sg[i][k]) for i in range(len(shape) - 1)):
-            assert iters[k] == g["iters"], f"term {k}: sweep count"
-        else:
-            assert f32 and g["margin"].min() < 10 * TIE_TOL, \
-                f"term {k}: signs differ although the oracle's margin is {g['margin'].min():.2e}"
+        match_tensor_term(oracle, r, start, [s[k] for s in sg], iters[k], f32, f"term {k}", modes=len(shape) - 1)
         lead = lead_product(sg, k, shape)                      # the GPU's sign vectors (adopted where they differ)
         ck = np.tensordot(lead, r, axes=len(shape) - 1) / P
         np.testing.assert_allclose(c[k], ck, rtol=C_RTOL, atol=C_RTOL * np.abs(ck).max())

@@ -1,7 +1,5 @@
 """The sparse engine (cached products updated from the flipped signs only, Section 3.1) against the
 oracle in lockstep and against the launch-stream engine, f32 and f64, square, ragged and large."""
-import os
-
 import numpy as np
 import pytest
 import torch
@@ -20,26 +18,36 @@ def scd():
     return mod
 
 
+OPTS = {}
+
+
 @pytest.fixture(autouse=True, params=["immediate", "delayed"])
 def engines(request):
-    os.environ["SCD_RESIDENT"] = "0"        # so that the sparse engine also serves the resident engine's shapes
-    os.environ["SCD_SPARSE_MIN_MIB"] = "0"  # ... and matrices below the size from which it pays off
-    os.environ.pop("SCD_SPARSE", None)
-    # updates subtracted at once, or kept in a list of pending terms (Section 3.2)
-    os.environ["SCD_SPARSE_DELAY"] = "1" if request.param == "delayed" else "0"
+    """Options for every context of a test: the sparse engine also for the register-resident engine's shapes
+    and for matrices below the size from which it pays off; updates subtracted at once, or kept in a list of
+    pending terms (Section 3.2)."""
+    OPTS.clear()
+    OPTS.update({"resident": 0, "sparse_min_mib": 0, "sparse_delay_width": 8 if request.param == "delayed" else 0})
     yield request.param
-    for k in ("SCD_RESIDENT", "SCD_SPARSE", "SCD_SPARSE_MIN_MIB", "SCD_SPARSE_DELAY"):
-        os.environ.pop(k, None)
+    OPTS.clear()
+
+
+def context(scd, A, w, seed, **extra):
+    return scd.ScdContext(A, w, seed, options={**OPTS, **extra})
+
+
+def decompose(scd, A, w, seed, **extra):
+    return scd.scd_decompose(A, w, seed, options={**OPTS, **extra})
 
 
 def gauss(shape, seed, dtype=np.float32):
     return np.random.Generator(np.random.PCG64(seed)).standard_normal(shape).astype(dtype)
 
 
-def run_and_check(scd, oracle, A, w, seed, share=0):
+def run_and_check(scd, oracle, A, w, seed, share=0, **extra):
     m, n = A.shape
     Ad = torch.from_numpy(A).cuda()
-    with scd.ScdContext(Ad, w, seed) as ctx:
+    with context(scd, Ad, w, seed, **extra) as ctx:
         if share:
             ctx.set_workgroups(share)
         assert ctx.engine()["engine"] == 2
@@ -81,12 +89,8 @@ def test_sparse_more_terms_than_the_pending_list_holds(scd, oracle, m, n, w, dty
 
 def test_sparse_pending_list_of_the_papers_length(scd, oracle, engines):
     # the default list holds 8 terms; Section 3.2's 32 (and the shortest, 4) go through the same code
-    for width in ("32", "4"):
-        os.environ["SCD_SPARSE_DELAY_WIDTH"] = width
-        try:
-            run_and_check(scd, oracle, gauss((300, 260), 31 + int(width)), 70, 23)
-        finally:
-            os.environ.pop("SCD_SPARSE_DELAY_WIDTH", None)
+    for width in (32, 4):
+        run_and_check(scd, oracle, gauss((300, 260), 31 + width), 70, 23, sparse_delay_width=width)
 
 
 def test_sparse_large_layer_shape(scd, oracle):
@@ -105,9 +109,8 @@ def test_sparse_embedding_shape(scd, oracle):
 
 def test_sparse_and_stream_engines_agree(scd):
     A = torch.from_numpy(gauss((768, 1280), 5)).cuda()
-    a = scd.scd_decompose(A, 16, 3)
-    os.environ["SCD_SPARSE"] = "0"
-    b = scd.scd_decompose(A, 16, 3)
+    a = decompose(scd, A, 16, 3)
+    b = decompose(scd, A, 16, 3, sparse=0)
     ta, tb = a["trace"].cpu().numpy(), b["trace"].cpu().numpy()
     np.testing.assert_allclose(ta / ta[0], tb / tb[0], rtol=CURVE_RTOL)
     if torch.equal(a["signs"][0], b["signs"][0]) and torch.equal(a["signs"][1], b["signs"][1]):
@@ -118,11 +121,11 @@ def test_sparse_and_stream_engines_agree(scd):
 def test_sparse_chunking_determinism_and_handover(scd, engines):
     m, n = 640, 896
     A = torch.from_numpy(gauss((m, n), 9)).cuda()
-    one = scd.scd_decompose(A, 10, 4)
-    two = scd.scd_decompose(A, 10, 4)
+    one = decompose(scd, A, 10, 4)
+    two = decompose(scd, A, 10, 4)
     for k in ("c", "trace", "iters"):
         assert torch.equal(one[k], two[k])
-    with scd.ScdContext(A, 14, 4) as ctx:
+    with context(scd, A, 14, 4) as ctx:
         ctx.step()
         ctx.run(6)
         ctx.step()
@@ -152,7 +155,8 @@ def test_sparse_chunking_determinism_and_handover(scd, engines):
 
 def test_sparse_iteration_cap_and_set_remainder(scd):
     A = torch.from_numpy(gauss((512, 512), 2)).cuda()
-    with scd.ScdContext(A, 6, 1) as ctx:
+    with context(scd, A, 6, 1) as ctx:
+        assert ctx.engine()["engine"] == 2
         ctx.set_max_iters(1)
         assert ctx.run(2) == scd.WMAXITER
         assert ctx.results()["iters"].cpu().tolist() == [1, 1]
@@ -182,8 +186,6 @@ def test_share_f64_and_large(scd, oracle):
 
 
 def test_share_limits_and_engine_choice(scd):
-    os.environ.pop("SCD_RESIDENT", None)
-    os.environ.pop("SCD_SPARSE_MIN_MIB", None)
     A = torch.from_numpy(gauss((4096, 4096), 1)).cuda()
     with scd.ScdContext(A, 4, 1) as ctx:
         assert ctx.engine()["engine"] == 1            # the whole device: register-resident
@@ -224,7 +226,7 @@ def test_contexts_side_by_side_reproduce_their_solo_runs(scd):
         torch.cuda.set_device(0)
         st = torch.cuda.Stream()
         with torch.cuda.stream(st):
-            with scd.ScdContext(mats[i], w, 100 + i) as ctx:
+            with context(scd, mats[i], w, 100 + i) as ctx:
                 ctx.set_workgroups(64)
                 assert ctx.engine()["engine"] == 2
                 for _ in range(3):
@@ -258,7 +260,7 @@ def test_contexts_side_by_side_reproduce_their_solo_runs(scd):
 
 def test_sparse_flip_counts(scd):
     A = torch.from_numpy(gauss((512, 1024), 77)).cuda()
-    with scd.ScdContext(A, 6, 3) as ctx:
+    with context(scd, A, 6, 3) as ctx:
         assert ctx.engine()["engine"] == 2
         assert ctx.sparse_flips() == dict(rows=0, cols=0)
         ctx.run(6)
@@ -267,7 +269,6 @@ def test_sparse_flip_counts(scd):
     # every alternation after a term's first changes at least one sign of each kind (else it would have stopped
     # one earlier, or be the last), and never more than all of them
     assert 0 < fl["rows"] <= 512 * alts and 0 < fl["cols"] <= 1024 * alts
-    os.environ["SCD_SPARSE"] = "0"
-    with scd.ScdContext(A, 2, 3) as ctx:
+    with context(scd, A, 2, 3, sparse=0) as ctx:
         ctx.run(2)
         assert ctx.sparse_flips() == dict(rows=0, cols=0)
