@@ -1,5 +1,6 @@
 // Probes of workgroup-to-workgroup exchange latency inside one persistent launch (measurement only).
 #include "scd_device.h"
+#include "scd_rng.h"
 
 namespace scd {
 
@@ -91,26 +92,7 @@ hipError_t launch_exchange_probe(int which, int grid, uint64_t* buf, unsigned* c
     return hipGetLastError();
 }
 
-// ---- helpers of the engine (kept local to this file: the two translation units share no device code)
-
-__device__ __forceinline__ uint64_t mix64_res(uint64_t z)
-{
-    // SplitMix64 finaliser
-    z ^= z >> 30;
-    z *= 0xBF58476D1CE4E5B9ull;
-    z ^= z >> 27;
-    z *= 0x94D049BB133111EBull;
-    z ^= z >> 31;
-    return z;
-}
-
-__device__ __forceinline__ uint64_t rng_word_res(uint64_t seed, uint64_t term, uint32_t mode, uint64_t word)
-{
-    uint64_t h = mix64_res(seed ^ (0x9E3779B97F4A7C15ull * (term + 1)));
-    h = mix64_res(h + 0xD1B54A32D192ED03ull * ((uint64_t)mode + 1));
-    h = mix64_res(h + 0x8CB92BA72F3D8DD7ull * (word + 1));
-    return h;
-}
+// ---- helpers of the engine
 
 // Sum over the 64 lanes, the same bits in every lane, without LDS traffic (a chain of ds_bpermute would cost
 // an LDS round trip per step): distances 1, 2, 4, 8 by the data-parallel lane modes (4 = mirror of half a row
@@ -360,7 +342,7 @@ __global__ void __launch_bounds__(kResThreads) resident_kernel(ResidentArgs a)
             // t_0 of term k from the keyed stream (Algorithm 4 line 2)
             if (tid < BN) {
                 const int64_t col = (int64_t)pc * BN + tid;
-                lds_t[tid] = (uint8_t)((rng_word_res(a.seed, (uint64_t)k, 1u, (uint64_t)(col >> 6)) >> (col & 63)) & 1ull);
+                lds_t[tid] = (uint8_t)((rng_word(a.seed, (uint64_t)k, 1u, (uint64_t)(col >> 6)) >> (col & 63)) & 1ull);
             }
             need_t0 = false;
             __syncthreads();

@@ -23,6 +23,7 @@
 // terms live in LDS, the products are corrected from their bitsets, one pass flushes the list and, while
 // it is at it, forms the first products R' t_0 of the next terms (their random starts are known in advance).
 #include "scd_device.h"
+#include "scd_rng.h"
 
 namespace scd {
 
@@ -41,25 +42,6 @@ constexpr size_t kSpMaxLds = 150 * 1024;          // most dynamic LDS a launch m
 // grid * slice <= 65536 + 8 * grid: at most 67584 / 32 + 256 + 512 = 2880 words for the 512 threads
 // (sparse_supported checks it).
 constexpr int kSpMaxItems = 6;
-
-__device__ __forceinline__ uint64_t sp_mix64(uint64_t z)
-{
-    // SplitMix64 finaliser
-    z ^= z >> 30;
-    z *= 0xBF58476D1CE4E5B9ull;
-    z ^= z >> 27;
-    z *= 0x94D049BB133111EBull;
-    z ^= z >> 31;
-    return z;
-}
-
-__device__ __forceinline__ uint64_t sp_rng_word(uint64_t seed, uint64_t term, uint32_t mode, uint64_t word)
-{
-    uint64_t h = sp_mix64(seed ^ (0x9E3779B97F4A7C15ull * (term + 1)));
-    h = sp_mix64(h + 0xD1B54A32D192ED03ull * ((uint64_t)mode + 1));
-    h = sp_mix64(h + 0x8CB92BA72F3D8DD7ull * (word + 1));
-    return h;
-}
 
 // The value of lane (l ^ D) for D = 1, 2, 4, 8 by the data-parallel lane modes (vector-unit latency; a
 // ds_bpermute would cost an LDS round trip per step of a dependent chain).
@@ -586,7 +568,7 @@ __global__ void __launch_bounds__(kSpThreads) sparse_kernel(SparseArgs a)
         // ================= start of term k (dense): subtract the finished term, first alternation
         // t_0 from the keyed stream (Algorithm 4 line 2), into the other column buffer
         for (int64_t i = tid; i < nwords32; i += kSpThreads) {
-            uint32_t v = (uint32_t)(sp_rng_word(a.seed, (uint64_t)k, 1u, (uint64_t)(i >> 1)) >> (32 * (i & 1)));
+            uint32_t v = (uint32_t)(rng_word(a.seed, (uint64_t)k, 1u, (uint64_t)(i >> 1)) >> (32 * (i & 1)));
             const int64_t rem = n - i * 32;
             if (rem < 32) v &= (1u << rem) - 1u;
             t_oth[i] = v;
@@ -989,7 +971,7 @@ __global__ void __launch_bounds__(kSpThreads) sparse_delay_kernel(SparseArgs a)
         const bool pass = flush || (np == 0 && ahead == 0);
         // t_0 of term k (Algorithm 4 line 2), into the other column buffer
         for (int64_t i = tid; i < nwords32; i += kSpThreads) {
-            uint32_t v = (uint32_t)(sp_rng_word(a.seed, (uint64_t)k, 1u, (uint64_t)(i >> 1)) >> (32 * (i & 1)));
+            uint32_t v = (uint32_t)(rng_word(a.seed, (uint64_t)k, 1u, (uint64_t)(i >> 1)) >> (32 * (i & 1)));
             const int64_t rem = n - i * 32;
             if (rem < 32) v &= (1u << rem) - 1u;
             t_oth[i] = v;
@@ -1003,7 +985,7 @@ __global__ void __launch_bounds__(kSpThreads) sparse_delay_kernel(SparseArgs a)
             const int nvec = (int)(left < kSpAhead ? (left > 0 ? left : 0) : kSpAhead);
             for (int64_t i = tid; i < (int64_t)nvec * nwords32; i += kSpThreads) {
                 const int64_t jv = i / nwords32, iw = i - jv * nwords32;
-                uint32_t v = (uint32_t)(sp_rng_word(a.seed, (uint64_t)(k + jv), 1u, (uint64_t)(iw >> 1)) >> (32 * (iw & 1)));
+                uint32_t v = (uint32_t)(rng_word(a.seed, (uint64_t)(k + jv), 1u, (uint64_t)(iw >> 1)) >> (32 * (iw & 1)));
                 const int64_t rem = n - iw * 32;
                 if (rem < 32) v &= (1u << rem) - 1u;
                 pd.T0[jv * pd.pt_stride + iw] = v;
