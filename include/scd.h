@@ -119,7 +119,9 @@ typedef enum {
     SCD_OPT_SWEEP_BATCH = 7,        /* launch-stream engine: sweeps enqueued between two looks at the device
                                        state (default 64) */
     SCD_OPT_VERBOSE = 8,            /* 0/1: persistent engines print counters of each launch to stderr */
-    SCD_OPT_COUNT = 9
+    SCD_OPT_PERSISTENT_STREAM = 9,  /* 0/1 (default 1): matrices that neither persistent engine above takes are
+                                       streamed by one persistent launch instead of a launch per alternation */
+    SCD_OPT_COUNT = 10
 } scd_option;
 int scd_set_option(scd_ctx* ctx, int option, int64_t value);
 int scd_get_option(const scd_ctx* ctx, int option, int64_t* value /* host */);

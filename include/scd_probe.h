@@ -31,7 +31,9 @@ int scd_traffic(const scd_ctx* ctx, double* bytes, int64_t* passes, int64_t* swe
  * device; keeps a transposed copy of the remainder; finished terms wait in a list of SCD_OPT_SPARSE_DELAY_WIDTH
  * before they are subtracted, Section 3.2.  With delayed updates ||R_k||_F is measured from the remainder at
  * every flush of the list and at the end of every scd_run; between flushes it follows Section 3.2's identity
- * ||R - c s t^T||^2 = ||R||^2 - 2 c <s, R t> + c^2 mn from the cut value).  For engines 1 and 2 also the
+ * ||R - c s t^T||^2 = ||R||^2 - 2 c <s, R t> + c^2 mn from the cut value); 3 = one persistent launch that
+ * streams the remainder from memory once per alternation (matrices whose rows are a multiple of 16 bytes and at
+ * most 64 KB long; the first rows of every workgroup's block stay in LDS).  For engines 1, 2 and 3 also the
  * duration of the most recent launch by HIP events on the context's stream and its dense-equivalent bytes:
  * (alternations + updates) * bytes of the remainder, what a streaming pass per alternation would move.  host
  * pointers, each may be NULL. */

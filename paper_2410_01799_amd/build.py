@@ -11,7 +11,7 @@ from pathlib import Path
 
 PKG = Path(__file__).resolve().parent
 ROOT = PKG.parent
-SRC = [PKG / "csrc" / name for name in ("scd_kernels.hip", "scd_resident.hip", "scd_sparse.hip",
+SRC = [PKG / "csrc" / name for name in ("scd_kernels.hip", "scd_stream.hip", "scd_resident.hip", "scd_sparse.hip",
                                         "scd_apply.hip", "scd_lsq.hip", "scd_api.hip")]
 LIB = PKG / "libscd.so"
 

@@ -89,6 +89,7 @@ struct scd_ctx {
         1 << 22,   // SCD_OPT_MAX_SPIN
         64,        // SCD_OPT_SWEEP_BATCH
         0,         // SCD_OPT_VERBOSE
+        1,         // SCD_OPT_PERSISTENT_STREAM: the persistent streaming engine may be used
     };
     // register-resident engine
     bool resident = false;          // shape and dtype fit, and not switched off
@@ -105,6 +106,13 @@ struct scd_ctx {
     uint64_t* xbuf_sp = nullptr;
     uint32_t seq_sp = 0;
     int rs = 0, cs = 0;
+    // persistent streaming engine
+    bool pstream = false;
+    PStreamGeometry ps_geo = {};
+    uint64_t* xbuf_p1 = nullptr;
+    uint64_t* xbuf_p2 = nullptr;
+    size_t xbuf_p1_bytes = 0, xbuf_p2_bytes = 0;
+    uint32_t seq_ps = 0;
     int sp_grid = kSpGrid;          // workgroups of the sparse engine's launch
     int share = 0;                  // most workgroups a persistent launch may take (0: the whole device)
     int cus = 256;                  // compute units of the device
@@ -428,12 +436,30 @@ int setup_engines(scd_ctx* c)
             if (!hip_ok(hipMemsetAsync(c->xbuf_sp, 0, sparse_xbuf_bytes(), c->stream))) return SCD_EHIP;
         }
     }
+    c->pstream = false;
+    if (!c->resident && !c->sparse && c->opt[SCD_OPT_PERSISTENT_STREAM] != 0 &&
+        pstream_supported(c->dt, c->order, c->dims, limit, &c->ps_geo)) {
+        c->pstream = true;
+        // the exchange slots follow the geometry (the share of the device may have changed it)
+        if (c->xbuf_p1_bytes < c->ps_geo.xp_bytes) {
+            SCD_TRY(dev_alloc(c, (void**)&c->xbuf_p1, c->ps_geo.xp_bytes));
+            c->xbuf_p1_bytes = c->ps_geo.xp_bytes;
+        }
+        if (c->xbuf_p2_bytes < c->ps_geo.xq_bytes) {
+            SCD_TRY(dev_alloc(c, (void**)&c->xbuf_p2, c->ps_geo.xq_bytes));
+            c->xbuf_p2_bytes = c->ps_geo.xq_bytes;
+        }
+        // a new geometry reads other slots than the last one wrote: start the numbering again on cleared slots
+        if (!hip_ok(hipMemsetAsync(c->xbuf_p1, 0, c->xbuf_p1_bytes, c->stream))) return SCD_EHIP;
+        if (!hip_ok(hipMemsetAsync(c->xbuf_p2, 0, c->xbuf_p2_bytes, c->stream))) return SCD_EHIP;
+        c->seq_ps = 0;
+    }
     if (c->resident && !c->xbuf) {
         const size_t xb = (size_t)4 * kResGrid * kResGrid * kResSlotWords * 8;
         SCD_TRY(dev_alloc(c, (void**)&c->xbuf, xb));
         if (!hip_ok(hipMemsetAsync(c->xbuf, 0, xb, c->stream))) return SCD_EHIP;
     }
-    if ((c->resident || c->sparse) && !c->res_dev) {
+    if ((c->resident || c->sparse || c->pstream) && !c->res_dev) {
         SCD_TRY(dev_alloc(c, (void**)&c->res_dev, sizeof(ResidentResult)));
         if (!hip_ok(pool_malloc((void**)&c->res_pin, sizeof(ResidentResult), true))) return SCD_EHIP;
         if (!hip_ok(hipEventCreate(&c->ev0)) || !hip_ok(hipEventCreate(&c->ev1))) return SCD_EHIP;
@@ -512,6 +538,74 @@ int run_sparse(scd_ctx* c, int64_t n)
     c->seq_sp = r.seq_u;
     c->flips += r.flips;
     c->flips_rows += r.flips_rows;
+    c->hs.k = r.k;
+    c->hs.passes += r.alternations;
+    c->hs.updates += r.updates;
+    if (r.warn) c->hs.warn = 1;
+    c->stream_stale = true;
+    return SCD_OK;
+}
+
+// n terms in one persistent launch that streams the remainder once per alternation.
+int run_pstream(scd_ctx* c, int64_t n)
+{
+    PStreamArgs a;
+    memset(&a, 0, sizeof(a));
+    const PStreamGeometry& geo = c->ps_geo;
+    a.R = c->R;
+    a.m = c->dims[0];
+    a.n = c->dims[1];
+    a.seed = c->seed;
+    a.k_start = c->hs.k;
+    a.w_target = c->hs.k + n;
+    a.max_iters = c->hs.max_iters;
+    a.max_spin = (int32_t)c->opt[SCD_OPT_MAX_SPIN];
+    a.poll_delay = (int32_t)c->opt[SCD_OPT_POLL_DELAY];
+    a.seq = c->seq_ps;
+    a.xp = c->xbuf_p1;
+    a.xq = c->xbuf_p2;
+    a.S = c->out_signs[0];
+    a.T = c->out_signs[1];
+    a.c = c->c_out;
+    a.iters = c->iters;
+    a.trace = c->trace;
+    a.mw = (int32_t)words_for(c->dims[0]);
+    a.nw = (int32_t)words_for(c->dims[1]);
+    a.grid = geo.grid;
+    a.rpw = geo.rpw;
+    a.cs = geo.cs;
+    a.lds_rows = geo.lds_rows;
+    a.profile = (int32_t)c->opt[SCD_OPT_VERBOSE];
+    a.res = c->res_dev;
+    SlotLease lease;
+    lease.acquire(a.grid, c->cus);
+    // the workgroups OR their rows' bits into S: the terms of this launch start from zero
+    HIP_TRY(hipMemsetAsync(c->out_signs[0] + c->hs.k * a.mw, 0, (size_t)n * (size_t)a.mw * 8, c->stream));
+    HIP_TRY(hipMemsetAsync(c->res_dev, 0, sizeof(ResidentResult), c->stream));
+    HIP_TRY(hipEventRecord(c->ev0, c->stream));
+    HIP_TRY(launch_pstream(a, c->dt, geo.lds_bytes, c->stream));
+    HIP_TRY(hipEventRecord(c->ev1, c->stream));
+    HIP_TRY(hipMemcpyAsync(c->res_pin, c->res_dev, sizeof(ResidentResult), hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(hipStreamSynchronize(c->stream));
+    const ResidentResult r = *c->res_pin;
+    {
+        float ms = 0.f;
+        HIP_TRY(hipEventElapsedTime(&ms, c->ev0, c->ev1));
+        c->last_launch_seconds = (double)ms * 1e-3;
+        // one read of R per pass, one more write per update
+        c->last_launch_bytes = ((double)r.alternations + (double)r.updates) * (double)c->total * (double)c->esize;
+    }
+    if (r.err || r.k != a.w_target) {
+        c->broken = true;
+        return SCD_ETIMEOUT;
+    }
+    if (c->opt[SCD_OPT_VERBOSE])
+        fprintf(stderr, "[scd stream] terms %lld passes %lld re-reads %lld; grid %d, %d rows per workgroup, %d of them in LDS; "
+                        "us per pass: rows %.2f, publish %.2f, hop-1 gather %.2f, slice %.2f, hop-2 %.2f, decide %.2f\n",
+                (long long)n, (long long)r.alternations, (long long)r.spins, geo.grid, geo.rpw, geo.lds_rows,
+                r.ticks[0] * 0.01 / r.alternations, r.ticks[1] * 0.01 / r.alternations, r.ticks[2] * 0.01 / r.alternations,
+                r.ticks[3] * 0.01 / r.alternations, r.ticks[4] * 0.01 / r.alternations, r.ticks[5] * 0.01 / r.alternations);
+    c->seq_ps = r.seq_u;
     c->hs.k = r.k;
     c->hs.passes += r.alternations;
     c->hs.updates += r.updates;
@@ -738,6 +832,7 @@ int scd_set_option(scd_ctx* c, int option, int64_t value)
     switch (option) {
         case SCD_OPT_RESIDENT:
         case SCD_OPT_SPARSE:
+        case SCD_OPT_PERSISTENT_STREAM:
         case SCD_OPT_ROWPASS_KERNEL:
         case SCD_OPT_VERBOSE:
             if (value != 0 && value != 1) return SCD_EINVAL;
@@ -760,7 +855,8 @@ int scd_set_option(scd_ctx* c, int option, int64_t value)
         default: return SCD_EINVAL;
     }
     c->opt[option] = value;
-    if (option == SCD_OPT_RESIDENT || option == SCD_OPT_SPARSE || option == SCD_OPT_SPARSE_MIN_MIB) {
+    if (option == SCD_OPT_RESIDENT || option == SCD_OPT_SPARSE || option == SCD_OPT_SPARSE_MIN_MIB ||
+        option == SCD_OPT_PERSISTENT_STREAM) {
         if (c->broken) return SCD_ETIMEOUT;
         return setup_engines(c);
     }
@@ -780,8 +876,8 @@ int scd_run(scd_ctx* c, int64_t n)
     if (c->broken) return SCD_ETIMEOUT;
     if (n == 0) return c->hs.warn ? SCD_WMAXITER : SCD_OK;
     if (c->hs.k + n > c->w_capacity) return SCD_EFULL;
-    if (c->resident || c->sparse) {
-        SCD_TRY(c->resident ? run_resident(c, n) : run_sparse(c, n));
+    if (c->resident || c->sparse || c->pstream) {
+        SCD_TRY(c->resident ? run_resident(c, n) : (c->sparse ? run_sparse(c, n) : run_pstream(c, n)));
         return c->hs.warn ? SCD_WMAXITER : SCD_OK;
     }
     SCD_TRY(resync_stream_state(c));  // a persistent engine may have advanced the context before it lost its share
@@ -864,7 +960,9 @@ int scd_set_remainder(scd_ctx* c, const void* R_in)
         // stale word can pass for a fresh one.
         if (c->xbuf) HIP_TRY(hipMemsetAsync(c->xbuf, 0, (size_t)4 * kResGrid * kResGrid * kResSlotWords * 8, c->stream));
         if (c->xbuf_sp) HIP_TRY(hipMemsetAsync(c->xbuf_sp, 0, sparse_xbuf_bytes(), c->stream));
-        c->seq_u = c->seq_v = c->seq_sp = 0;
+        if (c->xbuf_p1) HIP_TRY(hipMemsetAsync(c->xbuf_p1, 0, c->xbuf_p1_bytes, c->stream));
+        if (c->xbuf_p2) HIP_TRY(hipMemsetAsync(c->xbuf_p2, 0, c->xbuf_p2_bytes, c->stream));
+        c->seq_u = c->seq_v = c->seq_sp = c->seq_ps = 0;
     }
     c->broken = false;
     HIP_TRY(hipMemcpyAsync(c->R, R_in, (size_t)c->total * c->esize, hipMemcpyDeviceToDevice, c->stream));
@@ -886,7 +984,7 @@ int scd_set_remainder(scd_ctx* c, const void* R_in)
 int scd_engine(const scd_ctx* c, int* engine, double* last_launch_seconds, double* last_launch_bytes)
 {
     if (!c) return SCD_EINVAL;
-    if (engine) *engine = c->resident ? 1 : (c->sparse ? 2 : 0);
+    if (engine) *engine = c->resident ? 1 : (c->sparse ? 2 : (c->pstream ? 3 : 0));
     if (last_launch_seconds) *last_launch_seconds = c->last_launch_seconds;
     if (last_launch_bytes) *last_launch_bytes = c->last_launch_bytes;
     return SCD_OK;

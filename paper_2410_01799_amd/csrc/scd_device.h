@@ -176,6 +176,39 @@ size_t sparse_xbuf_bytes();
 hipError_t launch_sparse(const SparseArgs& a, scd_dtype dt, hipStream_t st);
 hipError_t launch_transpose(const void* in, void* out, scd_dtype dt, int64_t rows, int64_t cols, hipStream_t st);
 
+// Persistent streaming engine (scd_stream.hip): one launch that streams the remainder once per alternation.
+struct PStreamGeometry {
+    int grid;        // workgroups (one per compute unit)
+    int rpw;         // rows per workgroup
+    int cs;          // columns per slice of the hop-1 reduction (multiple of 8, at most 256)
+    int lds_rows;    // rows of a workgroup's block kept in LDS for the whole launch
+    size_t lds_bytes, xp_bytes, xq_bytes;
+};
+
+struct PStreamArgs {
+    void* R;                 // m x n
+    int64_t m, n;
+    uint64_t seed;
+    int64_t k_start, w_target;
+    int32_t max_iters, max_spin;
+    int32_t poll_delay;
+    uint32_t seq;            // exchange sequence numbers already used
+    uint64_t* xp;            // hop 1: [2 parities][grid][n values as tagged words]
+    uint64_t* xq;            // hop 2: [2 parities][grid][16 words]
+    uint64_t* S;             // term-major outputs; rows k_start.. of S must be zero (bits are OR-ed in)
+    uint64_t* T;
+    void* c;
+    int32_t* iters;
+    double* trace;
+    int32_t mw, nw;
+    int32_t grid, rpw, cs, lds_rows;
+    int32_t profile;         // 1: workgroup 0 times its phases
+    ResidentResult* res;
+};
+
+bool pstream_supported(scd_dtype dt, int order, const int64_t* dims, int limit, PStreamGeometry* geo);
+hipError_t launch_pstream(const PStreamArgs& a, scd_dtype dt, size_t lds_bytes, hipStream_t st);
+
 // ---- product with a vector from the packed factors (scd_apply.hip) ---------------------------------
 struct ApplyPlan {
     int chunks;               // chunks of 4096 input entries

@@ -32,7 +32,7 @@ EXPORTS = [
 
 # scd_option of include/scd.h
 OPTIONS = {"resident": 0, "sparse": 1, "sparse_min_mib": 2, "sparse_delay_width": 3, "rowpass_kernel": 4,
-           "poll_delay": 5, "max_spin": 6, "sweep_batch": 7, "verbose": 8}
+           "poll_delay": 5, "max_spin": 6, "sweep_batch": 7, "verbose": 8, "persistent_stream": 9}
 
 
 class ScdError(RuntimeError):

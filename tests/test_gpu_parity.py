@@ -27,10 +27,13 @@ def scd():
     return mod
 
 
-@pytest.fixture(params=[1, 0], ids=["tiled", "generic"])
+@pytest.fixture(params=["tiled", "generic", "persistent"])
 def variant(request):
-    """Options that select the launch-stream engine with either row-pass kernel (persistent engines off)."""
-    return {"rowpass_kernel": request.param, "resident": 0, "sparse": 0}
+    """Options that select the streaming engines: a launch per alternation with either row-pass kernel, or the
+    one persistent launch (matrices; tensors then still take a launch per sweep)."""
+    if request.param == "persistent":
+        return {"resident": 0, "sparse": 0}
+    return {"rowpass_kernel": 1 if request.param == "tiled" else 0, "resident": 0, "sparse": 0, "persistent_stream": 0}
 
 
 def gauss(shape, seed, dtype=np.float32):
@@ -240,7 +243,8 @@ def test_two_runs_are_bit_identical(scd):
 
 def test_tiled_and_generic_kernels_agree(scd):
     A = dev(gauss((384, 1024), 12))
-    out = [scd.scd_decompose(A, 10, 3, options={"rowpass_kernel": v, "resident": 0, "sparse": 0}) for v in (1, 0)]
+    out = [scd.scd_decompose(A, 10, 3, options={"rowpass_kernel": v, "resident": 0, "sparse": 0, "persistent_stream": 0})
+           for v in (1, 0)]
     np.testing.assert_allclose(out[0]["trace"].cpu().numpy(), out[1]["trace"].cpu().numpy(), rtol=1e-5)
 
 

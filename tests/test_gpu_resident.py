@@ -21,7 +21,7 @@ def scd():
 
 
 RESIDENT = {"resident": 1}
-STREAM = {"resident": 0, "sparse": 0}
+STREAM = {"resident": 0, "sparse": 0, "persistent_stream": 0}
 
 
 def gauss(shape, seed):
@@ -113,10 +113,10 @@ def test_exchange_probe_runs(scd):
 def test_a_context_that_loses_its_share_continues_on_the_launch_stream(scd):
     m = n = 1024
     A = torch.from_numpy(gauss((m, n), 21)).cuda()
-    with scd.ScdContext(A, 8, 6, options={"sparse": 0}) as ctx:
+    with scd.ScdContext(A, 8, 6, options={"sparse": 0, "persistent_stream": 0}) as ctx:
         assert ctx.engine()["engine"] == 1
         ctx.run(4)
-        ctx.set_workgroups(16)            # the 8 x 8 grid no longer fits, the sparse engine is switched off
+        ctx.set_workgroups(16)            # the 8 x 8 grid no longer fits, the other persistent engines are switched off
         assert ctx.engine()["engine"] == 0
         ctx.run(4)
         mixed = ctx.results()

@@ -23,7 +23,8 @@ def gauss(shape, seed):
 
 @pytest.mark.parametrize("name,opts,engine", [("resident", {"resident": 1}, 1),
                                               ("sparse", {"resident": 0, "sparse_min_mib": 0}, 2),
-                                              ("sparse-immediate", {"resident": 0, "sparse_min_mib": 0, "sparse_delay_width": 0}, 2)])
+                                              ("sparse-immediate", {"resident": 0, "sparse_min_mib": 0, "sparse_delay_width": 0}, 2),
+                                              ("persistent-stream", {"resident": 0, "sparse": 0}, 3)])
 def test_a_wait_that_runs_out_is_reported_and_the_context_recovers(scd, name, opts, engine):
     A = torch.from_numpy(gauss((1024, 1024), 31)).cuda()
     seed, w = 8, 6
