@@ -39,6 +39,13 @@ int scd_traffic(const scd_ctx* ctx, double* bytes, int64_t* passes, int64_t* swe
  * pointers, each may be NULL. */
 int scd_engine(const scd_ctx* ctx, int* engine, double* last_launch_seconds, double* last_launch_bytes);
 
+/* The launch geometry the persistent streaming engine would use for an array of this dtype and shape on at most
+ * `limit` workgroups (host arrays; no GPU work): out[0] = 1 if the engine takes the shape (else 0 and the rest is
+ * unspecified), out[1] workgroups, out[2] rows per workgroup, out[3] columns per slice of the first exchange,
+ * out[4] rows of a block kept in LDS, out[5] bytes of dynamic LDS, out[6] / out[7] bytes of the two exchange
+ * buffers.  For tests of the host arithmetic against the bounds the kernel assumes. */
+int scd_stream_geometry(scd_dtype dt, int order, const int64_t* dims, int limit, int64_t out[8]);
+
 /* Measurement: run n (<= 4096) further sweeps of the greedy loop with a HIP event before and after
  * each kernel of the pass over the remainder; returns the average duration of the row-pass launch
  * and of the reduce launch that follows it (host pointers, seconds).  The terms found meanwhile are

@@ -554,7 +554,13 @@ int run_pstream(scd_ctx* c, int64_t n)
     const PStreamGeometry& geo = c->ps_geo;
     a.R = c->R;
     a.m = c->dims[0];
-    a.n = c->dims[1];
+    a.n = c->order == 2 ? c->dims[1] : c->dims[1] * c->dims[2];
+    if (c->order == 3) {
+        a.n2 = (int32_t)c->dims[1];
+        a.n3 = (int32_t)c->dims[2];
+        a.w2 = (int32_t)words_for(c->dims[1]);
+        a.S3 = c->out_signs[2];
+    }
     a.seed = c->seed;
     a.k_start = c->hs.k;
     a.w_target = c->hs.k + n;
@@ -570,7 +576,7 @@ int run_pstream(scd_ctx* c, int64_t n)
     a.iters = c->iters;
     a.trace = c->trace;
     a.mw = (int32_t)words_for(c->dims[0]);
-    a.nw = (int32_t)words_for(c->dims[1]);
+    a.nw = (int32_t)words_for(a.n);
     a.grid = geo.grid;
     a.rpw = geo.rpw;
     a.cs = geo.cs;
@@ -987,6 +993,22 @@ int scd_engine(const scd_ctx* c, int* engine, double* last_launch_seconds, doubl
     if (engine) *engine = c->resident ? 1 : (c->sparse ? 2 : (c->pstream ? 3 : 0));
     if (last_launch_seconds) *last_launch_seconds = c->last_launch_seconds;
     if (last_launch_bytes) *last_launch_bytes = c->last_launch_bytes;
+    return SCD_OK;
+}
+
+int scd_stream_geometry(scd_dtype dt, int order, const int64_t* dims, int limit, int64_t out[8])
+{
+    if (!dims || !out || !dtype_ok(dt) || order < 2 || order > SCD_MAX_ORDER) return SCD_EINVAL;
+    PStreamGeometry g = {};
+    const bool ok = pstream_supported(dt, order, dims, limit, &g);
+    out[0] = ok ? 1 : 0;
+    out[1] = g.grid;
+    out[2] = g.rpw;
+    out[3] = g.cs;
+    out[4] = g.lds_rows;
+    out[5] = (int64_t)g.lds_bytes;
+    out[6] = (int64_t)g.xp_bytes;
+    out[7] = (int64_t)g.xq_bytes;
     return SCD_OK;
 }
 

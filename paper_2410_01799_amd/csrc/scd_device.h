@@ -186,8 +186,9 @@ struct PStreamGeometry {
 };
 
 struct PStreamArgs {
-    void* R;                 // m x n
+    void* R;                 // m x n (an order-3 tensor n_1 x n_2 x n_3 as m = n_1, n = n_2 n_3)
     int64_t m, n;
+    int32_t n2, n3, w2;      // order 3: the two trailing modes and the words of a mode-2 sign vector; else 0
     uint64_t seed;
     int64_t k_start, w_target;
     int32_t max_iters, max_spin;
@@ -196,7 +197,8 @@ struct PStreamArgs {
     uint64_t* xp;            // hop 1: [2 parities][grid][n values as tagged words]
     uint64_t* xq;            // hop 2: [2 parities][grid][16 words]
     uint64_t* S;             // term-major outputs; rows k_start.. of S must be zero (bits are OR-ed in)
-    uint64_t* T;
+    uint64_t* T;             // second mode's sign vectors
+    uint64_t* S3;            // order 3: third mode's sign vectors (one word per term)
     void* c;
     int32_t* iters;
     double* trace;

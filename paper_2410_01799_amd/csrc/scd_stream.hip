@@ -34,7 +34,8 @@ constexpr int kPsThreads = 512;
 constexpr int kPsWaves = kPsThreads / 64;
 constexpr int kPsMaxSlice = 256;   // most positions per slice of hop 1
 constexpr int kPsSlot2 = 16;       // words of a hop-2 slot: up to 8 sign words, c and ||.||^2 as two halves each
-constexpr int kPsMaxItems2 = 6;    // hop-2 words a thread gathers: 256 * (8 + 4) / 512
+constexpr int kPsMaxLast = 4;      // order 3: largest last mode (colour channels)
+constexpr int kPsMaxItems2 = 6;    // hop-2 words a thread gathers: at most 256 * 12 / 512
 constexpr size_t kPsMaxLds = 150 * 1024;  // dynamic LDS a launch may ask for
 
 template <typename TE>
@@ -127,10 +128,10 @@ __device__ __forceinline__ uint64_t ps_load(const uint64_t* p)
 // profile mode: 100 MHz ticks of workgroup 0 per phase
 #define PS_TICK(slot)                                                  \
     do {                                                               \
-        if (a.profile) {                                               \
+        if (a.profile && threadIdx.x == 0) {                           \
             const uint64_t now_ = __builtin_amdgcn_s_memrealtime();    \
-            ticks[slot] += (int64_t)(now_ - tick0);                    \
-            tick0 = now_;                                              \
+            sh.ticks[slot] += (int64_t)(now_ - sh.tick0);              \
+            sh.tick0 = now_;                                           \
         }                                                              \
     } while (0)
 
@@ -138,8 +139,12 @@ struct PsShared {
     double u[2][8][kPsWaves];      // row sums of a batch [row][wave] (two parities: one barrier per batch)
     double part[kPsThreads];       // hop 1: partial sums per (member group, position)
     double red[2][kPsWaves];
-    uint32_t scal[4][kSpGrid];     // hop 2: low/high halves of c shares and of ||.||^2 shares
+    uint32_t scal[2 * kPsMaxLast + 2][kSpGrid];  // hop 2: low/high halves of the members' scalars
     uint32_t tw32[8];              // sign words of the own slice
+    double v[kPsMaxSlice];         // order 3: the own slice of W_1
+    double w2part[kPsMaxLast];     // order 3: the own slice's part of the last mode's sums
+    int64_t ticks[6];              // profile mode
+    uint64_t tick0;
 };
 
 template <typename TE, int CPT, int RB>
@@ -298,7 +303,8 @@ __device__ __forceinline__ void ps_process(PsTile<TE, CPT, RB>& t, TE* base, int
 // holds their first batch, loaded while the previous exchange was waiting).  s_old / s_new: sign bytes of the
 // block's rows before and after this pass.
 template <typename TE, int CPT, int RB>
-__device__ __forceinline__ void ps_pass(int mode, TE* lds_rows, int nl, TE* grows, int ng, PsTile<TE, CPT, RB>& first,
+__device__ __forceinline__ void ps_pass(int mode, TE* lds_rows, int nl, TE* grows, const TE* gsafe, int ng,
+                                        PsTile<TE, CPT, RB>& first,
                                         int64_t cols, uint64_t sumb, uint64_t updb, TE ck, TE* acc, double& fsq,
                                         const uint8_t* s_old, uint8_t* s_new, PsShared& sh)
 {
@@ -311,8 +317,16 @@ __device__ __forceinline__ void ps_pass(int mode, TE* lds_rows, int nl, TE* grow
     TE sf[NE];  // the signs of this thread's columns as factors +-1.0
 #pragma unroll
     for (int e = 0; e < NE; ++e) sf[e] = ((sumb >> e) & 1ull) ? (TE)-1 : (TE)1;
+    // streamed rows: `first` holds their first batch already; the second one is asked for now, so that it arrives
+    // while the rows kept in LDS are worked on
+    PsTile<TE, CPT, RB> tb;
+    const int nb = (ng + RB - 1) / RB;
+    // (a load that is not wanted still reads 16 bytes at its base: `gsafe` is a row of the block in every case,
+    // whereas `grows` is one past the end of the matrix for the last workgroup when nothing is streamed)
+    ps_tile_load<TE, CPT, RB>(tb, nb > 1 ? grows : gsafe, cols, RB, ng > 0 ? ng : 1, nch, nb > 1);
     {
         PsTile<TE, CPT, RB> tl;
+#pragma nounroll
         for (int rb = 0; rb < nl; rb += RB) {
             ps_tile_load<TE, CPT, RB>(tl, lds_rows, cols, rb, nl, nch, true);
             if (mode == 1) tl.rowsign = ps_rowsigns(s_old, rb, nl);
@@ -321,13 +335,12 @@ __device__ __forceinline__ void ps_pass(int mode, TE* lds_rows, int nl, TE* grow
             parity ^= 1;
         }
     }
-    // streamed rows: two register tiles alternate, the loads of the next batch are in flight while this one
-    // is reduced; every load inside the loop is unconditional
-    PsTile<TE, CPT, RB> tb;
-    const int nb = (ng + RB - 1) / RB;
+    // two register tiles alternate, the loads of the next batch are in flight while this one is reduced; every
+    // load inside the loop is unconditional
+#pragma nounroll
     for (int b = 0; b < nb; b += 2) {
         const int rb = b * RB;
-        ps_tile_load<TE, CPT, RB>(tb, grows, cols, rb + RB, ng, nch, b + 1 < nb);
+        if (b > 0) ps_tile_load<TE, CPT, RB>(tb, grows, cols, rb + RB, ng, nch, b + 1 < nb);
         if (mode == 1) first.rowsign = ps_rowsigns(s_old + nl, rb, ng);
         ps_process<TE, CPT, RB>(first, grows, cols, rb, ng, nch, mode, full_cols && rb + RB <= ng, sf, updb, ck, acc, fsq,
                                 s_new + nl, sh, parity);
@@ -340,14 +353,47 @@ __device__ __forceinline__ void ps_pass(int mode, TE* lds_rows, int nl, TE* grow
     }
 }
 
+// sum over the members' shares held one per thread (thread t < grid holds member t's), the same order in every
+// workgroup: lanes by butterfly, then the first four waves in order.  All threads must call it.
+__device__ __forceinline__ double ps_sum_members(double v, PsShared& sh, int slot)
+{
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    if (wv < kSpGrid / 64) {
+        v = ps_wave_sum(v);
+        if (lane == 0) sh.red[slot][wv] = v;
+    }
+    __syncthreads();
+    double t = 0.0;
+#pragma unroll
+    for (int q = 0; q < kSpGrid / 64; ++q) t += sh.red[slot][q];
+    return t;
+}
+
+// Column signs of the level-0 view of an order-3 tensor: bit q = s2[q / n3] xor s3[q % n3] (Algorithm 12 lines
+// 5-7: the sign of the tensor product of the other modes' vectors), written word by word from ballots.
+__device__ __forceinline__ void ps_kron_bits(uint64_t* out, int64_t n, int n3, const uint64_t* s2, uint64_t s3)
+{
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const float rn3 = 1.0f / (float)n3;
+    for (int64_t qb = (int64_t)wv * 64; qb < n; qb += kPsThreads) {
+        const int64_t q = qb + lane;
+        // q / n3 by a float product, exact here: (q + 0.5) / n3 is at least 0.5 / n3 away from an integer and
+        // q stays below 2^20
+        const int64_t qc = q < n ? q : n - 1;  // (lanes past the end read a valid word and drop it)
+        const int j = (int)(((float)qc + 0.5f) * rn3);
+        const int c = (int)qc - j * n3;
+        const bool bit = q < n && ((((s2[j >> 6] >> (j & 63)) ^ (s3 >> c)) & 1ull) != 0);
+        const uint64_t word = __ballot(bit);
+        if (lane == 0) out[qb >> 6] = word;
+    }
+}
+
 template <typename TE, int CPT, int RB>
 __global__ void __launch_bounds__(kPsThreads) pstream_kernel(PStreamArgs a)
 {
     constexpr int VE = PsVec<TE>::N;
     constexpr int NE = CPT * VE;
     constexpr int WPE = PsVec<TE>::WPE;
-    constexpr int NPOS = NE * kPsThreads;      // positions of the exchange: value q of thread t at q * 512 + t
-    constexpr int PW = NPOS / 64;              // words of a sign vector in position order
     typedef typename PsVec<TE>::type V;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int g = blockIdx.x, G = a.grid;
@@ -357,17 +403,22 @@ __global__ void __launch_bounds__(kPsThreads) pstream_kernel(PStreamArgs a)
     const int nl = nrows < a.lds_rows ? nrows : a.lds_rows;                 // rows kept in LDS
     const int ng = nrows - nl;                                              // rows streamed every alternation
     const int nw = a.nw;
+    const bool tensor = a.n3 > 0;               // order 3: the columns are (mode 1) x (mode 2), n = n2 * n3
+    const int n3 = a.n3, w2 = a.w2;             // w2: words of a mode-1 sign vector (n2 bits)
 
     extern __shared__ __align__(16) unsigned char ps_lds[];
-    // layout: [rows kept in LDS][t in position order][t_0 in column order][T_k in column order][sign bytes x 2][fixed part]
+    // layout: [rows kept in LDS][one row of partial sums][column signs t][t_0 of the coming term][sign bytes x 2]
+    //         [order 3: s^(2) and its random start][fixed part]
     TE* lds_rows = (TE*)ps_lds;
     size_t off = (((size_t)a.lds_rows * (size_t)n * sizeof(TE)) + 15) & ~(size_t)15;
-    uint64_t* t_pos = (uint64_t*)(ps_lds + off);
-    off += (size_t)PW * 8;
+    TE* pub = (TE*)(ps_lds + off);
+    off += (((size_t)n * sizeof(TE)) + 15) & ~(size_t)15;
+    uint64_t* t_cur = (uint64_t*)(ps_lds + off);
+    off += (size_t)nw * 8;
     uint64_t* t_rng = (uint64_t*)(ps_lds + off);
     off += (size_t)nw * 8;
-    uint64_t* t_nat = (uint64_t*)(ps_lds + off);
-    off += (size_t)nw * 8;
+    uint64_t* s2_cur = (uint64_t*)(ps_lds + off);
+    off += (size_t)w2 * 8;
     uint8_t* sbuf0 = ps_lds + off;
     off += ((size_t)a.rpw + 15) & ~(size_t)15;
     uint8_t* sbuf1 = ps_lds + off;
@@ -384,22 +435,31 @@ __global__ void __launch_bounds__(kPsThreads) pstream_kernel(PStreamArgs a)
         const int64_t tot = (int64_t)nl * nch;
         for (int64_t i = tid; i < tot; i += kPsThreads) dst[i] = src[i];
     }
-    for (int p = tid; p < PW; p += kPsThreads) t_pos[p] = 0;
-    for (int p = tid; p < nw; p += kPsThreads) {
-        t_nat[p] = 0;
-        t_rng[p] = rng_word_masked(a.seed, (uint64_t)a.k_start, 1u, p, n);  // t_0 of the first term (Algorithm 4 line 2)
+    // the random start of the first term (Algorithm 4 line 2; Algorithm 12 line 1 for the modes after the first)
+    uint64_t s3_cur = 0;  // order 3: the signs of the last mode (at most 64), the same in every thread
+    if (tensor) {
+        for (int p = tid; p < w2; p += kPsThreads) s2_cur[p] = rng_word_masked(a.seed, (uint64_t)a.k_start, 1u, p, a.n2);
+        s3_cur = rng_word_masked(a.seed, (uint64_t)a.k_start, 2u, 0, n3);
+        __syncthreads();
+        ps_kron_bits(t_rng, n, n3, s2_cur, s3_cur);
+    } else {
+        for (int p = tid; p < nw; p += kPsThreads) t_rng[p] = rng_word_masked(a.seed, (uint64_t)a.k_start, 1u, p, n);
     }
+    for (int p = tid; p < nw; p += kPsThreads) t_cur[p] = 0;
     for (int i = tid; i < a.rpw; i += kPsThreads) sbuf0[i] = sbuf1[i] = 0;
     __syncthreads();
 
-    // positions this workgroup reduces in hop 1: [c0, c0 + ncol)
+    // columns this workgroup reduces in hop 1: [c0, c0 + ncol)
     const int cs = a.cs;
-    const int c0 = g * cs;
-    const int ncol = c0 >= NPOS ? 0 : (NPOS - c0 < cs ? NPOS - c0 : cs);
-    const int Q = kPsThreads / cs;            // member groups of the hop-1 reduction (cs <= 256)
-    const int tw = (cs + 31) / 32;            // sign words of a slice
-    const int sbytes = cs >> 3;               // bytes of a slice (cs is a multiple of 8)
-    const size_t slot1 = (size_t)NPOS * WPE;  // words of a hop-1 slot
+    const int64_t c0 = (int64_t)g * cs;
+    const int ncol = (int)(c0 >= n ? 0 : (n - c0 < cs ? n - c0 : cs));
+    const int Q = kPsThreads / cs;                // member groups of the hop-1 reduction (cs <= 256)
+    const int unit = tensor ? n3 : 1;             // columns per sign bit that a slice publishes
+    const int sbits = cs / unit;                  // sign bits of a slice (a multiple of 8)
+    const int tw = (sbits + 31) / 32;             // sign words of a slice
+    const int sbytes = sbits >> 3;
+    const int nsc = tensor ? 2 * n3 : 2;          // words of scalars per slot: c (or the n3 mode sums) as halves
+    const size_t slot1 = (size_t)n * WPE;         // words of a hop-1 slot
 
     int64_t k = a.k_start;
     int64_t alternations = 0, updates = 0, spins = 0;
@@ -413,8 +473,10 @@ __global__ void __launch_bounds__(kPsThreads) pstream_kernel(PStreamArgs a)
 
     PsTile<TE, CPT, RB> first;
     ps_tile_load<TE, CPT, RB>(first, gfirst, n, 0, ng > 0 ? ng : 1, nch, ng > 0);
-    int64_t ticks[6] = {0, 0, 0, 0, 0, 0};
-    uint64_t tick0 = a.profile ? __builtin_amdgcn_s_memrealtime() : 0;
+    if (tid == 0) {
+        for (int i = 0; i < 6; ++i) sh.ticks[i] = 0;
+        sh.tick0 = __builtin_amdgcn_s_memrealtime();
+    }
 
     for (;;) {
         // ================= the pass over the block
@@ -424,8 +486,8 @@ __global__ void __launch_bounds__(kPsThreads) pstream_kernel(PStreamArgs a)
         double fsq = 0.0;
         uint8_t* s_old = sp ? sbuf1 : sbuf0;
         uint8_t* s_new = sp ? sbuf0 : sbuf1;
-        ps_pass<TE, CPT, RB>(mode, lds_rows, nl, grows, ng, first, n, mode == 0 ? bcur : brng, bcur, ck, acc, fsq, s_old,
-                             s_new, sh);
+        ps_pass<TE, CPT, RB>(mode, lds_rows, nl, grows, gfirst, ng, first, n, mode == 0 ? bcur : brng, bcur, ck, acc, fsq,
+                             s_old, s_new, sh);
         sp ^= 1;  // s_new is the current s
         PS_TICK(0);
         ++alternations;
@@ -433,26 +495,38 @@ __global__ void __launch_bounds__(kPsThreads) pstream_kernel(PStreamArgs a)
         const bool with_norm = mode != 0;
 
         // ================= hop 1: publish the partial column sums, reduce the own slice
+        // (through LDS, so that every store instruction writes 512 consecutive tagged words: the 16-byte chunks
+        // of a thread are 2 KB apart, and partial-line stores to the fabric are what costs)
+#pragma unroll
+        for (int c = 0; c < CPT; ++c) {
+            const int64_t ch = tid + c * kPsThreads;
+            if (ch < nch) {
+                V v;
+                if constexpr (VE == 4) v = V{acc[c * 4], acc[c * 4 + 1], acc[c * 4 + 2], acc[c * 4 + 3]};
+                else v = V{acc[c * 2], acc[c * 2 + 1]};
+                ((V*)pub)[ch] = v;
+            }
+        }
+        if (with_norm) {
+            fsq = ps_wave_sum(fsq);
+            if (lane == 0) sh.red[1][wv] = fsq;
+        }
+        __syncthreads();
         {
             uint64_t* mine = a.xp + ((size_t)(seq & 1u) * G + g) * slot1;
-#pragma unroll
-            for (int q = 0; q < NE; ++q) {
-                // (chunks past the end of the row hold zeros: their positions are published like the others)
+#pragma nounroll
+            for (int64_t col = tid; col < n; col += kPsThreads) {
                 if constexpr (WPE == 1) {
-                    ps_store_tagged(mine + q * kPsThreads + tid, __float_as_uint((float)acc[q]), seq);
+                    ps_store_tagged(mine + col, __float_as_uint((float)pub[col]), seq);
                 } else {
-                    const uint64_t b = (uint64_t)__double_as_longlong((double)acc[q]);
-                    ps_store_tagged(mine + q * kPsThreads + tid, (uint32_t)b, seq);
-                    ps_store_tagged(mine + NPOS + q * kPsThreads + tid, (uint32_t)(b >> 32), seq);
+                    const uint64_t b = (uint64_t)__double_as_longlong((double)pub[col]);
+                    ps_store_tagged(mine + col, (uint32_t)b, seq);
+                    ps_store_tagged(mine + n + col, (uint32_t)(b >> 32), seq);
                 }
             }
         }
         // the first streamed batch of the next pass does not depend on the exchange: its loads fly meanwhile
         ps_tile_load<TE, CPT, RB>(first, gfirst, n, 0, ng > 0 ? ng : 1, nch, ng > 0);
-        if (with_norm) {
-            fsq = ps_wave_sum(fsq);
-            if (lane == 0) sh.red[1][wv] = fsq;
-        }
         PS_TICK(1);
         for (int d = 0; d < a.poll_delay; ++d) __builtin_amdgcn_s_sleep(1);
         bool ok = true;
@@ -463,6 +537,7 @@ __global__ void __launch_bounds__(kPsThreads) pstream_kernel(PStreamArgs a)
             if (q < Q && jc < ncol) {
                 const uint64_t* basep = a.xp + ((size_t)(seq & 1u) * G) * slot1 + (size_t)(c0 + jc);
                 int spin = 0;
+#pragma nounroll
                 for (int m0 = q; m0 < G && ok; m0 += 8 * Q) {
                     uint64_t w[8][WPE];
                     for (;;) {
@@ -471,7 +546,7 @@ __global__ void __launch_bounds__(kPsThreads) pstream_kernel(PStreamArgs a)
                         for (int i = 0; i < 8; ++i) {
                             const int mem = m0 + i * Q < G ? m0 + i * Q : m0;
 #pragma unroll
-                            for (int h = 0; h < WPE; ++h) w[i][h] = ps_load(basep + (size_t)mem * slot1 + (size_t)h * NPOS);
+                            for (int h = 0; h < WPE; ++h) w[i][h] = ps_load(basep + (size_t)mem * slot1 + (size_t)h * n);
                         }
 #pragma unroll
                         for (int i = 0; i < 8; ++i)
@@ -504,8 +579,8 @@ __global__ void __launch_bounds__(kPsThreads) pstream_kernel(PStreamArgs a)
             return;
         }
         PS_TICK(2);
-        // v at the own positions: L neighbouring lanes share a position, each adds every L-th member group in
-        // order, a butterfly joins them; t = sgn(v), share of c = sum |v|
+        // v at the own columns: L neighbouring lanes share a column, each adds every L-th member group in order,
+        // a butterfly joins them
         {
             const int L = cs <= 64 ? 8 : (cs <= 128 ? 4 : 2);
             const int jc = tid / L, ql = tid - jc * L;
@@ -521,38 +596,68 @@ __global__ void __launch_bounds__(kPsThreads) pstream_kernel(PStreamArgs a)
             if (L >= 4) vj += ps_dpp_f64<0x4E, 0>(vj);        // lane ^ 2
             if (L >= 8) vj += ps_dpp_f64<0x141, 0x1B>(vj);    // lane ^ 4
             const bool mine = jc < ncol && ql == 0;
-            if (mine && vj < 0.0) atomicOr(&sh.tw32[jc >> 5], 1u << (jc & 31));
-            const double ca = ps_wave_sum(mine ? fabs(vj) : 0.0);
-            if (lane == 0) sh.red[0][wv] = ca;
+            if (!tensor) {
+                // t_l = sgn(v_l), share of c = sum |v_l| (Algorithm 4 lines 6-7)
+                if (mine && vj < 0.0) atomicOr(&sh.tw32[jc >> 5], 1u << (jc & 31));
+                const double ca = ps_wave_sum(mine ? fabs(vj) : 0.0);
+                if (lane == 0) sh.red[0][wv] = ca;
+            } else if (mine) {
+                sh.v[jc] = vj;  // the slice of W_1 = a x_1 s^(1): whole rows of the n2 x n3 array
+            }
         }
         __syncthreads();
+        if (tensor) {
+            // mode 2 on the own rows of W_1: s^(2)_j = sgn(sum_c W_1[j][c] s^(3)_c) with the last mode's signs of the
+            // previous sweep (Algorithm 12: modes before the current one new, modes after it old), then this
+            // slice's part of the last mode's sums W_2[c] = sum_j s^(2)_j W_1[j][c]
+            const int nr2 = ncol / n3;
+            if (tid < nr2) {
+                double u2 = 0.0;
+                for (int c = 0; c < n3; ++c) u2 += ((s3_cur >> c) & 1ull) ? -sh.v[tid * n3 + c] : sh.v[tid * n3 + c];
+                if (u2 < 0.0) atomicOr(&sh.tw32[tid >> 5], 1u << (tid & 31));
+            }
+            __syncthreads();
+            if (tid < n3) {
+                double w2c = 0.0;
+                for (int jr = 0; jr < nr2; ++jr)
+                    w2c += ((sh.tw32[jr >> 5] >> (jr & 31)) & 1u) ? -sh.v[jr * n3 + tid] : sh.v[jr * n3 + tid];
+                sh.w2part[tid] = w2c;
+            }
+            __syncthreads();
+        }
         PS_TICK(3);
-        // ================= hop 2: publish the slice's sign bits and shares, gather everybody's
+        // ================= hop 2: publish the slice's sign bits and scalars, gather everybody's
         {
             uint64_t* mine = a.xq + ((size_t)(seq & 1u) * G + g) * kPsSlot2;
             if (tid < tw) ps_store_tagged(mine + tid, sh.tw32[tid], seq);
-            if (tid == 64) {
-                double cq[kPsWaves], cshare = 0.0;
+            if (!tensor) {
+                if (tid == 64) {
+                    double cq[kPsWaves], cshare = 0.0;
 #pragma unroll
-                for (int q = 0; q < kPsWaves; ++q) cq[q] = sh.red[0][q];
+                    for (int q = 0; q < kPsWaves; ++q) cq[q] = sh.red[0][q];
 #pragma unroll
-                for (int q = 0; q < kPsWaves; ++q) cshare += cq[q];
-                const uint64_t b = (uint64_t)__double_as_longlong(cshare);
-                ps_store_tagged(mine + tw, (uint32_t)b, seq);
-                ps_store_tagged(mine + tw + 1, (uint32_t)(b >> 32), seq);
+                    for (int q = 0; q < kPsWaves; ++q) cshare += cq[q];
+                    const uint64_t b = (uint64_t)__double_as_longlong(cshare);
+                    ps_store_tagged(mine + tw, (uint32_t)b, seq);
+                    ps_store_tagged(mine + tw + 1, (uint32_t)(b >> 32), seq);
+                }
+            } else if (tid >= 64 && tid < 64 + n3) {
+                const uint64_t b = (uint64_t)__double_as_longlong(sh.w2part[tid - 64]);
+                ps_store_tagged(mine + tw + 2 * (tid - 64), (uint32_t)b, seq);
+                ps_store_tagged(mine + tw + 2 * (tid - 64) + 1, (uint32_t)(b >> 32), seq);
             }
             if (with_norm && tid == 128) {
                 double f = 0.0;
 #pragma unroll
                 for (int q = 0; q < kPsWaves; ++q) f += sh.red[1][q];
                 const uint64_t b = (uint64_t)__double_as_longlong(f);
-                ps_store_tagged(mine + tw + 2, (uint32_t)b, seq);
-                ps_store_tagged(mine + tw + 3, (uint32_t)(b >> 32), seq);
+                ps_store_tagged(mine + tw + nsc, (uint32_t)b, seq);
+                ps_store_tagged(mine + tw + nsc + 1, (uint32_t)(b >> 32), seq);
             }
         }
         for (int d = 0; d < a.poll_delay; ++d) __builtin_amdgcn_s_sleep(1);
         {
-            const int per = tw + (with_norm ? 4 : 2);
+            const int per = tw + nsc + (with_norm ? 2 : 0);
             const int items = G * per;
             int where[kPsMaxItems2];  // member * kPsSlot2 + word, or -1
 #pragma unroll
@@ -582,7 +687,9 @@ __global__ void __launch_bounds__(kPsThreads) pstream_kernel(PStreamArgs a)
             }
             spins += spin;
             if (ok) {
-                uint8_t* tbytes = (uint8_t*)t_pos;
+                // sign bits: the columns' t (matrix) or the rows' s^(2) (order 3), member after member
+                uint8_t* tbytes = tensor ? (uint8_t*)s2_cur : (uint8_t*)t_cur;
+                const int nbytes = tensor ? w2 * 8 : nw * 8;
 #pragma unroll
                 for (int it = 0; it < kPsMaxItems2; ++it) {
                     if (where[it] >= 0) {
@@ -592,7 +699,7 @@ __global__ void __launch_bounds__(kPsThreads) pstream_kernel(PStreamArgs a)
                             const int b0 = mem * sbytes + 4 * wd;
 #pragma unroll
                             for (int b = 0; b < 4; ++b)
-                                if (4 * wd + b < sbytes && b0 + b < NPOS / 8) tbytes[b0 + b] = (uint8_t)(v >> (8 * b));
+                                if (4 * wd + b < sbytes && b0 + b < nbytes) tbytes[b0 + b] = (uint8_t)(v >> (8 * b));
                         } else {
                             sh.scal[wd - tw][mem] = v;
                         }
@@ -605,46 +712,40 @@ __global__ void __launch_bounds__(kPsThreads) pstream_kernel(PStreamArgs a)
             return;
         }
         PS_TICK(4);
-        // c = sum of the shares, the same order in every workgroup (member t in lane order, then the waves)
-        double c_tot, f_tot = 0.0;
-        {
-            double cv = 0.0, fv = 0.0;
-            if (tid < G) {
-                cv = __longlong_as_double((long long)(((uint64_t)sh.scal[1][tid] << 32) | sh.scal[0][tid]));
-                if (with_norm) fv = __longlong_as_double((long long)(((uint64_t)sh.scal[3][tid] << 32) | sh.scal[2][tid]));
+        // the scalars: sums of the members' shares, the same order in every workgroup
+        double c_tot = 0.0, f_tot = 0.0;
+        auto share = [&](int slot) {
+            return tid < G ? __longlong_as_double((long long)(((uint64_t)sh.scal[2 * slot + 1][tid] << 32) | sh.scal[2 * slot][tid]))
+                           : 0.0;
+        };
+        if (!tensor) {
+            c_tot = ps_sum_members(share(0), sh, 0);
+        } else {
+            // last mode: s^(3)_c = sgn(W_2[c]); the cut value is <s, a> = sum_c |W_2[c]| (Algorithm 12 line 10)
+            uint64_t s3n = 0;
+            for (int c = 0; c < n3; ++c) {
+                const double w2c = ps_sum_members(share(c), sh, 0);
+                __syncthreads();  // sh.red[0] is reused by the next sum
+                if (w2c < 0.0) s3n |= 1ull << c;
+                c_tot += fabs(w2c);
             }
-            if (wv < kSpGrid / 64) {
-                cv = ps_wave_sum(cv);
-                if (with_norm) fv = ps_wave_sum(fv);
-                if (lane == 0) {
-                    sh.red[0][wv] = cv;
-                    sh.red[1][wv] = fv;
-                }
-            }
-            __syncthreads();
-            c_tot = 0.0;
-#pragma unroll
-            for (int q = 0; q < kSpGrid / 64; ++q) c_tot += sh.red[0][q];
-            if (with_norm)
-#pragma unroll
-                for (int q = 0; q < kSpGrid / 64; ++q) f_tot += sh.red[1][q];
+            s3_cur = s3n;
+            ps_kron_bits(t_cur, n, n3, s2_cur, s3_cur);
         }
+        if (with_norm) f_tot = ps_sum_members(share(nsc / 2), sh, 1);
         if (with_norm && g == 0 && tid == 0) a.trace[k] = sqrt(f_tot);
         if (final_pass) break;
         ++j;
-        // this thread's bits of t_j (row sums of the next pass, or the update): value q of thread t sits at
-        // position q * 512 + t, i.e. bit `lane` of word q * 8 + wave
-        bcur = 0;
-#pragma unroll
-        for (int q = 0; q < NE; ++q) bcur |= ((t_pos[q * kPsWaves + wv] >> lane) & 1ull) << q;
-        const bool conv = (c_tot <= c_prev) || (j >= a.max_iters);  // Algorithm 4 line 8
+        __syncthreads();  // (order 3: t_cur was just rebuilt)
+        bcur = ps_gather_bits<TE, CPT>(t_cur, nch);  // this thread's bits of t_j: row sums of the next pass, or the update
+        const bool conv = (c_tot <= c_prev) || (j >= a.max_iters);  // Algorithm 4 line 8 / Algorithm 12 line 11
         if (conv) {
-            // the term is (c, s_j, t_j): append it (Algorithm 5 lines 7-9); the next pass subtracts it (line 10)
+            // the term is complete: append it (Algorithm 5 lines 7-9); the next pass subtracts it (line 10)
             if (!(c_tot <= c_prev)) warn = 1;
             const double ckd = c_tot / total;
             ck = (TE)ckd;
             {
-                // own rows' bits of s_k: the rows of a workgroup need not start at a word boundary
+                // own rows' bits of the first mode: the rows of a workgroup need not start at a word boundary
                 const uint8_t* sc = sp ? sbuf1 : sbuf0;
                 unsigned long long* Sk = (unsigned long long*)(a.S + k * a.mw);
                 for (int i0 = wv * 64; i0 < nrows; i0 += kPsThreads) {
@@ -659,21 +760,11 @@ __global__ void __launch_bounds__(kPsThreads) pstream_kernel(PStreamArgs a)
                 }
             }
             if (g == 0) {
-                // T_k in column order: every thread puts the bits of its own chunks in place
-                uint32_t* tn32 = (uint32_t*)t_nat;
-#pragma unroll
-                for (int c = 0; c < CPT; ++c) {
-                    const int64_t ch = tid + c * kPsThreads;
-                    const uint32_t nib = (uint32_t)((bcur >> (c * VE)) & ((1ull << VE) - 1));
-                    if (ch < nch && nib) {
-                        const int64_t col = ch * VE;  // VE divides 32: a chunk never straddles a word
-                        atomicOr(tn32 + (col >> 5), nib << (col & 31));
-                    }
-                }
-                __syncthreads();
-                for (int p = tid; p < nw; p += kPsThreads) {
-                    a.T[k * nw + p] = t_nat[p];
-                    t_nat[p] = 0;
+                if (!tensor) {
+                    for (int p = tid; p < nw; p += kPsThreads) a.T[k * nw + p] = t_cur[p];
+                } else {
+                    for (int p = tid; p < w2; p += kPsThreads) a.T[k * w2 + p] = s2_cur[p];
+                    if (tid == 0) a.S3[k] = s3_cur;
                 }
                 if (tid == 0) {
                     ((TE*)a.c)[k] = ck;
@@ -686,15 +777,23 @@ __global__ void __launch_bounds__(kPsThreads) pstream_kernel(PStreamArgs a)
             c_prev = -INFINITY;
             mode = 1;
             final_pass = k >= a.w_target;
-            for (int p = tid; p < nw; p += kPsThreads) t_rng[p] = rng_word_masked(a.seed, (uint64_t)k, 1u, p, n);
+            __syncthreads();  // t_cur / s2_cur were read above
+            // the random start of the coming term
+            if (tensor) {
+                for (int p = tid; p < w2; p += kPsThreads) s2_cur[p] = rng_word_masked(a.seed, (uint64_t)k, 1u, p, a.n2);
+                s3_cur = rng_word_masked(a.seed, (uint64_t)k, 2u, 0, n3);
+                __syncthreads();
+                ps_kron_bits(t_rng, n, n3, s2_cur, s3_cur);
+            } else {
+                for (int p = tid; p < nw; p += kPsThreads) t_rng[p] = rng_word_masked(a.seed, (uint64_t)k, 1u, p, n);
+            }
             __syncthreads();
             brng = ps_gather_bits<TE, CPT>(t_rng, nch);
         } else {
             c_prev = c_tot;
             mode = 0;
         }
-        // what this iteration read from LDS (t_pos, t_rng, the scalars) is next written after the barriers of the
-        // coming pass and hops
+        // what this iteration read from LDS is next written after the barriers of the coming pass and hops
         __syncthreads();
         PS_TICK(5);
     }
@@ -714,7 +813,7 @@ __global__ void __launch_bounds__(kPsThreads) pstream_kernel(PStreamArgs a)
         a.res->seq_u = seq;
         a.res->warn = warn;
         a.res->spins = spins;
-        for (int i = 0; i < 6; ++i) a.res->ticks[i] = ticks[i];
+        for (int i = 0; i < 6; ++i) a.res->ticks[i] = sh.ticks[i];
     }
 }
 
@@ -768,33 +867,36 @@ int ps_cpt(int64_t nch)
     return 0;
 }
 
-size_t ps_fixed_lds(int64_t n, int npos, int rpw)
+size_t ps_fixed_lds(int64_t n, size_t es, int64_t n2, int rpw)
 {
-    const size_t nw = (size_t)((n + 63) / 64);
-    return (size_t)npos / 8 + 2 * nw * 8 + 2 * (((size_t)rpw + 15) & ~(size_t)15) + sizeof(PsShared) + 64;
+    const size_t nw = (size_t)((n + 63) / 64), w2 = (size_t)((n2 + 63) / 64);
+    return (((size_t)n * es + 15) & ~(size_t)15) + 2 * nw * 8 + w2 * 8 + 2 * (((size_t)rpw + 15) & ~(size_t)15) +
+           sizeof(PsShared) + 64;
 }
 
 }  // namespace
 
-// Geometry of a launch on `limit` workgroups, or false when the engine does not take the shape: matrices whose
-// rows are a multiple of 16 bytes and at most 64 KB long, on enough workgroups for slices of at most 256 positions.
+// Geometry of a launch on `limit` workgroups, or false when the engine does not take the shape.  Matrices, and
+// order-3 tensors with a last mode of at most 4 (seen as n_1 x (n_2 n_3)), whose rows are a multiple of 16 bytes
+// and at most 64 KB long, on enough workgroups for slices of at most 256 columns.
 bool pstream_supported(scd_dtype dt, int order, const int64_t* dims, int limit, PStreamGeometry* geo)
 {
-    if (order != 2 || limit < 1) return false;
-    const int64_t m = dims[0], n = dims[1];
+    if ((order != 2 && order != 3) || limit < 1) return false;
+    const int64_t m = dims[0], n = order == 2 ? dims[1] : dims[1] * dims[2];
+    const int64_t n3 = order == 3 ? dims[2] : 0, n2 = order == 3 ? dims[1] : 0;
+    if (order == 3 && (n3 < 1 || n3 > kPsMaxLast || n2 < 1)) return false;
     const int ve = dt == SCD_F32 ? 4 : 2;
     const size_t es = dt == SCD_F32 ? 4 : 8;
-    if (m < 1 || n < ve || (n % ve) || m > (1ll << 30)) return false;
-    const int cpt = ps_cpt(n / ve);
-    if (cpt == 0) return false;
-    const int npos = cpt * ve * kPsThreads;
+    if (m < 1 || n < ve || (n % ve) || m > (1ll << 30) || n > (1 << 20)) return false;
+    if (ps_cpt(n / ve) == 0) return false;
     if (limit > kSpGrid) limit = kSpGrid;
     const int64_t rpw = (m + limit - 1) / limit;
     const int64_t grid = (m + rpw - 1) / rpw;
-    int64_t cs = (npos + grid - 1) / grid;
-    cs = (cs + 7) / 8 * 8;
+    const int64_t unit = order == 3 ? 8 * n3 : 8;  // slices hold whole bytes of sign bits (of whole rows of W_1)
+    int64_t cs = (n + grid - 1) / grid;
+    cs = (cs + unit - 1) / unit * unit;
     if (cs > kPsMaxSlice || rpw > (1 << 20)) return false;
-    const size_t fixed = ps_fixed_lds(n, npos, (int)rpw);
+    const size_t fixed = ps_fixed_lds(n, es, n2, (int)rpw);
     if (fixed > kPsMaxLds) return false;
     int64_t lds_rows = (int64_t)((kPsMaxLds - fixed) / ((size_t)n * es));
     if (lds_rows > rpw) lds_rows = rpw;
@@ -804,7 +906,7 @@ bool pstream_supported(scd_dtype dt, int order, const int64_t* dims, int limit, 
         geo->cs = (int)cs;
         geo->lds_rows = (int)lds_rows;
         geo->lds_bytes = ((((size_t)lds_rows * (size_t)n * es) + 15) & ~(size_t)15) + fixed;
-        geo->xp_bytes = (size_t)2 * (size_t)grid * (size_t)npos * (dt == SCD_F32 ? 1 : 2) * 8;
+        geo->xp_bytes = (size_t)2 * (size_t)grid * (size_t)n * (dt == SCD_F32 ? 1 : 2) * 8;
         geo->xq_bytes = (size_t)2 * (size_t)grid * kPsSlot2 * 8;
     }
     return true;

@@ -27,7 +27,7 @@ EXPORTS = [
     "scd_expand", "scd_pack", "scd_unpack", "scd_rng_signs", "scd_strerror", "scd_last_hip_error", "scd_traffic",
     "scd_probe_stream", "scd_profile_sweeps", "scd_probe_exchange", "scd_engine", "scd_set_workgroups",
     "scd_apply", "scd_apply_workspace_bytes", "scd_lsq_decompose", "scd_lsq_decompose_tensor", "scd_decompose_scalars", "scd_sparse_flips",
-    "scd_col_signed_sum_noalloc", "scd_set_option", "scd_get_option",
+    "scd_col_signed_sum_noalloc", "scd_set_option", "scd_get_option", "scd_stream_geometry",
 ]
 
 # scd_option of include/scd.h
@@ -61,6 +61,7 @@ def lib() -> C.CDLL:
         L.scd_destroy.restype = None
         L.scd_set_max_iters.argtypes = [vp, i32]
         L.scd_set_workgroups.argtypes = [vp, C.c_int]
+        L.scd_stream_geometry.argtypes = [C.c_int, C.c_int, pi64, C.c_int, pi64]
         L.scd_set_option.argtypes = [vp, C.c_int, i64]
         L.scd_get_option.argtypes = [vp, C.c_int, pi64]
         L.scd_sparse_flips.argtypes = [vp, pi64, pi64]
@@ -301,6 +302,17 @@ def scd_col_signed_sum_noalloc(R: torch.Tensor, sbits: torch.Tensor, v: torch.Te
     st = lib().scd_col_signed_sum_noalloc(_ptr(R), _dt(R), m, n, _ptr(_dev(sbits, "sbits")), _stream(), _ptr(v), _ptr(t),
                                           _ptr(c))
     _check(st, "scd_col_signed_sum_noalloc")
+
+
+def scd_stream_geometry(dtype, dims: Sequence[int], limit: int = 256) -> Optional[dict]:
+    """Launch geometry of the persistent streaming engine for this dtype and shape (host arithmetic only), or None
+    when the engine does not take the shape."""
+    out = (C.c_int64 * 8)()
+    dt = F32 if dtype == torch.float32 else F64
+    _check(lib().scd_stream_geometry(dt, len(dims), _dims(dims), int(limit), out), "scd_stream_geometry")
+    if not out[0]:
+        return None
+    return dict(grid=out[1], rpw=out[2], cs=out[3], lds_rows=out[4], lds_bytes=out[5], xp_bytes=out[6], xq_bytes=out[7])
 
 
 def scd_probe_stream(src: torch.Tensor, dst: Optional[torch.Tensor] = None, grid: int = 2048, reps: int = 20) -> float:

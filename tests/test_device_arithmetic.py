@@ -39,3 +39,54 @@ def test_halving_butterfly_leaves_sum_i_in_lane_pair_i():
     total = vals.sum(axis=0)
     for lane in range(64):
         assert vv[lane][0] + vv[lane ^ 1][0] == total[lane >> 1]
+
+
+def test_stream_engine_geometry_stays_inside_what_the_kernel_assumes():
+    """Host model of the persistent streaming kernel's index arithmetic: for every shape the engine accepts, each
+    workgroup owns at least one row, the slices of the first exchange cover all columns in whole bytes of sign
+    bits (whole rows of the contracted array for order 3), slots and LDS hold what is indexed, and a thread never
+    has more words to gather than its registers are declared for."""
+    import torch
+
+    from paper_2410_01799_amd import scd
+
+    scd.lib()
+    threads, max_slice, slot2, max_items2, max_lds = 512, 256, 16, 6, 150 * 1024
+    shapes = [(256, 256), (100, 76), (8, 8), (77, 1024), (1000, 4096), (2052, 516), (1030, 520), (130, 8200), (16, 64),
+              (8, 4), (4096, 4096), (700, 16384), (512, 512), (14336, 4096), (4096, 14336), (32000, 4096), (1, 4), (3, 64),
+              (65, 130), (300, 8192), (2048, 2048), (4000, 3000, 3), (40, 30, 3), (130, 64, 4), (300, 200, 3), (50, 40, 2),
+              (64, 33, 1), (9, 8, 7), (20, 30, 5)]
+    seen = 0
+    for dtype, es, ve in ((torch.float32, 4, 4), (torch.float64, 8, 2)):
+        for dims in shapes:
+            for limit in (256, 85, 64, 16):
+                geo = scd.scd_stream_geometry(dtype, dims, limit)
+                m = dims[0]
+                n = dims[1] if len(dims) == 2 else dims[1] * dims[2]
+                n3 = dims[2] if len(dims) == 3 else 0
+                if geo is None:
+                    continue
+                seen += 1
+                G, rpw, cs, lds_rows = geo["grid"], geo["rpw"], geo["cs"], geo["lds_rows"]
+                assert 1 <= G <= min(limit, 256) and rpw >= 1
+                assert (G - 1) * rpw < m <= G * rpw, (dims, limit)         # the last workgroup has a row, all rows are owned
+                assert n % ve == 0 and (n // ve + threads - 1) // threads <= 8   # chunks per thread the kernel is built for
+                assert cs % 8 == 0 and 8 <= cs <= max_slice and G * cs >= n      # slices cover the columns
+                assert threads // cs >= 1
+                unit = n3 if n3 else 1
+                assert n3 <= 4 and cs % (8 * unit) == 0                          # whole bytes of sign bits per slice
+                tw = (cs // unit + 31) // 32
+                per = tw + (2 * n3 if n3 else 2) + 2
+                assert per <= slot2 and (G * per + threads - 1) // threads <= max_items2
+                nw, w2 = (n + 63) // 64, ((dims[1] + 63) // 64 if n3 else 0)
+                bits = dims[1] if n3 else n
+                assert G * (cs // unit // 8) >= (bits + 7) // 8            # the slices' sign bytes cover the whole vector
+                assert 0 <= lds_rows <= rpw
+                need = -(-lds_rows * n * es // 16) * 16 + -(-n * es // 16) * 16 + 2 * nw * 8 + w2 * 8 + 2 * (-(-rpw // 16) * 16)
+                assert need < geo["lds_bytes"] <= max_lds + 64, (dims, limit)
+                assert geo["xp_bytes"] == 2 * G * n * (1 if es == 4 else 2) * 8 and geo["xq_bytes"] == 2 * G * slot2 * 8
+    assert seen > 60
+    # shapes it must refuse: rows that are no multiple of 16 bytes or longer than 64 KB, too few workgroups for the
+    # slices, orders above 3, a last mode above 4
+    for dims in [(100, 77), (64, 16388), (64, 20000), (3, 4096), (9, 8, 7, 6), (20, 30, 5)]:
+        assert scd.scd_stream_geometry(torch.float32, dims, 256) is None, dims

@@ -5,7 +5,7 @@ import numpy as np
 import pytest
 import torch
 
-from helpers import C_RTOL, CURVE_RTOL, ID_RTOL, to_np_bits
+from helpers import C_RTOL, CURVE_RTOL, ID_RTOL, dense, match_tensor_term, to_np_bits
 from test_gpu_parity import lockstep_check
 
 pytestmark = pytest.mark.gpu
@@ -139,3 +139,58 @@ def test_stream_and_launch_stream_engines_agree(scd):
     if torch.equal(a["signs"][0], b["signs"][0]) and torch.equal(a["signs"][1], b["signs"][1]):
         np.testing.assert_allclose(a["c"].cpu().numpy(), b["c"].cpu().numpy(), rtol=C_RTOL)
         assert torch.equal(a["iters"], b["iters"])
+
+
+# ---- order-3 tensors (Algorithms 12 and 13) on the same engine
+
+
+def kron_dense(sign_rows, shape):
+    out = np.array([1.0])
+    for b, d in zip(sign_rows, shape):
+        out = np.multiply.outer(out, dense(b, d))
+    return out.reshape(shape)
+
+
+@pytest.mark.parametrize("shape,w,dtype", [((64, 40, 3), 16, np.float32), ((40, 30, 3), 16, np.float64),
+                                           ((130, 64, 4), 12, np.float32), ((300, 200, 3), 8, np.float32),
+                                           ((50, 44, 2), 10, np.float32), ((33, 16, 1), 8, np.float32),
+                                           ((700, 1000, 3), 5, np.float32), ((90, 130, 3), 8, np.float64)])
+def test_stream_tensor_matches_oracle(scd, oracle, shape, w, dtype):
+    seed = 4
+    a = gauss(shape, int(np.prod(shape)), dtype)
+    a64 = a.astype(np.float64)
+    N = a.size
+    ad = torch.from_numpy(a).cuda()
+    with scd.ScdContext(ad, w, seed, options=OPTS) as ctx:
+        assert ctx.engine()["engine"] == 3
+        ctx.run(w // 2)
+        ctx.run(w - w // 2)
+        res = ctx.results()
+        R = ctx.remainder()
+    signs = [to_np_bits(s) for s in res["signs"]]
+    c = res["c"].cpu().numpy().astype(np.float64)
+    trace = res["trace"].cpu().numpy()
+    iters = res["iters"].cpu().numpy()
+    f32 = dtype == np.float32
+    np.testing.assert_allclose(trace[1:] ** 2, trace[:-1] ** 2 - N * c ** 2, rtol=ID_RTOL)
+    r = a64.copy()
+    for k in range(w):
+        s0 = [oracle.rng_signs(seed, k, i, d) for i, d in enumerate(shape)]
+        mine = [sg[k] for sg in signs]
+        flips, g = match_tensor_term(oracle, r, s0, mine, iters[k], f32, f"term {k}")
+        if flips == 0:
+            assert c[k] == pytest.approx(g["c"] / N, rel=C_RTOL)
+        ck = (r * kron_dense(mine, shape)).sum() / N
+        assert c[k] == pytest.approx(ck, rel=C_RTOL)
+        oracle.tensor_update(r, ck, mine)
+        assert trace[k + 1] == pytest.approx(np.linalg.norm(r), rel=2e-5 if f32 else 1e-11)
+        for i, d in enumerate(shape):
+            if d % 64:
+                assert int(mine[i][-1]) >> (d % 64) == 0, "padding bits"
+    E = scd.scd_expand(res["signs"], res["c"], shape)
+    assert float((ad - E - R).abs().max()) <= (2e-6 if f32 else 1e-13) * float(ad.abs().max())
+    assert float(R.double().norm()) == pytest.approx(trace[-1], rel=1e-6 if f32 else 1e-12)
+    # the launch-per-sweep engine on the same input: the same curve, the same terms unless a near tie split them
+    other = scd.scd_decompose(ad, w, seed, options={**OPTS, "persistent_stream": 0})
+    to = other["trace"].cpu().numpy()
+    np.testing.assert_allclose(trace / trace[0], to / to[0], rtol=CURVE_RTOL)
