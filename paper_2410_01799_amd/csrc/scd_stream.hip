@@ -36,7 +36,7 @@ constexpr int kPsMaxSlice = 256;   // most positions per slice of hop 1
 constexpr int kPsSlot2 = 16;       // words of a hop-2 slot: up to 8 sign words, c and ||.||^2 as two halves each
 constexpr int kPsMaxLast = 4;      // order 3: largest last mode (colour channels)
 constexpr int kPsMaxItems2 = 6;    // hop-2 words a thread gathers: at most 256 * 12 / 512
-constexpr size_t kPsMaxLds = 150 * 1024;  // dynamic LDS a launch may ask for
+constexpr size_t kPsMaxLds = 160 * 1024 - 512;  // dynamic LDS a launch may ask for (the compute unit has 160 KB)
 
 template <typename TE>
 struct PsVec;
@@ -137,11 +137,16 @@ __device__ __forceinline__ uint64_t ps_load(const uint64_t* p)
 
 struct PsShared {
     double u[2][8][kPsWaves];      // row sums of a batch [row][wave] (two parities: one barrier per batch)
-    double part[kPsThreads];       // hop 1: partial sums per (member group, position)
+    union {
+        // the two exchanges use this space one after the other (barriers in between)
+        struct {
+            double part[kPsThreads];   // hop 1: partial sums per (member group, column)
+            double v[kPsMaxSlice];     // order 3: the own slice of W_1
+        };
+        uint32_t scal[2 * kPsMaxLast + 2][kSpGrid];  // hop 2: low/high halves of the members' scalars
+    };
     double red[2][kPsWaves];
-    uint32_t scal[2 * kPsMaxLast + 2][kSpGrid];  // hop 2: low/high halves of the members' scalars
     uint32_t tw32[8];              // sign words of the own slice
-    double v[kPsMaxSlice];         // order 3: the own slice of W_1
     double w2part[kPsMaxLast];     // order 3: the own slice's part of the last mode's sums
     int64_t ticks[6];              // profile mode
     uint64_t tick0;
@@ -317,30 +322,24 @@ __device__ __forceinline__ void ps_pass(int mode, TE* lds_rows, int nl, TE* grow
     TE sf[NE];  // the signs of this thread's columns as factors +-1.0
 #pragma unroll
     for (int e = 0; e < NE; ++e) sf[e] = ((sumb >> e) & 1ull) ? (TE)-1 : (TE)1;
-    // streamed rows: `first` holds their first batch already; the second one is asked for now, so that it arrives
-    // while the rows kept in LDS are worked on
     PsTile<TE, CPT, RB> tb;
     const int nb = (ng + RB - 1) / RB;
-    // (a load that is not wanted still reads 16 bytes at its base: `gsafe` is a row of the block in every case,
-    // whereas `grows` is one past the end of the matrix for the last workgroup when nothing is streamed)
-    ps_tile_load<TE, CPT, RB>(tb, nb > 1 ? grows : gsafe, cols, RB, ng > 0 ? ng : 1, nch, nb > 1);
-    {
-        PsTile<TE, CPT, RB> tl;
+    (void)gsafe;
+    // (the rows kept in LDS go through the second tile: it is free until the streamed rows start)
 #pragma nounroll
-        for (int rb = 0; rb < nl; rb += RB) {
-            ps_tile_load<TE, CPT, RB>(tl, lds_rows, cols, rb, nl, nch, true);
-            if (mode == 1) tl.rowsign = ps_rowsigns(s_old, rb, nl);
-            ps_process<TE, CPT, RB>(tl, lds_rows, cols, rb, nl, nch, mode, full_cols && rb + RB <= nl, sf, updb, ck, acc, fsq,
-                                    s_new, sh, parity);
-            parity ^= 1;
-        }
+    for (int rb = 0; rb < nl; rb += RB) {
+        ps_tile_load<TE, CPT, RB>(tb, lds_rows, cols, rb, nl, nch, true);
+        if (mode == 1) tb.rowsign = ps_rowsigns(s_old, rb, nl);
+        ps_process<TE, CPT, RB>(tb, lds_rows, cols, rb, nl, nch, mode, full_cols && rb + RB <= nl, sf, updb, ck, acc, fsq, s_new,
+                                sh, parity);
+        parity ^= 1;
     }
     // two register tiles alternate, the loads of the next batch are in flight while this one is reduced; every
     // load inside the loop is unconditional
 #pragma nounroll
     for (int b = 0; b < nb; b += 2) {
         const int rb = b * RB;
-        if (b > 0) ps_tile_load<TE, CPT, RB>(tb, grows, cols, rb + RB, ng, nch, b + 1 < nb);
+        ps_tile_load<TE, CPT, RB>(tb, grows, cols, rb + RB, ng, nch, b + 1 < nb);
         if (mode == 1) first.rowsign = ps_rowsigns(s_old + nl, rb, ng);
         ps_process<TE, CPT, RB>(first, grows, cols, rb, ng, nch, mode, full_cols && rb + RB <= ng, sf, updb, ck, acc, fsq,
                                 s_new + nl, sh, parity);
@@ -821,7 +820,9 @@ template <typename TE, int CPT>
 hipError_t ps_launch_rb(const PStreamArgs& a, size_t lds_bytes, hipStream_t st)
 {
     constexpr int VE = PsVec<TE>::N;
-    // rows per register tile: about 32 registers per tile (three tiles are live around the LDS / streamed boundary)
+    // rows per register tile: at most 32 registers per tile (two tiles are live; more rows per batch would
+    // mean fewer joins across the waves, but with 48 registers per tile the register allocator spills 64-bit
+    // values to odd register pairs, which this compiler then rejects)
     constexpr int kRegsPerRow = CPT * VE * (int)sizeof(TE) / 4;
     constexpr int RB = kRegsPerRow > 16 ? 1 : (kRegsPerRow > 8 ? 2 : (kRegsPerRow > 4 ? 4 : 8));
     auto kern = pstream_kernel<TE, CPT, RB>;

@@ -51,7 +51,7 @@ def test_stream_engine_geometry_stays_inside_what_the_kernel_assumes():
     from paper_2410_01799_amd import scd
 
     scd.lib()
-    threads, max_slice, slot2, max_items2, max_lds = 512, 256, 16, 6, 150 * 1024
+    threads, max_slice, slot2, max_items2, max_lds = 512, 256, 16, 6, 160 * 1024 - 512
     shapes = [(256, 256), (100, 76), (8, 8), (77, 1024), (1000, 4096), (2052, 516), (1030, 520), (130, 8200), (16, 64),
               (8, 4), (4096, 4096), (700, 16384), (512, 512), (14336, 4096), (4096, 14336), (32000, 4096), (1, 4), (3, 64),
               (65, 130), (300, 8192), (2048, 2048), (4000, 3000, 3), (40, 30, 3), (130, 64, 4), (300, 200, 3), (50, 40, 2),
