@@ -306,15 +306,19 @@ __global__ void __launch_bounds__(kResThreads) resident_kernel(ResidentArgs a)
     __shared__ double lds_red[kResThreads / 64];
     __shared__ double lds_x[2][P];
 
-    // ---- load the block
+    // ---- load the block.  The grid may overhang the matrix: rows and columns past its end are zeros in the
+    // registers (they add nothing to any sum and stay zero through every update) and are never read or written.
+    const int64_t row0 = (int64_t)pr * BM + tr * TR, col0 = (int64_t)pc * BN + tc * TC;
+    const bool padded = (int64_t)P * BM != a.m || (int64_t)P * BN != a.n;  // the same in every workgroup
     float x[TR][TC];
     {
-        const float* base = a.R + ((int64_t)pr * BM + tr * TR) * a.n + (int64_t)pc * BN + tc * TC;
+        const float* base = a.R + row0 * a.n + col0;
 #pragma unroll
         for (int r = 0; r < TR; ++r)
 #pragma unroll
             for (int c4 = 0; c4 < TC / 4; ++c4) {
-                const float4 v = *(const float4*)(base + (int64_t)r * a.n + 4 * c4);
+                float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (!padded || (row0 + r < a.m && col0 + 4 * c4 < a.n)) v = *(const float4*)(base + (int64_t)r * a.n + 4 * c4);
                 x[r][4 * c4 + 0] = v.x;
                 x[r][4 * c4 + 1] = v.y;
                 x[r][4 * c4 + 2] = v.z;
@@ -342,7 +346,7 @@ __global__ void __launch_bounds__(kResThreads) resident_kernel(ResidentArgs a)
             // t_0 of term k from the keyed stream (Algorithm 4 line 2)
             if (tid < BN) {
                 const int64_t col = (int64_t)pc * BN + tid;
-                lds_t[tid] = (uint8_t)((rng_word(a.seed, (uint64_t)k, 1u, (uint64_t)(col >> 6)) >> (col & 63)) & 1ull);
+                lds_t[tid] = col < a.n ? (uint8_t)((rng_word(a.seed, (uint64_t)k, 1u, (uint64_t)(col >> 6)) >> (col & 63)) & 1ull) : 0;
             }
             need_t0 = false;
             __syncthreads();
@@ -443,11 +447,11 @@ __global__ void __launch_bounds__(kResThreads) resident_kernel(ResidentArgs a)
                 const float ckf = (float)ck;
                 if (pc == 0 && wv < BM / 64) {
                     const uint64_t word = __ballot(lds_s[cur][wv * 64 + lane] != 0);
-                    if (lane == 0) a.S[k * a.mw + pr * (BM / 64) + wv] = word;
+                    if (lane == 0 && pr * (BM / 64) + wv < a.mw) a.S[k * a.mw + pr * (BM / 64) + wv] = word;
                 }
                 if (pr == 0 && wv < BN / 64) {
                     const uint64_t word = __ballot(lds_t[wv * 64 + lane] != 0);
-                    if (lane == 0) a.T[k * a.nw + pc * (BN / 64) + wv] = word;
+                    if (lane == 0 && pc * (BN / 64) + wv < a.nw) a.T[k * a.nw + pc * (BN / 64) + wv] = word;
                 }
                 if (wg == 0 && tid == 0) {
                     a.c[k] = ckf;
@@ -461,7 +465,7 @@ __global__ void __launch_bounds__(kResThreads) resident_kernel(ResidentArgs a)
                     for (int c = 0; c < TC; ++c) {
                         // R_il - ck s_i t_l: the signs choose +ck or -ck
                         const float d = __uint_as_float(__float_as_uint(ckf) ^ sr ^ (__float_as_uint(tf[c]) & 0x80000000u));
-                        x[r][c] = x[r][c] - d;
+                        x[r][c] = (!padded || (row0 + r < a.m && col0 + c < a.n)) ? x[r][c] - d : 0.f;  // padding stays zero
                         f += (double)x[r][c] * (double)x[r][c];
                     }
                 }
@@ -581,13 +585,14 @@ __global__ void __launch_bounds__(kResThreads) resident_kernel(ResidentArgs a)
 
     // ---- write the block back
     {
-        float* base = a.R + ((int64_t)pr * BM + tr * TR) * a.n + (int64_t)pc * BN + tc * TC;
+        float* base = a.R + row0 * a.n + col0;
 #pragma unroll
         for (int r = 0; r < TR; ++r)
 #pragma unroll
             for (int c4 = 0; c4 < TC / 4; ++c4)
-                *(float4*)(base + (int64_t)r * a.n + 4 * c4) =
-                    make_float4(x[r][4 * c4], x[r][4 * c4 + 1], x[r][4 * c4 + 2], x[r][4 * c4 + 3]);
+                if (!padded || (row0 + r < a.m && col0 + 4 * c4 < a.n))
+                    *(float4*)(base + (int64_t)r * a.n + 4 * c4) =
+                        make_float4(x[r][4 * c4], x[r][4 * c4 + 1], x[r][4 * c4 + 2], x[r][4 * c4 + 3]);
     }
     if (wg == 0 && tid == 0) {
         a.res->k = k;
@@ -600,22 +605,38 @@ __global__ void __launch_bounds__(kResThreads) resident_kernel(ResidentArgs a)
     }
 }
 
-// Grid side and thread tile for a shape the engine is built for: m = P * 32 * TR, n = P * 16 * TC.
+// Grid side P and thread tile TR x TC for an m x n matrix: the P x P workgroups of 32 x 16 threads cover
+// P * 32 * TR rows and P * 16 * TC columns, at least the matrix (the overhang is kept as zeros).  Fewer
+// workgroups mean fewer partners per exchange, more workgroups less arithmetic each; measured on the square
+// sizes (256 and 512 fastest with 8 values per thread on 4 x 4 and 8 x 8 workgroups, 1024 with 32 values on
+// 8 x 8, 2048 with 32 values on 16 x 16), which gives the order of preference: the smallest grid of at most
+// 8 x 8 with at most 8 values per thread, else the smallest grid with at most 32, else the grid that fits with
+// the smallest tile.  Rows must be a multiple of 16 bytes.
 static bool resident_shape(int64_t m, int64_t n, int* p, int* tr, int* tc)
 {
-    static const int table[][5] = {
-        // m, n, P, TR, TC
-        {4096, 4096, 16, 8, 16}, {1024, 4096, 16, 2, 16}, {2048, 2048, 16, 4, 8},
-        {1024, 1024, 8, 4, 8},   {512, 512, 8, 2, 4},     {256, 256, 4, 2, 4},
-    };
-    for (const auto& e : table)
-        if (m == e[0] && n == e[1]) {
-            *p = e[2];
-            *tr = e[3];
-            *tc = e[4];
-            return true;
+    if (m < 1 || n < 4 || (n % 4)) return false;
+    static const int grids[3] = {4, 8, 16};
+    static const int trs[3] = {2, 4, 8}, tcs[3] = {4, 8, 16};
+    int best = -1, bp = 0, btr = 0, btc = 0;
+    for (int pass = 0; pass < 2; ++pass) {
+        for (int P : grids) {
+            int r = 0, c = 0;
+            for (int t : trs)
+                if (!r && (int64_t)P * 32 * t >= m) r = t;
+            for (int t : tcs)
+                if (!c && (int64_t)P * 16 * t >= n) c = t;
+            if (!r || !c) continue;
+            if (P == 4 && r * c > 32) continue;  // (the 4 x 4 grid is built with the small tiles only)
+            if (pass == 0 ? (P <= 8 && r * c <= 8) : (r * c <= 32)) {
+                *p = P, *tr = r, *tc = c;
+                return true;
+            }
+            if (best < 0 || r * c < best) best = r * c, bp = P, btr = r, btc = c;
         }
-    return false;
+    }
+    if (best < 0) return false;
+    *p = bp, *tr = btr, *tc = btc;
+    return true;
 }
 
 bool resident_supported(scd_dtype dt, int order, const int64_t* dims)
@@ -648,16 +669,37 @@ static hipError_t launch_resident_t(const ResidentArgs& a, hipStream_t st)
     return hipGetLastError();
 }
 
+template <int P>
+static hipError_t launch_resident_p(const ResidentArgs& a, int tr, int tc, hipStream_t st)
+{
+    const int key = tr * 100 + tc;
+    switch (key) {
+        case 204: return launch_resident_t<2, 4, P>(a, st);
+        case 208: return launch_resident_t<2, 8, P>(a, st);
+        case 404: return launch_resident_t<4, 4, P>(a, st);
+        case 408: return launch_resident_t<4, 8, P>(a, st);
+        default: break;
+    }
+    if constexpr (P >= 8) {
+        switch (key) {
+            case 216: return launch_resident_t<2, 16, P>(a, st);
+            case 416: return launch_resident_t<4, 16, P>(a, st);
+            case 804: return launch_resident_t<8, 4, P>(a, st);
+            case 808: return launch_resident_t<8, 8, P>(a, st);
+            case 816: return launch_resident_t<8, 16, P>(a, st);
+            default: break;
+        }
+    }
+    return hipErrorInvalidValue;
+}
+
 hipError_t launch_resident(const ResidentArgs& a, hipStream_t st)
 {
     int p = 0, tr = 0, tc = 0;
     if (!resident_shape(a.m, a.n, &p, &tr, &tc)) return hipErrorInvalidValue;
-    if (p == 16 && tr == 8) return launch_resident_t<8, 16, 16>(a, st);
-    if (p == 16 && tr == 2) return launch_resident_t<2, 16, 16>(a, st);
-    if (p == 16 && tr == 4) return launch_resident_t<4, 8, 16>(a, st);
-    if (p == 8 && tr == 4) return launch_resident_t<4, 8, 8>(a, st);
-    if (p == 8 && tr == 2) return launch_resident_t<2, 4, 8>(a, st);
-    return launch_resident_t<2, 4, 4>(a, st);
+    if (p == 16) return launch_resident_p<16>(a, tr, tc, st);
+    if (p == 8) return launch_resident_p<8>(a, tr, tc, st);
+    return launch_resident_p<4>(a, tr, tc, st);
 }
 
 }  // namespace scd
