@@ -12,9 +12,15 @@ from __future__ import annotations
 
 import argparse
 import json
+import os
 import sys
 import time
 from pathlib import Path
+
+# The layer figure runs up to seven decompositions side by side, each a persistent launch on its own stream.
+# Streams that share a hardware queue run one after the other, and HIP's default is four queues per process:
+# ask for eight before the runtime starts (read once, when the first HIP call initialises it).
+os.environ.setdefault("GPU_MAX_HW_QUEUES", "8")
 
 ROOT = Path(__file__).resolve().parent
 if str(ROOT) not in sys.path:
@@ -27,6 +33,7 @@ FP32_VECTOR_PEAK_TFLOPS = 157.3  # MI355X published fp32 vector rate: 256 CUs x 
 # one flop where the published rate counts two per FMA.
 UNPACKED_LANE_OPS_PER_S = 256 * 64 * 2.4e9
 TRAFFIC_FILE = ROOT / "profiles" / "memory_traffic_pmc.txt"
+ENGINES = ["launch-stream", "register-resident", "sparse", "persistent-stream"]
 
 
 def measured_traffic() -> dict:
@@ -61,11 +68,14 @@ def cpu_baseline(A64, seed: int, budget_s: float):
 
 def layer_mode(args, scd, workloads, torch, np) -> dict:
     """Seconds per decoder layer at 50 % of the bf16 size (workload 3): every matrix decomposed to its
-    Table 2 width, all inputs resident in HBM before the timer starts.  With --concurrency K the seven
-    matrices are taken from a queue (largest first) by K host threads, each decomposition on its own
-    stream; the compute units are split evenly among the matrices in flight (64 each with four, all 256 for the
-    last one); the figure is the wall time of the whole layer."""
+    Table 2 width, all inputs resident in HBM before the timer starts.  With --concurrency K up to K of the
+    seven matrices are in flight (largest first), each decomposition on its own stream and host thread, in
+    launches of 512 terms; the compute units are shared out at the start so that the matrices in flight would
+    finish together, and what a finished matrix leaves goes to the one that would finish last (shares.py).
+    The figure is the wall time of the whole layer."""
     import threading
+
+    from paper_2410_01799_amd.shares import ShareBoard
 
     K = args.concurrency
     jobs = []
@@ -74,40 +84,35 @@ def layer_mode(args, scd, workloads, torch, np) -> dict:
                          w=max(1, int(round(wfull * args.layer_fraction)))))
     order = sorted(range(len(jobs)), key=lambda i: -jobs[i]["wfull"] * jobs[i]["shape"][0] * jobs[i]["shape"][1])
     rows, lock, errors = [None] * len(jobs), threading.Lock(), []
-    busy = [0]   # workers that hold a matrix right now
+    board = ShareBoard()
+    info = lambda i: dict(m=jobs[i]["shape"][0], n=jobs[i]["shape"][1], left=jobs[i]["w"], alt=40.0)
+    first, waiting = order[:K], order[K:]
+    board.register({i: info(i) for i in first})
     t_begin = [0.0]
 
-    def fair_share():
-        # the device is split among the matrices in flight: 64 compute units each with four, 128 with two, all of
-        # them for the last one (a context can change its share between launches)
-        with lock:
-            n = max(1, busy[0])
-        sh = 256 // n
-        return 0 if sh >= 256 else sh
-
-    def worker():
+    def worker(i):
         torch.cuda.set_device(0)
         stream = torch.cuda.Stream() if K > 1 else torch.cuda.current_stream()
         with torch.cuda.stream(stream):
-            while True:
-                with lock:
-                    if not order or errors:
-                        return
-                    i = order.pop(0)
-                    busy[0] += 1
+            while i is not None:
                 j = jobs[i]
                 try:
                     t0 = time.perf_counter()
                     with scd.ScdContext(j["A"], j["w"], j["seed"]) as ctx:
-                        step = j["w"] if K == 1 else 1024
-                        share_now = None
+                        step = j["w"] if K == 1 else 512
+                        share_now, shares_used, busy_s = None, [], 0.0
                         for k in range(0, j["w"], step):
                             if K > 1:
-                                want = fair_share()
+                                want = board.share(i)
                                 if want != share_now:
                                     ctx.set_workgroups(want)
                                     share_now = want
-                            ctx.run(min(step, j["w"] - k))
+                                    shares_used.append(want or 256)
+                            done = min(step, j["w"] - k)
+                            ctx.run(done)
+                            busy_s += ctx.engine()["last_launch_seconds"]
+                            if K > 1:
+                                board.progress(i, j["w"] - k - done, ctx.traffic()["passes"] / (k + done))
                         res = ctx.results()
                         eng = ctx.engine()["engine"]
                         stream.synchronize()
@@ -115,39 +120,52 @@ def layer_mode(args, scd, workloads, torch, np) -> dict:
                 except Exception as err:  # noqa: BLE001 - reported by the main thread
                     with lock:
                         errors.append((j["name"], repr(err)))
-                        busy[0] -= 1
+                    board.finish(i)
                     return
-                with lock:
-                    busy[0] -= 1
                 tr = res["trace"].cpu().numpy()
                 it = res["iters"].cpu().numpy()
                 rows[i] = {"matrix": j["name"], "shape": j["shape"], "width": j["wfull"], "terms_run": j["w"],
                            "started_at": round(t0 - t_begin[0], 3), "seconds": round(dt, 3),
+                           "ended_at": round(t0 - t_begin[0] + dt, 3),
                            "terms_per_s": round(j["w"] / dt, 1),
                            "alternations_per_term": round(float(it.mean()), 2),
                            "relative_error": round(float(tr[-1] / tr[0]), 5),
-                           "engine_at_the_end": ["launch-stream", "register-resident", "sparse"][eng]}
+                           "workgroups": shares_used if K > 1 else [256],
+                           "seconds_inside_launches": round(busy_s, 3),
+                           "engine_at_the_end": ENGINES[eng]}
+                with lock:
+                    # the next waiting matrix takes this one's place, before the room is given to the others
+                    nxt = waiting.pop(0) if waiting and not errors else None
+                    if nxt is not None:
+                        board.jobs.pop(i, None)
+                        board.shares.pop(i, None)
+                        if not board.admit(nxt, info(nxt)):
+                            waiting.insert(0, nxt)
+                            nxt = None
+                    board.finish(i)
+                i = nxt
 
     torch.cuda.synchronize()
     t_begin[0] = time.perf_counter()
     if K == 1:
-        worker()
+        for i in order:
+            worker(i)
     else:
-        threads = [threading.Thread(target=worker) for _ in range(K)]
+        threads = [threading.Thread(target=worker, args=(i,)) for i in first]
         for t in threads:
             t.start()
         for t in threads:
             t.join()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t_begin[0]
-    if errors:
-        raise RuntimeError(f"layer run failed: {errors}")
+    if errors or waiting:
+        raise RuntimeError(f"layer run failed: {errors} (not started: {waiting})")
     total_terms = sum(j["wfull"] for j in jobs)
     total_s = wall / args.layer_fraction
     return {"metric": "seconds per Mistral-7B-shaped decoder layer at 50% of bf16 size", "value": round(total_s, 2),
             "unit": "s/layer", "n_gpus": 1, "higher_is_better": False, "dtype": "f32", "data": "synthetic",
             "extrapolated": args.layer_fraction < 1.0, "terms": total_terms, "concurrency": K,
-            "compute_units_per_matrix": "256 / matrices in flight",
+            "compute_units_per_matrix": "shared out so that the matrices in flight finish together",
             "terms_per_s": round(total_terms / total_s, 1), "matrices": rows}
 
 
@@ -305,8 +323,8 @@ def main() -> int:
     ap.add_argument("--layer-fraction", type=float, default=1.0,
                     help="with --layer: run only this fraction of every matrix's width (the rest is extrapolated "
                          "and the line says so)")
-    ap.add_argument("--concurrency", type=int, default=4, choices=list(range(1, 9)),
-                    help="with --layer: matrices decomposed side by side, each on 256/K compute units")
+    ap.add_argument("--concurrency", type=int, default=7, choices=list(range(1, 9)),
+                    help="with --layer: most matrices decomposed side by side (the compute units are shared out among them)")
     ap.add_argument("--apply", action="store_true",
                     help="instead of the headline: time the product of a decomposition with a vector from the "
                          "packed factors (scd_apply) on the layer shapes")
@@ -495,7 +513,7 @@ def main() -> int:
         "config": {"workload": f"config 2: {m}x{n} f32 i.i.d. N(0,1) (PCG64 seed {seed}), greedy decomposition to w={w}",
                    "terms": w, "alternations_per_term": round(iters_total / w, 2),
                    "final_relative_error": round(final_rel, 6),
-                   "engine": ["launch-stream", "register-resident", "sparse"][eng["engine"]]},
+                   "engine": ENGINES[eng["engine"]]},
         "roofline": roof,
     }
     out.update(extra)
@@ -528,7 +546,7 @@ def main() -> int:
                                    "exchanges, not by bandwidth"}
         out["f64"] = {"workload": "the f64 copy of the same matrix to w=2048", "w": 2048, "terms_per_s": round(2048 / dt64, 2),
                       "seconds": round(dt64, 3), "alternations_per_term": round(it64 / 2048, 2),
-                      "engine": ["launch-stream", "register-resident", "sparse"][e64["engine"]],
+                      "engine": ENGINES[e64["engine"]],
                       "final_relative_error": round(float(tr64[-1] / tr64[0]), 6)}
         if sparse_roof:
             out["roofline_sparse"] = sparse_roof
@@ -543,7 +561,7 @@ def main() -> int:
         del A
         lay = layer_mode(args, scd, workloads, torch, np)
         out["layer"] = {k: lay[k] for k in ("metric", "value", "unit", "terms", "terms_per_s", "concurrency", "extrapolated")}
-        out["layer"]["matrix_seconds"] = {r["matrix"]: r["seconds"] for r in lay["matrices"]}
+        out["layer"]["matrix_ended_at"] = {r["matrix"]: r["ended_at"] for r in lay["matrices"]}
     print(json.dumps(out))
     return 0
 

@@ -612,6 +612,7 @@ int run_pstream(scd_ctx* c, int64_t n)
                 r.ticks[0] * 0.01 / r.alternations, r.ticks[1] * 0.01 / r.alternations, r.ticks[2] * 0.01 / r.alternations,
                 r.ticks[3] * 0.01 / r.alternations, r.ticks[4] * 0.01 / r.alternations, r.ticks[5] * 0.01 / r.alternations);
     c->seq_ps = r.seq_u;
+    c->rt_stale = true;  // the remainder changed, the transposed copy of the sparse engine did not
     c->hs.k = r.k;
     c->hs.passes += r.alternations;
     c->hs.updates += r.updates;
@@ -670,6 +671,7 @@ int run_resident(scd_ctx* c, int64_t n)
                 (long long)r.alternations, (long long)r.spins);
     c->seq_u = r.seq_u;
     c->seq_v = r.seq_v;
+    c->rt_stale = true;  // the remainder changed, the transposed copy of the sparse engine did not
     c->hs.k = r.k;
     c->hs.passes += r.alternations;
     c->hs.updates += r.updates;

@@ -11,12 +11,16 @@ from __future__ import annotations
 
 import argparse
 import json
+import os
 import sys
 import threading
 import time
 from pathlib import Path
 
-import torch
+# matrices side by side need a hardware queue each (HIP's default is four per process); read when HIP starts
+os.environ.setdefault("GPU_MAX_HW_QUEUES", "8")
+
+import torch  # noqa: E402
 
 from . import scd, workloads
 
