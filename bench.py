@@ -20,7 +20,8 @@ from pathlib import Path
 # The layer figure runs up to seven decompositions side by side, each a persistent launch on its own stream.
 # Streams that share a hardware queue run one after the other, and HIP's default is four queues per process:
 # ask for eight before the runtime starts (read once, when the first HIP call initialises it).
-os.environ.setdefault("GPU_MAX_HW_QUEUES", "8")
+if int(os.environ.get("GPU_MAX_HW_QUEUES", "0") or 0) < 8:
+    os.environ["GPU_MAX_HW_QUEUES"] = "8"
 
 ROOT = Path(__file__).resolve().parent
 if str(ROOT) not in sys.path:
@@ -310,9 +311,8 @@ def main() -> int:
     ap.add_argument("--size", type=int, default=4096, help="matrix side (headline: 4096)")
     ap.add_argument("--width", type=int, default=8192, help="terms per decomposition (headline: 8192)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the CPU oracle leg (0 = skip)")
-    ap.add_argument("--profile-sweeps", type=int, default=512)
     ap.add_argument("--engine", choices=["auto", "stream"], default="auto",
-                    help="auto: register-resident engine when the shape fits; stream: one launch per pass")
+                    help="auto: register-resident engine when the shape fits; stream: the persistent streaming engine")
     ap.add_argument("--layer", action="store_true",
                     help="instead of the headline: decompose one synthetic Mistral-7B-shaped decoder layer (7 "
                          "matrices, each to 50 %% of its bf16 footprint) and print seconds per layer")
@@ -414,27 +414,33 @@ def main() -> int:
     stream_s = scd.scd_probe_stream(A, None, 256, 50)
     stream_gbs = m * n * esize / stream_s / 1e9
 
-    def stream_roofline(ctx_terms):
-        """The row pass of the launch-stream engine (one launch = one read of R = one alternation, or the fused
-        update + first alternation): HIP events around each launch of a sample of sweeps."""
-        with scd.ScdContext(A, ctx_terms, seed, options={"resident": 0, "sparse": 0}) as ctx:
-            ctx.run(8)
-            before = ctx.traffic()
-            rowpass_s, reduce_s = ctx.profile_sweeps(args.profile_sweeps)
-            after = ctx.traffic()
-        passes = after["passes"] - before["passes"]
-        bytes_per_launch = (after["bytes"] - before["bytes"]) / max(passes, 1)
-        achieved = bytes_per_launch / rowpass_s / 1e9
-        return {"bound": "hbm", "kernel": "rowpass_tiled_kernel<float,4,4>", "achieved": round(achieved, 1),
-                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": traffic.get("rowpass_tiled_4096x4096_f32_per_launch") if (m, n) == (4096, 4096) else None,
+    def stream_roofline(M, terms, label):
+        """The persistent streaming kernel (one launch = `terms` terms; every pass reads the remainder once, the pass
+        that ends a term also writes it): algorithmic bytes of the launch over its duration by HIP events on the
+        library's stream.  The matrix is of the engine's own choosing only when the other engines are switched off."""
+        mm, nn = M.shape
+        with scd.ScdContext(M, terms, seed, options={"resident": 0, "sparse": 0}) as ctx:
+            ctx.run(min(8, terms))
+        with scd.ScdContext(M, terms, seed, options={"resident": 0, "sparse": 0}) as ctx:
+            ctx.run(terms)
+            e = ctx.engine()
+            its = int(ctx.results()["iters"].sum())
+        if e["engine"] != 3:
+            return None
+        gbs = e["last_launch_bytes"] / e["last_launch_seconds"] / 1e9
+        passes = e["last_launch_bytes"] / (mm * nn * M.element_size()) - terms
+        key = f"pstream_kernel_{mm}x{nn}_f32_per_pass"
+        return {"bound": "hbm", "kernel": "pstream_kernel (one persistent launch)", "workload": label,
+                "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4),
+                "traffic": round(traffic[key] * passes) if key in traffic else None,
                 "traffic_source": str(TRAFFIC_FILE.relative_to(ROOT)),
-                "bytes_per_launch": round(bytes_per_launch), "launch_us": round(rowpass_s * 1e6, 3),
-                "reduce_launch_us": round(reduce_s * 1e6, 3),
-                "frac_with_reduce": round(bytes_per_launch / (rowpass_s + reduce_s) / 1e9 / HBM_PEAK_GBS, 4),
+                "bytes_per_launch": round(e["last_launch_bytes"]), "launch_us": round(e["last_launch_seconds"] * 1e6, 1),
+                "us_per_pass": round(e["last_launch_seconds"] * 1e6 / passes, 3), "terms": terms,
+                "terms_per_s": round(terms / e["last_launch_seconds"], 1), "alternations_per_term": round(its / terms, 2),
                 "measured_stream_read_gbs": round(stream_gbs, 1),
-                "note": "launch_us by HIP events around every launch (2-4 us of dispatch overhead included); "
-                        "rocprofv3's kernel-only duration is in profiles/"}
+                "note": "rows of a workgroup's block that fit in LDS are read from memory once per launch, so traffic is "
+                        "below the algorithmic bytes; the rest of a pass is the latency of two exchanges among all "
+                        "workgroups"}
 
     extra = {}
     if eng["engine"] == 1:
@@ -471,9 +477,13 @@ def main() -> int:
                 "note": "the remainder is held in registers: hbm_equivalent_gbs is what a streaming pass per "
                         "alternation would have to move, not traffic, and is no roofline fraction"}
         if headline and not args.no_extra:
-            extra["roofline_stream"] = stream_roofline(args.profile_sweeps // 8 + 64)
+            extra["roofline_stream"] = stream_roofline(A, 256, "the headline matrix, first 256 terms")
+            big = torch.randn(14336, 4096, device="cuda") * 0.02
+            extra["roofline_stream_large"] = stream_roofline(big, 64, "14336x4096 f32 N(0, 0.02^2), 64 terms (224 MiB: "
+                                                                      "not cache-resident)")
+            del big
     else:
-        roof = stream_roofline(args.profile_sweeps // 8 + 64)
+        roof = stream_roofline(A, w, "the headline matrix")
 
     # Bytes the paper's own scheme would move for this run (Section 3.1's cached products, Section 3.2's
     # delayed update): dense first alternation of a term (R once for u, once for v), then one row of R per

@@ -18,7 +18,8 @@ import time
 from pathlib import Path
 
 # matrices side by side need a hardware queue each (HIP's default is four per process); read when HIP starts
-os.environ.setdefault("GPU_MAX_HW_QUEUES", "8")
+if int(os.environ.get("GPU_MAX_HW_QUEUES", "0") or 0) < 8:
+    os.environ["GPU_MAX_HW_QUEUES"] = "8"
 
 import torch  # noqa: E402
 
