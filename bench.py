@@ -309,10 +309,14 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--size", type=int, default=4096, help="matrix side (headline: 4096)")
+    ap.add_argument("--rows", type=int, default=0, help="rows, when they differ from --size (profiling runs)")
+    ap.add_argument("--f64", action="store_true",
+                    help="instead of the headline: only the f64 copy of the matrix, to --width (profiling runs)")
     ap.add_argument("--width", type=int, default=8192, help="terms per decomposition (headline: 8192)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the CPU oracle leg (0 = skip)")
-    ap.add_argument("--engine", choices=["auto", "stream"], default="auto",
-                    help="auto: register-resident engine when the shape fits; stream: the persistent streaming engine")
+    ap.add_argument("--engine", choices=["auto", "stream", "launch"], default="auto",
+                    help="auto: register-resident engine when the shape fits; stream: the persistent streaming engine; "
+                         "launch: one kernel launch per alternation (the engine of last resort)")
     ap.add_argument("--layer", action="store_true",
                     help="instead of the headline: decompose one synthetic Mistral-7B-shaped decoder layer (7 "
                          "matrices, each to 50 %% of its bf16 footprint) and print seconds per layer")
@@ -373,15 +377,30 @@ def main() -> int:
         return lsq_mode(args, scd, workloads, torch, np)
     if args.image:
         return image_mode(args, scd, workloads, torch, np)
-    m = n = args.size
+    n = args.size
+    m = args.rows or n
     w, seed = args.width, 2
+    if args.f64:
+        A64d = torch.from_numpy(workloads.gaussian_matrix(m, n, seed, np.float64)).cuda()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        with scd.ScdContext(A64d, w, seed) as ctx:
+            ctx.run(w)
+            e = ctx.engine()
+            tr = ctx.results()["trace"].cpu().numpy()
+        dt = time.perf_counter() - t0
+        print(json.dumps({"metric": f"signed-cut terms/s on {m}x{n} f64 (w={w})", "value": round(w / dt, 2), "unit": "terms/s",
+                          "engine": ENGINES[e["engine"]], "launch_us": round(e["last_launch_seconds"] * 1e6, 1),
+                          "final_relative_error": round(float(tr[-1] / tr[0]), 6)}))
+        return 0
     A64 = workloads.gaussian_matrix(m, n, seed, np.float64)
     A = torch.from_numpy(A64.astype(np.float32)).cuda()
     torch.cuda.synchronize()
     esize = A.element_size()
     headline = (m, n, w) == (4096, 4096, 8192)
     traffic = measured_traffic()
-    engine_opts = {"resident": 0, "sparse": 0} if args.engine == "stream" else {}
+    engine_opts = {"auto": {}, "stream": {"resident": 0, "sparse": 0},
+                   "launch": {"resident": 0, "sparse": 0, "persistent_stream": 0}}[args.engine]
 
     def one_step():
         # one whole decomposition through the stateful calls (what scd_decompose does internally),
@@ -482,8 +501,21 @@ def main() -> int:
             extra["roofline_stream_large"] = stream_roofline(big, 64, "14336x4096 f32 N(0, 0.02^2), 64 terms (224 MiB: "
                                                                       "not cache-resident)")
             del big
+    elif eng["engine"] == 3:
+        roof = stream_roofline(A, w, f"the {m}x{n} matrix of this run, {w} terms")
     else:
-        roof = stream_roofline(A, w, "the headline matrix")
+        # one launch of the row pass per alternation: 64 further alternations with an event around every kernel
+        with scd.ScdContext(A, w + 64, seed, options=engine_opts) as ctx:
+            ctx.run(min(w, 4))
+            rp_s, rd_s = ctx.profile_sweeps(64)
+        gbs = m * n * esize / rp_s / 1e9
+        key = f"rowpass_tiled_{m}x{n}_f32_per_launch"
+        roof = {"bound": "hbm", "kernel": "rowpass kernel (one launch per alternation)", "achieved": round(gbs, 1),
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4),
+                "traffic": round(traffic[key]) if key in traffic else None,
+                "traffic_source": str(TRAFFIC_FILE.relative_to(ROOT)), "bytes_per_launch": m * n * esize,
+                "launch_us": round(rp_s * 1e6, 2), "reduce_launch_us": round(rd_s * 1e6, 2),
+                "measured_stream_read_gbs": round(stream_gbs, 1)}
 
     # Bytes the paper's own scheme would move for this run (Section 3.1's cached products, Section 3.2's
     # delayed update): dense first alternation of a term (R once for u, once for v), then one row of R per
