@@ -11,12 +11,10 @@
 //               launch (they are read from memory once per launch, not once per alternation); the others are
 //               streamed with a second register tile in flight.  On a converged term the same pass first
 //               subtracts c_k s t^T (Algorithm 5 line 10) and sums the squares.
-//   hop 1       every workgroup publishes its partial column sums as tagged 8-byte words, in "position" order
-//               (value q of thread t at position q * 512 + t: every store instruction writes 512 contiguous
-//               bytes per wave); the owner of a slice of `cs` positions adds the partials of all workgroups in
-//               a fixed order (f64) -> its entries of v = R^T s, its bits of t = sgn(v) and its share of
-//               c = sum |v| (lines 6-7).  t lives in position order inside the kernel (a thread's own bits are
-//               bit `lane` of the words q * 8 + wave); only the appended T_k is put back into column order.
+//   hop 1       every workgroup lays its partial column sums out in column order in LDS and publishes them as
+//               tagged 8-byte words, every store instruction writing contiguous words; the owner of a slice of
+//               `cs` columns adds the partials of all workgroups in a fixed order (f64) -> its entries of
+//               v = R^T s, its bits of t = sgn(v) and its share of c = sum |v| (lines 6-7).
 //   hop 2       the owners publish sign bits and shares, every workgroup gathers all of them: the full t,
 //               c (and ||R||_F^2 after an update), added in the same order everywhere, so that every
 //               workgroup takes the same decision of line 8 without any further communication.
@@ -32,7 +30,7 @@ namespace {
 
 constexpr int kPsThreads = 512;
 constexpr int kPsWaves = kPsThreads / 64;
-constexpr int kPsMaxSlice = 256;   // most positions per slice of hop 1
+constexpr int kPsMaxSlice = 256;   // most columns per slice of hop 1
 constexpr int kPsSlot2 = 16;       // words of a hop-2 slot: up to 8 sign words, c and ||.||^2 as two halves each
 constexpr int kPsMaxLast = 4;      // order 3: largest last mode (colour channels)
 constexpr int kPsMaxItems2 = 6;    // hop-2 words a thread gathers: at most 256 * 12 / 512
