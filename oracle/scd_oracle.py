@@ -9,6 +9,7 @@ Every function takes and returns numpy arrays; sign vectors are ``uint64`` bitse
 from __future__ import annotations
 
 import ctypes as C
+import math
 import os
 import subprocess
 from pathlib import Path
@@ -521,6 +522,16 @@ def apply(S, T, c, m: int, n: int, x, transpose: bool = False) -> np.ndarray:
     y = np.empty(n if transpose else m, dtype=np.float64)
     _load().scdo_apply(m, n, c.size, S, T, c, 1 if transpose else 0, x, y)
     return y
+
+
+def relative_error(approx, exact) -> float:
+    """r = ||approx - exact||_F / ||exact||_F in f64: the error measure of Section 4.1 (Figure 7's r_k with
+    approx = A - R_k), written out entry by entry."""
+    a, e = _f64(approx).ravel(), _f64(exact).ravel()
+    assert a.size == e.size
+    num = math.fsum((x - y) * (x - y) for x, y in zip(a.tolist(), e.tolist())) if a.size <= 4096 else float(np.sum((a - e) ** 2))
+    den = math.fsum(y * y for y in e.tolist()) if a.size <= 4096 else float(np.sum(e ** 2))
+    return math.sqrt(num / den)
 
 
 def bruteforce_signed_cut_norm(A):

@@ -545,15 +545,22 @@ def read_scalars():
     return out
 
 
-def test_fig7_cast_errors():
-    # Figure 7: bf16 and f16 down-cast errors of an N(0,1) matrix -- pins the error metric r_k.
+def test_fig7_cast_errors(oracle):
+    # Figure 7: bf16 and f16 down-cast errors of an N(0,1) matrix -- pins the oracle's error measure r_k
+    # (the casts are the library's: torch for bf16, numpy for f16; the package only draws the matrix).
+    import torch
     from paper_2410_01799_amd import workloads as W
 
     g = read_scalars()
     A = W.gaussian_matrix(1024, 1024, 2, np.float64)
-    bf = W.round_to_bf16(A.astype(np.float32)).astype(np.float64)
-    assert W.relative_error(bf, A) == pytest.approx(g["bf16_cast_rel_error"], rel=0.02)
-    assert W.relative_error(A.astype(np.float16), A) == pytest.approx(g["f16_cast_rel_error"], rel=0.02)
+    bf = torch.from_numpy(A).to(torch.bfloat16).to(torch.float64).numpy()
+    assert oracle.relative_error(bf, A) == pytest.approx(g["bf16_cast_rel_error"], rel=0.02)
+    assert oracle.relative_error(A.astype(np.float16), A) == pytest.approx(g["f16_cast_rel_error"], rel=0.02)
+    # small case entry by entry: (3,4) against (3,0) and against itself
+    assert oracle.relative_error([3.0, 4.0], [3.0, 0.0]) == pytest.approx(4.0 / 3.0, rel=1e-15)
+    assert oracle.relative_error([3.0, 4.0], [3.0, 4.0]) == 0.0
+    # the package's helper (bench and the GPU tests print it) is the same measure
+    assert W.relative_error(bf, A) == pytest.approx(oracle.relative_error(bf, A), rel=1e-12)
 
 
 def test_fig7_decay_slope(oracle):

@@ -71,6 +71,11 @@ def test_bf16_rounding_is_nearest_even():
     assert r[0] == 1.0 and r[1] == 1.0 and r[2] == np.float32(1.0078125)
     assert np.all((r.view(np.uint32) & 0xFFFF) == 0)
     assert np.all(np.abs(r - x) <= np.abs(x) * 2.0 ** -8)
+    # against the library's cast on random values
+    import torch
+
+    y = np.random.default_rng(3).standard_normal(10000).astype(np.float32)
+    np.testing.assert_array_equal(W.round_to_bf16(y), torch.from_numpy(y).to(torch.bfloat16).to(torch.float32).numpy())
 
 
 def test_weight_like_recipe():
