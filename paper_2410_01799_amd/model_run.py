@@ -17,13 +17,18 @@ import threading
 import time
 from pathlib import Path
 
-# matrices side by side need a hardware queue each (HIP's default is four per process); read when HIP starts
-if int(os.environ.get("GPU_MAX_HW_QUEUES", "0") or 0) < 8:
-    os.environ["GPU_MAX_HW_QUEUES"] = "8"
+# matrices side by side need a hardware queue each (HIP's default is four per process); read when HIP starts,
+# so the command line is looked at before torch is imported
+_queues = 8
+if "--hw-queues" in sys.argv[:-1]:
+    _queues = max(4, min(32, int(sys.argv[sys.argv.index("--hw-queues") + 1])))
+if int(os.environ.get("GPU_MAX_HW_QUEUES", "0") or 0) < _queues:
+    os.environ["GPU_MAX_HW_QUEUES"] = str(_queues)
 
 import torch  # noqa: E402
 
 from . import scd, workloads
+from .shares import ShareBoard
 
 
 def device_weight_like(m: int, n: int, seed: int, kind: str) -> torch.Tensor:
@@ -42,23 +47,30 @@ def device_weight_like(m: int, n: int, seed: int, kind: str) -> torch.Tensor:
     return G.bfloat16().float().contiguous()   # bf16-representable values, stored as f32
 
 
-def decompose_one(e: dict, share_fn, chunk: int) -> dict:
+def decompose_one(e: dict, share_fn, chunk: int, progress_fn=None) -> dict:
     """One matrix of the manifest on the current stream; returns its result row.  share_fn() says, before every
-    launch, how many compute units this matrix may take (0 = all)."""
+    launch, how many compute units this matrix may take (0 = all); progress_fn(terms left, alternations per term)
+    is told after every launch."""
     m, n = e["m"], e["n"]
     A = device_weight_like(m, n, e["seed"], e["kind"])
     w = e["widths"]["1/2"]
     torch.cuda.current_stream().synchronize()
     t0 = time.perf_counter()
     with scd.ScdContext(A, w, e["seed"]) as ctx:
-        share_now = 0
+        share_now, shares_used = 0, [256]
         # launches of bounded length, so that the split of the device can follow the matrices in flight
         for k in range(0, w, chunk):
             want = share_fn()
             if want != share_now:
                 ctx.set_workgroups(want)
                 share_now = want
-            ctx.run(min(chunk, w - k))
+                shares_used.append(want or 256)
+            done = min(chunk, w - k)
+            ctx.run(done)
+            if progress_fn is not None:
+                progress_fn(w - k - done, ctx.traffic()["passes"] / (k + done))
+        if len(shares_used) > 1:
+            shares_used = shares_used[1:]
         res = ctx.results()
         eng = ctx.engine()["engine"]
         torch.cuda.current_stream().synchronize()
@@ -69,7 +81,7 @@ def decompose_one(e: dict, share_fn, chunk: int) -> dict:
     rel = {p: float(tr[e["widths"][p]] / tr[0]) for p in ("1/4", "3/8", "1/2")}
     return dict(index=e["index"], name=e["name"], m=m, n=n, seed=e["seed"], width=w, seconds=round(dt, 3),
                 terms_per_s=round(w / dt, 1), alternations_per_term=round(float(res["iters"].float().mean()), 2),
-                rel_err=rel, identity_max_violation=ident, engine_at_the_end=eng)
+                rel_err=rel, identity_max_violation=ident, engine_at_the_end=eng, workgroups=shares_used)
 
 
 def main() -> int:
@@ -78,10 +90,14 @@ def main() -> int:
     ap.add_argument("--stop", type=int, default=226)
     ap.add_argument("--out", type=str, required=True)
     ap.add_argument("--budget-seconds", type=float, default=1e9, help="take no new matrix that would overrun")
-    ap.add_argument("--concurrency", type=int, default=1, choices=list(range(1, 9)),
-                    help="matrices decomposed side by side, the compute units split evenly among those in flight "
-                         "(the matrices of a model are independent, and one decomposition is latency-bound)")
-    ap.add_argument("--chunk", type=int, default=1024, help="terms per launch when matrices run side by side")
+    ap.add_argument("--concurrency", type=int, default=1, choices=list(range(1, 17)),
+                    help="most matrices decomposed side by side (the matrices of a model are independent, and one "
+                         "decomposition is latency-bound); every one gets a share of the compute units")
+    ap.add_argument("--share", type=int, default=32,
+                    help="workgroups a newly started matrix gets when others wait behind it (more if its shape needs "
+                         "more); room that no waiting matrix can use goes to the matrix that would finish last")
+    ap.add_argument("--chunk", type=int, default=512, help="terms per launch when matrices run side by side")
+    ap.add_argument("--hw-queues", type=int, default=8, help="hardware queues of the process (one per matrix in flight)")
     args = ap.parse_args()
     man = workloads.config5_manifest()
     for i, e in enumerate(man):
@@ -91,63 +107,85 @@ def main() -> int:
     out.parent.mkdir(parents=True, exist_ok=True)
     K = args.concurrency
     chunk = 1 << 30 if K == 1 else args.chunk
-    lock = threading.Lock()
-    busy = [0]           # workers that hold a matrix right now
-
-    def fair_share() -> int:
-        # the compute units are split evenly among the matrices in flight (64 each with four, all for the last one)
-        if K == 1:
-            return 0
-        with lock:
-            n = max(1, busy[0])
-        sh = 256 // n
-        return 0 if sh >= 256 else sh
-
+    cv = threading.Condition()
+    board = ShareBoard()
+    running: dict = {}   # index -> thread
     t_begin = time.perf_counter()
     cost: dict = {}      # (m, n) -> seconds the last matrix of that shape took
     failures = []
     scd.lib()
     torch.cuda.set_device(0)
+
+    def info(e):
+        return dict(m=e["m"], n=e["n"], left=e["widths"]["1/2"], alt=40.0)
+
     with out.open("a") as fh:
-        def worker():
+        # one stream per matrix in flight, made once and handed from a finished matrix to the next: streams made
+        # later would share a hardware queue with one that is busy, and every launch of theirs would wait for a
+        # whole launch of the other matrix
+        free_streams = [torch.cuda.Stream() for _ in range(K)] if K > 1 else []
+
+        def worker(e):
             torch.cuda.set_device(0)
-            stream = torch.cuda.Stream() if K > 1 else torch.cuda.current_stream()
-            with torch.cuda.stream(stream):
-                while True:
-                    with lock:
-                        if not todo or failures:
-                            return
-                        e = man[todo[0]]
-                        guess = cost.get((e["m"], e["n"]), 0.0)
-                        if time.perf_counter() - t_begin + 1.2 * guess > args.budget_seconds:
-                            return
-                        todo.pop(0)
-                        busy[0] += 1
-                    try:
-                        row = decompose_one(e, fair_share, chunk)
-                    except Exception as err:  # noqa: BLE001 - reported by the main thread
-                        with lock:
-                            failures.append((e["index"], repr(err)))
-                            busy[0] -= 1
-                        return
-                    with lock:
-                        busy[0] -= 1
-                        cost[(e["m"], e["n"])] = row["seconds"]
-                        fh.write(json.dumps(row) + "\n")
-                        fh.flush()
-                        rel = row["rel_err"]
-                        print(f"[{row['index']}] {row['name']} {row['m']}x{row['n']} w={row['width']}: "
-                              f"{row['seconds']:.1f} s, {row['terms_per_s']:.0f} terms/s, rel err 1/4 {rel['1/4']:.4f} "
-                              f"3/8 {rel['3/8']:.4f} 1/2 {rel['1/2']:.4f}", flush=True)
+            idx = e["index"]
+            if K > 1:
+                with cv:
+                    stream = free_streams.pop()
+            else:
+                stream = torch.cuda.current_stream()
+            try:
+                with torch.cuda.stream(stream):
+                    row = decompose_one(e, (lambda: board.share(idx)) if K > 1 else (lambda: 0), chunk,
+                                        (lambda left, alt: board.progress(idx, left, alt)) if K > 1 else None)
+            except Exception as err:  # noqa: BLE001 - reported by the main thread
+                with cv:
+                    failures.append((idx, repr(err)))
+                    free_streams.append(stream)
+                    board.release(idx)
+                    running.pop(idx, None)
+                    cv.notify_all()
+                return
+            with cv:
+                cost[(e["m"], e["n"])] = row["seconds"]
+                fh.write(json.dumps(row) + "\n")
+                fh.flush()
+                rel = row["rel_err"]
+                print(f"[{row['index']}] {row['name']} {row['m']}x{row['n']} w={row['width']}: "
+                      f"{row['seconds']:.1f} s, {row['terms_per_s']:.0f} terms/s on {row['workgroups']} workgroups, "
+                      f"rel err 1/4 {rel['1/4']:.4f} 3/8 {rel['3/8']:.4f} 1/2 {rel['1/2']:.4f}", flush=True)
+                board.release(idx)        # the room stays free until the main thread has tried the waiting matrices
+                free_streams.append(stream)
+                running.pop(idx, None)
+                cv.notify_all()
 
         if K == 1:
-            worker()
+            while todo and not failures:
+                e = man[todo[0]]
+                if time.perf_counter() - t_begin + 1.2 * cost.get((e["m"], e["n"]), 0.0) > args.budget_seconds:
+                    break
+                todo.pop(0)
+                running[e["index"]] = None
+                worker(e)
         else:
-            threads = [threading.Thread(target=worker) for _ in range(K)]
-            for t in threads:
-                t.start()
-            for t in threads:
-                t.join()
+            with cv:
+                while True:
+                    # waiting matrices first (in manifest order, each into room that is free now), then what is
+                    # left over to the matrices in flight
+                    while todo and not failures and len(running) < K:
+                        e = man[todo[0]]
+                        if time.perf_counter() - t_begin + 1.2 * cost.get((e["m"], e["n"]), 0.0) > args.budget_seconds:
+                            break
+                        more_wait = len(todo) > 1
+                        if not board.admit(e["index"], info(e), args.share if more_wait else 0):
+                            break
+                        todo.pop(0)
+                        t = threading.Thread(target=worker, args=(e,))
+                        running[e["index"]] = t
+                        t.start()
+                    board.grow()
+                    if not running:
+                        break
+                    cv.wait()
         torch.cuda.synchronize()
         wall = time.perf_counter() - t_begin
         fh.write(json.dumps(dict(summary=True, start=args.start, next_index=todo[0] if todo else None,

@@ -50,18 +50,31 @@ class ShareBoard:
             self.jobs = {k: dict(v) for k, v in jobs.items()}
             self.shares = solve_shares(self.jobs, self.device)
 
-    def admit(self, job: int, info: dict) -> bool:
-        """A further job, if the room that is free now holds the smallest share its shape allows."""
+    def admit(self, job: int, info: dict, target: int = 0) -> bool:
+        """A further job, if the room that is free now holds the smallest share its shape allows.  It gets the
+        largest power of two that fits the room, or at most `target` (if given and its shape allows so little):
+        a stream of waiting jobs then fills the device with many small shares, which do the most work per
+        compute unit."""
         with self.lock:
             room = self.device - sum(self.shares.values())
             g = min_share(info["m"], info["n"])
             if g > room:
                 return False
-            while 2 * g <= room:
+            while 2 * g <= room and (target <= 0 or 2 * g <= target):
                 g *= 2
             self.jobs[job] = dict(info)
             self.shares[job] = g
             return True
+
+    def release(self, job: int) -> None:
+        """A finished job leaves; its room stays free until admit() or grow() hands it out."""
+        with self.lock:
+            self.jobs.pop(job, None)
+            self.shares.pop(job, None)
+
+    def grow(self) -> None:
+        with self.lock:
+            self._grow()
 
     def progress(self, job: int, terms_left: int, alternations_per_term: float) -> None:
         with self.lock:

@@ -49,3 +49,24 @@ def test_a_waiting_job_is_admitted_into_free_room_only():
     assert not b.admit(3, info(3)) or sum(b.shares.values()) <= 256
     b.jobs.pop(0), b.shares.pop(0)
     assert b.admit(3, info(3)) and sum(b.shares.values()) <= 256
+
+
+def test_a_stream_of_waiting_jobs_fills_the_device_with_small_shares():
+    # the model run: jobs admitted one by one with a target share while others wait behind them
+    b = ShareBoard()
+    order = [0, 1, 2, 3, 4, 5, 6, 0, 1, 2]
+    started = []
+    for j, i in enumerate(order):
+        if len(started) < 8 and b.admit(100 + j, info(i), 32):
+            started.append(100 + j)
+    b.grow()
+    assert len(started) == 8 and sum(b.shares.values()) <= 256
+    assert all(g == 32 for g in b.shares.values())               # eight times 32: nothing left to grow into
+    b.release(started[1])                                        # a finished job leaves room for exactly one more
+    assert sum(b.shares.values()) == 224
+    assert b.admit(200, info(4), 32) and b.shares[200] == 32
+    b.release(started[0])
+    b.release(started[2])
+    assert b.admit(201, dict(m=32000, n=4096, left=29023, alt=30.0), 32) and b.shares[201] == 64   # its shape needs 64
+    b.grow()
+    assert sum(b.shares.values()) <= 256
