@@ -123,6 +123,42 @@ __device__ __forceinline__ uint64_t ps_load(const uint64_t* p)
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// Hop 1, one thread: the partial sums of members q, q + Q, q + 2 Q, ... < G for one column (at basep + member *
+// slot1, WPE tagged words n apart), added in that order; NF members are in flight together.  false: a wait ran out.
+template <int WPE, int NF>
+__device__ __forceinline__ bool ps_hop1_gather(const uint64_t* basep, int q, int Q, int G, size_t slot1, int64_t n, uint32_t seq,
+                                               int max_spin, double& s, int& spin)
+{
+#pragma nounroll
+    for (int m0 = q; m0 < G; m0 += NF * Q) {
+        uint64_t w[NF][WPE];
+        for (;;) {
+            bool fresh = true;
+#pragma unroll
+            for (int i = 0; i < NF; ++i) {
+                const int mem = m0 + i * Q < G ? m0 + i * Q : m0;
+#pragma unroll
+                for (int h = 0; h < WPE; ++h) w[i][h] = ps_load(basep + (size_t)mem * slot1 + (size_t)h * n);
+            }
+#pragma unroll
+            for (int i = 0; i < NF; ++i)
+#pragma unroll
+                for (int h = 0; h < WPE; ++h) fresh = fresh && ((uint32_t)(w[i][h] >> 32) == seq);
+            if (fresh) break;
+            if (++spin > max_spin) return false;
+            __builtin_amdgcn_s_sleep(1);
+        }
+#pragma unroll
+        for (int i = 0; i < NF; ++i) {
+            if (m0 + i * Q < G) {
+                if constexpr (WPE == 1) s += (double)__uint_as_float((uint32_t)w[i][0]);
+                else s += __longlong_as_double((long long)((w[i][1] << 32) | (w[i][0] & 0xFFFFFFFFull)));
+            }
+        }
+    }
+    return true;
+}
+
 // profile mode: 100 MHz ticks of workgroup 0 per phase
 #define PS_TICK(slot)                                                  \
     do {                                                               \
@@ -144,6 +180,7 @@ struct PsShared {
         uint32_t scal[2 * kPsMaxLast + 2][kSpGrid];  // hop 2: low/high halves of the members' scalars
     };
     double red[2][kPsWaves];
+    double redn[kPsMaxLast][kSpGrid / 64];  // order 3: wave sums of the last mode's shares
     uint32_t tw32[8];              // sign words of the own slice
     double w2part[kPsMaxLast];     // order 3: the own slice's part of the last mode's sums
     int64_t ticks[6];              // profile mode
@@ -366,22 +403,57 @@ __device__ __forceinline__ double ps_sum_members(double v, PsShared& sh, int slo
     return t;
 }
 
-// Column signs of the level-0 view of an order-3 tensor: bit q = s2[q / n3] xor s3[q % n3] (Algorithm 12 lines
-// 5-7: the sign of the tensor product of the other modes' vectors), written word by word from ballots.
-__device__ __forceinline__ void ps_kron_bits(uint64_t* out, int64_t n, int n3, const uint64_t* s2, uint64_t s3)
+// The same for the cnt <= kPsMaxLast shares of the last mode of an order-3 tensor at once (one barrier for all;
+// each sum in the order ps_sum_members takes).  All threads must call it.
+__device__ __forceinline__ void ps_sum_members_n(const double (&v)[kPsMaxLast], int cnt, PsShared& sh, double (&out)[kPsMaxLast])
 {
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    if (wv < kSpGrid / 64) {
+#pragma unroll
+        for (int c = 0; c < kPsMaxLast; ++c) {
+            const double t = ps_wave_sum(c < cnt ? v[c] : 0.0);
+            if (lane == 0) sh.redn[c][wv] = t;
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int c = 0; c < kPsMaxLast; ++c) {
+        double t = 0.0;
+#pragma unroll
+        for (int q = 0; q < kSpGrid / 64; ++q) t += sh.redn[c][q];
+        out[c] = t;
+    }
+}
+
+// Column signs of the level-0 view of an order-3 tensor: bit q = s2[q / n3] xor s3[q % n3] (Algorithm 12 lines
+// 5-7: the sign of the tensor product of the other modes' vectors).  A thread forms 32 consecutive bits from the
+// at most 33 rows of s2 that they touch (n2 bits of s2 are valid, the rest of its last word is zero).
+__device__ __forceinline__ void ps_kron_bits(uint64_t* out, int64_t n, int n3, const uint64_t* s2, int n2, uint64_t s3)
+{
+    uint32_t* o32 = (uint32_t*)out;
+    const int w2 = (n2 + 63) / 64;
+    const int nh = (int)((n + 63) / 64) * 2;  // half words of the array
     const float rn3 = 1.0f / (float)n3;
-    for (int64_t qb = (int64_t)wv * 64; qb < n; qb += kPsThreads) {
-        const int64_t q = qb + lane;
-        // q / n3 by a float product, exact here: (q + 0.5) / n3 is at least 0.5 / n3 away from an integer and
-        // q stays below 2^20
-        const int64_t qc = q < n ? q : n - 1;  // (lanes past the end read a valid word and drop it)
-        const int j = (int)(((float)qc + 0.5f) * rn3);
-        const int c = (int)qc - j * n3;
-        const bool bit = q < n && ((((s2[j >> 6] >> (j & 63)) ^ (s3 >> c)) & 1ull) != 0);
-        const uint64_t word = __ballot(bit);
-        if (lane == 0) out[qb >> 6] = word;
+    for (int h = threadIdx.x; h < nh; h += kPsThreads) {
+        const int q0 = h * 32;
+        // q0 / n3 by a float product, exact here: (q0 + 0.5) / n3 is at least 0.5 / n3 away from an integer and
+        // q0 stays below 2^20 + 64
+        const int j = (int)(((float)q0 + 0.5f) * rn3);
+        int cc = q0 - j * n3, jj = 0;
+        const int wi = j >> 6, sh = j & 63;
+        const uint64_t lo = s2[wi < w2 ? wi : w2 - 1], hi = s2[wi + 1 < w2 ? wi + 1 : w2 - 1];
+        const uint64_t x = sh ? (lo >> sh) | (hi << (64 - sh)) : lo;  // rows j, j + 1, ... from bit 0
+        uint32_t o = 0;
+#pragma unroll 8
+        for (int b = 0; b < 32; ++b) {
+            o |= (((uint32_t)(x >> jj) ^ (uint32_t)(s3 >> cc)) & 1u) << b;
+            if (++cc == n3) {
+                cc = 0;
+                ++jj;
+            }
+        }
+        const int64_t valid = n - q0;  // bits of this half word inside the array: the padding stays zero
+        o32[h] = valid >= 32 ? o : (valid > 0 ? o & ((1u << (int)valid) - 1u) : 0u);
     }
 }
 
@@ -438,7 +510,7 @@ __global__ void __launch_bounds__(kPsThreads) pstream_kernel(PStreamArgs a)
         for (int p = tid; p < w2; p += kPsThreads) s2_cur[p] = rng_word_masked(a.seed, (uint64_t)a.k_start, 1u, p, a.n2);
         s3_cur = rng_word_masked(a.seed, (uint64_t)a.k_start, 2u, 0, n3);
         __syncthreads();
-        ps_kron_bits(t_rng, n, n3, s2_cur, s3_cur);
+        ps_kron_bits(t_rng, n, n3, s2_cur, a.n2, s3_cur);
     } else {
         for (int p = tid; p < nw; p += kPsThreads) t_rng[p] = rng_word_masked(a.seed, (uint64_t)a.k_start, 1u, p, n);
     }
@@ -534,38 +606,10 @@ __global__ void __launch_bounds__(kPsThreads) pstream_kernel(PStreamArgs a)
             if (q < Q && jc < ncol) {
                 const uint64_t* basep = a.xp + ((size_t)(seq & 1u) * G) * slot1 + (size_t)(c0 + jc);
                 int spin = 0;
-#pragma nounroll
-                for (int m0 = q; m0 < G && ok; m0 += 8 * Q) {
-                    uint64_t w[8][WPE];
-                    for (;;) {
-                        bool fresh = true;
-#pragma unroll
-                        for (int i = 0; i < 8; ++i) {
-                            const int mem = m0 + i * Q < G ? m0 + i * Q : m0;
-#pragma unroll
-                            for (int h = 0; h < WPE; ++h) w[i][h] = ps_load(basep + (size_t)mem * slot1 + (size_t)h * n);
-                        }
-#pragma unroll
-                        for (int i = 0; i < 8; ++i)
-#pragma unroll
-                            for (int h = 0; h < WPE; ++h) fresh = fresh && ((uint32_t)(w[i][h] >> 32) == seq);
-                        if (fresh) break;
-                        if (++spin > a.max_spin) {
-                            ok = false;
-                            break;
-                        }
-                        __builtin_amdgcn_s_sleep(1);
-                    }
-                    if (ok) {
-#pragma unroll
-                        for (int i = 0; i < 8; ++i) {
-                            if (m0 + i * Q < G) {
-                                if constexpr (WPE == 1) s += (double)__uint_as_float((uint32_t)w[i][0]);
-                                else s += __longlong_as_double((long long)((w[i][1] << 32) | (w[i][0] & 0xFFFFFFFFull)));
-                            }
-                        }
-                    }
-                }
+                // members q, q + Q, ... in that order; 16 in flight when a thread has more than 8 of them (one-word
+                // values only: 32 words in flight would not fit the registers)
+                if (WPE == 1 && G > 8 * Q) ok = ps_hop1_gather<WPE, WPE == 1 ? 16 : 8>(basep, q, Q, G, slot1, n, seq, a.max_spin, s, spin);
+                else ok = ps_hop1_gather<WPE, 8>(basep, q, Q, G, slot1, n, seq, a.max_spin, s, spin);
                 spins += spin;
             }
             sh.part[tid] = s;
@@ -616,8 +660,15 @@ __global__ void __launch_bounds__(kPsThreads) pstream_kernel(PStreamArgs a)
             __syncthreads();
             if (tid < n3) {
                 double w2c = 0.0;
-                for (int jr = 0; jr < nr2; ++jr)
-                    w2c += ((sh.tw32[jr >> 5] >> (jr & 31)) & 1u) ? -sh.v[jr * n3 + tid] : sh.v[jr * n3 + tid];
+                for (int j0 = 0; j0 < nr2; j0 += 8) {
+                    double x[8];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) x[i] = sh.v[(j0 + i < nr2 ? j0 + i : nr2 - 1) * n3 + tid];
+                    const uint32_t bits = sh.tw32[j0 >> 5] >> (j0 & 31);  // (eight rows never straddle a word)
+#pragma unroll
+                    for (int i = 0; i < 8; ++i)
+                        if (j0 + i < nr2) w2c += ((bits >> i) & 1u) ? -x[i] : x[i];
+                }
                 sh.w2part[tid] = w2c;
             }
             __syncthreads();
@@ -720,14 +771,19 @@ __global__ void __launch_bounds__(kPsThreads) pstream_kernel(PStreamArgs a)
         } else {
             // last mode: s^(3)_c = sgn(W_2[c]); the cut value is <s, a> = sum_c |W_2[c]| (Algorithm 12 line 10)
             uint64_t s3n = 0;
-            for (int c = 0; c < n3; ++c) {
-                const double w2c = ps_sum_members(share(c), sh, 0);
-                __syncthreads();  // sh.red[0] is reused by the next sum
-                if (w2c < 0.0) s3n |= 1ull << c;
-                c_tot += fabs(w2c);
+            double sv[kPsMaxLast], wl[kPsMaxLast];
+#pragma unroll
+            for (int c = 0; c < kPsMaxLast; ++c) sv[c] = c < n3 ? share(c) : 0.0;
+            ps_sum_members_n(sv, n3, sh, wl);
+#pragma unroll
+            for (int c = 0; c < kPsMaxLast; ++c) {
+                if (c < n3) {
+                    if (wl[c] < 0.0) s3n |= 1ull << c;
+                    c_tot += fabs(wl[c]);
+                }
             }
             s3_cur = s3n;
-            ps_kron_bits(t_cur, n, n3, s2_cur, s3_cur);
+            ps_kron_bits(t_cur, n, n3, s2_cur, a.n2, s3_cur);
         }
         if (with_norm) f_tot = ps_sum_members(share(nsc / 2), sh, 1);
         if (with_norm && g == 0 && tid == 0) a.trace[k] = sqrt(f_tot);
@@ -780,7 +836,7 @@ __global__ void __launch_bounds__(kPsThreads) pstream_kernel(PStreamArgs a)
                 for (int p = tid; p < w2; p += kPsThreads) s2_cur[p] = rng_word_masked(a.seed, (uint64_t)k, 1u, p, a.n2);
                 s3_cur = rng_word_masked(a.seed, (uint64_t)k, 2u, 0, n3);
                 __syncthreads();
-                ps_kron_bits(t_rng, n, n3, s2_cur, s3_cur);
+                ps_kron_bits(t_rng, n, n3, s2_cur, a.n2, s3_cur);
             } else {
                 for (int p = tid; p < nw; p += kPsThreads) t_rng[p] = rng_word_masked(a.seed, (uint64_t)k, 1u, p, n);
             }

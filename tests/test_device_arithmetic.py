@@ -90,3 +90,48 @@ def test_stream_engine_geometry_stays_inside_what_the_kernel_assumes():
     # slices, orders above 3, a last mode above 4
     for dims in [(100, 77), (64, 16388), (64, 20000), (3, 4096), (9, 8, 7, 6), (20, 30, 5)]:
         assert scd.scd_stream_geometry(torch.float32, dims, 256) is None, dims
+
+
+def test_column_signs_of_a_tensor_built_32_bits_per_thread():
+    # Host model of ps_kron_bits (scd_stream.hip): the sign of column q of the n_1 x (n_2 n_3) view is
+    # s2[q / n3] xor s3[q % n3]; a thread forms 32 consecutive bits from a 64-bit window of s2 that starts at row
+    # q0 / n3, with the division by a float32 product.  Checked against the definition for all last modes, ragged
+    # lengths and the padding; the float division exhaustively on the whole range the engine admits.
+    f32 = np.float32
+    M64 = (1 << 64) - 1
+    for n3 in (1, 2, 3, 4):
+        q = np.arange(0, (1 << 20) + 64, dtype=np.int64)
+        j = ((q.astype(f32) + f32(0.5)) * (f32(1.0) / f32(n3))).astype(np.int64)
+        assert np.array_equal(j, q // n3)
+    rs = np.random.default_rng(5)
+    for n3 in (1, 2, 3, 4):
+        for n2 in (1, 5, 63, 64, 65, 700, 3000):
+            n = n2 * n3
+            s2 = rs.integers(0, 2, n2).astype(np.uint8)
+            s3 = rs.integers(0, 2, n3).astype(np.uint8)
+            w2 = (n2 + 63) // 64
+            words = [0] * w2                                              # packed, LSB first, padding zero
+            for i in np.nonzero(s2)[0]:
+                words[i >> 6] |= 1 << (int(i) & 63)
+            s3w = int(sum(int(b) << i for i, b in enumerate(s3)))
+            nw = (n + 63) // 64
+            out = []
+            for h in range(2 * nw):
+                q0 = 32 * h
+                jx = int((f32(q0) + f32(0.5)) * (f32(1.0) / f32(n3)))
+                cc, jj, wi, sh = q0 - jx * n3, 0, jx >> 6, jx & 63
+                lo, hi = words[min(wi, w2 - 1)], words[min(wi + 1, w2 - 1)]
+                x = ((lo >> sh) | (hi << (64 - sh))) & M64 if sh else lo
+                o = 0
+                for b in range(32):
+                    o |= (((x >> jj) ^ (s3w >> cc)) & 1) << b
+                    cc += 1
+                    if cc == n3:
+                        cc, jj = 0, jj + 1
+                assert jj <= 33
+                valid = n - q0
+                out.append(o if valid >= 32 else (o & ((1 << valid) - 1) if valid > 0 else 0))
+            bits = np.array([(out[q >> 5] >> (q & 31)) & 1 for q in range(64 * nw)], dtype=np.uint8)
+            want = np.bitwise_xor.outer(s2, s3).reshape(-1)               # q = j * n3 + c
+            assert np.array_equal(bits[:n], want), (n3, n2)
+            assert not bits[n:].any()
