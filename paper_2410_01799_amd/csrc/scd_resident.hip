@@ -286,7 +286,10 @@ __device__ __forceinline__ float sum_xor32(float v)
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-template <int TR, int TC, int P>
+// PAD: the grid overhangs the matrix (a template parameter: the 128 row/column tests of a thread's tile are
+// invariants of the whole launch, and a kernel that has to keep them takes twice the instructions and runs out of
+// scalar registers even when no test ever fails).
+template <int TR, int TC, int P, bool PAD>
 __global__ void __launch_bounds__(kResThreads) resident_kernel(ResidentArgs a)
 {
     constexpr int H = P / 2;  // members per half of an exchange group
@@ -309,7 +312,7 @@ __global__ void __launch_bounds__(kResThreads) resident_kernel(ResidentArgs a)
     // ---- load the block.  The grid may overhang the matrix: rows and columns past its end are zeros in the
     // registers (they add nothing to any sum and stay zero through every update) and are never read or written.
     const int64_t row0 = (int64_t)pr * BM + tr * TR, col0 = (int64_t)pc * BN + tc * TC;
-    const bool padded = (int64_t)P * BM != a.m || (int64_t)P * BN != a.n;  // the same in every workgroup
+    constexpr bool padded = PAD;
     float x[TR][TC];
     {
         const float* base = a.R + row0 * a.n + col0;
@@ -651,8 +654,8 @@ int resident_workgroups(const int64_t* dims)
     return resident_shape(dims[0], dims[1], &p, &tr, &tc) ? p * p : 0;
 }
 
-template <int TR, int TC, int P>
-static hipError_t launch_resident_t(const ResidentArgs& a, hipStream_t st)
+template <int TR, int TC, int P, bool PAD>
+static hipError_t launch_resident_k(const ResidentArgs& a, hipStream_t st)
 {
     // All P x P workgroups must be resident at once.  One workgroup of 512 threads fits every compute
     // unit (checked here against the occupancy the runtime reports); an ordinary launch on an idle
@@ -662,11 +665,19 @@ static hipError_t launch_resident_t(const ResidentArgs& a, hipStream_t st)
     hipError_t e = hipGetDevice(&dev);
     if (e == hipSuccess) e = hipGetDeviceProperties(&prop, dev);
     if (e == hipSuccess)
-        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, resident_kernel<TR, TC, P>, kResThreads, 0);
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, resident_kernel<TR, TC, P, PAD>, kResThreads, 0);
     if (e != hipSuccess) return e;
     if ((int64_t)per_cu * prop.multiProcessorCount < P * P) return hipErrorCooperativeLaunchTooLarge;
-    hipLaunchKernelGGL((resident_kernel<TR, TC, P>), dim3(P * P), dim3(kResThreads), 0, st, a);
+    hipLaunchKernelGGL((resident_kernel<TR, TC, P, PAD>), dim3(P * P), dim3(kResThreads), 0, st, a);
     return hipGetLastError();
+}
+
+template <int TR, int TC, int P>
+static hipError_t launch_resident_t(const ResidentArgs& a, hipStream_t st)
+{
+    // does the grid of P x P blocks of 32 TR x 16 TC overhang the matrix?
+    const bool padded = (int64_t)P * 32 * TR != a.m || (int64_t)P * 16 * TC != a.n;
+    return padded ? launch_resident_k<TR, TC, P, true>(a, st) : launch_resident_k<TR, TC, P, false>(a, st);
 }
 
 template <int P>
