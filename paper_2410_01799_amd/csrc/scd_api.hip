@@ -108,6 +108,7 @@ struct scd_ctx {
     int rs = 0, cs = 0;
     // persistent streaming engine
     bool pstream = false;
+    void* c_scal = nullptr;         // real last mode (scd_decompose_scalars): n3 coefficients per term; else null
     PStreamGeometry ps_geo = {};
     uint64_t* xbuf_p1 = nullptr;
     uint64_t* xbuf_p2 = nullptr;
@@ -560,6 +561,7 @@ int run_pstream(scd_ctx* c, int64_t n)
         a.n3 = (int32_t)c->dims[2];
         a.w2 = (int32_t)words_for(c->dims[1]);
         a.S3 = c->out_signs[2];
+        a.scalars = c->c_scal ? 1 : 0;
     }
     a.seed = c->seed;
     a.k_start = c->hs.k;
@@ -572,7 +574,7 @@ int run_pstream(scd_ctx* c, int64_t n)
     a.xq = c->xbuf_p2;
     a.S = c->out_signs[0];
     a.T = c->out_signs[1];
-    a.c = c->c_out;
+    a.c = a.scalars ? c->c_scal : c->c_out;
     a.iters = c->iters;
     a.trace = c->trace;
     a.mw = (int32_t)words_for(c->dims[0]);
@@ -1522,6 +1524,47 @@ int scd_decompose_scalars(const void* A, scd_dtype dt, int order, const int64_t*
     hipStream_t st = (hipStream_t)stream;
     const size_t es = dt == SCD_F32 ? 4 : 8;
     const int64_t q = dims[order - 1], P = total / q;
+    if (w > 0 && pstream_supported(dt, order, dims, kSpGrid, nullptr)) {
+        // order 3 with a short last mode (images): the sweeps are those of the all-signs variant, so the
+        // persistent streaming engine runs them; it forms the real coefficients from the last mode's sums it
+        // already has and subtracts them slice by slice
+        scd_ctx* c = nullptr;
+        int rc = scd_create(&c, A, dt, order, dims, w, seed, stream);
+        if (rc < 0) return rc;
+        rc = scd_set_max_iters(c, max_iters);
+        if (rc >= 0 && c->pstream) {
+            hipError_t e = hipMalloc(&c->c_scal, (size_t)w * (size_t)q * es);
+            if (e != hipSuccess) {
+                g_last_hip = (int)e;
+                (void)hipGetLastError();
+                c->c_scal = nullptr;
+                rc = SCD_ENOMEM;
+            }
+            int run = rc;
+            if (rc >= 0) run = scd_run(c, w);
+            if (run >= 0) {
+                hipError_t h = hipSuccess;
+                for (int i = 0; i + 1 < order && h == hipSuccess; ++i)
+                    h = hipMemcpyAsync(signs[i], c->out_signs[i], (size_t)w * words_for(dims[i]) * 8, hipMemcpyDeviceToDevice, st);
+                if (h == hipSuccess) h = hipMemcpyAsync(cvec, c->c_scal, (size_t)w * (size_t)q * es, hipMemcpyDeviceToDevice, st);
+                if (h == hipSuccess) h = hipMemcpyAsync(fro_trace, c->trace, (size_t)(w + 1) * 8, hipMemcpyDeviceToDevice, st);
+                if (h == hipSuccess && iters) h = hipMemcpyAsync(iters, c->iters, (size_t)w * 4, hipMemcpyDeviceToDevice, st);
+                if (h == hipSuccess) h = hipStreamSynchronize(st);
+                if (h != hipSuccess) {
+                    g_last_hip = (int)h;
+                    (void)hipGetLastError();
+                    run = SCD_EHIP;
+                }
+            }
+            (void)hipStreamSynchronize(st);
+            if (c->c_scal) (void)hipFree(c->c_scal);
+            c->c_scal = nullptr;
+            scd_destroy(c);
+            return run;
+        }
+        scd_destroy(c);
+        if (rc < 0) return rc;
+    }
     const int nsq = 256;
     ModeSums ms;
     double* host = nullptr;  // pinned: [0], [1] sums read back, [2] upload slot

@@ -205,6 +205,7 @@ struct PStreamArgs {
     int32_t mw, nw;
     int32_t grid, rpw, cs, lds_rows;
     int32_t profile;         // 1: workgroup 0 times its phases
+    int32_t scalars;         // order 3, 1: real last mode ("RGB scalars"): c holds n3 coefficients per term, S3 is not written
     ResidentResult* res;
 };
 

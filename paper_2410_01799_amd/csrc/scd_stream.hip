@@ -264,7 +264,7 @@ __device__ __forceinline__ void ps_tile_load(PsTile<TE, CPT, RB>& t, const TE* b
 // thread: the branches on them are scalar.
 template <typename TE, int CPT, int RB>
 __device__ __forceinline__ void ps_process(PsTile<TE, CPT, RB>& t, TE* base, int64_t cols, int rb, int rows, int64_t nch,
-                                           int mode, bool full, const TE* sf, uint64_t updb, TE ck, TE* acc, double& fsq,
+                                           int mode, bool full, const TE* sf, uint64_t updb, TE ck, const TE* magrow, TE* acc, double& fsq,
                                            uint8_t* s_new, PsShared& sh, int parity)
 {
     constexpr int VE = PsVec<TE>::N;
@@ -294,9 +294,20 @@ __device__ __forceinline__ void ps_process(PsTile<TE, CPT, RB>& t, TE* base, int
 #pragma unroll
             for (int c = 0; c < CPT; ++c) {
                 const bool ok = full || (rok && (threadIdx.x + c * kPsThreads < nch));
+                // real last mode (magrow != null): the magnitude depends on the column; the row of magnitudes sits in LDS
+                TE mg[VE];
+                if (magrow) {
+                    const V mv = ((const V*)magrow)[ok ? threadIdx.x + c * kPsThreads : 0];
+                    if constexpr (VE == 4) mg[0] = mv.x, mg[1] = mv.y, mg[2] = mv.z, mg[3] = mv.w;
+                    else mg[0] = mv.x, mg[1] = mv.y;
+                } else {
+#pragma unroll
+                    for (int e = 0; e < VE; ++e) mg[e] = ck;
+                }
 #pragma unroll
                 for (int e = 0; e < VE; ++e) {
-                    const TE d = t.x[r][c * VE + e] - ps_flip(ck, sold ^ (uint32_t)((updb >> (c * VE + e)) & 1ull));
+                    const TE mag = mg[e];
+                    const TE d = t.x[r][c * VE + e] - ps_flip(mag, sold ^ (uint32_t)((updb >> (c * VE + e)) & 1ull));
                     t.x[r][c * VE + e] = ok ? d : (TE)0;  // padding stays zero
                 }
                 V v;
@@ -345,7 +356,7 @@ __device__ __forceinline__ void ps_process(PsTile<TE, CPT, RB>& t, TE* base, int
 template <typename TE, int CPT, int RB>
 __device__ __forceinline__ void ps_pass(int mode, TE* lds_rows, int nl, TE* grows, const TE* gsafe, int ng,
                                         PsTile<TE, CPT, RB>& first,
-                                        int64_t cols, uint64_t sumb, uint64_t updb, TE ck, TE* acc, double& fsq,
+                                        int64_t cols, uint64_t sumb, uint64_t updb, TE ck, const TE* magrow, TE* acc, double& fsq,
                                         const uint8_t* s_old, uint8_t* s_new, PsShared& sh)
 {
     static_assert(RB <= 8, "ps_rowsigns packs at most 8 rows");
@@ -365,7 +376,7 @@ __device__ __forceinline__ void ps_pass(int mode, TE* lds_rows, int nl, TE* grow
     for (int rb = 0; rb < nl; rb += RB) {
         ps_tile_load<TE, CPT, RB>(tb, lds_rows, cols, rb, nl, nch, true);
         if (mode == 1) tb.rowsign = ps_rowsigns(s_old, rb, nl);
-        ps_process<TE, CPT, RB>(tb, lds_rows, cols, rb, nl, nch, mode, full_cols && rb + RB <= nl, sf, updb, ck, acc, fsq, s_new,
+        ps_process<TE, CPT, RB>(tb, lds_rows, cols, rb, nl, nch, mode, full_cols && rb + RB <= nl, sf, updb, ck, magrow, acc, fsq, s_new,
                                 sh, parity);
         parity ^= 1;
     }
@@ -376,12 +387,12 @@ __device__ __forceinline__ void ps_pass(int mode, TE* lds_rows, int nl, TE* grow
         const int rb = b * RB;
         ps_tile_load<TE, CPT, RB>(tb, grows, cols, rb + RB, ng, nch, b + 1 < nb);
         if (mode == 1) first.rowsign = ps_rowsigns(s_old + nl, rb, ng);
-        ps_process<TE, CPT, RB>(first, grows, cols, rb, ng, nch, mode, full_cols && rb + RB <= ng, sf, updb, ck, acc, fsq,
+        ps_process<TE, CPT, RB>(first, grows, cols, rb, ng, nch, mode, full_cols && rb + RB <= ng, sf, updb, ck, magrow, acc, fsq,
                                 s_new + nl, sh, parity);
         if (b + 1 < nb) {
             ps_tile_load<TE, CPT, RB>(first, grows, cols, rb + 2 * RB, ng, nch, b + 2 < nb);
             if (mode == 1) tb.rowsign = ps_rowsigns(s_old + nl, rb + RB, ng);
-            ps_process<TE, CPT, RB>(tb, grows, cols, rb + RB, ng, nch, mode, full_cols && rb + 2 * RB <= ng, sf, updb, ck, acc,
+            ps_process<TE, CPT, RB>(tb, grows, cols, rb + RB, ng, nch, mode, full_cols && rb + 2 * RB <= ng, sf, updb, ck, magrow, acc,
                                     fsq, s_new + nl, sh, parity ^ 1);
         }
     }
@@ -474,6 +485,7 @@ __global__ void __launch_bounds__(kPsThreads) pstream_kernel(PStreamArgs a)
     const int nw = a.nw;
     const bool tensor = a.n3 > 0;               // order 3: the columns are (mode 1) x (mode 2), n = n2 * n3
     const int n3 = a.n3, w2 = a.w2;             // w2: words of a mode-1 sign vector (n2 bits)
+    const int sc_n3 = a.scalars ? n3 : 0;       // real last mode: one coefficient per slice of the last mode
 
     extern __shared__ __align__(16) unsigned char ps_lds[];
     // layout: [rows kept in LDS][one row of partial sums][column signs t][t_0 of the coming term][sign bytes x 2]
@@ -555,7 +567,7 @@ __global__ void __launch_bounds__(kPsThreads) pstream_kernel(PStreamArgs a)
         double fsq = 0.0;
         uint8_t* s_old = sp ? sbuf1 : sbuf0;
         uint8_t* s_new = sp ? sbuf0 : sbuf1;
-        ps_pass<TE, CPT, RB>(mode, lds_rows, nl, grows, gfirst, ng, first, n, mode == 0 ? bcur : brng, bcur, ck, acc, fsq,
+        ps_pass<TE, CPT, RB>(mode, lds_rows, nl, grows, gfirst, ng, first, n, mode == 0 ? bcur : brng, bcur, ck, sc_n3 > 0 ? pub : (TE*)nullptr, acc, fsq,
                              s_old, s_new, sh);
         sp ^= 1;  // s_new is the current s
         PS_TICK(0);
@@ -762,6 +774,7 @@ __global__ void __launch_bounds__(kPsThreads) pstream_kernel(PStreamArgs a)
         PS_TICK(4);
         // the scalars: sums of the members' shares, the same order in every workgroup
         double c_tot = 0.0, f_tot = 0.0;
+        double wl[kPsMaxLast] = {0.0, 0.0, 0.0, 0.0};  // order 3: the last mode's sums W_2[c] of this sweep
         auto share = [&](int slot) {
             return tid < G ? __longlong_as_double((long long)(((uint64_t)sh.scal[2 * slot + 1][tid] << 32) | sh.scal[2 * slot][tid]))
                            : 0.0;
@@ -771,7 +784,7 @@ __global__ void __launch_bounds__(kPsThreads) pstream_kernel(PStreamArgs a)
         } else {
             // last mode: s^(3)_c = sgn(W_2[c]); the cut value is <s, a> = sum_c |W_2[c]| (Algorithm 12 line 10)
             uint64_t s3n = 0;
-            double sv[kPsMaxLast], wl[kPsMaxLast];
+            double sv[kPsMaxLast];
 #pragma unroll
             for (int c = 0; c < kPsMaxLast; ++c) sv[c] = c < n3 ? share(c) : 0.0;
             ps_sum_members_n(sv, n3, sh, wl);
@@ -797,6 +810,30 @@ __global__ void __launch_bounds__(kPsThreads) pstream_kernel(PStreamArgs a)
             if (!(c_tot <= c_prev)) warn = 1;
             const double ckd = c_tot / total;
             ck = (TE)ckd;
+            if (sc_n3 > 0) {
+                // real last mode: the coefficient of slice c is <s (x) t, r[..., c]> / (n_1 n_2) = W_2[c] / (n_1 n_2), the
+                // least squares coefficient for these sign vectors; its sign is s^(3)_c, so the update of the next
+                // pass subtracts its magnitude with the signs of the all-signs term.  Stored rounded; what is stored
+                // is what is subtracted.  The magnitudes go, column by column, into the LDS row that holds the partial
+                // sums during an exchange (it is free during a pass).
+                TE coef[kPsMaxLast];
+#pragma unroll
+                for (int c = 0; c < kPsMaxLast; ++c) coef[c] = (TE)(wl[c] / (total / (double)n3));
+                const float rn3 = 1.0f / (float)n3;
+                for (int64_t col = tid; col < n; col += kPsThreads) {
+                    const int cc = (int)col - (int)(((float)col + 0.5f) * rn3) * n3;  // col mod n3 (exact below 2^20)
+                    TE v = coef[0];
+#pragma unroll
+                    for (int c = 1; c < kPsMaxLast; ++c) v = cc == c ? coef[c] : v;
+                    pub[col] = v < (TE)0 ? -v : v;
+                }
+                if (g == 0 && tid < n3) {
+                    TE v = coef[0];
+#pragma unroll
+                    for (int c = 1; c < kPsMaxLast; ++c) v = tid == c ? coef[c] : v;
+                    ((TE*)a.c)[k * n3 + tid] = v;
+                }
+            }
             {
                 // own rows' bits of the first mode: the rows of a workgroup need not start at a word boundary
                 const uint8_t* sc = sp ? sbuf1 : sbuf0;
@@ -817,10 +854,10 @@ __global__ void __launch_bounds__(kPsThreads) pstream_kernel(PStreamArgs a)
                     for (int p = tid; p < nw; p += kPsThreads) a.T[k * nw + p] = t_cur[p];
                 } else {
                     for (int p = tid; p < w2; p += kPsThreads) a.T[k * w2 + p] = s2_cur[p];
-                    if (tid == 0) a.S3[k] = s3_cur;
+                    if (tid == 0 && sc_n3 == 0) a.S3[k] = s3_cur;
                 }
                 if (tid == 0) {
-                    ((TE*)a.c)[k] = ck;
+                    if (sc_n3 == 0) ((TE*)a.c)[k] = ck;
                     a.iters[k] = j;
                 }
             }

@@ -61,7 +61,10 @@ def run_and_check(scd, oracle, a, w, seed):
 
 @pytest.mark.parametrize("shape,w,dtype", [((40, 30, 3), 12, np.float32), ((40, 30, 3), 10, np.float64), ((9, 70, 5, 2), 8, np.float32),
                                            ((130, 1, 3), 6, np.float64), ((66, 9, 1), 7, np.float32), ((50, 64), 8, np.float32),
-                                           ((300, 200, 3), 10, np.float32)])
+                                           ((300, 200, 3), 10, np.float32),
+                                           # order 3 with rows of whole 16-byte pieces: the persistent streaming engine
+                                           ((257, 64, 4), 8, np.float32), ((100, 50, 2), 8, np.float32), ((513, 33, 4), 6, np.float64),
+                                           ((1000, 750, 3), 6, np.float32)])
 def test_scalars_match_oracle_in_lockstep(scd, oracle, shape, w, dtype):
     run_and_check(scd, oracle, gauss(shape, sum(shape) + w, dtype), w, 7)
 
