@@ -13,7 +13,6 @@ import argparse
 import json
 import os
 import sys
-import threading
 import time
 from pathlib import Path
 
@@ -28,7 +27,7 @@ if int(os.environ.get("GPU_MAX_HW_QUEUES", "0") or 0) < _queues:
 import torch  # noqa: E402
 
 from . import scd, workloads
-from .shares import ShareBoard
+from .shares import run_stream_of_jobs
 
 
 def device_weight_like(m: int, n: int, seed: int, kind: str) -> torch.Tensor:
@@ -107,90 +106,50 @@ def main() -> int:
     out.parent.mkdir(parents=True, exist_ok=True)
     K = args.concurrency
     chunk = 1 << 30 if K == 1 else args.chunk
-    cv = threading.Condition()
-    board = ShareBoard()
-    running: dict = {}   # index -> thread
     t_begin = time.perf_counter()
     cost: dict = {}      # (m, n) -> seconds the last matrix of that shape took
-    failures = []
     scd.lib()
     torch.cuda.set_device(0)
-
-    def info(e):
-        return dict(m=e["m"], n=e["n"], left=e["widths"]["1/2"], alt=40.0)
+    jobs = [dict(id=i, m=man[i]["m"], n=man[i]["n"], left=man[i]["widths"]["1/2"], alt=40.0) for i in todo]
 
     with out.open("a") as fh:
-        # one stream per matrix in flight, made once and handed from a finished matrix to the next: streams made
-        # later would share a hardware queue with one that is busy, and every launch of theirs would wait for a
-        # whole launch of the other matrix
-        free_streams = [torch.cuda.Stream() for _ in range(K)] if K > 1 else []
+        def report(row):
+            cost[(row["m"], row["n"])] = row["seconds"]
+            fh.write(json.dumps(row) + "\n")
+            fh.flush()
+            rel = row["rel_err"]
+            print(f"[{row['index']}] {row['name']} {row['m']}x{row['n']} w={row['width']}: "
+                  f"{row['seconds']:.1f} s, {row['terms_per_s']:.0f} terms/s on {row['workgroups']} workgroups, "
+                  f"rel err 1/4 {rel['1/4']:.4f} 3/8 {rel['3/8']:.4f} 1/2 {rel['1/2']:.4f}", flush=True)
 
-        def worker(e):
-            torch.cuda.set_device(0)
-            idx = e["index"]
-            if K > 1:
-                with cv:
-                    stream = free_streams.pop()
-            else:
-                stream = torch.cuda.current_stream()
-            try:
-                with torch.cuda.stream(stream):
-                    row = decompose_one(e, (lambda: board.share(idx)) if K > 1 else (lambda: 0), chunk,
-                                        (lambda left, alt: board.progress(idx, left, alt)) if K > 1 else None)
-            except Exception as err:  # noqa: BLE001 - reported by the main thread
-                with cv:
-                    failures.append((idx, repr(err)))
-                    free_streams.append(stream)
-                    board.release(idx)
-                    running.pop(idx, None)
-                    cv.notify_all()
-                return
-            with cv:
-                cost[(e["m"], e["n"])] = row["seconds"]
-                fh.write(json.dumps(row) + "\n")
-                fh.flush()
-                rel = row["rel_err"]
-                print(f"[{row['index']}] {row['name']} {row['m']}x{row['n']} w={row['width']}: "
-                      f"{row['seconds']:.1f} s, {row['terms_per_s']:.0f} terms/s on {row['workgroups']} workgroups, "
-                      f"rel err 1/4 {rel['1/4']:.4f} 3/8 {rel['3/8']:.4f} 1/2 {rel['1/2']:.4f}", flush=True)
-                board.release(idx)        # the room stays free until the main thread has tried the waiting matrices
-                free_streams.append(stream)
-                running.pop(idx, None)
-                cv.notify_all()
+        def guess(job):
+            return 1.2 * cost.get((job["m"], job["n"]), 0.0)
 
+        failures = []
         if K == 1:
-            while todo and not failures:
-                e = man[todo[0]]
-                if time.perf_counter() - t_begin + 1.2 * cost.get((e["m"], e["n"]), 0.0) > args.budget_seconds:
+            while jobs:
+                if time.perf_counter() - t_begin + guess(jobs[0]) > args.budget_seconds:
                     break
-                todo.pop(0)
-                running[e["index"]] = None
-                worker(e)
+                report(decompose_one(man[jobs.pop(0)["id"]], lambda: 0, chunk))
+            left = jobs
         else:
-            with cv:
-                while True:
-                    # waiting matrices first (in manifest order, each into room that is free now), then what is
-                    # left over to the matrices in flight
-                    while todo and not failures and len(running) < K:
-                        e = man[todo[0]]
-                        if time.perf_counter() - t_begin + 1.2 * cost.get((e["m"], e["n"]), 0.0) > args.budget_seconds:
-                            break
-                        more_wait = len(todo) > 1
-                        if not board.admit(e["index"], info(e), args.share if more_wait else 0):
-                            break
-                        todo.pop(0)
-                        t = threading.Thread(target=worker, args=(e,))
-                        running[e["index"]] = t
-                        t.start()
-                    board.grow()
-                    if not running:
-                        break
-                    cv.wait()
+            def run_one(job, share_fn, progress_fn, stream):
+                torch.cuda.set_device(0)
+                with torch.cuda.stream(stream):
+                    return decompose_one(man[job["id"]], share_fn, chunk, progress_fn)
+
+            # one stream per matrix in flight, made once and handed from a finished matrix to the next: streams made
+            # later would share a hardware queue with one that is busy, and every launch of theirs would wait for a
+            # whole launch of the other matrix
+            res = run_stream_of_jobs(jobs, K, args.share, run_one, [torch.cuda.Stream() for _ in range(K)],
+                                     budget_seconds=args.budget_seconds, guess_seconds=guess, on_done=report)
+            left, failures = res["not_started"], res["failures"]
         torch.cuda.synchronize()
         wall = time.perf_counter() - t_begin
-        fh.write(json.dumps(dict(summary=True, start=args.start, next_index=todo[0] if todo else None,
-                                 concurrency=K, wall_seconds=round(wall, 2))) + "\n")
-    print(f"wall {wall:.1f} s, next index {todo[0] if todo else None}", flush=True)
+        nxt = left[0]["id"] if left else None
+        fh.write(json.dumps(dict(summary=True, start=args.start, next_index=nxt, concurrency=K,
+                                 wall_seconds=round(wall, 2))) + "\n")
+    print(f"wall {wall:.1f} s, next index {nxt}", flush=True)
     if failures:
         print(f"failed: {failures}", file=sys.stderr)
         return 1

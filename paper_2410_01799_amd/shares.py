@@ -13,7 +13,8 @@ doubling the share of the job that would finish last, while the device has room.
 from __future__ import annotations
 
 import threading
-from typing import Dict
+import time
+from typing import Callable, Dict, List, Optional
 
 LATENCY_US = 10.0
 DEVICE = 256
@@ -137,3 +138,66 @@ def solve_shares(jobs: Dict[int, dict], device: int = DEVICE) -> Dict[int, int]:
 def alternation_us(m: int, n: int, g: int) -> float:
     """Cost model: microseconds per alternation of an m x n matrix on g workgroups."""
     return LATENCY_US + work_us(m, n) / g
+
+
+def run_stream_of_jobs(jobs: List[dict], concurrency: int, target_share: int, run_one: Callable, streams: List,
+                       budget_seconds: float = float("inf"), guess_seconds: Optional[Callable] = None,
+                       on_done: Optional[Callable] = None, board: Optional[ShareBoard] = None) -> dict:
+    """Run `jobs` (dicts with id, m, n, left, alt; in this order) with at most `concurrency` in flight, each on a
+    share of the device: a waiting job starts as soon as room that is free holds its share (`target_share`, or what
+    its shape needs; the last waiting job takes all the room there is), and room no waiting job can use goes to the
+    job that would finish last.  `run_one(job, share_fn, progress_fn, stream)` does the work on one of `streams`
+    (one per job in flight, handed from a finished job to the next: on the GPU a stream made later would share a
+    hardware queue with a busy one) and returns a row; `share_fn()` gives the share for the next launch (0 = the
+    whole device), `progress_fn(terms left, alternations per term)` feeds the board.  No job is started once
+    `guess_seconds(job)` more would overrun `budget_seconds`.  Returns dict(rows, not_started, failures, wall_seconds,
+    most_in_flight)."""
+    assert len(streams) >= concurrency >= 1
+    board = board or ShareBoard()
+    cv = threading.Condition()
+    todo = list(jobs)
+    free = list(streams)
+    running: Dict[int, threading.Thread] = {}
+    rows, failures = [], []
+    t_begin = time.perf_counter()
+    most = [0]
+
+    def worker(job, stream):
+        jid = job["id"]
+        try:
+            row = run_one(job, lambda: board.share(jid), lambda left, alt: board.progress(jid, left, alt), stream)
+        except Exception as err:  # noqa: BLE001 - handed to the caller
+            row = None
+            with cv:
+                failures.append((jid, repr(err)))
+        with cv:
+            if row is not None:
+                rows.append(row)
+                if on_done:
+                    on_done(row)
+            board.release(jid)  # the room stays free until the loop below has tried the waiting jobs
+            free.append(stream)
+            running.pop(jid, None)
+            cv.notify_all()
+
+    with cv:
+        while True:
+            while todo and not failures and len(running) < concurrency:
+                job = todo[0]
+                ahead = guess_seconds(job) if guess_seconds else 0.0
+                if time.perf_counter() - t_begin + ahead > budget_seconds:
+                    break
+                info = dict(m=job["m"], n=job["n"], left=job["left"], alt=job.get("alt", 40.0))
+                if not board.admit(job["id"], info, target_share if len(todo) > 1 else 0):
+                    break
+                todo.pop(0)
+                t = threading.Thread(target=worker, args=(job, free.pop()))
+                running[job["id"]] = t
+                most[0] = max(most[0], len(running))
+                t.start()
+            board.grow()
+            if not running:
+                break
+            cv.wait()
+    return dict(rows=rows, not_started=todo, failures=failures, wall_seconds=time.perf_counter() - t_begin,
+                most_in_flight=most[0])

@@ -70,3 +70,54 @@ def test_a_stream_of_waiting_jobs_fills_the_device_with_small_shares():
     assert b.admit(201, dict(m=32000, n=4096, left=29023, alt=30.0), 32) and b.shares[201] == 64   # its shape needs 64
     b.grow()
     assert sum(b.shares.values()) <= 256
+
+
+def test_a_stream_of_jobs_runs_all_of_them_within_the_device_and_the_limit():
+    # the scheduler of the model run with a stand-in for the decomposition: every job runs exactly once, never more
+    # than `concurrency` at a time, the shares in flight never exceed the device, streams are handed on
+    import threading
+    import time
+
+    from paper_2410_01799_amd.shares import run_stream_of_jobs
+
+    jobs = [dict(id=100 + j, m=LAYER[j % 7][0], n=LAYER[j % 7][1], left=LAYER[j % 7][2], alt=40.0) for j in range(23)]
+    jobs.append(dict(id=999, m=32000, n=4096, left=29023, alt=30.0))
+    board = ShareBoard()
+    lock = threading.Lock()
+    in_flight, seen, worst = set(), [], [0, 0]
+    streams = [object() for _ in range(8)]
+
+    def run_one(job, share_fn, progress_fn, stream):
+        with lock:
+            assert stream not in in_flight
+            in_flight.add(stream)
+            seen.append(job["id"])
+            worst[0] = max(worst[0], len(in_flight))
+        for step in range(3):
+            g = share_fn() or 256
+            assert g >= min_share(job["m"], job["n"])
+            with board.lock:
+                worst[1] = max(worst[1], sum(board.shares.values()))
+            time.sleep(0.002 * (1 + job["id"] % 3))
+            progress_fn(job["left"] * (2 - step) // 3, 38.0)
+        with lock:
+            in_flight.discard(stream)
+        return dict(id=job["id"], share=g)
+
+    res = run_stream_of_jobs(jobs, 8, 32, run_one, streams, board=board)
+    assert sorted(seen) == sorted(j["id"] for j in jobs) and len(res["rows"]) == len(jobs)
+    assert not res["failures"] and not res["not_started"]
+    assert worst[0] <= 8 and res["most_in_flight"] <= 8 and worst[1] <= 256
+    assert board.shares == {} and board.jobs == {}
+    # a failing job is reported, nothing new is started after it, and the call still returns
+    def boom(job, share_fn, progress_fn, stream):
+        if job["id"] == 103:
+            raise RuntimeError("no")
+        time.sleep(0.001)
+        return dict(id=job["id"])
+
+    res = run_stream_of_jobs(jobs, 4, 32, boom, streams[:4])
+    assert [f[0] for f in res["failures"]] == [103] and res["not_started"]
+    # a budget that is already spent starts nothing
+    res = run_stream_of_jobs(jobs, 4, 32, boom, streams[:4], budget_seconds=-1.0)
+    assert len(res["not_started"]) == len(jobs) and not res["rows"]
