@@ -85,6 +85,34 @@ def test_scalars_beat_signs_on_an_image_like_tensor(scd):
     assert float((a.double() - E).norm()) == pytest.approx(float(sc["trace"][w]), rel=1e-4)
 
 
+def test_scalars_image_tensor_full_size(scd, oracle):
+    """Workload 4 at its real shape with a real last mode: the first term in lockstep with the oracle (the sweeps are
+    Algorithm 12's, the coefficients the slice-wise least squares ones), the following terms by the definition
+    rebuilt with torch and by the norm identity ||r_{j+1}||^2 = ||r_j||^2 - mn sum_c c_j[c]^2."""
+    from paper_2410_01799_amd import workloads
+
+    a = workloads.image_like_tensor(blobs=24)
+    m, n, q = a.shape
+    ad = torch.from_numpy(a).cuda()
+    w = 4
+    res = scd.scd_decompose_scalars(ad, w, 4)
+    c = res["c"].double()
+    tr = res["trace"].cpu().numpy()
+    cc = c.cpu().numpy()
+    # (the first term removes most of the energy: the tolerance is relative to the minuend; c is stored in f32)
+    assert np.all(np.abs(tr[1:] ** 2 - (tr[:-1] ** 2 - m * n * (cc ** 2).sum(axis=1))) <= 1e-6 * tr[:-1] ** 2)
+    s0 = [oracle.rng_signs(4, 0, i, d) for i, d in enumerate(a.shape)]
+    match_tensor_term(oracle, a.astype(np.float64), s0, [to_np_bits(res["signs"][i])[0] for i in range(2)],
+                      int(res["iters"][0]), True, "first term of the image tensor, real last mode", modes=2)
+    S = 1.0 - 2.0 * torch.from_numpy(np.stack([dense(r_, m) for r_ in to_np_bits(res["signs"][0])]) < 0).double().cuda()
+    T = 1.0 - 2.0 * torch.from_numpy(np.stack([dense(r_, n) for r_ in to_np_bits(res["signs"][1])]) < 0).double().cuda()
+    lead0 = torch.outer(S[0], T[0])
+    want0 = torch.tensordot(lead0, ad.double(), dims=2) / (m * n)   # slice-wise least squares coefficients of term 0
+    assert torch.allclose(c[0], want0, rtol=1e-5, atol=0)
+    E = torch.einsum("ji,jl,jc->ilc", S, T, c)
+    assert float((ad.double() - E).norm()) == pytest.approx(float(tr[w]), rel=1e-4)
+
+
 def test_scalars_edges_and_errors(scd):
     a = torch.from_numpy(gauss((20, 30, 3), 1)).cuda()
     r0 = scd.scd_decompose_scalars(a, 0, 1)
