@@ -468,7 +468,8 @@ __device__ __forceinline__ void ps_kron_bits(uint64_t* out, int64_t n, int n3, c
     }
 }
 
-template <typename TE, int CPT, int RB>
+// SC: real last mode (a template parameter: the all-signs kernels then carry none of its code).
+template <typename TE, int CPT, int RB, bool SC>
 __global__ void __launch_bounds__(kPsThreads) pstream_kernel(PStreamArgs a)
 {
     constexpr int VE = PsVec<TE>::N;
@@ -485,7 +486,6 @@ __global__ void __launch_bounds__(kPsThreads) pstream_kernel(PStreamArgs a)
     const int nw = a.nw;
     const bool tensor = a.n3 > 0;               // order 3: the columns are (mode 1) x (mode 2), n = n2 * n3
     const int n3 = a.n3, w2 = a.w2;             // w2: words of a mode-1 sign vector (n2 bits)
-    const int sc_n3 = a.scalars ? n3 : 0;       // real last mode: one coefficient per slice of the last mode
 
     extern __shared__ __align__(16) unsigned char ps_lds[];
     // layout: [rows kept in LDS][one row of partial sums][column signs t][t_0 of the coming term][sign bytes x 2]
@@ -567,7 +567,7 @@ __global__ void __launch_bounds__(kPsThreads) pstream_kernel(PStreamArgs a)
         double fsq = 0.0;
         uint8_t* s_old = sp ? sbuf1 : sbuf0;
         uint8_t* s_new = sp ? sbuf0 : sbuf1;
-        ps_pass<TE, CPT, RB>(mode, lds_rows, nl, grows, gfirst, ng, first, n, mode == 0 ? bcur : brng, bcur, ck, sc_n3 > 0 ? pub : (TE*)nullptr, acc, fsq,
+        ps_pass<TE, CPT, RB>(mode, lds_rows, nl, grows, gfirst, ng, first, n, mode == 0 ? bcur : brng, bcur, ck, SC ? pub : (TE*)nullptr, acc, fsq,
                              s_old, s_new, sh);
         sp ^= 1;  // s_new is the current s
         PS_TICK(0);
@@ -810,7 +810,7 @@ __global__ void __launch_bounds__(kPsThreads) pstream_kernel(PStreamArgs a)
             if (!(c_tot <= c_prev)) warn = 1;
             const double ckd = c_tot / total;
             ck = (TE)ckd;
-            if (sc_n3 > 0) {
+            if constexpr (SC) {
                 // real last mode: the coefficient of slice c is <s (x) t, r[..., c]> / (n_1 n_2) = W_2[c] / (n_1 n_2), the
                 // least squares coefficient for these sign vectors; its sign is s^(3)_c, so the update of the next
                 // pass subtracts its magnitude with the signs of the all-signs term.  Stored rounded; what is stored
@@ -854,10 +854,10 @@ __global__ void __launch_bounds__(kPsThreads) pstream_kernel(PStreamArgs a)
                     for (int p = tid; p < nw; p += kPsThreads) a.T[k * nw + p] = t_cur[p];
                 } else {
                     for (int p = tid; p < w2; p += kPsThreads) a.T[k * w2 + p] = s2_cur[p];
-                    if (tid == 0 && sc_n3 == 0) a.S3[k] = s3_cur;
+                    if (tid == 0 && !SC) a.S3[k] = s3_cur;
                 }
                 if (tid == 0) {
-                    if (sc_n3 == 0) ((TE*)a.c)[k] = ck;
+                    if (!SC) ((TE*)a.c)[k] = ck;
                     a.iters[k] = j;
                 }
             }
@@ -907,16 +907,10 @@ __global__ void __launch_bounds__(kPsThreads) pstream_kernel(PStreamArgs a)
     }
 }
 
-template <typename TE, int CPT>
-hipError_t ps_launch_rb(const PStreamArgs& a, size_t lds_bytes, hipStream_t st)
+template <typename TE, int CPT, int RB, bool SC>
+hipError_t ps_launch_k(const PStreamArgs& a, size_t lds_bytes, hipStream_t st)
 {
-    constexpr int VE = PsVec<TE>::N;
-    // rows per register tile: at most 32 registers per tile (two tiles are live; more rows per batch would
-    // mean fewer joins across the waves, but with 48 registers per tile the register allocator spills 64-bit
-    // values to odd register pairs, which this compiler then rejects)
-    constexpr int kRegsPerRow = CPT * VE * (int)sizeof(TE) / 4;
-    constexpr int RB = kRegsPerRow > 16 ? 1 : (kRegsPerRow > 8 ? 2 : (kRegsPerRow > 4 ? 4 : 8));
-    auto kern = pstream_kernel<TE, CPT, RB>;
+    auto kern = pstream_kernel<TE, CPT, RB, SC>;
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
     if (e != hipSuccess) return e;
     // every workgroup of the grid must be resident at once: one per compute unit is enough
@@ -929,6 +923,19 @@ hipError_t ps_launch_rb(const PStreamArgs& a, size_t lds_bytes, hipStream_t st)
     if ((int64_t)per_cu * prop.multiProcessorCount < a.grid) return hipErrorCooperativeLaunchTooLarge;
     hipLaunchKernelGGL(kern, dim3(a.grid), dim3(kPsThreads), lds_bytes, st, a);
     return hipGetLastError();
+}
+
+template <typename TE, int CPT>
+hipError_t ps_launch_rb(const PStreamArgs& a, size_t lds_bytes, hipStream_t st)
+{
+    constexpr int VE = PsVec<TE>::N;
+    // rows per register tile: at most 32 registers per tile (two tiles are live; more rows per batch would
+    // mean fewer joins across the waves, but with 48 registers per tile the register allocator spills 64-bit
+    // values to odd register pairs, which this compiler then rejects)
+    constexpr int kRegsPerRow = CPT * VE * (int)sizeof(TE) / 4;
+    constexpr int RB = kRegsPerRow > 16 ? 1 : (kRegsPerRow > 8 ? 2 : (kRegsPerRow > 4 ? 4 : 8));
+    if (a.scalars && a.n3 > 0) return ps_launch_k<TE, CPT, RB, true>(a, lds_bytes, st);
+    return ps_launch_k<TE, CPT, RB, false>(a, lds_bytes, st);
 }
 
 template <typename TE>
